@@ -1,0 +1,303 @@
+"""Pins for the oracle's bit allocation (Eq. 4, Alg. 2 SBA, App. C/D), main loop (Alg. 1 with
+GPTQ's compensation) and storage format (App. B.2)."""
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+from oracle import slim_oracle as orc
+from paper_2405_14917_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_constants.txt")
+
+
+def _golden():
+    out = {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            key, *vals = line.split()
+            out[key] = vals
+    return out
+
+
+# ----------------------------------------------------------------------------- SBA ------
+def _small_layer(seed, n=24, m=64, t=96, beta=8):
+    rng = np.random.default_rng(seed)
+    W = rng.standard_normal((n, m)) * 0.05
+    X = rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]
+    G = X @ X.T
+    U, d, _ = orc.hessian_inverse(G, t, 0.01)
+    _, gs, _ = orc.salience(W, d, beta)
+    return W, X, U, d, gs
+
+
+def test_sba_integer_invariants_and_search_range():
+    g = _golden()
+    for N in (2, 3):
+        for m, beta in ((64, 8), (72, 8), (40, 8)):          # k = 8, 9 (odd), 5 (odd)
+            W, X, U, d, gs = _small_layer(N * 100 + m, m=m, beta=beta)
+            bits, p_star, obj, margin = orc.sba_allocate(W, gs, beta, N, X)
+            k = m // beta
+            assert obj.shape == (k // 2 + 1,)                 # p = 0 .. floor(k/2)
+            allowed = {N + int(o) for o in g["width_offsets"]}
+            assert set(bits.tolist()) <= allowed
+            assert (bits == N - 1).sum() == (bits == N + 1).sum() == p_star
+            assert bits.astype(int).sum() == N * k            # average is exactly N
+            assert np.all(obj >= -1e-12)
+    # the paper's count for LLaMA-7B: 16 search steps beyond uniform precision
+    k7 = int(g["llama7b_m"][0]) // int(g["llama7b_group"][0])
+    assert k7 // 2 == int(g["llama7b_search_iterations"][0])
+
+
+def test_sba_extremes_of_the_double_pointer():
+    order = np.array([3, 0, 2, 1, 5, 4])
+    assert orc.bits_for_p(order, 6, 2, 0).tolist() == [2] * 6             # uniform precision
+    assert orc.bits_for_p(order, 6, 2, 3).tolist() == [1, 3, 1, 1, 3, 3]  # no N-bit group left
+    assert orc.bits_for_p(order, 6, 2, 1).tolist() == [2, 2, 2, 1, 3, 2]
+
+
+def test_sba_brute_force_with_independent_objective():
+    N, beta = 2, 8
+    W, X, U, d, gs = _small_layer(11)
+    n, m = W.shape
+    k = m // beta
+    bits, p_star, obj, _ = orc.sba_allocate(W, gs, beta, N, X)
+    order = sorted(range(k), key=lambda g: (gs[g], g))
+    P = scipy.special.softmax(X.T @ W.T, axis=1)
+    ref = []
+    for p in range(k // 2 + 1):
+        b = [N] * k
+        for g in order[:p]:
+            b[g] = N - 1
+        for g in order[k - p:] if p else []:
+            b[g] = N + 1
+        Wq = orc.rtn_fakequant(W, np.array(b), beta)          # loop form, not the fast one
+        Q = scipy.special.softmax(X.T @ Wq.T, axis=1)
+        ref.append(sum(scipy.stats.entropy(P[s], Q[s]) for s in range(X.shape[1])))
+    assert np.allclose(obj, ref, rtol=1e-9)
+    assert p_star == int(np.argmin(ref))
+    b = [N] * k
+    for g in order[:p_star]:
+        b[g] = N - 1
+    for g in order[k - p_star:] if p_star else []:
+        b[g] = N + 1
+    assert bits.tolist() == b
+
+
+def test_sba_objective_zero_when_quantisation_is_exact():
+    # weights already on a 4-level grid anchored at an integer multiple of the step (Eq. 1 has an
+    # integer zero point): 2-bit RTN reproduces them, KL(p=0) = 0
+    rng = np.random.default_rng(12)
+    n, m, beta = 6, 32, 8
+    levels = np.array([-0.25, 0.0, 0.25, 0.5])
+    W = levels[rng.integers(0, 4, (n, m))]
+    W[:, ::8] = -0.25
+    W[:, 1::8] = 0.5                                           # every group spans the full range
+    X = rng.standard_normal((m, 40))
+    assert np.allclose(orc.rtn_fakequant(W, np.full(4, 2), beta), W, atol=1e-16)
+    gs = np.arange(4, dtype=float)
+    bits, p_star, obj, _ = orc.sba_allocate(W, gs, beta, 2, X)
+    assert abs(obj[0]) < 1e-12 and p_star == 0 and bits.tolist() == [2, 2, 2, 2]
+    assert orc.softmax_kl(X.T @ W.T, X.T @ W.T) == 0.0
+
+
+def test_sba_stable_ties():
+    # equal salience: the lower group index ranks first (is demoted first)
+    rng = np.random.default_rng(13)
+    W = rng.standard_normal((8, 32)) * 0.05
+    X = rng.standard_normal((32, 30))
+    gs = np.array([1.0, 1.0, 1.0, 1.0])
+    bits, p_star, obj, _ = orc.sba_allocate(W, gs, 8, 2, X)
+    if p_star == 1:
+        assert bits.tolist() == [1, 2, 2, 3]
+    if p_star == 2:
+        assert bits.tolist() == [1, 1, 3, 3]
+    assert orc.bits_for_p(np.argsort(gs, kind="stable"), 4, 2, 1).tolist() == [1, 2, 2, 3]
+
+
+# ----------------------------------------------------------------------------- main loop -
+def _obq_reference(W, Hd, scale, zero, bits, beta):
+    """Independent column-serial reference without any Cholesky factor: optimal-brain style
+    update with the explicit inverse, eliminating one column at a time
+    (w -= err / Hinv_cc * Hinv[c, :], then Hinv <- Hinv - Hinv[:,c] Hinv[c,:] / Hinv_cc).
+    Quantiser parameters are given."""
+    W = W.copy()
+    n, m = W.shape
+    Hinv = np.linalg.inv(Hd)
+    codes = np.zeros((n, m), dtype=np.uint8)
+    for c in range(m):
+        g = c // beta
+        bt = int(bits[g])
+        for i in range(n):
+            s, z = scale[i, g], zero[i, g]
+            if bt == 1:
+                q = 1.0 if W[i, c] >= 0 else 0.0
+            else:
+                q = min(max(round(W[i, c] / s) + z, 0.0), 2.0 ** bt - 1)
+            codes[i, c] = int(q)
+            err = W[i, c] - s * (q - z)
+            W[i, c:] -= err / Hinv[c, c] * Hinv[c, c:]
+        Hinv = Hinv - np.outer(Hinv[:, c], Hinv[c, :]) / Hinv[c, c]
+    return codes
+
+
+def test_gptq_identity_hessian_is_round_to_nearest():
+    rng = np.random.default_rng(20)
+    n, m, beta = 16, 64, 16
+    W = rng.standard_normal((n, m)) * 0.02
+    U, d, _ = orc.hessian_inverse(np.eye(m), 2, 0.01)         # H = I
+    assert np.allclose(U, np.eye(m) * U[0, 0])
+    bits = np.array([2, 3, 1, 2], dtype=np.uint8)
+    tau = orc.tau_grid()
+    out = orc.gptq_quantize(W, U, bits, beta, tau)
+    for g in range(4):
+        blk = W[:, g * beta:(g + 1) * beta]
+        s, z, c, _ = orc.sqc_calibrate(blk, int(bits[g]), tau)     # parameters from the ORIGINAL weights
+        assert np.array_equal(out["scale"][:, g], s) and np.array_equal(out["zero"][:, g], z)
+        if bits[g] == 1:
+            q = (blk >= 0).astype(np.uint8)
+        else:
+            q = np.stack([orc.quantize_affine(blk[i], s[i], z[i], int(bits[g])) for i in range(n)]).astype(np.uint8)
+        assert np.array_equal(out["codes"][:, g * beta:(g + 1) * beta], q)
+
+
+def test_gptq_identities_and_blocking():
+    rng = np.random.default_rng(21)
+    n, m, beta, t = 12, 48, 8, 200
+    W = rng.standard_normal((n, m)) * 0.02
+    X = rng.standard_normal((m, t))
+    X = X + 0.6 * rng.standard_normal((m, 3)) @ rng.standard_normal((3, t))     # correlated channels
+    G = X @ X.T
+    U, d, lam = orc.hessian_inverse(G, t, 0.01)
+    Hd = 2.0 / t * G + lam * np.eye(m)
+    bits = np.array([2, 3, 1, 2, 3, 1], dtype=np.uint8)
+    tau = orc.tau_grid()
+    out = orc.gptq_quantize(W, U, bits, beta, tau)
+    dW = W - out["What"]
+    # W - What = E U   and   sum e^2 = tr(dW (H + lam I) dW^T)
+    assert np.allclose(dW, out["E"] @ U, rtol=1e-9, atol=1e-12)
+    assert out["sum_e2"] == pytest.approx(np.sum((dW @ Hd) * dW), rel=1e-9)
+    # What is the dequantisation of the codes with the reported parameters
+    deq = np.repeat(out["scale"], beta, axis=1) * (out["codes"] - np.repeat(out["zero"], beta, axis=1))
+    assert np.allclose(out["What"], deq, rtol=1e-15, atol=0)
+    # the block size of the lazy update does not change the result
+    for B in (m, 2 * beta):
+        o2 = orc.gptq_quantize(W, U, bits, beta, tau, gptq_block=B)
+        assert np.array_equal(o2["codes"], out["codes"])
+        assert np.allclose(o2["scale"], out["scale"], rtol=1e-12)
+    # ||dW X||^2 = tr(dW G dW^T)
+    assert orc.reconstruction_error(W, out["What"], G) == pytest.approx(np.sum((dW @ X) ** 2), rel=1e-10)
+    # compensation helps: the layer-output error is below plain round-to-nearest with the same grids
+    rtn = np.zeros_like(W)
+    for g in range(m // beta):
+        for i in range(n):
+            blk = W[i, g * beta:(g + 1) * beta]
+            s, z = out["scale"][i, g], out["zero"][i, g]
+            q = (blk >= 0).astype(float) if bits[g] == 1 else orc.quantize_affine(blk, s, z, int(bits[g]))
+            rtn[i, g * beta:(g + 1) * beta] = s * (q - z)
+    assert orc.reconstruction_error(W, out["What"], G) < orc.reconstruction_error(W, rtn, G)
+
+
+def test_gptq_matches_cholesky_free_reference():
+    # with the quantiser parameters fixed, the codes equal those of the explicit-inverse
+    # elimination form (the compensation row U[c, c:] / U_cc is Hinv_c[c, c:] / Hinv_c[c, c])
+    rng = np.random.default_rng(22)
+    n, m, beta, t = 6, 24, 8, 100
+    W = rng.standard_normal((n, m)) * 0.02
+    X = rng.standard_normal((m, t)) + 0.8 * rng.standard_normal((m, 2)) @ rng.standard_normal((2, t))
+    G = X @ X.T
+    U, d, lam = orc.hessian_inverse(G, t, 0.01)
+    Hd = 2.0 / t * G + lam * np.eye(m)
+    bits = np.array([2, 1, 3], dtype=np.uint8)
+    out = orc.gptq_quantize(W, U, bits, beta, orc.tau_grid())
+    assert out["round_margin"].min() > 1e-9
+    ref_codes = _obq_reference(W, Hd, out["scale"], out["zero"], bits, beta)
+    # the parameters of group g were fixed from the compensated weights at the group's start,
+    # which the reference reproduces because it applies the same updates in the same order
+    assert np.array_equal(ref_codes, out["codes"])
+
+
+def test_pipeline_invariant_under_hessian_scale():
+    # scaling X by 2 scales H by 4: bits, codes, scale, zero must not move (relative damping)
+    cfg = synth.scaled(synth.CONFIGS["C1"], n=32, m=64, t=256, beta=16)
+    W = synth.make_weights(cfg)
+    X = synth.make_activations(cfg, correlated=True).astype(np.float64)
+    a = orc.slim_layer(W, [X], cfg.beta, 2, t_sba=64, do_pack=False)
+    b = orc.slim_layer(W, [2.0 * X], cfg.beta, 2, t_sba=64, do_pack=False)
+    assert np.array_equal(a["codes"], b["codes"])
+    assert np.array_equal(a["scale"], b["scale"]) and np.array_equal(a["zero"], b["zero"])
+    assert np.allclose(a["group_sal"] * 16.0, b["group_sal"], rtol=1e-9)   # salience scales, its ranking does not
+    assert np.array_equal(np.argsort(a["group_sal"], kind="stable"), np.argsort(b["group_sal"], kind="stable"))
+
+
+def test_pipeline_c1_properties():
+    cfg = synth.CONFIGS["C1"]
+    W = synth.make_weights(cfg)
+    X = synth.make_activations(cfg)
+    out = orc.slim_layer(W, [X], cfg.beta, cfg.N)
+    bits = out["bits"]
+    assert set(bits.tolist()) <= {1, 2, 3} and int(bits.sum()) == cfg.N * cfg.k
+    assert out["m_star"] == cfg.m * cfg.N // 32
+    # Theorem 1: the group holding the activation outlier channels is the most salient one
+    ch = synth.outlier_activation_channels(cfg)
+    assert np.argmax(out["group_sal"]) in set((ch // cfg.beta).tolist())
+    codes2, bits2 = orc.unpack(out["packed"], out["gbits"], cfg.beta, cfg.k)
+    assert np.array_equal(codes2, out["codes"]) and np.array_equal(bits2, bits)
+    # every group's SQC result is at least as good as its tau = 1 candidate (L* <= L(min-max))
+    assert np.all(out["cand_idx"] >= 0) and np.all(out["cand_idx"] < 100)
+
+
+# ----------------------------------------------------------------------------- storage ---
+def test_pack_worked_examples_by_hand():
+    # 2-bit codes 0,1,2,3 repeating: each byte is 0b11100100 = 0xE4
+    codes = np.tile(np.array([0, 1, 2, 3], dtype=np.uint8), 8)[None, :]          # n = 1, beta = 32
+    packed, gbits, row_off, m_star = orc.pack(codes, np.array([2]), 32)
+    assert m_star == 2 and row_off.tolist() == [0, 2]
+    assert packed[:, 0].tolist() == [0xE4E4E4E4, 0xE4E4E4E4]
+    assert gbits.tolist() == [1]                                                  # width 2 stored as 1
+    # 3-bit codes straddle word boundaries: element 10 occupies stream bits 30..32
+    c3 = np.zeros((1, 32), dtype=np.uint8)
+    c3[0, 10] = 0b101
+    c3[0, 0] = 0b111
+    c3[0, 31] = 0b110
+    packed, gbits, row_off, m_star = orc.pack(c3, np.array([3]), 32)
+    assert m_star == 3
+    assert packed[:, 0].tolist() == [0b111 | (0b01 << 30), 0b1, 0b110 << 29]
+    assert gbits.tolist() == [2]
+    # two output rows, two groups of different width: layout (m_star, n), groups stacked, no padding
+    cc = np.zeros((2, 64), dtype=np.uint8)
+    cc[1, 0] = 1                  # group 0 (1 bit), row 1, element 0
+    cc[0, 32 + 5] = 0xF           # group 1 (4 bits), row 0, element 5 -> bits 20..23 of word 0
+    packed, gbits, row_off, m_star = orc.pack(cc, np.array([1, 4]), 32)
+    assert row_off.tolist() == [0, 1, 5] and packed.shape == (5, 2)
+    assert packed[0].tolist() == [0, 1]
+    assert packed[1].tolist() == [0xF << 20, 0]
+    assert gbits.tolist() == [0 | (3 << 2)]
+
+
+def test_pack_roundtrip_sizes_and_fast_form():
+    g = _golden()
+    beta = int(g["pack_group"][0])
+    rng = np.random.default_rng(30)
+    k, n = 6, 5
+    bits = np.array([1, 2, 3, 4, 3, 1], dtype=np.uint8)
+    codes = np.concatenate([rng.integers(0, 2 ** b, (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    packed, gbits, row_off, m_star = orc.pack(codes, bits, beta)
+    # a 128-element group fills whole 32-bit words at every width (no padding, App. B.2)
+    assert all((beta * b) % int(g["pack_word_bits"][0]) == 0 for b in (1, 2, 3, 4))
+    assert m_star == sum(beta * int(b) // 32 for b in bits) == packed.shape[0]
+    assert np.array_equal(np.diff(row_off), beta * bits.astype(int) // 32)
+    c2, b2 = orc.unpack(packed, gbits, beta, k)
+    assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
+    pf = orc.pack_fast(codes, bits, beta)
+    assert np.array_equal(pf[0], packed) and np.array_equal(pf[1], gbits) and np.array_equal(pf[2], row_off)
+    # balanced allocation: m_star = m N / 32
+    bits_bal = np.array([1, 3, 2, 2, 3, 1], dtype=np.uint8)
+    assert orc.pack_fast(np.zeros((1, k * beta), np.uint8), bits_bal, beta)[3] == k * beta * 2 // 32
+    # more than 16 groups: second word of the width array
+    bits17 = np.array([1] * 16 + [4], dtype=np.uint8)
+    gb = orc.pack_fast(np.zeros((1, 17 * 32), np.uint8), bits17, 32)[1]
+    assert gb.tolist() == [0, 3]
