@@ -1,0 +1,210 @@
+/*
+ * libslim -- the per-linear-layer quantisation pass of SliM-LLM (salience-driven mixed-precision
+ * group quantisation, arXiv 2405.14917) as hand-written gfx950 (MI355X) HIP kernels.
+ *
+ * Notation is the paper's (Sec. 3.1, Alg. 1):  W in R^{n x m} with n output rows and m input
+ * channels; calibration activations are handed over as X in R^{m x t} (input channels x tokens);
+ * beta = group size along the input dimension, k = m / beta groups; N = target average width;
+ * allowed widths {N-1, N, N+1}.
+ *
+ * Conventions for every entry point
+ *  - Pointers are DEVICE pointers unless the comment says "host".  All matrices are row-major with
+ *    an explicit leading dimension counted in elements.  The caller owns every buffer passed in;
+ *    the library keeps an internal, grow-only device workspace tied to the context and frees it in
+ *    slim_destroy.
+ *  - Work is enqueued on the HIP stream given to slim_create.  A call returns as soon as its work
+ *    is enqueued, except where it has a host output (info, p_star, obj_curve, m_star): those calls
+ *    synchronise the stream before returning.
+ *  - Return value: SLIM_OK or a negative slim_status.  No exceptions, no aborts.  After an error
+ *    slim_last_error(ctx) describes it; on SLIM_ERR_INVALID_ARG / SLIM_ERR_UNSUPPORTED nothing has
+ *    been launched and no output was touched.
+ *  - Device pointers must be 16-byte aligned, leading dimensions of 16-bit matrices multiples
+ *    of 8 elements.
+ *  - Calls on one context must not overlap in time (one stream, one workspace).
+ *  - Results are deterministic: the same inputs give the same bytes on every run.
+ */
+#ifndef SLIM_H
+#define SLIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct slim_ctx slim_ctx;
+
+typedef enum {
+  SLIM_OK = 0,
+  SLIM_ERR_INVALID_ARG = -1, /* bad size, null / misaligned pointer, inconsistent arguments   */
+  SLIM_ERR_NOT_PD = -2,      /* H + lambda I is not positive definite                           */
+  SLIM_ERR_ALLOC = -3,       /* the internal workspace could not be grown                       */
+  SLIM_ERR_HIP = -4,         /* a HIP runtime call failed                                       */
+  SLIM_ERR_UNSUPPORTED = -5  /* valid in the paper's terms but not built (dtype, mode, size)    */
+} slim_status;
+
+typedef enum { SLIM_F16 = 0, SLIM_BF16 = 1, SLIM_F32 = 2, SLIM_F64 = 3 } slim_dtype;
+
+/* Mode switches for the points the paper leaves open; value 0 is the default everywhere. */
+enum { SLIM_WEIGHT_MASK_MEAN = 0, SLIM_WEIGHT_UNIFORM = 1, SLIM_WEIGHT_ELEMENT = 2 };
+enum { SLIM_Q1_SIGN = 0, SLIM_Q1_AFFINE = 1 };
+enum { SLIM_SCOPE_BLOCK = 0, SLIM_SCOPE_ROW = 1 };
+enum { SLIM_SAL_HINV_DIAG = 0, SLIM_SAL_CHOL_DIAG = 1 };
+enum { SLIM_OBJ_KL = 0 };
+
+typedef struct slim_params {
+  /* SQC loss weights (Eq. 5, Alg. 2 SQC lines 13-15):
+   *   MASK_MEAN  L = L_s/|s| + L_us/|us|  (mean squared error of the 3-sigma salient part plus that
+   *              of the rest; a part without elements contributes nothing),
+   *   UNIFORM    L = L_s + L_us (Eq. 5 as printed),
+   *   ELEMENT    L = sum_j delta_j e_j^2 with delta_j = w_j^2 / [H^-1]_jj^2 (Def. 1).             */
+  int sqc_weight_mode;
+  /* statistics of the 3-sigma rule (Sec. 3.3.2): over the whole current n x beta block, or per row */
+  int mask_scope;
+  /* width-1 groups: sign / mean-absolute-value quantiser of Eq. 2, or two-level Eq. 1              */
+  int q1_mode;
+  /* salience denominator: [H^-1]_jj (Def. 1) or U_jj (Alg. 2 SBA line 6 read literally)            */
+  int sal_mode;
+} slim_params;
+
+/* Host only.  Fills *p with the defaults (all zero). */
+void slim_default_params(slim_params* p);
+
+/* Host only.  Writes the default SQC candidate grid tau_c = (1 - lambda) + c * (lambda / n),
+ * c = 0 .. 2n-1, lambda = 0.1, n = 50 (Sec. 3.3.2; Alg. 2 SQC lines 3-4 and 8) into tau_host[0..cap)
+ * and returns the number of candidates (100).  tau_host may be NULL to query the count. */
+int slim_default_tau(double* tau_host, int cap);
+
+/* Creates a context bound to `hip_stream` (a hipStream_t, may be NULL for the default stream) on
+ * the current device.  Allocates small fixed device buffers (default tau grid, flags). */
+slim_status slim_create(slim_ctx** out, void* hip_stream);
+slim_status slim_destroy(slim_ctx* ctx);
+const char* slim_last_error(const slim_ctx* ctx);
+/* Bytes of device workspace currently held by the context (host only). */
+size_t slim_workspace_bytes(const slim_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------------------
+ * a1  Proxy Hessian (Eq. 3; Alg. 1 line 1).   G += X_c X_c^T  for one chunk of t_c tokens.
+ *   X        m x t_c, F16 or BF16, tokens contiguous (ldx >= t_c), read only
+ *   G        m x m fp32 raw Gram matrix, both triangles kept up to date; the caller zero-initialises
+ *            it before the first chunk.  H = (2 / n_tokens) G is formed lazily by slim_hessian_inverse.
+ *   n_tokens host, in/out: incremented by t_c
+ * Products are exact (fp16 x fp16 in fp32), accumulation is fp32 in the matrix cores.
+ * t_c may be any positive number (a ragged tail is zero-padded internally); m must be a multiple of 8.
+ */
+slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, slim_dtype x_dtype, int m, int64_t t_c,
+                                    int64_t ldx, float* G, int64_t ldg, int64_t* n_tokens);
+
+/* ---------------------------------------------------------------------------------------------
+ * a2  Damped inverse and its Cholesky factor (Def. 1; Alg. 1 line 2).
+ *   H = (2 / n_tokens) G,  lambda = percdamp * mean(diag H),
+ *   U = upper-triangular factor with (H + lambda I)^-1 = U^T U  (fp64, m x m; the strictly lower
+ *       triangle is written as zero),  hinv_diag_j = [(H + lambda I)^-1]_jj = sum_i U_ij^2.
+ *   info  host: 0 on success, otherwise the 1-based index of a column at which a non-positive pivot
+ *         appeared; the call then returns SLIM_ERR_NOT_PD and U / hinv_diag hold no valid result.
+ * Only the upper triangle of G is read.  All arithmetic after widening G is fp64.
+ */
+slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64_t ldg, int m, int64_t n_tokens,
+                                 double percdamp, double* U, int64_t ldu, double* hinv_diag, int* info);
+
+/* ---------------------------------------------------------------------------------------------
+ * a3  Salience (Def. 1; Alg. 2 SBA line 6).
+ *   col_sal_j   = sum_i w_ij^2 / d_j^2          (m values)
+ *   group_sal_g = mean over the n x beta entries of group g of w_ij^2 / d_j^2   (k values)
+ *   elem_sal    = optional n x m map (ld = m), may be NULL
+ *   d_j = hinv_diag_j (SLIM_SAL_HINV_DIAG) or U_jj (SLIM_SAL_CHOL_DIAG).
+ *   W is F16, BF16 or F32, n x m, read only.
+ */
+slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                          const double* U, int64_t ldu, const double* hinv_diag, int sal_mode, int beta,
+                          double* col_sal, double* group_sal, double* elem_sal);
+
+/* ---------------------------------------------------------------------------------------------
+ * a4  Salience-Determined Bit Allocation (Eq. 4; Alg. 2 SBA; App. C and D).
+ *   Groups are ranked by group_sal (stable, ascending).  For p = 0 .. floor(k/2): the p least salient
+ *   groups get N-1 bits, the p most salient N+1, the rest N; the original W is fake-quantised per
+ *   (row, group) with the default parameters of Eq. 1 (Eq. 2 for width 1) and the objective is
+ *   sum over the t_s tokens of KL(softmax(x W^T) || softmax(x W_p^T)), softmax over the n outputs.
+ *   The smallest p attaining the minimum is kept.
+ *   X_s       m x t_s (F16/BF16), tokens contiguous, the calibration tokens used by the objective
+ *   bits      device, k bytes: the chosen width of every group
+ *   p_star    host
+ *   obj_curve host, floor(k/2)+1 doubles or NULL: the objective for every p
+ *   N must be 2 or 3 (widths 1..4).  All arithmetic is fp64.
+ */
+slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                              const double* group_sal, int beta, int N, int objective, const void* X_s,
+                              slim_dtype x_dtype, int64_t t_s, int64_t ldxs, const slim_params* params,
+                              uint8_t* bits, int* p_star, double* obj_curve);
+
+/* ---------------------------------------------------------------------------------------------
+ * a5 + a6  3-sigma mask and Salience-Weighted Quantizer Calibration on ONE n x beta block of
+ * current weights (Sec. 3.3.2; Eq. 5; Alg. 1 line 8; Alg. 2 SQC).
+ *   For every row: delta0, z from Eq. 1 on the row's beta values (z does not depend on tau); for each
+ *   candidate c: delta = tau_c delta0, loss L_c = sum_j omega_j (w_j - w_hat_j)^2; first minimum wins.
+ *   Width 1 with SLIM_Q1_SIGN: alpha = mean|w|, w_hat = tau_c alpha sign(w); reported as
+ *   scale = 2 tau alpha, zero = 1/2, so that w_hat = scale * (q - zero) holds for every width.
+ *   Wblk      n x beta fp64 (ldw >= beta)
+ *   omega     optional n x beta fp64 (ld = beta) explicit loss weights; NULL = derive from params
+ *   hinv_diag_blk  beta values of [H^-1]_jj for the block's columns, needed by SLIM_WEIGHT_ELEMENT only
+ *   tau       ncand candidates (device), or NULL for the default grid (then ncand is ignored)
+ *   scale, zero  n doubles each;  cand_idx  n ints or NULL
+ *   beta in {32, 64, 128, 256}; bits in 1..4.
+ */
+slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, int n, int beta, int bits,
+                               const double* omega, const double* hinv_diag_blk, const slim_params* params,
+                               const double* tau, int ncand, double* scale, double* zero, int* cand_idx);
+
+/* ---------------------------------------------------------------------------------------------
+ * a5 - a8  Main loop (Alg. 1 lines 5-13) with GPTQ's column-serial error compensation.
+ *   For each group b (beta columns): mask + SQC on the current weights of the group; then column by
+ *   column q = Q(w_c), w_hat = scale (q - zero), e = (w_c - w_hat) / U_cc, remaining columns of the
+ *   group get w_j -= e U_cj; after the group all later columns get W[:, later] -= E_b U[b, later].
+ *   W         n x m, F16/BF16/F32, read only; the working copy (fp64) lives in the workspace
+ *   U         from slim_hessian_inverse (fp64, upper triangular, zero below the diagonal)
+ *   bits      device, k bytes, every value in 1..4
+ *   gptq_block  must equal beta (the lazy-update block is the group)
+ *   hinv_diag needed by SLIM_WEIGHT_ELEMENT only, else may be NULL
+ *   codes     n x m bytes (ld = m);  scale, zero  n x k doubles (ld = k)
+ *   What      optional dequantised weights n x m (ld = m) in what_dtype (F32 or F64), or NULL
+ *   sum_e2    optional device double: sum of squares of all compensation errors e
+ * All arithmetic is fp64, so that rounding decisions agree with a float64 reference.
+ */
+slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                               const double* U, int64_t ldu, const uint8_t* bits, int beta, int gptq_block,
+                               const slim_params* params, const double* hinv_diag, const double* tau,
+                               int ncand, uint8_t* codes, double* scale, double* zero, void* What,
+                               slim_dtype what_dtype, double* sum_e2);
+
+/* ---------------------------------------------------------------------------------------------
+ * a9  Storage format (App. B.2).
+ *   row_off[g] = sum_{g' < g} beta * bits[g'] / 32  (k+1 ints; row_off[k] = m_star)
+ *   packed     m_star x n 32-bit words (ld = n): for group g and output row i the beta codes form a
+ *              little-endian bit stream (element r at bits [r b, (r+1) b)) whose words occupy rows
+ *              row_off[g] .. of column i.  No padding, no word mixes two widths.
+ *   gbits      ceil(k/16) words: bits[g]-1 as a 2-bit value, 16 groups per word, least significant first
+ *   packed_rows  capacity of `packed` in rows; if m_star exceeds it the call fails with
+ *              SLIM_ERR_INVALID_ARG and writes nothing beyond the capacity
+ *   m_star     host
+ *   beta * b must be a multiple of 32 for every width in use (beta a multiple of 32).
+ */
+slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,
+                      int beta, uint32_t* packed, int64_t packed_rows, uint32_t* gbits, int32_t* row_off,
+                      int* m_star);
+
+/* ---------------------------------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the context's stream (measurement aid, host only).
+ * While enabled, every kernel launch of the library is bracketed by an event pair.
+ * slim_profile_collect synchronises, folds the pending pairs into per-kernel totals and returns
+ * the number of distinct kernel names; slim_profile_entry reads entry i.
+ */
+slim_status slim_profile_enable(slim_ctx* ctx, int on);
+int slim_profile_collect(slim_ctx* ctx);
+slim_status slim_profile_entry(const slim_ctx* ctx, int i, const char** name, double* total_ms, int* launches);
+slim_status slim_profile_reset(slim_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIM_H */

@@ -1,0 +1,325 @@
+// a2  Damped inverse Hessian and its upper Cholesky factor (Def. 1; Alg. 1 line 2), all in fp64.
+//
+// Wanted: upper-triangular U with (H + lambda I)^-1 = U^T U.  Writing R = U^-1 (upper triangular) gives
+// H + lambda I = R R^T, a Cholesky factorisation taken from the bottom-right corner upwards, so the
+// textbook route (factor, invert, factor again) collapses to ONE factorisation and ONE triangular
+// inverse, (2/3) m^3 flops instead of (4/3) m^3:
+//
+//   1. widen:   A = (2 / n_tokens) G + lambda I,  lambda = percdamp * mean(diag(2 / n_tokens G))
+//   2. for the diagonal blocks J = last .. first (64 columns each):
+//        chol_diag   A_JJ = R_JJ R_JJ^T in LDS by one workgroup, plus V_JJ = R_JJ^-1 (written into U)
+//        panel       R[0:J, J] = A[0:J, J] V_JJ^T                    (fp64 MFMA GEMM)
+//        update      A[0:J, 0:J] -= R[0:J, J] R[0:J, J]^T, upper tiles only   (fp64 MFMA GEMM)
+//   3. triangular inverse by recursive doubling: ranges of 2^l diagonal blocks that are already inverted
+//      are merged pairwise, U12 = -U11 (R12 U22); all pairs of a level form one batched GEMM launch.
+//   4. hinv_diag_j = sum_i U_ij^2.
+#include "slim_device.h"
+#include "slim_internal.h"
+
+namespace {
+
+constexpr int NB = 64;          // diagonal block
+constexpr int LDA = NB + 1;     // LDS row stride of the block being factored
+
+// mean of the diagonal of H = s * G, then lambda; single workgroup, fixed order
+__global__ __launch_bounds__(256) void damp_lambda(const float* __restrict__ G, int64_t ldg, int m, double s,
+                                                   double percdamp, double* __restrict__ lam_out,
+                                                   int* __restrict__ flag) {
+  __shared__ double red[256];
+  if (threadIdx.x == 0) *flag = 0;
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < m; i += 256) acc += s * (double)G[(int64_t)i * ldg + i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *lam_out = percdamp * (red[0] / (double)m);
+}
+
+// A = s * G + lambda I on and above the diagonal, zero below
+__global__ __launch_bounds__(256) void widen_damp(const float* __restrict__ G, int64_t ldg, int m, double s,
+                                                  const double* __restrict__ lam, double* __restrict__ A,
+                                                  int64_t lda) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int r = blockIdx.y;
+  if (c >= m) return;
+  double v = 0.0;
+  if (c >= r) {
+    v = s * (double)G[(int64_t)r * ldg + c];
+    if (c == r) v += *lam;
+  }
+  A[(int64_t)r * lda + c] = v;
+}
+
+__global__ __launch_bounds__(256) void zero_matrix(double* __restrict__ A, int64_t lda, int m) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < m) A[(int64_t)blockIdx.y * lda + c] = 0.0;
+}
+
+// One workgroup factors the nbk x nbk diagonal block at A (upper triangle valid) as R R^T with R upper
+// triangular, from the last column to the first, writes R back (zero below the diagonal) and its inverse V
+// into Vout.  A non-positive pivot is recorded in flag[0] (1-based global column) and replaced by 1.
+__global__ __launch_bounds__(256) void chol_diag(double* __restrict__ A, int64_t lda, int nbk, double* __restrict__ Vout,
+                                                 int64_t ldv, int* __restrict__ flag, int col_base) {
+  extern __shared__ __align__(16) double sm[];
+  double* a = sm;               // [NB][LDA]
+  double* b = sm + NB * LDA;    // [NB][LDA]
+  const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
+  for (int idx = tid; idx < NB * NB; idx += 256) {
+    const int i = idx >> 6, l = idx & 63;
+    double v = (i == l) ? 1.0 : 0.0;
+    if (i < nbk && l < nbk) v = (l >= i) ? A[(int64_t)i * lda + l] : 0.0;
+    a[i * LDA + l] = v;
+    b[i * LDA + l] = (i == l) ? 1.0 : 0.0;
+  }
+  __syncthreads();
+  // factorisation: after step j, column j holds R[:, j] * R[j][j] (scaled at the end)
+  for (int j = NB - 1; j >= 0; --j) {
+    double piv = a[j * LDA + j];
+    if (!(piv > 0.0)) {
+      if (tid == 0 && j < nbk && flag[0] == 0) flag[0] = col_base + j + 1;
+      piv = 1.0;
+    }
+    const double inv = 1.0 / piv;
+    if (tx < j) {
+      const double alj = a[tx * LDA + j] * inv;
+      for (int i = ty; i <= tx; i += 4) a[i * LDA + tx] -= a[i * LDA + j] * alj;
+    }
+    __syncthreads();
+    // nothing reads a[j][j] again before the scaling pass: keep the sanitised pivot for it
+    if (tid == 0 && !(a[j * LDA + j] > 0.0)) a[j * LDA + j] = 1.0;
+  }
+  __syncthreads();
+  // scale: R[i][j] = a[i][j] / sqrt(a[j][j])
+  {
+    const double d = sqrt(a[tx * LDA + tx]);
+    __syncthreads();
+    for (int i = ty; i <= tx; i += 4) a[i * LDA + tx] = (i == tx) ? d : a[i * LDA + tx] / d;
+    __syncthreads();
+  }
+  // inverse by back substitution on all columns at once: R V = I
+  for (int i = NB - 1; i > 0; --i) {
+    const double rinv = 1.0 / a[i * LDA + i];
+    if (tx >= i) {
+      const double v = b[i * LDA + tx] * rinv;
+      for (int ip = ty; ip < i; ip += 4) b[ip * LDA + tx] -= a[ip * LDA + i] * v;
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < NB * NB; idx += 256) {
+    const int i = idx >> 6, l = idx & 63;
+    if (i < nbk && l < nbk) {
+      A[(int64_t)i * lda + l] = (l >= i) ? a[i * LDA + l] : 0.0;
+      Vout[(int64_t)i * ldv + l] = (l >= i) ? b[i * LDA + l] / a[i * LDA + i] : 0.0;
+    }
+  }
+}
+
+// partial column sums of squares of the upper triangle of U: grid (ceil(m/64), parts); part p owns 256 rows
+__global__ __launch_bounds__(256) void colsumsq_upper(const double* __restrict__ U, int64_t ldu, int m,
+                                                      double* __restrict__ partial) {
+  __shared__ double red[4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
+  const int r0 = blockIdx.y * 256;
+  double acc = 0.0;
+  if (c < m) {
+    const int r1 = min(min(m, r0 + 256), c + 1);
+    for (int r = r0 + ty; r < r1; r += 4) {
+      const double v = U[(int64_t)r * ldu + c];
+      acc += v * v;
+    }
+  }
+  red[ty][tx] = acc;
+  __syncthreads();
+  if (ty == 0 && c < m) partial[(int64_t)blockIdx.y * m + c] = ((red[0][tx] + red[1][tx]) + red[2][tx]) + red[3][tx];
+}
+
+__global__ __launch_bounds__(256) void colsum_finalize(const double* __restrict__ partial, int parts, int m,
+                                                       double* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= m) return;
+  double s = 0.0;
+  const int pmax = min(parts, c / 256 + 1);   // parts whose rows lie above the diagonal entry of column c
+  for (int p = 0; p < pmax; ++p) s += partial[(int64_t)p * m + c];
+  out[c] = s;
+}
+
+}  // namespace
+
+extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64_t ldg, int m, int64_t n_tokens,
+                                            double percdamp, double* U, int64_t ldu, double* hinv_diag, int* info) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, G && U && hinv_diag && info, "slim_hessian_inverse: null pointer");
+  SLIM_REQUIRE(ctx, m > 0 && m % 2 == 0, "slim_hessian_inverse: m must be positive and even (got %d)", m);
+  SLIM_REQUIRE(ctx, ldg >= m && ldu >= m && ldu % 2 == 0, "slim_hessian_inverse: bad leading dimension");
+  SLIM_REQUIRE(ctx, n_tokens > 0, "slim_hessian_inverse: n_tokens must be positive");
+  SLIM_REQUIRE(ctx, percdamp >= 0.0, "slim_hessian_inverse: percdamp must be >= 0");
+  SLIM_REQUIRE(ctx, slim_aligned16(U), "slim_hessian_inverse: U must be 16-byte aligned");
+  *info = 0;
+
+  const int nblk = slim_cdiv(m, NB);
+  const int64_t lda = m;
+  const int parts = slim_cdiv(m, 256);
+  // descriptors of the triangular inverse, built on the host
+  std::vector<slim_gemm_desc> descs;
+  struct Level { int first, count, maxM, maxN; };
+  std::vector<Level> levels;
+
+  const size_t bytes_A = slim_ws_round(sizeof(double) * (size_t)m * m);
+  const size_t bytes_P = slim_ws_round(sizeof(double) * (size_t)m * NB);
+  const size_t bytes_part = slim_ws_round(sizeof(double) * (size_t)parts * m);
+  const size_t bytes_desc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * nblk + 8));
+  slim_status st = slim_ws_reserve(ctx, 2 * bytes_A + bytes_P + bytes_part + bytes_desc + 256);
+  if (st != SLIM_OK) return st;
+  double* A = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
+  double* T = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
+  double* P = static_cast<double*>(slim_ws_alloc(ctx, bytes_P));
+  double* partial = static_cast<double*>(slim_ws_alloc(ctx, bytes_part));
+  slim_gemm_desc* descs_dev = static_cast<slim_gemm_desc*>(slim_ws_alloc(ctx, bytes_desc));
+  double* lam = static_cast<double*>(slim_ws_alloc(ctx, 256));
+  int* flag = ctx->dflags + 1;
+
+  const double s = 2.0 / (double)n_tokens;
+  SLIM_LAUNCH(ctx, "inv_lambda", damp_lambda, dim3(1), dim3(256), 0, G, ldg, m, s, percdamp, lam, flag);
+  const dim3 mgrid(slim_cdiv(m, 256), m);
+  SLIM_LAUNCH(ctx, "inv_widen", widen_damp, mgrid, dim3(256), 0, G, ldg, m, s, lam, A, lda);
+  SLIM_LAUNCH(ctx, "inv_zero_u", zero_matrix, mgrid, dim3(256), 0, U, ldu, m);
+
+  static bool attr_done = false;
+  const size_t diag_smem = sizeof(double) * 2 * NB * LDA;
+  if (!attr_done) {
+    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_diag),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_smem));
+    attr_done = true;
+  }
+
+  // ---- descriptors of the triangular inverse (pairwise merging of inverted diagonal ranges), staged first so
+  //      that no host synchronisation falls between the factorisation and the inverse
+  for (int64_t sz = NB; sz < m; sz *= 2) {
+    Level lv{(int)descs.size(), 0, 0, 0};
+    for (int64_t lo = 0; lo + sz < m; lo += 2 * sz) {
+      const int64_t mid = lo + sz, hi = std::min<int64_t>(lo + 2 * sz, m);
+      const int a = (int)sz, b = (int)(hi - mid);
+      slim_gemm_desc d;
+      // T12 = R12 * U22
+      d.A = A + lo * lda + mid;
+      d.lda = lda;
+      d.B = U + mid * ldu + mid;
+      d.ldb = ldu;
+      d.C = T + lo * lda + mid;
+      d.ldc = lda;
+      d.C2 = nullptr;
+      d.ldc2 = 0;
+      d.M = a;
+      d.N = b;
+      d.K = b;
+      d.flags = SLIM_GEMM_B_UPPER;
+      d.alpha = 1.0;
+      d.beta = 0.0;
+      descs.push_back(d);
+      lv.count += 1;
+      lv.maxM = std::max(lv.maxM, a);
+      lv.maxN = std::max(lv.maxN, b);
+    }
+    levels.push_back(lv);
+  }
+  const int n_first = (int)descs.size();
+  // second product of every pair: U12 = -U11 * T12
+  for (int i = 0; i < n_first; ++i) {
+    const slim_gemm_desc& t = descs[i];
+    const int64_t off = t.C - T;   // element offset of the (lo, mid) block
+    const int64_t lo = off / lda, mid = off % lda;
+    slim_gemm_desc d;
+    d.A = U + lo * ldu + lo;
+    d.lda = ldu;
+    d.B = t.C;
+    d.ldb = lda;
+    d.C = U + lo * ldu + mid;
+    d.ldc = ldu;
+    d.C2 = nullptr;
+    d.ldc2 = 0;
+    d.M = t.M;
+    d.N = t.N;
+    d.K = t.M;
+    d.flags = SLIM_GEMM_A_UPPER;
+    d.alpha = -1.0;
+    d.beta = 0.0;
+    descs.push_back(d);
+  }
+  if (!descs.empty()) {
+    if (descs.size() * sizeof(slim_gemm_desc) > (size_t)SLIM_HPIN_BYTES)
+      return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_hessian_inverse: m too large for the descriptor staging buffer");
+    // the staging buffer may still be read by an earlier asynchronous copy
+    SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    memcpy(ctx->hpin, descs.data(), descs.size() * sizeof(slim_gemm_desc));
+    SLIM_HIP_TRY(ctx, hipMemcpyAsync(descs_dev, ctx->hpin, descs.size() * sizeof(slim_gemm_desc),
+                                     hipMemcpyHostToDevice, ctx->stream));
+  }
+
+  // ---- factorisation from the bottom-right corner upwards
+  for (int blk = nblk - 1; blk >= 0; --blk) {
+    const int j0 = blk * NB;
+    const int nbk = std::min(NB, m - j0);
+    SLIM_LAUNCH(ctx, "inv_chol_diag", chol_diag, dim3(1), dim3(256), diag_smem, A + (int64_t)j0 * lda + j0, lda, nbk,
+                U + (int64_t)j0 * ldu + j0, ldu, flag, j0);
+    if (j0 == 0) break;
+    slim_gemm_desc d;
+    d.A = A + j0;                       // A[0:j0, j0:j0+nbk]
+    d.lda = lda;
+    d.B = U + (int64_t)j0 * ldu + j0;   // V_JJ, used transposed
+    d.ldb = ldu;
+    d.C = P;
+    d.ldc = NB;
+    d.C2 = A + j0;                      // the panel of R replaces the panel of A
+    d.ldc2 = lda;
+    d.M = j0;
+    d.N = nbk;
+    d.K = nbk;
+    d.flags = 0;
+    d.alpha = 1.0;
+    d.beta = 0.0;
+    st = slim_dgemm(ctx, "inv_panel_dgemm", 1, d);
+    if (st != SLIM_OK) return st;
+    d.A = P;
+    d.lda = NB;
+    d.B = P;
+    d.ldb = NB;
+    d.C = A;
+    d.ldc = lda;
+    d.C2 = nullptr;
+    d.ldc2 = 0;
+    d.M = j0;
+    d.N = j0;
+    d.K = nbk;
+    d.flags = SLIM_GEMM_UPPER_ONLY;
+    d.alpha = -1.0;
+    d.beta = 1.0;
+    st = slim_dgemm(ctx, "inv_syrk_dgemm", 1, d);
+    if (st != SLIM_OK) return st;
+  }
+
+  // ---- triangular inverse U = R^-1: two batched GEMM launches per level
+  if (!descs.empty()) {
+    for (const Level& lv : levels) {
+      if (lv.count == 0) continue;
+      st = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + lv.first, lv.count, lv.maxM, lv.maxN);
+      if (st != SLIM_OK) return st;
+      st = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + n_first + lv.first, lv.count, lv.maxM, lv.maxN);
+      if (st != SLIM_OK) return st;
+    }
+  }
+
+  SLIM_LAUNCH(ctx, "inv_diag_colsumsq", colsumsq_upper, dim3(slim_cdiv(m, 64), parts), dim3(256), 0, U, ldu, m, partial);
+  SLIM_LAUNCH(ctx, "inv_diag_finalize", colsum_finalize, dim3(slim_cdiv(m, 256)), dim3(256), 0, partial, parts, m, hinv_diag);
+
+  int* host = reinterpret_cast<int*>(ctx->hpin);
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  *info = host[0];
+  if (host[0] != 0)
+    return slim_fail(ctx, SLIM_ERR_NOT_PD, "slim_hessian_inverse: H + lambda I is not positive definite (pivot at column %d)", host[0]);
+  return SLIM_OK;
+}

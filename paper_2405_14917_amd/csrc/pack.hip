@@ -1,0 +1,119 @@
+// a9  Storage format (App. B.2): running row offsets of the groups (the cumulative sum that gives every
+// group its start row in the packed matrix), the 2-bit-per-group width array, and the bit-packing of the
+// codes.  Integer work only; bound by HBM traffic (1 byte read per weight, N/8 bytes written).
+//
+// pack_codes: one workgroup per (group, slab of 64 output rows).  The slab's 64 x beta codes are read
+// with coalesced row accesses into LDS; then thread i of the slab assembles the words of output row i
+// one by one, so that the 64 threads write 64 consecutive words of one row of the packed matrix.
+#include "slim_internal.h"
+
+namespace {
+
+constexpr int PACK_ROWS = 64;
+
+// single workgroup: validates widths, exclusive scan of beta * b_g / 32, width array
+__global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bits, int k, int beta,
+                                                 int32_t* __restrict__ row_off, uint32_t* __restrict__ gbits,
+                                                 int* __restrict__ flags) {
+  __shared__ int32_t part[256];
+  const int tid = threadIdx.x;
+  const int per = (k + 255) / 256;
+  const int g0 = tid * per, g1 = min(k, g0 + per);
+  int32_t s = 0;
+  int bad = 0;
+  for (int g = g0; g < g1; ++g) {
+    const int b = bits[g];
+    if (b < 1 || b > 4 || (beta * b) % 32 != 0) bad = 1;
+    s += beta * b / 32;
+  }
+  part[tid] = s;
+  if (tid == 0) flags[0] = 0;
+  __syncthreads();
+  if (bad) atomicOr(&flags[0], 1);
+  // serial prefix over 256 partial sums by every thread for its own start (k is small)
+  int32_t base = 0;
+  for (int t = 0; t < tid; ++t) base += part[t];
+  for (int g = g0; g < g1; ++g) {
+    row_off[g] = base;
+    base += beta * bits[g] / 32;
+  }
+  if (g1 == k && g0 < k) row_off[k] = base;
+  if (k == 0 && tid == 0) row_off[0] = 0;
+  const int nw = (k + 15) / 16;
+  for (int w = tid; w < nw; w += 256) {
+    uint32_t v = 0;
+    for (int j = 0; j < 16 && w * 16 + j < k; ++j) v |= (uint32_t)((bits[w * 16 + j] - 1) & 3) << (2 * j);
+    gbits[w] = v;
+  }
+}
+
+__global__ __launch_bounds__(PACK_ROWS) void pack_codes(const uint8_t* __restrict__ codes, int n, int64_t ldc,
+                                                        const uint8_t* __restrict__ bits, int beta,
+                                                        const int32_t* __restrict__ row_off,
+                                                        uint32_t* __restrict__ packed, int64_t packed_rows) {
+  extern __shared__ uint8_t tile[];   // [PACK_ROWS][beta + 4]
+  const int g = blockIdx.y;
+  const int i0 = blockIdx.x * PACK_ROWS;
+  const int rows = min(PACK_ROWS, n - i0);
+  const int stride = beta + 4;
+  const int b = bits[g];
+  if (b < 1 || b > 4) return;
+  // beta is a multiple of 32: read 4 codes per thread and step
+  const int quads = beta / 4;
+  for (int idx = threadIdx.x; idx < rows * quads; idx += PACK_ROWS) {
+    const int r = idx / quads, q = idx - r * quads;
+    const uint32_t v = *reinterpret_cast<const uint32_t*>(codes + (int64_t)(i0 + r) * ldc + (int64_t)g * beta + 4 * q);
+    *reinterpret_cast<uint32_t*>(tile + r * stride + 4 * q) = v;
+  }
+  __syncthreads();
+  const int i = threadIdx.x;
+  if (i >= rows) return;
+  const uint8_t* c = tile + i * stride;
+  const int nw = beta * b / 32;
+  const uint32_t mask = (1u << b) - 1u;
+  const int64_t base = row_off[g];
+  for (int w = 0; w < nw; ++w) {
+    // the word covers stream bits [32 w, 32 w + 32): elements floor(32 w / b) .. ceil((32 w + 32) / b) - 1
+    const int e0 = (32 * w) / b;
+    const int e1 = min(beta, (32 * w + 32 + b - 1) / b);
+    uint32_t word = 0;
+    for (int e = e0; e < e1; ++e) {
+      const uint32_t v = c[e] & mask;
+      const int sh = e * b - 32 * w;
+      word |= (sh >= 0) ? (v << sh) : (v >> (-sh));
+    }
+    const int64_t r = base + w;
+    if (r < packed_rows) packed[r * n + i0 + i] = word;
+  }
+}
+
+}  // namespace
+
+extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,
+                                 int beta, uint32_t* packed, int64_t packed_rows, uint32_t* gbits, int32_t* row_off,
+                                 int* m_star) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, codes && bits && packed && gbits && row_off && m_star, "slim_pack: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_pack: need n, m > 0 and beta | m");
+  SLIM_REQUIRE(ctx, beta % 32 == 0, "slim_pack: beta must be a multiple of 32 (got %d)", beta);
+  SLIM_REQUIRE(ctx, ldc >= m && ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0,
+               "slim_pack: codes must be 4-byte aligned with ldc a multiple of 4");
+  SLIM_REQUIRE(ctx, packed_rows >= 0, "slim_pack: negative capacity");
+  const int k = m / beta;
+  int* flags = ctx->dflags;   // flags[0] is cleared by pack_scan itself
+  SLIM_LAUNCH(ctx, "pack_scan", pack_scan, dim3(1), dim3(256), 0, bits, k, beta, row_off, gbits, flags);
+  const size_t smem = (size_t)PACK_ROWS * (beta + 4);
+  SLIM_LAUNCH(ctx, "pack_codes", pack_codes, dim3(slim_cdiv(n, PACK_ROWS), k), dim3(PACK_ROWS), smem, codes, n, ldc,
+              bits, beta, row_off, packed, packed_rows);
+  int* host = reinterpret_cast<int*>(ctx->hpin);
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(&host[0], row_off + k, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(&host[1], flags, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  *m_star = host[0];
+  if (host[1] != 0)
+    return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "slim_pack: a width is outside 1..4 or beta * width is not a multiple of 32");
+  if (host[0] > packed_rows)
+    return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "slim_pack: packed needs %d rows, capacity is %lld", host[0],
+                     (long long)packed_rows);
+  return SLIM_OK;
+}

@@ -1,0 +1,588 @@
+// a5 - a8  3-sigma mask, Salience-Weighted Quantizer Calibration and the GPTQ-style column sweep
+// (Sec. 3.3.2; Eq. 1, 2, 5; Alg. 1 lines 5-13; Alg. 2 SQC).
+//
+// Everything here is fp64: the rounding decisions of a sequential, error-feeding sweep only agree
+// with a float64 reference if the working copy of W, the quantiser parameters and the compensation
+// are carried at that precision.  CDNA4 runs fp64 vector and matrix work at full rate, so this
+// costs little next to the Hessian.
+//
+// Per group of beta columns four kernels run back to back on the stream:
+//   block_stats   shifted sums of the current block (for the block-wide 3-sigma rule), per row slab
+//   sqc_search    one workgroup per 8 rows: row min/max/mean|w|, loss weights, then every
+//                 (row, candidate) pair is one thread that walks the row's beta weights in LDS;
+//                 wavefront argmin with ties to the lower candidate index
+//   gptq_sweep    one wavefront per row, the row's beta weights in registers, the beta x beta block
+//                 of U in LDS; beta serial steps of quantise -> error -> rank-1 update of the row
+//   dgemm         W[:, later] -= E_b U[b, later] on the fp64 matrix cores
+#include <algorithm>
+
+#include "slim_device.h"
+#include "slim_internal.h"
+
+namespace {
+
+using namespace slimdev;
+
+constexpr int SQC_ROWS = 8;       // rows per workgroup in sqc_search
+constexpr int SQC_THREADS = 256;
+constexpr int STAT_ROWS = 64;     // rows per workgroup in block_stats
+constexpr int SWEEP_WAVES = 16;   // rows (= wavefronts) per workgroup in gptq_sweep
+
+// ------------------------------------------------------------------------------------------
+// Shifted first and second moments of an n x beta block, one partial pair per slab of STAT_ROWS rows.
+// The shift (the block's first element) keeps sigma^2 = E[(w-s)^2] - E[w-s]^2 well conditioned.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void block_stats(const double* __restrict__ W, int64_t ldw, int n, int beta,
+                                                   double* __restrict__ partial) {
+  __shared__ double red[2][4];
+  const double shift = W[0];
+  const int r0 = blockIdx.x * STAT_ROWS;
+  const int rows = min(STAT_ROWS, n - r0);
+  double s1 = 0.0, s2 = 0.0;
+  for (int idx = threadIdx.x; idx < rows * beta; idx += 256) {
+    const int r = idx / beta, c = idx - r * beta;
+    const double d = W[(int64_t)(r0 + r) * ldw + c] - shift;
+    s1 += d;
+    s2 += d * d;
+  }
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    red[0][wave] = s1;
+    red[1][wave] = s2;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+    partial[2 * blockIdx.x + 1] = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
+  }
+}
+
+struct SqcArgs {
+  const double* W;       // n x beta block of current weights
+  int64_t ldw;
+  int n, beta, bits;
+  const double* omega;   // explicit weights (n x beta, ld = beta) or null
+  const double* dblk;    // [H^-1]_jj of the block's columns (ELEMENT weights) or null
+  const double* stat_partial;  // block_stats output or null (ROW scope / no mask needed)
+  int nstat;
+  int weight_mode, scope, q1_mode;
+  const double* tau;
+  int ncand;
+  double* scale;         // element i at scale[i * out_stride]
+  double* zero;
+  int64_t out_stride;
+  int* cand_idx;         // optional, same stride
+};
+
+// Eq. 1 parameters of one row; identical operation order to the reference definition.
+__device__ __forceinline__ void minmax_params(double wmin, double wmax, int bits, double& delta0, double& z) {
+  const double qmax = (double)((1 << bits) - 1);
+  if (wmax == wmin) {
+    wmin = fmin(wmin, 0.0);
+    wmax = fmax(wmax, 0.0);
+  }
+  if (wmax == wmin) {
+    delta0 = 1.0;
+    z = 0.0;
+    return;
+  }
+  delta0 = (wmax - wmin) / qmax;
+  z = -rint(wmin / delta0);
+}
+
+__global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
+  extern __shared__ __align__(16) double smem[];
+  const int beta = a.beta, ncand = a.ncand;
+  double* wrow = smem;                            // [SQC_ROWS][beta]
+  double* om = wrow + SQC_ROWS * beta;            // [SQC_ROWS][beta]
+  double* loss = om + SQC_ROWS * beta;            // [SQC_ROWS][ncand]
+  double* rp = loss + SQC_ROWS * ncand;           // [SQC_ROWS][4]: delta0, z, alpha, unused
+  double* red = rp + SQC_ROWS * 4;                // [256] + 2
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r0 = blockIdx.x * SQC_ROWS;
+  const int rows = min(SQC_ROWS, a.n - r0);
+  const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
+  const bool need_mask = (a.omega == nullptr && a.weight_mode == SLIM_WEIGHT_MASK_MEAN);
+
+  // block-wide mu and 3 sigma from the slab partials, reduced in a fixed order
+  double mu = 0.0, thr = 0.0;
+  if (need_mask && a.scope == SLIM_SCOPE_BLOCK) {
+    double s1 = 0.0, s2 = 0.0;
+    for (int p = tid; p < a.nstat; p += SQC_THREADS) {
+      s1 += a.stat_partial[2 * p];
+      s2 += a.stat_partial[2 * p + 1];
+    }
+    red[tid] = s1;
+    __syncthreads();
+    for (int s = SQC_THREADS / 2; s > 0; s >>= 1) {
+      if (tid < s) red[tid] += red[tid + s];
+      __syncthreads();
+    }
+    const double S1 = red[0];
+    __syncthreads();
+    red[tid] = s2;
+    __syncthreads();
+    for (int s = SQC_THREADS / 2; s > 0; s >>= 1) {
+      if (tid < s) red[tid] += red[tid + s];
+      __syncthreads();
+    }
+    const double S2 = red[0];
+    const double cnt = (double)a.n * (double)beta;
+    const double m1 = S1 / cnt;
+    const double var = fmax(S2 / cnt - m1 * m1, 0.0);
+    mu = a.W[0] + m1;
+    thr = 3.0 * sqrt(var);
+  }
+
+  for (int idx = tid; idx < rows * beta; idx += SQC_THREADS) {
+    const int r = idx / beta, c = idx - r * beta;
+    wrow[r * beta + c] = a.W[(int64_t)(r0 + r) * a.ldw + c];
+  }
+  __syncthreads();
+
+  // per-row statistics and loss weights: wavefront w takes rows w, w + 4
+  for (int r = wave; r < rows; r += SQC_THREADS / 64) {
+    const double* w = wrow + r * beta;
+    double mn = INFINITY, mx = -INFINITY, sabs = 0.0, sum = 0.0;
+    for (int c = lane; c < beta; c += 64) {
+      const double v = w[c];
+      mn = fmin(mn, v);
+      mx = fmax(mx, v);
+      sabs += fabs(v);
+      sum += v;
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+    sabs = wave_sum(sabs);
+    if (lane == 0) {
+      double d0 = 1.0, z = 0.0;
+      if (!sign_mode) minmax_params(mn, mx, a.bits, d0, z);
+      rp[r * 4 + 0] = d0;
+      rp[r * 4 + 1] = z;
+      rp[r * 4 + 2] = sabs / (double)beta;
+    }
+    if (a.omega) {
+      for (int c = lane; c < beta; c += 64) om[r * beta + c] = a.omega[(int64_t)(r0 + r) * beta + c];
+    } else if (a.weight_mode == SLIM_WEIGHT_UNIFORM) {
+      for (int c = lane; c < beta; c += 64) om[r * beta + c] = 1.0;
+    } else if (a.weight_mode == SLIM_WEIGHT_ELEMENT) {
+      for (int c = lane; c < beta; c += 64) {
+        const double d = a.dblk[c];
+        om[r * beta + c] = (w[c] * w[c]) / (d * d);
+      }
+    } else {
+      double rmu = mu, rthr = thr;
+      if (a.scope == SLIM_SCOPE_ROW) {
+        sum = wave_sum(sum);
+        rmu = sum / (double)beta;
+        double ss = 0.0;
+        for (int c = lane; c < beta; c += 64) {
+          const double d = w[c] - rmu;
+          ss += d * d;
+        }
+        ss = wave_sum(ss);
+        rthr = 3.0 * sqrt(ss / (double)beta);
+      }
+      int ns = 0;
+      for (int c = lane; c < beta; c += 64) ns += (fabs(w[c] - rmu) > rthr) ? 1 : 0;
+      ns = wave_sum_int(ns);
+      const int nus = beta - ns;
+      const double ws = ns ? 1.0 / (double)ns : 0.0;
+      const double wus = nus ? 1.0 / (double)nus : 0.0;
+      for (int c = lane; c < beta; c += 64) om[r * beta + c] = (fabs(w[c] - rmu) > rthr) ? ws : wus;
+    }
+  }
+  __syncthreads();
+
+  // every (row, candidate) pair is one thread
+  const double qmax = (double)((1 << a.bits) - 1);
+  for (int s = tid; s < rows * ncand; s += SQC_THREADS) {
+    const int r = s / ncand, c = s - r * ncand;
+    const double* w = wrow + r * beta;
+    const double* o = om + r * beta;
+    const double tc = a.tau[c];
+    double L = 0.0;
+    if (sign_mode) {
+      const double ta = tc * rp[r * 4 + 2];
+      for (int j = 0; j < beta; ++j) {
+        const double v = w[j];
+        const double err = v - (v >= 0.0 ? ta : -ta);
+        L += o[j] * err * err;
+      }
+    } else {
+      const double delta = tc * rp[r * 4 + 0];
+      const double z = rp[r * 4 + 1];
+      for (int j = 0; j < beta; ++j) {
+        const double v = w[j];
+        const double q = fmin(fmax(rint(v / delta) + z, 0.0), qmax);
+        const double err = v - delta * (q - z);
+        L += o[j] * err * err;
+      }
+    }
+    loss[r * ncand + c] = L;
+  }
+  __syncthreads();
+
+  // first minimum per row
+  for (int r = wave; r < rows; r += SQC_THREADS / 64) {
+    double best = INFINITY;
+    int bi = 0x7fffffff;
+    for (int c = lane; c < ncand; c += 64) {
+      const double L = loss[r * ncand + c];
+      if (L < best) {
+        best = L;
+        bi = c;
+      }
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) {
+      const double ob = shfl_xor_f64(best, s);
+      const int oi = __shfl_xor(bi, s, 64);
+      if (ob < best || (ob == best && oi < bi)) {
+        best = ob;
+        bi = oi;
+      }
+    }
+    if (lane == 0) {
+      if (bi == 0x7fffffff) bi = 0;
+      const int64_t o = (int64_t)(r0 + r) * a.out_stride;
+      const double tc = a.tau[bi];
+      if (sign_mode) {
+        a.scale[o] = 2.0 * tc * rp[r * 4 + 2];
+        a.zero[o] = 0.5;
+      } else {
+        a.scale[o] = tc * rp[r * 4 + 0];
+        a.zero[o] = rp[r * 4 + 1];
+      }
+      if (a.cand_idx) a.cand_idx[o] = bi;
+    }
+  }
+}
+
+size_t sqc_smem_bytes(int beta, int ncand) {
+  return sizeof(double) * ((size_t)2 * SQC_ROWS * beta + (size_t)SQC_ROWS * ncand + SQC_ROWS * 4 + SQC_THREADS + 2);
+}
+
+// ------------------------------------------------------------------------------------------
+// Column sweep of one group.  One wavefront per row; lane l holds columns l, l + 64, ... of the group.
+// ------------------------------------------------------------------------------------------
+struct SweepArgs {
+  double* W;             // working copy, pointer to the block's first column
+  int64_t ldw;
+  int n, beta, bits, q1_mode;
+  const double* U;       // pointer to U[b0][b0]
+  int64_t ldu;
+  const double* scale;   // element i at scale[i * sz_stride]
+  const double* zero;
+  int64_t sz_stride;
+  uint8_t* codes;        // pointer to codes[0][b0]
+  int64_t ldc;
+  double* E;             // n x beta, ld = beta
+  double* row_e2;        // n running sums of e^2
+  void* What;            // pointer to What[0][b0] or null
+  int64_t ldwh;
+  int what_f64;
+};
+
+template <int EPL>
+__global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
+  extern __shared__ __align__(16) double Us[];   // [beta][beta]
+  const int beta = a.beta;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int idx = tid; idx < beta * beta; idx += SWEEP_WAVES * 64) {
+    const int j = idx / beta, l = idx - j * beta;
+    Us[idx] = (l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
+  }
+  __syncthreads();
+  const int row = blockIdx.x * SWEEP_WAVES + wave;
+  if (row >= a.n) return;
+
+  const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
+  const double qmax = (double)((1 << a.bits) - 1);
+  const double s = a.scale[(int64_t)row * a.sz_stride];
+  const double z = a.zero[(int64_t)row * a.sz_stride];
+
+  double w[EPL], ev[EPL], qv[EPL];
+  double* wr = a.W + (int64_t)row * a.ldw;
+#pragma unroll
+  for (int r = 0; r < EPL; ++r) {
+    const int c = r * 64 + lane;
+    w[r] = (c < beta) ? wr[c] : 0.0;
+    ev[r] = 0.0;
+    qv[r] = 0.0;
+  }
+  double e2 = 0.0;
+#pragma unroll
+  for (int r = 0; r < EPL; ++r) {
+    const int jend = min(64, beta - r * 64);
+    for (int jj = 0; jj < jend; ++jj) {
+      const int j = r * 64 + jj;
+      const double wj = read_lane_f64(w[r], jj);
+      double q;
+      if (sign_mode) {
+        q = (wj >= 0.0) ? 1.0 : 0.0;
+      } else {
+        q = fmin(fmax(rint(wj / s) + z, 0.0), qmax);
+      }
+      const double what = s * (q - z);
+      const double e = (wj - what) / Us[j * beta + j];
+      e2 += e * e;
+      if (lane == jj) {
+        ev[r] = e;
+        qv[r] = q;
+      }
+#pragma unroll
+      for (int r2 = r; r2 < EPL; ++r2) {
+        const int c = r2 * 64 + lane;
+        if (c < beta) w[r2] -= e * Us[j * beta + c];
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < EPL; ++r) {
+    const int c = r * 64 + lane;
+    if (c < beta) {
+      a.codes[(int64_t)row * a.ldc + c] = (uint8_t)qv[r];
+      a.E[(int64_t)row * beta + c] = ev[r];
+      if (a.What) {
+        const double what = s * (qv[r] - z);
+        if (a.what_f64)
+          static_cast<double*>(a.What)[(int64_t)row * a.ldwh + c] = what;
+        else
+          static_cast<float*>(a.What)[(int64_t)row * a.ldwh + c] = (float)what;
+      }
+    }
+  }
+  if (lane == 0) a.row_e2[row] += e2;
+}
+
+// Kernels that may need more than the default 64 KiB of dynamic LDS opt in once per process.
+template <typename K>
+slim_status allow_big_lds(slim_ctx* ctx, K kernel, bool& done) {
+  if (!done) {
+    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    done = true;
+  }
+  return SLIM_OK;
+}
+
+bool beta_supported(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256; }
+
+slim_status launch_stats_and_sqc(slim_ctx* ctx, SqcArgs a, double* stat_partial) {
+  const bool need_block_stats =
+      (a.omega == nullptr && a.weight_mode == SLIM_WEIGHT_MASK_MEAN && a.scope == SLIM_SCOPE_BLOCK);
+  a.stat_partial = nullptr;
+  a.nstat = 0;
+  if (need_block_stats) {
+    a.nstat = slim_cdiv(a.n, STAT_ROWS);
+    a.stat_partial = stat_partial;
+    SLIM_LAUNCH(ctx, "sqc_block_stats", block_stats, dim3(a.nstat), dim3(256), 0, a.W, a.ldw, a.n, a.beta, stat_partial);
+  }
+  const size_t smem = sqc_smem_bytes(a.beta, a.ncand);
+  if (smem > 160 * 1024) return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "sqc: beta * ncand too large for LDS");
+  if (smem > 64 * 1024) {
+    static bool done = false;
+    slim_status st = allow_big_lds(ctx, sqc_search, done);
+    if (st != SLIM_OK) return st;
+  }
+  SLIM_LAUNCH(ctx, "sqc_search", sqc_search, dim3(slim_cdiv(a.n, SQC_ROWS)), dim3(SQC_THREADS), smem, a);
+  return SLIM_OK;
+}
+
+slim_status check_params(slim_ctx* ctx, const slim_params* p, slim_params& out) {
+  slim_default_params(&out);
+  if (p) out = *p;
+  SLIM_REQUIRE(ctx, out.sqc_weight_mode >= 0 && out.sqc_weight_mode <= 2, "unknown sqc_weight_mode %d", out.sqc_weight_mode);
+  SLIM_REQUIRE(ctx, out.mask_scope == 0 || out.mask_scope == 1, "unknown mask_scope %d", out.mask_scope);
+  SLIM_REQUIRE(ctx, out.q1_mode == 0 || out.q1_mode == 1, "unknown q1_mode %d", out.q1_mode);
+  SLIM_REQUIRE(ctx, out.sal_mode == 0 || out.sal_mode == 1, "unknown sal_mode %d", out.sal_mode);
+  return SLIM_OK;
+}
+
+}  // namespace
+
+extern "C" slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, int n, int beta, int bits,
+                                          const double* omega, const double* hinv_diag_blk,
+                                          const slim_params* params, const double* tau, int ncand, double* scale,
+                                          double* zero, int* cand_idx) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  slim_params prm;
+  slim_status st = check_params(ctx, params, prm);
+  if (st != SLIM_OK) return st;
+  SLIM_REQUIRE(ctx, Wblk && scale && zero, "slim_sqc_calibrate: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && ldw >= beta, "slim_sqc_calibrate: need n > 0 and ldw >= beta");
+  SLIM_REQUIRE(ctx, bits >= 1 && bits <= 4, "slim_sqc_calibrate: bits must be in 1..4 (got %d)", bits);
+  if (!beta_supported(beta))
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sqc_calibrate: beta must be 32, 64, 128 or 256 (got %d)", beta);
+  if (!tau) {
+    tau = ctx->tau_default;
+    ncand = ctx->ncand_default;
+  }
+  SLIM_REQUIRE(ctx, ncand >= 1 && ncand <= SLIM_MAX_CAND, "slim_sqc_calibrate: ncand must be in 1..%d", SLIM_MAX_CAND);
+  SLIM_REQUIRE(ctx, !(omega == nullptr && prm.sqc_weight_mode == SLIM_WEIGHT_ELEMENT && hinv_diag_blk == nullptr),
+               "slim_sqc_calibrate: ELEMENT weights need hinv_diag_blk");
+  const int nstat = slim_cdiv(n, STAT_ROWS);
+  st = slim_ws_reserve(ctx, slim_ws_round(sizeof(double) * 2 * nstat));
+  if (st != SLIM_OK) return st;
+  double* stat_partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * 2 * nstat));
+  SqcArgs a;
+  a.W = Wblk;
+  a.ldw = ldw;
+  a.n = n;
+  a.beta = beta;
+  a.bits = bits;
+  a.omega = omega;
+  a.dblk = hinv_diag_blk;
+  a.weight_mode = prm.sqc_weight_mode;
+  a.scope = prm.mask_scope;
+  a.q1_mode = prm.q1_mode;
+  a.tau = tau;
+  a.ncand = ncand;
+  a.scale = scale;
+  a.zero = zero;
+  a.out_stride = 1;
+  a.cand_idx = cand_idx;
+  return launch_stats_and_sqc(ctx, a, stat_partial);
+}
+
+extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                                          const double* U, int64_t ldu, const uint8_t* bits, int beta,
+                                          int gptq_block, const slim_params* params, const double* hinv_diag,
+                                          const double* tau, int ncand, uint8_t* codes, double* scale, double* zero,
+                                          void* What, slim_dtype what_dtype, double* sum_e2) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  slim_params prm;
+  slim_status st = check_params(ctx, params, prm);
+  if (st != SLIM_OK) return st;
+  SLIM_REQUIRE(ctx, W && U && bits && codes && scale && zero, "slim_gptq_quantize: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_gptq_quantize: need n, m > 0 and beta | m");
+  SLIM_REQUIRE(ctx, ldw >= m && ldw % 4 == 0 && ldu >= m && ldu % 2 == 0, "slim_gptq_quantize: bad leading dimension");
+  SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(U), "slim_gptq_quantize: misaligned pointer");
+  if (!beta_supported(beta) || beta > 128)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: beta must be 32, 64 or 128 (got %d)", beta);
+  if (gptq_block != beta)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: gptq_block must equal beta");
+  if (w_dtype != SLIM_F16 && w_dtype != SLIM_BF16 && w_dtype != SLIM_F32)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: W must be F16, BF16 or F32");
+  if (What && what_dtype != SLIM_F32 && what_dtype != SLIM_F64)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: What must be F32 or F64");
+  if (!tau) {
+    tau = ctx->tau_default;
+    ncand = ctx->ncand_default;
+  }
+  SLIM_REQUIRE(ctx, ncand >= 1 && ncand <= SLIM_MAX_CAND, "slim_gptq_quantize: ncand must be in 1..%d", SLIM_MAX_CAND);
+  SLIM_REQUIRE(ctx, !(prm.sqc_weight_mode == SLIM_WEIGHT_ELEMENT && hinv_diag == nullptr),
+               "slim_gptq_quantize: ELEMENT weights need hinv_diag");
+  const int k = m / beta;
+  SLIM_REQUIRE(ctx, k <= SLIM_HPIN_BYTES, "slim_gptq_quantize: too many groups");
+
+  // widths to the host: they select kernel arguments, and they must be valid before anything runs
+  uint8_t* bits_h = reinterpret_cast<uint8_t*>(ctx->hpin);
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(bits_h, bits, k, hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  std::vector<int> gb(k);
+  for (int g = 0; g < k; ++g) {
+    gb[g] = bits_h[g];
+    SLIM_REQUIRE(ctx, gb[g] >= 1 && gb[g] <= 4, "slim_gptq_quantize: bits[%d] = %d is outside 1..4", g, gb[g]);
+  }
+
+  const int nstat = slim_cdiv(n, STAT_ROWS);
+  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * beta) +
+                      slim_ws_round(sizeof(double) * 2 * nstat) + slim_ws_round(sizeof(double) * n);
+  st = slim_ws_reserve(ctx, need);
+  if (st != SLIM_OK) return st;
+  double* Wc = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * m));
+  double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * beta));
+  double* stat_partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * 2 * nstat));
+  double* row_e2 = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * n));
+
+  st = slim_widen_f64(ctx, "gptq_widen", W, w_dtype, n, m, ldw, Wc, (int64_t)m);
+  if (st != SLIM_OK) return st;
+  st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
+  if (st != SLIM_OK) return st;
+
+  const size_t sweep_smem = sizeof(double) * (size_t)beta * beta;
+  if (sweep_smem > 64 * 1024) {
+    static bool done = false;
+    st = allow_big_lds(ctx, gptq_sweep<2>, done);
+    if (st != SLIM_OK) return st;
+  }
+
+  for (int g = 0; g < k; ++g) {
+    const int b0 = g * beta;
+    SqcArgs a;
+    a.W = Wc + b0;
+    a.ldw = m;
+    a.n = n;
+    a.beta = beta;
+    a.bits = gb[g];
+    a.omega = nullptr;
+    a.dblk = hinv_diag ? hinv_diag + b0 : nullptr;
+    a.weight_mode = prm.sqc_weight_mode;
+    a.scope = prm.mask_scope;
+    a.q1_mode = prm.q1_mode;
+    a.tau = tau;
+    a.ncand = ncand;
+    a.scale = scale + g;
+    a.zero = zero + g;
+    a.out_stride = k;
+    a.cand_idx = nullptr;
+    st = launch_stats_and_sqc(ctx, a, stat_partial);
+    if (st != SLIM_OK) return st;
+
+    SweepArgs s;
+    s.W = Wc + b0;
+    s.ldw = m;
+    s.n = n;
+    s.beta = beta;
+    s.bits = gb[g];
+    s.q1_mode = prm.q1_mode;
+    s.U = U + (int64_t)b0 * ldu + b0;
+    s.ldu = ldu;
+    s.scale = scale + g;
+    s.zero = zero + g;
+    s.sz_stride = k;
+    s.codes = codes + b0;
+    s.ldc = m;
+    s.E = E;
+    s.row_e2 = row_e2;
+    s.What = nullptr;
+    s.ldwh = m;
+    s.what_f64 = (what_dtype == SLIM_F64);
+    if (What) {
+      s.What = s.what_f64 ? static_cast<void*>(static_cast<double*>(What) + b0)
+                          : static_cast<void*>(static_cast<float*>(What) + b0);
+    }
+    const dim3 sgrid(slim_cdiv(n, SWEEP_WAVES)), sblock(SWEEP_WAVES * 64);
+    if (beta <= 64)
+      SLIM_LAUNCH(ctx, "gptq_sweep", gptq_sweep<1>, sgrid, sblock, sweep_smem, s);
+    else
+      SLIM_LAUNCH(ctx, "gptq_sweep", gptq_sweep<2>, sgrid, sblock, sweep_smem, s);
+
+    const int rest = m - b0 - beta;
+    if (rest > 0) {
+      slim_gemm_desc d;
+      d.A = E;
+      d.lda = beta;
+      d.B = U + (int64_t)b0 * ldu + (b0 + beta);
+      d.ldb = ldu;
+      d.C = Wc + (b0 + beta);
+      d.ldc = m;
+      d.C2 = nullptr;
+      d.ldc2 = 0;
+      d.M = n;
+      d.N = rest;
+      d.K = beta;
+      d.flags = 0;
+      d.alpha = -1.0;
+      d.beta = 1.0;
+      st = slim_dgemm(ctx, "gptq_trailing_dgemm", 0, d);
+      if (st != SLIM_OK) return st;
+    }
+  }
+  if (sum_e2) return slim_sum_f64(ctx, "gptq_sum_e2", row_e2, n, sum_e2);
+  return SLIM_OK;
+}

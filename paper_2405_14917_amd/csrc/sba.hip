@@ -1,0 +1,340 @@
+// a4  Salience-Determined Bit Allocation (Eq. 4; Alg. 2 SBA; App. C, App. D), all in fp64.
+//
+// The search evaluates floor(k/2)+1 allocations that differ from one another in two groups only, so the
+// layer outputs are carried incrementally:
+//   sba_rank        stable ascending rank of the k group saliences (one workgroup, counting sort by
+//                   comparison; NaN ranks last) -> order[]
+//   sba_fakequant   per (row, group), one wavefront: Eq. 1 / Eq. 2 round-to-nearest at the three widths;
+//                   stores W_N and the two differences D_lo = W_{N-1} - W_N, D_hi = W_{N+1} - W_N
+//   dgemm           Y^T = W X_s and Y_0^T = W_N X_s     (n x t_s, fp64 matrix cores)
+//   for p = 0 .. floor(k/2):
+//     kl_partial / kl_finalize   obj[p] = sum_tokens KL(softmax(Y_t) || softmax(Y_p,t)); the softmax runs
+//                   over the n outputs of a token, i.e. down a column of the transposed outputs, so
+//                   consecutive lanes read consecutive tokens
+//     dgemm x 2     Y_{p+1}^T = Y_p^T + D_lo[:, g_lo] X_s[g_lo, :] + D_hi[:, g_hi] X_s[g_hi, :]
+//                   (descriptors built on the device from order[], no host round trip)
+//   sba_finalize    first minimum of obj, bit vector of p*
+#include "slim_device.h"
+#include "slim_internal.h"
+
+namespace {
+
+using namespace slimdev;
+
+constexpr int KL_TOK = 64;     // tokens per workgroup
+constexpr int KL_PART = 5;     // doubles per (part, token): max y, sum exp y, max q, sum exp q, weighted diff
+
+__global__ __launch_bounds__(256) void sba_rank(const double* __restrict__ sal, int k, int* __restrict__ order) {
+  for (int g = threadIdx.x; g < k; g += 256) {
+    double v = sal[g];
+    if (v != v) v = INFINITY;
+    int rank = 0;
+    for (int h = 0; h < k; ++h) {
+      double u = sal[h];
+      if (u != u) u = INFINITY;
+      rank += (u < v || (u == v && h < g)) ? 1 : 0;
+    }
+    order[rank] = g;
+  }
+}
+
+// round-to-nearest fake quantisation of one value with the row-group's default parameters
+struct RtnParams {
+  double delta0, z, qmax, alpha;
+  bool sign;
+};
+
+__device__ __forceinline__ RtnParams rtn_params(double mn, double mx, double mean_abs, int bits, int q1_mode) {
+  RtnParams p;
+  p.sign = (bits == 1 && q1_mode == SLIM_Q1_SIGN);
+  p.alpha = mean_abs;
+  p.qmax = (double)((1 << bits) - 1);
+  p.delta0 = 1.0;
+  p.z = 0.0;
+  if (!p.sign) {
+    if (mx == mn) {
+      mn = fmin(mn, 0.0);
+      mx = fmax(mx, 0.0);
+    }
+    if (mx != mn) {
+      p.delta0 = (mx - mn) / p.qmax;
+      p.z = -rint(mn / p.delta0);
+    }
+  }
+  return p;
+}
+
+__device__ __forceinline__ double rtn_apply(const RtnParams& p, double w) {
+  if (p.sign) return (w >= 0.0) ? p.alpha : -p.alpha;
+  const double q = fmin(fmax(rint(w / p.delta0) + p.z, 0.0), p.qmax);
+  return p.delta0 * (q - p.z);
+}
+
+// one wavefront per (row, group); grid = ceil(n * k / 4) workgroups of 4 wavefronts
+__global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ W, int n, int m, int beta, int N,
+                                                     int q1_mode, double* __restrict__ WN, double* __restrict__ Dlo,
+                                                     double* __restrict__ Dhi) {
+  const int lane = threadIdx.x & 63;
+  const int k = m / beta;
+  const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (unit >= (int64_t)n * k) return;
+  const int row = (int)(unit / k), g = (int)(unit % k);
+  const int64_t base = (int64_t)row * m + (int64_t)g * beta;
+  double mn = INFINITY, mx = -INFINITY, sabs = 0.0;
+  for (int c = lane; c < beta; c += 64) {
+    const double v = W[base + c];
+    mn = fmin(mn, v);
+    mx = fmax(mx, v);
+    sabs += fabs(v);
+  }
+  mn = wave_min(mn);
+  mx = wave_max(mx);
+  sabs = wave_sum(sabs) / (double)beta;
+  const RtnParams pl = rtn_params(mn, mx, sabs, N - 1, q1_mode);
+  const RtnParams pn = rtn_params(mn, mx, sabs, N, q1_mode);
+  const RtnParams ph = rtn_params(mn, mx, sabs, N + 1, q1_mode);
+  for (int c = lane; c < beta; c += 64) {
+    const double v = W[base + c];
+    const double wn = rtn_apply(pn, v);
+    WN[base + c] = wn;
+    Dlo[base + c] = rtn_apply(pl, v) - wn;
+    Dhi[base + c] = rtn_apply(ph, v) - wn;
+  }
+}
+
+// device-built descriptors of the incremental updates: for step p (going from p to p+1 demoted/promoted
+// groups) two rank-beta products into the running outputs Yc
+__global__ __launch_bounds__(256) void sba_build_descs(const int* __restrict__ order, int k, int pmax, int n, int m,
+                                                       int beta, int64_t ts, const double* Dlo, const double* Dhi,
+                                                       const double* X64, double* Yc, slim_gemm_desc* descs) {
+  for (int p = threadIdx.x; p < pmax; p += 256) {
+    const int glo = order[p], ghi = order[k - 1 - p];
+    for (int h = 0; h < 2; ++h) {
+      const int g = h ? ghi : glo;
+      slim_gemm_desc d;
+      d.A = (h ? Dhi : Dlo) + (int64_t)g * beta;
+      d.lda = m;
+      d.B = X64 + (int64_t)g * beta * ts;
+      d.ldb = ts;
+      d.C = Yc;
+      d.ldc = ts;
+      d.C2 = nullptr;
+      d.ldc2 = 0;
+      d.M = n;
+      d.N = (int)ts;
+      d.K = beta;
+      d.flags = 0;
+      d.alpha = 1.0;
+      d.beta = 1.0;
+      descs[2 * p + h] = d;
+    }
+  }
+}
+
+// grid (ceil(ts / 64), parts): 64 tokens x 4 row lanes per workgroup; part r owns rows [r*rpp, (r+1)*rpp)
+__global__ __launch_bounds__(256) void kl_partial(const double* __restrict__ Y, const double* __restrict__ Q, int n,
+                                                  int64_t ts, int rows_per_part, double* __restrict__ partial) {
+  __shared__ double red[5][4][KL_TOK];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * KL_TOK + tx;
+  const int r0 = blockIdx.y * rows_per_part;
+  const int r1 = min(n, r0 + rows_per_part);
+  const bool live = t < ts;
+  double my = -INFINITY, mq = -INFINITY;
+  if (live) {
+    for (int r = r0 + ty; r < r1; r += 4) {
+      my = fmax(my, Y[(int64_t)r * ts + t]);
+      mq = fmax(mq, Q[(int64_t)r * ts + t]);
+    }
+  }
+  red[0][ty][tx] = my;
+  red[1][ty][tx] = mq;
+  __syncthreads();
+  my = fmax(fmax(red[0][0][tx], red[0][1][tx]), fmax(red[0][2][tx], red[0][3][tx]));
+  mq = fmax(fmax(red[1][0][tx], red[1][1][tx]), fmax(red[1][2][tx], red[1][3][tx]));
+  double zy = 0.0, zq = 0.0, a = 0.0;
+  if (live && my > -INFINITY) {
+    for (int r = r0 + ty; r < r1; r += 4) {
+      const double y = Y[(int64_t)r * ts + t], q = Q[(int64_t)r * ts + t];
+      const double ey = exp(y - my);
+      zy += ey;
+      zq += exp(q - mq);
+      a += ey * (y - q);
+    }
+  }
+  red[2][ty][tx] = zy;
+  red[3][ty][tx] = zq;
+  red[4][ty][tx] = a;
+  __syncthreads();
+  if (ty == 0 && live) {
+    double* o = partial + ((int64_t)blockIdx.y * ts + t) * KL_PART;
+    o[0] = my;
+    o[1] = ((red[2][0][tx] + red[2][1][tx]) + red[2][2][tx]) + red[2][3][tx];
+    o[2] = mq;
+    o[3] = ((red[3][0][tx] + red[3][1][tx]) + red[3][2][tx]) + red[3][3][tx];
+    o[4] = ((red[4][0][tx] + red[4][1][tx]) + red[4][2][tx]) + red[4][3][tx];
+  }
+}
+
+// single workgroup: merges the row parts of every token, then sums the tokens in a fixed order
+__global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
+                                                   double* __restrict__ out) {
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (int64_t t = threadIdx.x; t < ts; t += 256) {
+    double My = -INFINITY, Mq = -INFINITY;
+    for (int p = 0; p < parts; ++p) {
+      const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
+      My = fmax(My, o[0]);
+      Mq = fmax(Mq, o[2]);
+    }
+    double Zy = 0.0, Zq = 0.0, A = 0.0;
+    for (int p = 0; p < parts; ++p) {
+      const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
+      const double sy = exp(o[0] - My), sq = exp(o[2] - Mq);
+      Zy += o[1] * sy;
+      A += o[4] * sy;
+      Zq += o[3] * sq;
+    }
+    // KL_t = sum_i P_i ((y_i - lse_y) - (q_i - lse_q)) = A / Zy - lse_y + lse_q
+    acc += A / Zy - (My + log(Zy)) + (Mq + log(Zq));
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = red[0];
+}
+
+__global__ __launch_bounds__(256) void sba_finalize(const double* __restrict__ obj, int pmax, const int* __restrict__ order,
+                                                    int k, int N, uint8_t* __restrict__ bits, int* __restrict__ p_star) {
+  __shared__ int best_p;
+  if (threadIdx.x == 0) {
+    int bp = 0;
+    double bv = obj[0];
+    for (int p = 1; p <= pmax; ++p) {
+      if (obj[p] < bv) {
+        bv = obj[p];
+        bp = p;
+      }
+    }
+    best_p = bp;
+    *p_star = bp;
+  }
+  __syncthreads();
+  const int ps = best_p;
+  for (int r = threadIdx.x; r < k; r += 256) {
+    int b = N;
+    if (r < ps) b = N - 1;
+    if (r >= k - ps) b = N + 1;
+    bits[order[r]] = (uint8_t)b;
+  }
+}
+
+}  // namespace
+
+extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                                         const double* group_sal, int beta, int N, int objective, const void* X_s,
+                                         slim_dtype x_dtype, int64_t t_s, int64_t ldxs, const slim_params* params,
+                                         uint8_t* bits, int* p_star, double* obj_curve) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  slim_params prm;
+  slim_default_params(&prm);
+  if (params) prm = *params;
+  SLIM_REQUIRE(ctx, W && group_sal && X_s && bits && p_star, "slim_sba_allocate: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_sba_allocate: need n, m > 0 and beta | m");
+  SLIM_REQUIRE(ctx, N == 2 || N == 3, "slim_sba_allocate: N must be 2 or 3 (got %d)", N);
+  SLIM_REQUIRE(ctx, beta % 4 == 0 && ldw >= m && ldw % 4 == 0, "slim_sba_allocate: beta and ldw must be multiples of 4");
+  SLIM_REQUIRE(ctx, t_s > 0 && t_s % 4 == 0 && ldxs >= t_s && ldxs % 4 == 0,
+               "slim_sba_allocate: t_s and ldxs must be positive multiples of 4");
+  SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(X_s), "slim_sba_allocate: misaligned pointer");
+  SLIM_REQUIRE(ctx, prm.q1_mode == 0 || prm.q1_mode == 1, "slim_sba_allocate: unknown q1_mode");
+  if (objective != SLIM_OBJ_KL)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sba_allocate: only the KL objective is built");
+  if (w_dtype == SLIM_F64 || x_dtype == SLIM_F64 || x_dtype == SLIM_F32)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sba_allocate: W must be F16/BF16/F32 and X_s F16/BF16");
+  const int k = m / beta;
+  const int pmax = k / 2;
+  SLIM_REQUIRE(ctx, (size_t)(pmax + 2) * sizeof(double) <= (size_t)SLIM_HPIN_BYTES, "slim_sba_allocate: too many groups");
+
+  const int rpp = 256;                                  // rows per part of the KL reduction
+  const int parts = slim_cdiv(n, rpp);
+  const size_t bW = slim_ws_round(sizeof(double) * (size_t)n * m);
+  const size_t bX = slim_ws_round(sizeof(double) * (size_t)m * t_s);
+  const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
+  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);
+  const size_t bDesc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * pmax + 2));
+  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2));
+  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(k + 1));
+  slim_status st = slim_ws_reserve(ctx, 4 * bW + bX + 2 * bY + bPart + bDesc + bObj + bOrd + 256);
+  if (st != SLIM_OK) return st;
+  double* W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  double* WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  double* Dlo = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  double* Dhi = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  double* X64 = static_cast<double*>(slim_ws_alloc(ctx, bX));
+  double* Yt = static_cast<double*>(slim_ws_alloc(ctx, bY));
+  double* Yc = static_cast<double*>(slim_ws_alloc(ctx, bY));
+  double* partial = static_cast<double*>(slim_ws_alloc(ctx, bPart));
+  slim_gemm_desc* descs = static_cast<slim_gemm_desc*>(slim_ws_alloc(ctx, bDesc));
+  double* obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
+  int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
+  int* pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
+
+  SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order);
+  st = slim_widen_f64(ctx, "sba_widen_w", W, w_dtype, n, m, ldw, W64, (int64_t)m);
+  if (st != SLIM_OK) return st;
+  st = slim_widen_f64(ctx, "sba_widen_x", X_s, x_dtype, m, (int)t_s, ldxs, X64, t_s);
+  if (st != SLIM_OK) return st;
+  SLIM_LAUNCH(ctx, "sba_fakequant", sba_fakequant, dim3(slim_cdiv((int64_t)n * k, 4)), dim3(256), 0, W64, n, m, beta, N,
+              prm.q1_mode, WN, Dlo, Dhi);
+  if (pmax > 0)
+    SLIM_LAUNCH(ctx, "sba_build_descs", sba_build_descs, dim3(1), dim3(256), 0, order, k, pmax, n, m, beta, t_s, Dlo, Dhi,
+                X64, Yc, descs);
+
+  slim_gemm_desc d;
+  d.A = W64;
+  d.lda = m;
+  d.B = X64;
+  d.ldb = t_s;
+  d.C = Yt;
+  d.ldc = t_s;
+  d.C2 = nullptr;
+  d.ldc2 = 0;
+  d.M = n;
+  d.N = (int)t_s;
+  d.K = m;
+  d.flags = 0;
+  d.alpha = 1.0;
+  d.beta = 0.0;
+  st = slim_dgemm(ctx, "sba_output_dgemm", 0, d);
+  if (st != SLIM_OK) return st;
+  d.A = WN;
+  d.C = Yc;
+  st = slim_dgemm(ctx, "sba_output_dgemm", 0, d);
+  if (st != SLIM_OK) return st;
+
+  const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
+  for (int p = 0; p <= pmax; ++p) {
+    SLIM_LAUNCH(ctx, "sba_kl_partial", kl_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
+    SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(1), dim3(256), 0, partial, parts, t_s, obj + p);
+    if (p < pmax) {
+      st = slim_dgemm_batched(ctx, "sba_update_dgemm", 0, descs + 2 * p, 1, n, (int)t_s);
+      if (st != SLIM_OK) return st;
+      st = slim_dgemm_batched(ctx, "sba_update_dgemm", 0, descs + 2 * p + 1, 1, n, (int)t_s);
+      if (st != SLIM_OK) return st;
+    }
+  }
+  SLIM_LAUNCH(ctx, "sba_finalize", sba_finalize, dim3(1), dim3(256), 0, obj, pmax, order, k, N, bits, pstar_dev);
+
+  double* host_obj = reinterpret_cast<double*>(ctx->hpin);
+  int* host_p = reinterpret_cast<int*>(ctx->hpin + sizeof(double) * (size_t)(pmax + 1));
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host_obj, obj, sizeof(double) * (pmax + 1), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host_p, pstar_dev, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  *p_star = *host_p;
+  if (obj_curve) memcpy(obj_curve, host_obj, sizeof(double) * (pmax + 1));
+  return SLIM_OK;
+}

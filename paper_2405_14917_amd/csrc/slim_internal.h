@@ -1,0 +1,122 @@
+// Internal declarations shared by the translation units of libslim (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <new>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "slim.h"
+
+struct slim_prof_entry {
+  std::string name;
+  double total_ms = 0.0;
+  int launches = 0;
+};
+
+struct slim_prof_pending {
+  const char* name;
+  hipEvent_t start, stop;
+};
+
+struct slim_ctx {
+  hipStream_t stream = nullptr;
+  int device = 0;
+  char err[512] = {0};
+  // grow-only device workspace with a bump pointer that every entry point resets
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  size_t ws_off = 0;
+  // small fixed buffers
+  double* tau_default = nullptr;  // device, SLIM_DEFAULT_NCAND doubles
+  int ncand_default = 0;
+  int* dflags = nullptr;          // device, 64 ints (pivot failures, counters)
+  char* hpin = nullptr;           // pinned host staging, SLIM_HPIN_BYTES
+  // profiling
+  bool prof = false;
+  std::vector<slim_prof_pending> pending;
+  std::vector<hipEvent_t> free_events;
+  std::vector<slim_prof_entry> entries;
+};
+
+constexpr int SLIM_HPIN_BYTES = 1 << 20;
+constexpr int SLIM_MAX_CAND = 1024;
+
+slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...);
+
+// Workspace: reserve() makes sure at least `bytes` are available and rewinds the bump pointer;
+// alloc() hands out 256-byte aligned pieces of it.  reserve() may synchronise and reallocate.
+slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes);
+void* slim_ws_alloc(slim_ctx* ctx, size_t bytes);
+inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255); }
+
+// Profiling hooks used by SLIM_LAUNCH.
+void slim_prof_begin(slim_ctx* ctx, const char* name);
+void slim_prof_end(slim_ctx* ctx);
+
+#define SLIM_HIP_TRY(ctx, expr)                                                              \
+  do {                                                                                       \
+    hipError_t e__ = (expr);                                                                 \
+    if (e__ != hipSuccess)                                                                   \
+      return slim_fail((ctx), SLIM_ERR_HIP, "%s failed: %s (%s:%d)", #expr,                 \
+                       hipGetErrorString(e__), __FILE__, __LINE__);                          \
+  } while (0)
+
+// Launches `kernel<<<grid, block, shmem, ctx->stream>>>(args...)`, bracketed by profiling events
+// when enabled, and turns a launch error into SLIM_ERR_HIP.
+#define SLIM_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                              \
+  do {                                                                                       \
+    if ((ctx)->prof) slim_prof_begin((ctx), (name));                                         \
+    hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (ctx)->stream, __VA_ARGS__);        \
+    if ((ctx)->prof) slim_prof_end((ctx));                                                   \
+    hipError_t e__ = hipGetLastError();                                                      \
+    if (e__ != hipSuccess)                                                                   \
+      return slim_fail((ctx), SLIM_ERR_HIP, "launch of %s failed: %s", (name),              \
+                       hipGetErrorString(e__));                                              \
+  } while (0)
+
+#define SLIM_REQUIRE(ctx, cond, ...)                                                         \
+  do {                                                                                       \
+    if (!(cond)) return slim_fail((ctx), SLIM_ERR_INVALID_ARG, __VA_ARGS__);                 \
+  } while (0)
+
+inline bool slim_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int slim_cdiv(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
+
+// ---- fp64 matrix-core GEMM (dgemm.hip) --------------------------------------------------
+// C = alpha * A * op(B) + beta * C  for row-major operands.
+//   A: M x K (lda).  trans_b = 0: B is K x N (ldb);  trans_b = 1: B is N x K (ldb).
+//   C: M x N (ldc); C2 (optional, ldc2) receives a copy of the result.
+//   flags: SLIM_GEMM_UPPER_ONLY skips output tiles that lie entirely below the diagonal (M == N).
+//          SLIM_GEMM_A_UPPER / SLIM_GEMM_B_UPPER declare A (M x K, square) / op(B) (K x N, square) upper
+//          triangular with zeros below the diagonal so that the K range can be cut.
+// K and N even, all pointers 16-byte aligned, leading dimensions even.
+enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4 };
+struct slim_gemm_desc {
+  const double* A;
+  const double* B;
+  double* C;
+  double* C2;
+  int M, N, K;
+  int flags;
+  int64_t lda, ldb, ldc, ldc2;
+  double alpha, beta;
+};
+slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc& d);
+// Batched form: `descs` is a device array of `count` descriptors; max_M / max_N bound the grid.
+slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs_dev,
+                               int count, int max_M, int max_N);
+
+// ---- small utilities (util.hip) -----------------------------------------------------------
+// dst (fp64, rows x cols, ldd) = exact widening of src (F16 / BF16 / F32 / F64, lds); cols % 4 == 0.
+slim_status slim_widen_f64(slim_ctx* ctx, const char* name, const void* src, slim_dtype dt, int rows, int cols,
+                           int64_t lds, double* dst, int64_t ldd);
+slim_status slim_zero_f64(slim_ctx* ctx, const char* name, double* p, int64_t n);
+// *out = sum of v[0..n) in a fixed order (single workgroup)
+slim_status slim_sum_f64(slim_ctx* ctx, const char* name, const double* v, int n, double* out);

@@ -1,0 +1,400 @@
+"""Parity of the HIP path with the float64 oracle, entry point by entry point, through the C ABI.
+
+Every case hands the SAME seeded inputs to both sides.  Stage inputs that are themselves results of an
+earlier stage (G, U, group salience, bits) are taken from the ORACLE, never from the HIP path.
+
+Bars (the benchmark spec): integer outputs (bits, p*, codes, candidate indices, packed words, offsets) bit-exact
+wherever the oracle's recorded decision margin exceeds 1e-6 relative; dequantised weights within 1e-3
+relative Frobenius; reconstruction error within 1 %.  The fp64 kernels are far inside those bars, so the
+tests also assert much tighter figures where the arithmetic allows.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as orc
+from paper_2405_14917_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-6
+
+
+@pytest.fixture(scope="module")
+def slim():
+    from paper_2405_14917_amd import binding
+    s = binding.Slim("cuda:0")
+    yield s
+    s.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def small_layer(seed, n=96, m=256, t=640, beta=64, correlated=True, w_dtype=np.float16):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_t(4, (n, m)) / np.sqrt(2) * 0.02).astype(w_dtype)
+    X = rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]
+    if correlated:
+        R = rng.standard_normal((m, 8))
+        X = X + 0.5 / np.sqrt(8) * (R @ (R.T @ X))
+    X[5:9] *= 30.0
+    return W, X.astype(np.float16)
+
+
+# ------------------------------------------------------------------------------------------ a1
+@pytest.mark.parametrize("m,t,chunks", [(256, 512, 1), (264, 500, 2), (520, 1100, 3), (8, 8, 1), (256, 64 * 40, 1)])
+def test_hessian_accumulate(slim, m, t, chunks):
+    rng = np.random.default_rng(m + t)
+    X = (rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]).astype(np.float16)
+    G = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    Gref = np.zeros((m, m))
+    nt = 0
+    edges = np.linspace(0, t, chunks + 1).astype(int)
+    for a, b in zip(edges[:-1], edges[1:]):
+        # a chunk is a view with the full row stride (tokens contiguous) when its start is aligned
+        Xc = np.ascontiguousarray(X[:, a:b])
+        pad = (-Xc.shape[1]) % 8
+        Xd = dev(np.pad(Xc, ((0, 0), (0, pad))))[:, : Xc.shape[1]]
+        nt = slim.hessian_accumulate(Xd, G, nt)
+        orc.gram_accumulate(Gref, Xc)
+    assert nt == t
+    Gg = host(G).astype(np.float64)
+    assert np.array_equal(Gg, Gg.T)                       # both triangles, exactly symmetric
+    # products are exact; fp32 accumulation over t terms: error relative to the geometric mean of the
+    # diagonal stays within a few fp32 ulps times sqrt(t)
+    scale = np.sqrt(np.outer(np.diag(Gref), np.diag(Gref)))
+    err = np.max(np.abs(Gg - Gref) / scale)
+    print("gram max scaled error", err)
+    assert err < 2e-6 * max(1.0, np.sqrt(t / 512))
+
+
+def test_hessian_accumulate_bf16_and_determinism(slim):
+    rng = np.random.default_rng(7)
+    m, t = 256, 768
+    X = torch.from_numpy(rng.standard_normal((m, t)).astype(np.float32)).to(torch.bfloat16).cuda()
+    G1 = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    G2 = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    slim.hessian_accumulate(X, G1)
+    slim.hessian_accumulate(X, G2)
+    assert torch.equal(G1, G2)
+    Xf = X.float().cpu().numpy().astype(np.float64)
+    ref = Xf @ Xf.T
+    assert np.max(np.abs(host(G1) - ref)) / np.max(np.abs(ref)) < 1e-5
+
+
+# ------------------------------------------------------------------------------------------ a2
+@pytest.mark.parametrize("m", [64, 256, 320, 200, 72])
+def test_hessian_inverse(slim, m):
+    rng = np.random.default_rng(m)
+    t = 4 * m
+    X = rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]
+    R = rng.standard_normal((m, 4))
+    X = X + 0.5 * (R @ (R.T @ X)) / 2
+    G32 = (X @ X.T).astype(np.float32)
+    G32 = np.maximum(G32, G32.T)                          # exactly symmetric fp32 input for both sides
+    Uo, do, lam = orc.hessian_inverse(G32.astype(np.float64), t, 0.01)
+    U, d = slim.hessian_inverse(dev(G32), t, 0.01)
+    U, d = host(U), host(d)
+    assert np.all(np.tril(U, -1) == 0.0)
+    assert np.linalg.norm(U - Uo) / np.linalg.norm(Uo) < 1e-10
+    assert np.max(np.abs(U - Uo)) < 1e-9 * np.max(np.abs(Uo))
+    assert np.allclose(d, do, rtol=1e-9)
+    Hd = 2.0 / t * G32.astype(np.float64) + lam * np.eye(m)
+    assert np.max(np.abs(U.T @ U @ Hd - np.eye(m))) < 1e-8
+
+
+def test_hessian_inverse_not_positive_definite(slim):
+    from paper_2405_14917_amd import binding
+    m = 128
+    G = np.eye(m, dtype=np.float32)
+    G[37, 37] = -4.0
+    with pytest.raises(binding.SlimError) as ei:
+        slim.hessian_inverse(dev(G), 16, 0.0)
+    assert ei.value.status == binding.ERR_NOT_PD
+    assert slim.last_info == 38
+    # the context stays usable
+    U, d = slim.hessian_inverse(dev(np.eye(m, dtype=np.float32)), 2, 0.0)
+    assert np.allclose(host(U), np.eye(m))
+
+
+# ------------------------------------------------------------------------------------------ a3
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_salience(slim, dtype):
+    W, X = small_layer(3, n=100, m=256, beta=64, w_dtype=dtype)
+    G = np.zeros((256, 256))
+    orc.gram_accumulate(G, X)
+    Uo, do, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
+    col_o, grp_o, elem_o = orc.salience(W, do, 64)
+    col, grp, elem = slim.salience(dev(W), dev(do), 64, want_elem=True)
+    assert np.allclose(host(col), col_o, rtol=1e-12)
+    assert np.allclose(host(grp), grp_o, rtol=1e-12)
+    assert np.allclose(host(elem), elem_o, rtol=1e-14)
+    col2, grp2, _ = slim.salience(dev(W), None, 64, U=dev(Uo), sal_mode=orc.SAL_CHOL_DIAG)
+    c2o, g2o, _ = orc.salience(W, do, 64, U=Uo, sal_mode=orc.SAL_CHOL_DIAG)
+    assert np.allclose(host(col2), c2o, rtol=1e-12) and np.allclose(host(grp2), g2o, rtol=1e-12)
+    if dtype == np.float16:
+        Wb = torch.from_numpy(W.astype(np.float32)).to(torch.bfloat16)
+        col3, _, _ = slim.salience(Wb.cuda(), dev(do), 64)
+        c3o, _, _ = orc.salience(Wb.float().numpy(), do, 64)
+        assert np.allclose(host(col3), c3o, rtol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------ a4
+@pytest.mark.parametrize("N,beta,m,ts", [(2, 64, 256, 128), (3, 32, 288, 64), (2, 128, 640, 132)])
+def test_sba_allocate(slim, N, beta, m, ts):
+    W, X = small_layer(10 + N + beta, n=72, m=m, t=max(ts, 4 * m) // 4 * 4, beta=beta)
+    G = np.zeros((m, m))
+    orc.gram_accumulate(G, X)
+    _, do, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
+    _, grp_o, _ = orc.salience(W, do, beta)
+    Xs = np.ascontiguousarray(X[:, :ts])
+    bits_o, p_o, obj_o, margin = orc.sba_allocate(W, grp_o, beta, N, Xs)
+    Xd = dev(X)[:, :ts]                                   # a strided view: ld = t
+    bits, p_star, obj = slim.sba_allocate(dev(W), dev(grp_o), beta, N, Xd)
+    assert np.allclose(obj, obj_o, rtol=1e-9, atol=1e-12)
+    if margin > MARGIN:
+        assert p_star == p_o
+        assert np.array_equal(host(bits), bits_o)
+    b = host(bits).astype(int)
+    assert set(b.tolist()) <= {N - 1, N, N + 1} and b.sum() == N * (m // beta)
+
+
+def test_sba_ties_keep_lower_group_first(slim):
+    W, X = small_layer(21, n=40, m=256, t=512, beta=64)
+    gs = np.array([2.0, 1.0, 1.0, 2.0])
+    bits_o, p_o, obj_o, margin = orc.sba_allocate(W, gs, 64, 2, X[:, :64])
+    bits, p_star, obj = slim.sba_allocate(dev(W), dev(gs), 64, 2, dev(np.ascontiguousarray(X[:, :64])))
+    assert np.allclose(obj, obj_o, rtol=1e-9)
+    if margin > MARGIN:
+        assert p_star == p_o and np.array_equal(host(bits), bits_o)
+
+
+# ------------------------------------------------------------------------------------------ a5 + a6
+@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_sqc_calibrate(slim, beta, bits):
+    from paper_2405_14917_amd import binding
+    rng = np.random.default_rng(beta * 10 + bits)
+    n = 75
+    blk = rng.standard_t(4, (n, beta)) * 0.02
+    blk[3] = 0.0
+    blk[4] = 0.0125
+    blk[5, : beta // 2] = -0.5
+    tau = orc.tau_grid()
+    for mode in (orc.WEIGHT_MASK_MEAN, orc.WEIGHT_UNIFORM):
+        for scope in (orc.SCOPE_BLOCK, orc.SCOPE_ROW):
+            if mode == orc.WEIGHT_UNIFORM and scope == orc.SCOPE_ROW:
+                continue
+            so, zo, co, mg = orc.sqc_calibrate(blk, bits, tau, mode, scope)
+            s, z, c = slim.sqc_calibrate(dev(blk), bits, binding.make_params(mode, scope))
+            s, z, c = host(s), host(z), host(c)
+            ok = mg > MARGIN
+            assert ok.sum() >= n - 3
+            assert np.array_equal(c[ok], co[ok])
+            assert np.array_equal(z, zo)
+            assert np.allclose(s[ok], so[ok], rtol=1e-14, atol=0)
+
+
+def test_sqc_explicit_weights_element_mode_and_affine_one_bit(slim):
+    from paper_2405_14917_amd import binding
+    rng = np.random.default_rng(99)
+    n, beta = 40, 64
+    blk = rng.standard_normal((n, beta)) * 0.02
+    tau = orc.tau_grid()
+    omega = rng.uniform(0.1, 3.0, (n, beta))
+    so, zo, co, mg = orc.sqc_calibrate(blk, 2, tau, omega=omega)
+    s, z, c = slim.sqc_calibrate(dev(blk), 2, omega=dev(omega))
+    ok = mg > MARGIN
+    assert np.array_equal(host(c)[ok], co[ok]) and np.allclose(host(s)[ok], so[ok], rtol=1e-14)
+    d = rng.uniform(0.5, 2.0, beta)
+    so, zo, co, mg = orc.sqc_calibrate(blk, 3, tau, orc.WEIGHT_ELEMENT, d=d)
+    s, z, c = slim.sqc_calibrate(dev(blk), 3, binding.make_params(orc.WEIGHT_ELEMENT), hinv_diag_blk=dev(d))
+    ok = mg > MARGIN
+    assert np.array_equal(host(c)[ok], co[ok])
+    so, zo, co, mg = orc.sqc_calibrate(blk, 1, tau, q1_mode=orc.Q1_AFFINE)
+    s, z, c = slim.sqc_calibrate(dev(blk), 1, binding.make_params(q1_mode=orc.Q1_AFFINE))
+    ok = mg > MARGIN
+    assert np.array_equal(host(c)[ok], co[ok]) and np.array_equal(host(z), zo)
+    # a custom grid through the ABI
+    tau2 = np.linspace(0.8, 1.2, 37)
+    so, zo, co, mg = orc.sqc_calibrate(blk, 2, tau2)
+    s, z, c = slim.sqc_calibrate(dev(blk), 2, tau=dev(tau2))
+    ok = mg > MARGIN
+    assert np.array_equal(host(c)[ok], co[ok])
+
+
+# ------------------------------------------------------------------------------------------ a5 - a8
+def _gptq_case(slim, W, X, bits, beta, params=None, okw=None):
+    from paper_2405_14917_amd import binding
+    n, m = W.shape
+    G = np.zeros((m, m))
+    orc.gram_accumulate(G, X)
+    Uo, do, lam = orc.hessian_inverse(G, X.shape[1], 0.01)
+    okw = okw or {}
+    out_o = orc.gptq_quantize(W, Uo, bits, beta, orc.tau_grid(), hinv_diag=do, **okw)
+    out = slim.gptq_quantize(dev(W), dev(Uo), dev(bits), beta, params=params, hinv_diag=dev(do),
+                             want_what=torch.float64, want_sum_e2=True)
+    codes, scale, zero, What = host(out["codes"]), host(out["scale"]), host(out["zero"]), host(out["What"])
+    # rows whose every decision has a safe margin must agree exactly
+    k = m // beta
+    row_ok = (out_o["round_margin"].min(axis=1) > MARGIN) & (out_o["sqc_margin"].min(axis=1) > MARGIN)
+    assert row_ok.mean() > 0.95
+    assert np.array_equal(codes[row_ok], out_o["codes"][row_ok])
+    assert np.array_equal(zero[row_ok], out_o["zero"][row_ok])
+    assert np.allclose(scale[row_ok], out_o["scale"][row_ok], rtol=1e-12, atol=0)
+    fro = np.linalg.norm(What - out_o["What"]) / np.linalg.norm(out_o["What"])
+    print("rows with safe margins: %d / %d, relative Frobenius distance of What: %.3e" % (row_ok.sum(), n, fro))
+    assert fro < 1e-3
+    if row_ok.all():
+        assert fro < 1e-10
+        assert host(out["sum_e2"])[0] == pytest.approx(out_o["sum_e2"], rel=1e-9)
+    rec_o = orc.reconstruction_error(W, out_o["What"], G)
+    rec = orc.reconstruction_error(W, What, G)
+    assert abs(rec - rec_o) <= 0.01 * rec_o
+    # What is the dequantisation of the codes
+    deq = np.repeat(scale, beta, axis=1) * (codes - np.repeat(zero, beta, axis=1))
+    assert np.allclose(What, deq, rtol=1e-15, atol=0)
+    return out_o, out
+
+
+@pytest.mark.parametrize("beta,n,m", [(64, 96, 256), (128, 130, 512), (32, 50, 160)])
+def test_gptq_quantize(slim, beta, n, m):
+    W, X = small_layer(beta + n, n=n, m=m, t=4 * m, beta=beta)
+    k = m // beta
+    rng = np.random.default_rng(5)
+    allowed = [b for b in (1, 2, 3, 4) if (beta * b) % 32 == 0]
+    bits = rng.choice(allowed, size=k).astype(np.uint8)
+    _gptq_case(slim, W, X, bits, beta)
+
+
+def test_gptq_modes_and_fp32_weights(slim):
+    from paper_2405_14917_amd import binding
+    W, X = small_layer(77, n=64, m=256, t=1024, beta=64, w_dtype=np.float32)
+    bits = np.array([1, 2, 3, 2], dtype=np.uint8)
+    for mode, scope, q1 in ((orc.WEIGHT_UNIFORM, 0, 0), (orc.WEIGHT_MASK_MEAN, orc.SCOPE_ROW, 0),
+                            (orc.WEIGHT_ELEMENT, 0, 0), (orc.WEIGHT_MASK_MEAN, 0, orc.Q1_AFFINE)):
+        _gptq_case(slim, W, X, bits, 64, params=binding.make_params(mode, scope, q1),
+                   okw=dict(weight_mode=mode, scope=scope, q1_mode=q1))
+
+
+def test_gptq_degenerate_rows(slim):
+    W, X = small_layer(78, n=48, m=256, t=1024, beta=64)
+    W = W.astype(np.float32)
+    W[0] = 0.0                    # an all-zero output row
+    W[1, :64] = 0.25              # a constant group
+    W[2, 64:128] = -0.125
+    bits = np.array([2, 3, 1, 4], dtype=np.uint8)
+    _gptq_case(slim, W.astype(np.float16), X, bits, 64)
+
+
+def test_gptq_identity_hessian_is_round_to_nearest(slim):
+    rng = np.random.default_rng(8)
+    n, m, beta = 64, 256, 64
+    W = (rng.standard_normal((n, m)) * 0.02).astype(np.float16)
+    U = np.eye(m) * 0.7
+    bits = np.array([2, 3, 1, 2], dtype=np.uint8)
+    out = slim.gptq_quantize(dev(W), dev(U), dev(bits), beta)
+    codes = host(out["codes"])
+    tau = orc.tau_grid()
+    for g in range(4):
+        blk = W[:, g * beta:(g + 1) * beta].astype(np.float64)
+        s, z, c, mg = orc.sqc_calibrate(blk, int(bits[g]), tau)
+        if bits[g] == 1:
+            q = (blk >= 0).astype(np.uint8)
+        else:
+            q = np.stack([orc.quantize_affine(blk[i], s[i], z[i], int(bits[g])) for i in range(n)]).astype(np.uint8)
+        ok = mg > MARGIN
+        assert np.array_equal(codes[ok, g * beta:(g + 1) * beta], q[ok])
+
+
+# ------------------------------------------------------------------------------------------ a9
+@pytest.mark.parametrize("beta,n", [(128, 200), (64, 64), (32, 70)])
+def test_pack(slim, beta, n):
+    rng = np.random.default_rng(beta + n)
+    allowed = [b for b in (1, 2, 3, 4) if (beta * b) % 32 == 0]
+    k = 19
+    bits = rng.choice(allowed, size=k).astype(np.uint8)
+    codes = np.concatenate([rng.integers(0, 2 ** int(b), (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    po, go, ro, mo = orc.pack_fast(codes, bits, beta)
+    packed, gbits, row_off, m_star = slim.pack(dev(codes), dev(bits), beta)
+    assert m_star == mo
+    assert np.array_equal(host(row_off), ro)
+    assert np.array_equal(host(gbits).view(np.uint32), go)
+    assert np.array_equal(host(packed).view(np.uint32), po)
+    c2, b2 = orc.unpack(host(packed).view(np.uint32), host(gbits).view(np.uint32), beta, k)
+    assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
+
+
+def test_pack_rejects_bad_input(slim):
+    from paper_2405_14917_amd import binding
+    codes = dev(np.zeros((8, 128), dtype=np.uint8))
+    with pytest.raises(binding.SlimError) as ei:
+        slim.pack(codes, dev(np.array([2, 7], dtype=np.uint8)), 64)
+    assert ei.value.status == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimError):
+        slim.pack(codes, dev(np.array([2, 2], dtype=np.uint8)), 64, packed_rows=3)       # needs 8 rows
+    with pytest.raises(binding.SlimError):
+        slim.pack(codes, dev(np.array([2, 2, 2], dtype=np.uint8)), 48)                   # beta not a multiple of 32
+
+
+def test_invalid_arguments_are_rejected(slim):
+    from paper_2405_14917_amd import binding
+    W = dev(np.zeros((16, 128), dtype=np.float16))
+    U = dev(np.eye(128))
+    with pytest.raises(binding.SlimError) as ei:
+        slim.gptq_quantize(W, U, dev(np.array([2, 9], dtype=np.uint8)), 64)
+    assert ei.value.status == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimError) as ei:
+        slim.gptq_quantize(W, U, dev(np.array([2, 2], dtype=np.uint8)), 64, gptq_block=128)
+    assert ei.value.status == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.SlimError) as ei:
+        slim.sba_allocate(W, dev(np.ones(2)), 64, 5, dev(np.zeros((128, 64), dtype=np.float16)))
+    assert ei.value.status == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimError) as ei:
+        slim.hessian_accumulate(dev(np.zeros((12, 64), dtype=np.float16)), torch.zeros((12, 12), device="cuda"))
+    assert ei.value.status == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SlimError) as ei:
+        slim.salience(W, dev(np.ones(128)), 48)
+    assert ei.value.status == binding.ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------------------------------ whole pass
+@pytest.mark.parametrize("correlated", [False, True])
+def test_whole_pass_config1(slim, correlated):
+    """BASELINE config 1 end to end, every stage of the HIP path fed by the HIP path's own earlier stages."""
+    cfg = synth.CONFIGS["C1"]
+    W = synth.make_weights(cfg)
+    X = synth.make_activations(cfg, correlated=correlated)
+    ref = orc.slim_layer(W, [X], cfg.beta, cfg.N)
+    Wd, Xd = dev(W), dev(X)
+    G = torch.zeros((cfg.m, cfg.m), dtype=torch.float32, device="cuda")
+    nt = slim.hessian_accumulate(Xd, G, 0)
+    U, d = slim.hessian_inverse(G, nt, cfg.percdamp)
+    col, grp, _ = slim.salience(Wd, d, cfg.beta)
+    bits, p_star, obj = slim.sba_allocate(Wd, grp, cfg.beta, cfg.N, Xd[:, : min(2048, cfg.t)])
+    out = slim.gptq_quantize(Wd, U, bits, cfg.beta, want_what=torch.float64)
+    packed, gbits, row_off, m_star = slim.pack(out["codes"], bits, cfg.beta)
+    # the Gram matrix is accumulated in fp32, so U carries ~1e-7 relative differences and individual codes
+    # may legitimately differ from the all-float64 oracle; structure and quality must agree
+    assert np.allclose(host(grp), ref["group_sal"], rtol=1e-4)
+    assert np.allclose(obj, ref["obj_curve"], rtol=1e-6)
+    if ref["sba_margin"] > MARGIN:
+        assert p_star == ref["p_star"] and np.array_equal(host(bits), ref["bits"])
+    assert m_star == cfg.m * cfg.N // 32 == ref["m_star"]
+    assert np.array_equal(host(row_off), ref["row_off"]) and np.array_equal(host(gbits).view(np.uint32), ref["gbits"])
+    What = host(out["What"])
+    rec = orc.reconstruction_error(W, What, ref["G"])
+    print("config 1 (%s): codes equal %.4f, recon gpu %.6e oracle %.6e" %
+          ("correlated" if correlated else "independent", (host(out["codes"]) == ref["codes"]).mean(), rec, ref["recon"]))
+    assert abs(rec - ref["recon"]) <= 0.01 * ref["recon"]
+    c2, b2 = orc.unpack(host(packed).view(np.uint32), host(gbits).view(np.uint32), cfg.beta, cfg.k)
+    assert np.array_equal(c2, host(out["codes"]))

@@ -1,0 +1,69 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, and its host-only helpers agree with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import slim_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "slim.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2405_14917_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2405_14917_amd import build
+        build.build(verbose=False)
+    return b
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slim_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(binding):
+    lib = binding.load()
+    names = _declared_symbols()
+    assert len(names) >= 17
+    for name in names:
+        assert hasattr(lib, name), "libslim.so does not export %s" % name
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_default_tau_is_the_oracle_grid_bit_for_bit(binding):
+    tau = binding.default_tau()
+    ref = orc.tau_grid(0.1, 50)
+    assert tau.shape == ref.shape == (100,)
+    assert np.array_equal(tau.view(np.uint64), ref.view(np.uint64))
+
+
+def test_default_params_and_mode_constants(binding):
+    lib = binding.load()
+    p = binding.SlimParams(7, 7, 7, 7)
+    lib.slim_default_params(ctypes.byref(p))
+    assert (p.sqc_weight_mode, p.mask_scope, p.q1_mode, p.sal_mode) == (0, 0, 0, 0)
+    # the header's mode values are an interface shared with the oracle's switches
+    text = open(HEADER).read()
+    for name, val in (("SLIM_WEIGHT_MASK_MEAN", orc.WEIGHT_MASK_MEAN), ("SLIM_WEIGHT_UNIFORM", orc.WEIGHT_UNIFORM),
+                      ("SLIM_WEIGHT_ELEMENT", orc.WEIGHT_ELEMENT), ("SLIM_Q1_SIGN", orc.Q1_SIGN),
+                      ("SLIM_Q1_AFFINE", orc.Q1_AFFINE), ("SLIM_SCOPE_BLOCK", orc.SCOPE_BLOCK),
+                      ("SLIM_SCOPE_ROW", orc.SCOPE_ROW), ("SLIM_SAL_HINV_DIAG", orc.SAL_HINV_DIAG),
+                      ("SLIM_SAL_CHOL_DIAG", orc.SAL_CHOL_DIAG)):
+        assert re.search(r"\b%s\s*=\s*%d\b" % (name, val), text), name
+
+
+def test_null_context_is_rejected_without_a_gpu(binding):
+    lib = binding.load()
+    assert lib.slim_destroy(None) == binding.ERR_INVALID_ARG
+    assert lib.slim_profile_enable(None, 1) == binding.ERR_INVALID_ARG
+    assert lib.slim_workspace_bytes(None) == 0
+    assert lib.slim_last_error(None) == b"null context"
+    nt = ctypes.c_int64(0)
+    assert lib.slim_hessian_accumulate(None, None, 0, 8, 8, 8, None, 8, ctypes.byref(nt)) == binding.ERR_INVALID_ARG
