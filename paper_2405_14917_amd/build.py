@@ -30,9 +30,14 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# The fp64 GEMM keeps its 128 accumulator registers in ordinary VGPRs (MFMA "VGPR form"): without this the
+# compiler shuttles them between the two register files on every K slab and halves the occupancy.
+EXTRA_FLAGS = {"dgemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [hipcc(), *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)

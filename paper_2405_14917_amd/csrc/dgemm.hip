@@ -19,41 +19,53 @@ constexpr int BM = 128, BN = 128, BK = 16, NTHREADS = 256;
 struct Prefetch {
   double2 a[4];
   double2 b[4];
+  unsigned va, vb;   // bit j set: element pair j is inside the matrix and the K range
 };
 
+// Loads are branch-free: an out-of-range element is read from a clamped (valid) address and replaced by
+// zero only when it is written to LDS, so that the loads of the next slab stay in flight while the current
+// slab is multiplied.
 template <int TRANS_B>
 __device__ __forceinline__ void load_global(const slim_gemm_desc& d, int row0, int col0, int k0, int kend,
                                             int tid, Prefetch& p) {
+  p.va = 0;
+  p.vb = 0;
   // A slab: 128 rows x 16 k.  Thread -> (row, half of the k range), 4 x 16 bytes contiguous in k.
   {
     const int r = tid >> 1, kh = (tid & 1) * 8;
     const int row = row0 + r;
-    const double* src = d.A + (int64_t)row * d.lda + k0 + kh;
+    const bool rv = row < d.M;
+    const double* src = d.A + (int64_t)min(row, d.M - 1) * d.lda;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = k0 + kh + 2 * j;
-      p.a[j] = (row < d.M && k < kend) ? *reinterpret_cast<const double2*>(src + 2 * j) : make_double2(0.0, 0.0);
+      p.a[j] = *reinterpret_cast<const double2*>(src + min(k, d.K - 2));
+      p.va |= (rv && k < kend) ? (1u << j) : 0u;
     }
   }
   if (TRANS_B) {
     // B stored N x K: same pattern as A with n in the role of the row
     const int r = tid >> 1, kh = (tid & 1) * 8;
     const int col = col0 + r;
-    const double* src = d.B + (int64_t)col * d.ldb + k0 + kh;
+    const bool cv = col < d.N;
+    const double* src = d.B + (int64_t)min(col, d.N - 1) * d.ldb;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = k0 + kh + 2 * j;
-      p.b[j] = (col < d.N && k < kend) ? *reinterpret_cast<const double2*>(src + 2 * j) : make_double2(0.0, 0.0);
+      p.b[j] = *reinterpret_cast<const double2*>(src + min(k, d.K - 2));
+      p.vb |= (cv && k < kend) ? (1u << j) : 0u;
     }
   } else {
     // B stored K x N: thread -> (k, 8 consecutive n)
     const int kk = tid >> 4, n0 = (tid & 15) * 8;
     const int k = k0 + kk;
-    const double* src = d.B + (int64_t)k * d.ldb + col0 + n0;
+    const bool kv = k < kend;
+    const double* src = d.B + (int64_t)min(k, d.K - 1) * d.ldb;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int col = col0 + n0 + 2 * j;
-      p.b[j] = (k < kend && col < d.N) ? *reinterpret_cast<const double2*>(src + 2 * j) : make_double2(0.0, 0.0);
+      p.b[j] = *reinterpret_cast<const double2*>(src + min(col, d.N - 2));
+      p.vb |= (kv && col < d.N) ? (1u << j) : 0u;
     }
   }
 }
@@ -64,21 +76,26 @@ __device__ __forceinline__ void store_lds(double* As, double* Bs, int tid, const
     const int r = tid >> 1, kh = (tid & 1) * 8;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      As[(kh + 2 * j) * BM + r] = p.a[j].x;
-      As[(kh + 2 * j + 1) * BM + r] = p.a[j].y;
+      const bool v = (p.va >> j) & 1u;
+      As[(kh + 2 * j) * BM + r] = v ? p.a[j].x : 0.0;
+      As[(kh + 2 * j + 1) * BM + r] = v ? p.a[j].y : 0.0;
     }
   }
   if (TRANS_B) {
     const int r = tid >> 1, kh = (tid & 1) * 8;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      Bs[(kh + 2 * j) * BN + r] = p.b[j].x;
-      Bs[(kh + 2 * j + 1) * BN + r] = p.b[j].y;
+      const bool v = (p.vb >> j) & 1u;
+      Bs[(kh + 2 * j) * BN + r] = v ? p.b[j].x : 0.0;
+      Bs[(kh + 2 * j + 1) * BN + r] = v ? p.b[j].y : 0.0;
     }
   } else {
     const int kk = tid >> 4, n0 = (tid & 15) * 8;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) *reinterpret_cast<double2*>(&Bs[kk * BN + n0 + 2 * j]) = p.b[j];
+    for (int j = 0; j < 4; ++j) {
+      const bool v = (p.vb >> j) & 1u;
+      *reinterpret_cast<double2*>(&Bs[kk * BN + n0 + 2 * j]) = make_double2(v ? p.b[j].x : 0.0, v ? p.b[j].y : 0.0);
+    }
   }
 }
 
@@ -100,8 +117,9 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   const int wm = wave >> 1, wn = wave & 1;
   const int l16 = lane & 15, lk = lane >> 4;
 
-  double* As[2] = {smem, smem + BK * BM + BK * BN};
-  double* Bs[2] = {smem + BK * BM, smem + 2 * BK * BM + BK * BN};
+  // LDS stage s: A slab at smem + s * STAGE, B slab BK * BM behind it (plain offsets from one base keep the
+  // accesses in the LDS address space)
+  constexpr int STAGE = BK * BM + BK * BN;
 
   double4v acc[4][4];
 #pragma unroll
@@ -113,14 +131,16 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   int cur = 0;
   if (kbeg < kend) {
     load_global<TRANS_B>(d, row0, col0, kbeg, kend, tid, pf);
-    store_lds<TRANS_B>(As[0], Bs[0], tid, pf);
+    store_lds<TRANS_B>(smem, smem + BK * BM, tid, pf);
   }
   __syncthreads();
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
-    const bool more = k0 + BK < kend;
-    if (more) load_global<TRANS_B>(d, row0, col0, k0 + BK, kend, tid, pf);
-    const double* as = As[cur] + wm * 64 + l16;
-    const double* bs = Bs[cur] + wn * 64 + l16;
+    // unconditional (the slab behind the last one is all zeros read from clamped addresses): one basic
+    // block per iteration keeps the accumulators in place across the loop
+    load_global<TRANS_B>(d, row0, col0, k0 + BK, kend, tid, pf);
+    __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of, and its first use behind, the MFMA block
+    const double* as = smem + cur * STAGE + wm * 64 + l16;
+    const double* bs = smem + cur * STAGE + BK * BM + wn * 64 + l16;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 4) {
       double a[4], b[4];
@@ -134,28 +154,42 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (more) store_lds<TRANS_B>(As[cur ^ 1], Bs[cur ^ 1], tid, pf);
+    __builtin_amdgcn_sched_barrier(0);
+    store_lds<TRANS_B>(smem + (cur ^ 1) * STAGE, smem + (cur ^ 1) * STAGE + BK * BM, tid, pf);
     __syncthreads();
     cur ^= 1;
   }
 
   // Epilogue.  Accumulator register v of lane l holds C[4 * v + l / 16][l % 16] of its 16 x 16 tile.
+  // The old values of C are fetched 16 at a time (clamped addresses, no branches) before any store, so
+  // that the read-modify-write costs one memory round trip per 16 rows instead of one per element.
   const double alpha = d.alpha, beta = d.beta;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
+    double cold[4][4];
+    if (beta != 0.0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = min(row0 + wm * 64 + i * 16 + 4 * v + lk, d.M - 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int col = min(col0 + wn * 64 + j * 16 + l16, d.N - 1);
+          cold[v][j] = d.C[(int64_t)row * d.ldc + col];
+        }
+      }
+    }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int row = row0 + wm * 64 + i * 16 + 4 * v + lk;
-      if (row >= d.M) continue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int col = col0 + wn * 64 + j * 16 + l16;
-        if (col >= d.N) continue;
         double r = alpha * acc[i][j][v];
-        double* c = d.C + (int64_t)row * d.ldc + col;
-        if (beta != 0.0) r += beta * (*c);
-        *c = r;
-        if (d.C2) d.C2[(int64_t)row * d.ldc2 + col] = r;
+        if (beta != 0.0) r += beta * cold[v][j];
+        if (row < d.M && col < d.N) {
+          d.C[(int64_t)row * d.ldc + col] = r;
+          if (d.C2) d.C2[(int64_t)row * d.ldc2 + col] = r;
+        }
       }
     }
   }
@@ -178,6 +212,8 @@ constexpr size_t kSmemBytes = size_t(2) * (BK * BM + BK * BN) * sizeof(double);
 
 slim_status check_desc(slim_ctx* ctx, const slim_gemm_desc& d) {
   SLIM_REQUIRE(ctx, d.M >= 0 && d.N >= 0 && d.K >= 0, "dgemm: negative size");
+  if (d.M == 0 || d.N == 0) return SLIM_OK;
+  SLIM_REQUIRE(ctx, d.K >= 2, "dgemm: K must be at least 2");
   SLIM_REQUIRE(ctx, (d.K % 2) == 0 && (d.N % 2) == 0, "dgemm: K and N must be even (K=%d N=%d)", d.K, d.N);
   SLIM_REQUIRE(ctx, (d.lda % 2) == 0 && (d.ldb % 2) == 0 && (d.ldc % 2) == 0, "dgemm: odd leading dimension");
   SLIM_REQUIRE(ctx, slim_aligned16(d.A) && slim_aligned16(d.B) && slim_aligned16(d.C), "dgemm: misaligned pointer");

@@ -48,20 +48,26 @@ __device__ __forceinline__ void decode_tile(int t, int& bi, int& bj) {
   bi = t - j * (j + 1) / 2;
 }
 
-// 8 consecutive 16-bit elements of row `row` starting at token k; zero outside the matrix / the chunk.
-__device__ __forceinline__ uint4 load_chunk(const GramArgs& a, int row, int64_t k, int64_t kend) {
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (row >= a.m || k >= kend) return v;
-  const uint16_t* p = a.X + (int64_t)row * a.ldx + k;
-  if (k + 8 <= kend) return *reinterpret_cast<const uint4*>(p);
-  uint16_t tmp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int e = 0; e < 8; ++e)
-    if (k + e < kend) tmp[e] = p[e];
-  v.x = tmp[0] | ((uint32_t)tmp[1] << 16);
-  v.y = tmp[2] | ((uint32_t)tmp[3] << 16);
-  v.z = tmp[4] | ((uint32_t)tmp[5] << 16);
-  v.w = tmp[6] | ((uint32_t)tmp[7] << 16);
-  return v;
+// 8 consecutive 16-bit elements of one row starting at token k, read branch-free from a clamped (valid)
+// address; `valid` tells whether they belong to the matrix and the chunk.  Rows are ldx >= t elements apart
+// with ldx a multiple of 8, so the 16 bytes never leave the row's storage.
+__device__ __forceinline__ uint4 load_chunk(const uint16_t* rowp, int64_t k, int64_t klast8) {
+  return *reinterpret_cast<const uint4*>(rowp + min(k, klast8));
+}
+
+// component-wise select (a ternary on the whole vector is lowered through scratch memory)
+__device__ __forceinline__ uint4 keep_if(bool ok, uint4 v) {
+  return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
+// zero the elements at positions >= nvalid (0..8) of a chunk
+__device__ __forceinline__ uint4 mask_chunk(uint4 v, int nvalid) {
+  auto keep = [&](uint32_t w, int e0) -> uint32_t {
+    const uint32_t lo = (e0 < nvalid) ? 0x0000ffffu : 0u;
+    const uint32_t hi = (e0 + 1 < nvalid) ? 0xffff0000u : 0u;
+    return w & (lo | hi);
+  };
+  return make_uint4(keep(v.x, 0), keep(v.y, 2), keep(v.z, 4), keep(v.w, 6));
 }
 
 template <bool BF16>
@@ -75,7 +81,7 @@ __device__ __forceinline__ float16v mfma(const uint4& a, const uint4& b, float16
   }
 }
 
-template <bool BF16>
+template <bool BF16, bool RAGGED>
 __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -86,6 +92,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = (int64_t)split * a.kchunk;
   const int64_t kend = min(a.t, kbeg + a.kchunk);
+  const int64_t klast8 = ((a.t - 1) / 8) * 8;   // start of the last (possibly partial) 8-token chunk
 
   // stage s: A slab at smem + s * STAGE, B slab TM * LDS_STRIDE behind it
   constexpr int STAGE = 2 * TM * LDS_STRIDE;
@@ -98,36 +105,56 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // thread -> chunk (row r0 + 32 c, 16-byte column ch) of both operand slabs, c = 0 .. CHUNKS-1
+  const int r0 = tid >> 3, ch = tid & 7;
+  const uint16_t* pa_row[CHUNKS];
+  const uint16_t* pb_row[CHUNKS];
+  unsigned va = 0, vb = 0;   // bit c: the row exists
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    const int ra = rowA0 + r0 + 32 * c, rb = rowB0 + r0 + 32 * c;
+    pa_row[c] = a.X + (int64_t)min(ra, a.m - 1) * a.ldx;
+    pb_row[c] = a.X + (int64_t)min(rb, a.m - 1) * a.ldx;
+    va |= (ra < a.m) ? (1u << c) : 0u;
+    vb |= (rb < a.m) ? (1u << c) : 0u;
+  }
+
   uint4 pa[CHUNKS], pb[CHUNKS];
   auto fetch = [&](int64_t k0) {
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const int id = c * NTHREADS + tid;
-      const int r = id >> 3, ch = id & 7;
-      pa[c] = load_chunk(a, rowA0 + r, k0 + ch * 8, kend);
-      pb[c] = load_chunk(a, rowB0 + r, k0 + ch * 8, kend);
+      pa[c] = load_chunk(pa_row[c], k0 + ch * 8, klast8);
+      pb[c] = load_chunk(pb_row[c], k0 + ch * 8, klast8);
     }
   };
-  auto stash = [&](uint16_t* as, uint16_t* bs) {
+  // writes the fetched slab (tokens k0 ..) to LDS, zeroing what lies outside the matrix or the token range
+  auto stash = [&](uint16_t* as, uint16_t* bs, int64_t k0) {
+    const int64_t k = k0 + ch * 8;
+    const int nvalid = (int)max((int64_t)0, min((int64_t)8, kend - k));
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
-      const int id = c * NTHREADS + tid;
-      const int r = id >> 3, ch = id & 7;
-      *reinterpret_cast<uint4*>(as + r * LDS_STRIDE + ch * 8) = pa[c];
-      *reinterpret_cast<uint4*>(bs + r * LDS_STRIDE + ch * 8) = pb[c];
+      uint4 xa = pa[c], xb = pb[c];
+      if (RAGGED) {
+        xa = mask_chunk(xa, ((va >> c) & 1u) ? nvalid : 0);
+        xb = mask_chunk(xb, ((vb >> c) & 1u) ? nvalid : 0);
+      } else {
+        xa = keep_if(((va >> c) & 1u) && nvalid == 8, xa);
+        xb = keep_if(((vb >> c) & 1u) && nvalid == 8, xb);
+      }
+      *reinterpret_cast<uint4*>(as + (r0 + 32 * c) * LDS_STRIDE + ch * 8) = xa;
+      *reinterpret_cast<uint4*>(bs + (r0 + 32 * c) * LDS_STRIDE + ch * 8) = xb;
     }
   };
 
   int cur = 0;
-  if (kbeg < kend) {
-    fetch(kbeg);
-    stash(smem, smem + TM * LDS_STRIDE);
-  }
+  fetch(kbeg);
+  stash(smem, smem + TM * LDS_STRIDE, kbeg);
   __syncthreads();
   const int l32 = lane & 31, lh = lane >> 5;
   for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
-    const bool more = k0 + BK < kend;
-    if (more) fetch(k0 + BK);
+    // unconditional: behind the last slab the fetch reads clamped addresses and the stash writes zeros
+    fetch(k0 + BK);
+    __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of, and its first use behind, the MFMA block
     const uint16_t* as = smem + cur * STAGE + (wm * 128 + l32) * LDS_STRIDE + lh * 8;
     const uint16_t* bs = smem + cur * STAGE + TM * LDS_STRIDE + (wn * 128 + l32) * LDS_STRIDE + lh * 8;
 #pragma unroll
@@ -142,7 +169,8 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = mfma<BF16>(fa[i], fb[j], acc[i][j]);
     }
-    if (more) stash(smem + (cur ^ 1) * STAGE, smem + (cur ^ 1) * STAGE + TM * LDS_STRIDE);
+    __builtin_amdgcn_sched_barrier(0);
+    stash(smem + (cur ^ 1) * STAGE, smem + (cur ^ 1) * STAGE + TM * LDS_STRIDE, k0 + BK);
     __syncthreads();
     cur ^= 1;
   }
@@ -216,18 +244,29 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.S = S;
   a.P = static_cast<float*>(slim_ws_alloc(ctx, pbytes));
 
+  const bool ragged = (t_c % 8) != 0;
+  const void* variants[4] = {reinterpret_cast<const void*>(gram_kernel<false, false>),
+                             reinterpret_cast<const void*>(gram_kernel<false, true>),
+                             reinterpret_cast<const void*>(gram_kernel<true, false>),
+                             reinterpret_cast<const void*>(gram_kernel<true, true>)};
   static bool attr_done = false;
   if (!attr_done) {
-    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gram_kernel<false>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
-    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gram_kernel<true>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
+    for (const void* f : variants)
+      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
     attr_done = true;
   }
-  if (x_dtype == SLIM_BF16)
-    SLIM_LAUNCH(ctx, "gram_mfma_bf16", gram_kernel<true>, dim3(tiles * S), dim3(NTHREADS), kSmemBytes, a);
-  else
-    SLIM_LAUNCH(ctx, "gram_mfma_f16", gram_kernel<false>, dim3(tiles * S), dim3(NTHREADS), kSmemBytes, a);
+  const dim3 grid(tiles * S), block(NTHREADS);
+  if (x_dtype == SLIM_BF16) {
+    if (ragged)
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
+    else
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
+  } else {
+    if (ragged)
+      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
+    else
+      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
+  }
   SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, TM / 4), dim3(256), 0, a.P, S, m, G, ldg);
   *n_tokens += t_c;
   return SLIM_OK;

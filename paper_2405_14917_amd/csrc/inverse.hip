@@ -19,7 +19,6 @@
 namespace {
 
 constexpr int NB = 64;          // diagonal block
-constexpr int LDA = NB + 1;     // LDS row stride of the block being factored
 
 // mean of the diagonal of H = s * G, then lambda; single workgroup, fixed order
 __global__ __launch_bounds__(256) void damp_lambda(const float* __restrict__ G, int64_t ldg, int m, double s,
@@ -58,63 +57,112 @@ __global__ __launch_bounds__(256) void zero_matrix(double* __restrict__ A, int64
   if (c < m) A[(int64_t)blockIdx.y * lda + c] = 0.0;
 }
 
-// One workgroup factors the nbk x nbk diagonal block at A (upper triangle valid) as R R^T with R upper
-// triangular, from the last column to the first, writes R back (zero below the diagonal) and its inverse V
-// into Vout.  A non-positive pivot is recorded in flag[0] (1-based global column) and replaced by 1.
-__global__ __launch_bounds__(256) void chol_diag(double* __restrict__ A, int64_t lda, int nbk, double* __restrict__ Vout,
-                                                 int64_t ldv, int* __restrict__ flag, int col_base) {
-  extern __shared__ __align__(16) double sm[];
-  double* a = sm;               // [NB][LDA]
-  double* b = sm + NB * LDA;    // [NB][LDA]
-  const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    const int i = idx >> 6, l = idx & 63;
-    double v = (i == l) ? 1.0 : 0.0;
-    if (i < nbk && l < nbk) v = (l >= i) ? A[(int64_t)i * lda + l] : 0.0;
-    a[i * LDA + l] = v;
-    b[i * LDA + l] = (i == l) ? 1.0 : 0.0;
+// 1 / x to full double precision for positive finite x: hardware estimate plus two Newton steps
+__device__ __forceinline__ double fast_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = fma(fma(-x, r, 1.0), r, r);
+  r = fma(fma(-x, r, 1.0), r, r);
+  return r;
+}
+
+// One workgroup (16 wavefronts) factors the nbk x nbk diagonal block at A (upper triangle valid) as R R^T
+// with R upper triangular, from the last column to the first, writes R back (zero below the diagonal) and
+// its inverse V into Vout.  A non-positive pivot is recorded in flag[0] (1-based global column) and
+// replaced by 1.
+//
+// A lone wavefront issues roughly one instruction every 8 cycles on this chip, so the kernel is built to
+// execute few instructions per elimination step: lane = row, wavefront w owns columns w, w+16, w+32, w+48
+// in four registers.  The pivot column therefore sits in ONE register of ONE wavefront and is broadcast
+// with a single 64-lane LDS store; which columns still take part in a step is known statically (register
+// index) or per wavefront (scalar), never per lane.  Entries below the diagonal are never read.
+__global__ __launch_bounds__(1024) void chol_diag(double* __restrict__ A, int64_t lda, int nbk, double* __restrict__ Vout,
+                                                  int64_t ldv, int* __restrict__ flag, int col_base) {
+  constexpr int LD = NB + 1;
+  __shared__ double Rs[NB * LD];       // the block (row-major), later R, later V
+  __shared__ double cb[2][NB];         // broadcast column, double buffered
+  __shared__ double diag[NB], rdiag[NB];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  // coalesced load (lane = column), identity padding of a ragged block
+  for (int r = w; r < NB; r += 16) {
+    double v = (r == lane) ? 1.0 : 0.0;
+    if (r < nbk && lane < nbk) v = (lane >= r) ? A[(int64_t)r * lda + lane] : 0.0;
+    Rs[r * LD + lane] = v;
   }
   __syncthreads();
-  // factorisation: after step j, column j holds R[:, j] * R[j][j] (scaled at the end)
-  for (int j = NB - 1; j >= 0; --j) {
-    double piv = a[j * LDA + j];
-    if (!(piv > 0.0)) {
-      if (tid == 0 && j < nbk && flag[0] == 0) flag[0] = col_base + j + 1;
-      piv = 1.0;
+  double a[4], b[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    a[q] = Rs[lane * LD + w + 16 * q];
+    b[q] = (lane == w + 16 * q) ? 1.0 : 0.0;
+  }
+  // ---- factorisation: after step j, column j holds R[:, j] * R[j][j] (scaled afterwards)
+#pragma unroll
+  for (int qj = 3; qj >= 0; --qj) {
+    for (int wj = 15; wj >= 0; --wj) {
+      const int j = 16 * qj + wj;
+      double* c = cb[j & 1];
+      if (w == wj) c[lane] = a[qj];
+      __syncthreads();
+      double piv = c[j];
+      if (!(piv > 0.0)) {                                 // uniform over the workgroup, rare
+        if (tid == 0 && j < nbk && flag[0] == 0) flag[0] = col_base + j + 1;
+        piv = 1.0;
+        if (w == wj && lane == j) a[qj] = 1.0;            // keep the sanitised pivot for the scaling pass
+      }
+      const double s = c[lane] * fast_rcp(piv);           // a[i][j] / pivot for this lane's row
+      // columns of registers below qj are all left of j; register qj itself only in wavefronts left of wj
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q < qj) a[q] -= s * c[w + 16 * q];
+      }
+      if (w < wj) a[qj] -= s * c[w + 16 * qj];
     }
-    const double inv = 1.0 / piv;
-    if (tx < j) {
-      const double alj = a[tx * LDA + j] * inv;
-      for (int i = ty; i <= tx; i += 4) a[i * LDA + tx] -= a[i * LDA + j] * alj;
+  }
+  // ---- scale: R[i][j] = a[i][j] / sqrt(a[j][j]); zeros below the diagonal; R goes to LDS
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (lane == w + 16 * q) {
+      const double d = sqrt(a[q]);
+      diag[lane] = d;
+      rdiag[lane] = 1.0 / d;
     }
-    __syncthreads();
-    // nothing reads a[j][j] again before the scaling pass: keep the sanitised pivot for it
-    if (tid == 0 && !(a[j * LDA + j] > 0.0)) a[j * LDA + j] = 1.0;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int cq = w + 16 * q;
+    a[q] = (lane < cq) ? a[q] * rdiag[cq] : ((lane == cq) ? diag[cq] : 0.0);
+    Rs[lane * LD + cq] = a[q];
   }
   __syncthreads();
-  // scale: R[i][j] = a[i][j] / sqrt(a[j][j])
-  {
-    const double d = sqrt(a[tx * LDA + tx]);
-    __syncthreads();
-    for (int i = ty; i <= tx; i += 4) a[i * LDA + tx] = (i == tx) ? d : a[i * LDA + tx] / d;
-    __syncthreads();
-  }
-  // inverse by back substitution on all columns at once: R V = I
-  for (int i = NB - 1; i > 0; --i) {
-    const double rinv = 1.0 / a[i * LDA + i];
-    if (tx >= i) {
-      const double v = b[i * LDA + tx] * rinv;
-      for (int ip = ty; ip < i; ip += 4) b[ip * LDA + tx] -= a[ip * LDA + i] * v;
+  for (int r = w; r < NB; r += 16)
+    if (r < nbk && lane < nbk) A[(int64_t)r * lda + lane] = Rs[r * LD + lane];
+  // ---- inverse: V R = I, columns from left to right.  Column c of V is final once the columns left of it
+  //      have been eliminated; it is broadcast and subtracted from the columns to its right.
+#pragma unroll
+  for (int qc = 0; qc < 4; ++qc) {
+    for (int wc = 0; wc < 16; ++wc) {
+      const int cc = 16 * qc + wc;
+      double* c = cb[cc & 1];
+      if (w == wc) {
+        b[qc] *= rdiag[cc];
+        c[lane] = b[qc];
+      }
+      __syncthreads();
+      const double v = c[lane];
+      const double* rrow = Rs + cc * LD;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q > qc) b[q] -= v * rrow[w + 16 * q];
+      }
+      if (w > wc) b[qc] -= v * rrow[w + 16 * qc];
     }
-    __syncthreads();
   }
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    const int i = idx >> 6, l = idx & 63;
-    if (i < nbk && l < nbk) {
-      A[(int64_t)i * lda + l] = (l >= i) ? a[i * LDA + l] : 0.0;
-      Vout[(int64_t)i * ldv + l] = (l >= i) ? b[i * LDA + l] / a[i * LDA + i] : 0.0;
-    }
-  }
+  __syncthreads();   // every wavefront is done reading R from LDS
+#pragma unroll
+  for (int q = 0; q < 4; ++q) Rs[lane * LD + w + 16 * q] = b[q];
+  __syncthreads();
+  for (int r = w; r < NB; r += 16)
+    if (r < nbk && lane < nbk) Vout[(int64_t)r * ldv + lane] = (lane >= r) ? Rs[r * LD + lane] : 0.0;
 }
 
 // partial column sums of squares of the upper triangle of U: grid (ceil(m/64), parts); part p owns 256 rows
@@ -188,14 +236,6 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   SLIM_LAUNCH(ctx, "inv_widen", widen_damp, mgrid, dim3(256), 0, G, ldg, m, s, lam, A, lda);
   SLIM_LAUNCH(ctx, "inv_zero_u", zero_matrix, mgrid, dim3(256), 0, U, ldu, m);
 
-  static bool attr_done = false;
-  const size_t diag_smem = sizeof(double) * 2 * NB * LDA;
-  if (!attr_done) {
-    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_diag),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)diag_smem));
-    attr_done = true;
-  }
-
   // ---- descriptors of the triangular inverse (pairwise merging of inverted diagonal ranges), staged first so
   //      that no host synchronisation falls between the factorisation and the inverse
   for (int64_t sz = NB; sz < m; sz *= 2) {
@@ -263,7 +303,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   for (int blk = nblk - 1; blk >= 0; --blk) {
     const int j0 = blk * NB;
     const int nbk = std::min(NB, m - j0);
-    SLIM_LAUNCH(ctx, "inv_chol_diag", chol_diag, dim3(1), dim3(256), diag_smem, A + (int64_t)j0 * lda + j0, lda, nbk,
+    SLIM_LAUNCH(ctx, "inv_chol_diag", chol_diag, dim3(1), dim3(1024), 0, A + (int64_t)j0 * lda + j0, lda, nbk,
                 U + (int64_t)j0 * ldu + j0, ldu, flag, j0);
     if (j0 == 0) break;
     slim_gemm_desc d;

@@ -25,7 +25,7 @@ using namespace slimdev;
 
 constexpr int SQC_ROWS = 8;       // rows per workgroup in sqc_search
 constexpr int SQC_THREADS = 256;
-constexpr int STAT_ROWS = 64;     // rows per workgroup in block_stats
+constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
 constexpr int SWEEP_WAVES = 16;   // rows (= wavefronts) per workgroup in gptq_sweep
 
 // ------------------------------------------------------------------------------------------
@@ -212,11 +212,14 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
         L += o[j] * err * err;
       }
     } else {
+      // The loss is continuous across a rounding tie (both neighbouring codes are equally far), so the
+      // candidate losses may use a reciprocal; the codes themselves are decided with a true division.
       const double delta = tc * rp[r * 4 + 0];
+      const double rdelta = 1.0 / delta;
       const double z = rp[r * 4 + 1];
       for (int j = 0; j < beta; ++j) {
         const double v = w[j];
-        const double q = fmin(fmax(rint(v / delta) + z, 0.0), qmax);
+        const double q = fmin(fmax(rint(v * rdelta) + z, 0.0), qmax);
         const double err = v - delta * (q - z);
         L += o[j] * err * err;
       }
@@ -288,13 +291,15 @@ struct SweepArgs {
 
 template <int EPL>
 __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
-  extern __shared__ __align__(16) double Us[];   // [beta][beta]
+  extern __shared__ __align__(16) double Us[];   // [beta][beta], then [beta] reciprocals of the diagonal
   const int beta = a.beta;
+  double* rdiag = Us + beta * beta;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int idx = tid; idx < beta * beta; idx += SWEEP_WAVES * 64) {
     const int j = idx / beta, l = idx - j * beta;
     Us[idx] = (l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
   }
+  for (int j = tid; j < beta; j += SWEEP_WAVES * 64) rdiag[j] = 1.0 / a.U[(int64_t)j * a.ldu + j];
   __syncthreads();
   const int row = blockIdx.x * SWEEP_WAVES + wave;
   if (row >= a.n) return;
@@ -327,7 +332,7 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
         q = fmin(fmax(rint(wj / s) + z, 0.0), qmax);
       }
       const double what = s * (q - z);
-      const double e = (wj - what) / Us[j * beta + j];
+      const double e = (wj - what) * rdiag[j];   // the error is a continuous quantity: reciprocal is fine
       e2 += e * e;
       if (lane == jj) {
         ev[r] = e;
@@ -504,7 +509,7 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
 
-  const size_t sweep_smem = sizeof(double) * (size_t)beta * beta;
+  const size_t sweep_smem = sizeof(double) * ((size_t)beta * beta + beta);
   if (sweep_smem > 64 * 1024) {
     static bool done = false;
     st = allow_big_lds(ctx, gptq_sweep<2>, done);

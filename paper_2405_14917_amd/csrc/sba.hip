@@ -176,12 +176,13 @@ __global__ __launch_bounds__(256) void kl_partial(const double* __restrict__ Y, 
   }
 }
 
-// single workgroup: merges the row parts of every token, then sums the tokens in a fixed order
+// one thread per token: merges the row parts of its token; every workgroup of 256 tokens writes its sum
 __global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
-                                                   double* __restrict__ out) {
+                                                   double* __restrict__ block_sums) {
   __shared__ double red[256];
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   double acc = 0.0;
-  for (int64_t t = threadIdx.x; t < ts; t += 256) {
+  if (t < ts) {
     double My = -INFINITY, Mq = -INFINITY;
     for (int p = 0; p < parts; ++p) {
       const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ pa
       Zq += o[3] * sq;
     }
     // KL_t = sum_i P_i ((y_i - lse_y) - (q_i - lse_q)) = A / Zy - lse_y + lse_q
-    acc += A / Zy - (My + log(Zy)) + (Mq + log(Zq));
+    acc = A / Zy - (My + log(Zy)) + (Mq + log(Zq));
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -205,12 +206,20 @@ __global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ pa
     if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *out = red[0];
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
 }
 
-__global__ __launch_bounds__(256) void sba_finalize(const double* __restrict__ obj, int pmax, const int* __restrict__ order,
+// obj[p] = sum of the token-block sums of step p (fixed order); then the first minimum and its bit vector
+__global__ __launch_bounds__(256) void sba_finalize(const double* __restrict__ block_sums, int nblocks,
+                                                    double* __restrict__ obj, int pmax, const int* __restrict__ order,
                                                     int k, int N, uint8_t* __restrict__ bits, int* __restrict__ p_star) {
   __shared__ int best_p;
+  for (int p = threadIdx.x; p <= pmax; p += 256) {
+    double s = 0.0;
+    for (int w = 0; w < nblocks; ++w) s += block_sums[(int64_t)p * nblocks + w];
+    obj[p] = s;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int bp = 0;
     double bv = obj[0];
@@ -266,7 +275,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
   const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);
   const size_t bDesc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * pmax + 2));
-  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2));
+  const int kl_blocks = slim_cdiv(t_s, 256);
+  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
   const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(k + 1));
   slim_status st = slim_ws_reserve(ctx, 4 * bW + bX + 2 * bY + bPart + bDesc + bObj + bOrd + 256);
   if (st != SLIM_OK) return st;
@@ -280,6 +290,7 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   double* partial = static_cast<double*>(slim_ws_alloc(ctx, bPart));
   slim_gemm_desc* descs = static_cast<slim_gemm_desc*>(slim_ws_alloc(ctx, bDesc));
   double* obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
+  double* block_sums = obj + (pmax + 2);
   int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
   int* pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
 
@@ -319,7 +330,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
   for (int p = 0; p <= pmax; ++p) {
     SLIM_LAUNCH(ctx, "sba_kl_partial", kl_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
-    SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(1), dim3(256), 0, partial, parts, t_s, obj + p);
+    SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
+                block_sums + (int64_t)p * kl_blocks);
     if (p < pmax) {
       st = slim_dgemm_batched(ctx, "sba_update_dgemm", 0, descs + 2 * p, 1, n, (int)t_s);
       if (st != SLIM_OK) return st;
@@ -327,7 +339,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
       if (st != SLIM_OK) return st;
     }
   }
-  SLIM_LAUNCH(ctx, "sba_finalize", sba_finalize, dim3(1), dim3(256), 0, obj, pmax, order, k, N, bits, pstar_dev);
+  SLIM_LAUNCH(ctx, "sba_finalize", sba_finalize, dim3(1), dim3(256), 0, block_sums, kl_blocks, obj, pmax, order, k, N,
+              bits, pstar_dev);
 
   double* host_obj = reinterpret_cast<double*>(ctx->hpin);
   int* host_p = reinterpret_cast<int*>(ctx->hpin + sizeof(double) * (size_t)(pmax + 1));
