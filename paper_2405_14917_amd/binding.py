@@ -114,8 +114,12 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _need_cuda(*tensors):
     for t in tensors:
-        if t is not None and not t.is_cuda:
+        if t is None:
+            continue
+        if not t.is_cuda:
             raise ValueError("libslim takes device tensors")
+        if t.dim() >= 1 and t.stride(-1) != 1:
+            raise ValueError("libslim takes row-major tensors (last dimension contiguous)")
 
 
 class Slim:

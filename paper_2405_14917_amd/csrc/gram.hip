@@ -81,6 +81,91 @@ __device__ __forceinline__ float16v mfma(const uint4& a, const uint4& b, float16
   }
 }
 
+struct RowPtrs {
+  const uint16_t* a[CHUNKS];
+  const uint16_t* b[CHUNKS];
+  unsigned va, vb;   // bit c: row of chunk c exists
+};
+
+struct Slab {
+  uint4 a[CHUNKS], b[CHUNKS];
+};
+
+__device__ __forceinline__ void fetch_slab(Slab& s, const RowPtrs& rp, int64_t k, int64_t klast8) {
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    s.a[c] = load_chunk(rp.a[c], k, klast8);
+    s.b[c] = load_chunk(rp.b[c], k, klast8);
+  }
+}
+
+// writes a fetched slab to LDS, zeroing what lies outside the matrix or the token range [.., kend)
+template <bool RAGGED>
+__device__ __forceinline__ void stash_slab(const Slab& s, const RowPtrs& rp, uint16_t* as, uint16_t* bs, int64_t k,
+                                           int64_t kend) {
+  const int nvalid = (int)max((int64_t)0, min((int64_t)8, kend - k));
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    uint4 xa = s.a[c], xb = s.b[c];
+    if (RAGGED) {
+      xa = mask_chunk(xa, ((rp.va >> c) & 1u) ? nvalid : 0);
+      xb = mask_chunk(xb, ((rp.vb >> c) & 1u) ? nvalid : 0);
+    } else {
+      xa = keep_if(((rp.va >> c) & 1u) && nvalid == 8, xa);
+      xb = keep_if(((rp.vb >> c) & 1u) && nvalid == 8, xb);
+    }
+    *reinterpret_cast<uint4*>(as + 32 * c * LDS_STRIDE) = xa;
+    *reinterpret_cast<uint4*>(bs + 32 * c * LDS_STRIDE) = xb;
+  }
+}
+
+struct Frags {
+  uint4 a[4], b[4];
+};
+
+__device__ __forceinline__ void load_frags(Frags& f, const uint16_t* as, const uint16_t* bs, int kk) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const uint4*>(as + i * 32 * LDS_STRIDE + kk);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const uint4*>(bs + j * 32 * LDS_STRIDE + kk);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void mfma_block(float16v (&acc)[4][4], const Frags& f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = mfma<BF16>(f.a[i], f.b[j], acc[i][j]);
+}
+
+// One slab (64 tokens = 4 K steps of 16).  The operand fragments of step kk + 1 are read from LDS into a
+// second register set while the 16 MFMAs of step kk run, so the matrix pipe does not wait for LDS.  Left
+// alone, the compiler sinks every read next to its use and the pipe idles one LDS round trip per four MFMAs.
+template <bool BF16>
+__device__ __forceinline__ void multiply_slab(float16v (&acc)[4][4], const uint16_t* as, const uint16_t* bs) {
+  Frags f0, f1;
+  load_frags(f0, as, bs, 0);
+  load_frags(f1, as, bs, 16);
+  mfma_block<BF16>(acc, f0);
+  load_frags(f0, as, bs, 32);
+  mfma_block<BF16>(acc, f1);
+  load_frags(f1, as, bs, 48);
+  mfma_block<BF16>(acc, f0);
+  mfma_block<BF16>(acc, f1);
+  // requested issue order inside this scheduling region: 16 LDS reads, then 16 MFMAs with the next 8 reads
+  // spread between them, and so on (mask 0x100 = LDS read, 0x008 = MFMA)
+  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 32, 0);
+}
+
 template <bool BF16, bool RAGGED>
 __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
@@ -94,7 +179,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   const int64_t kend = min(a.t, kbeg + a.kchunk);
   const int64_t klast8 = ((a.t - 1) / 8) * 8;   // start of the last (possibly partial) 8-token chunk
 
-  // stage s: A slab at smem + s * STAGE, B slab TM * LDS_STRIDE behind it
+  // LDS stage s: A slab at smem + s * STAGE, B slab TM * LDS_STRIDE behind it
   constexpr int STAGE = 2 * TM * LDS_STRIDE;
 
   float16v acc[4][4];
@@ -107,72 +192,41 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
 
   // thread -> chunk (row r0 + 32 c, 16-byte column ch) of both operand slabs, c = 0 .. CHUNKS-1
   const int r0 = tid >> 3, ch = tid & 7;
-  const uint16_t* pa_row[CHUNKS];
-  const uint16_t* pb_row[CHUNKS];
-  unsigned va = 0, vb = 0;   // bit c: the row exists
+  RowPtrs rp;
+  rp.va = 0;
+  rp.vb = 0;
 #pragma unroll
   for (int c = 0; c < CHUNKS; ++c) {
     const int ra = rowA0 + r0 + 32 * c, rb = rowB0 + r0 + 32 * c;
-    pa_row[c] = a.X + (int64_t)min(ra, a.m - 1) * a.ldx;
-    pb_row[c] = a.X + (int64_t)min(rb, a.m - 1) * a.ldx;
-    va |= (ra < a.m) ? (1u << c) : 0u;
-    vb |= (rb < a.m) ? (1u << c) : 0u;
+    rp.a[c] = a.X + (int64_t)min(ra, a.m - 1) * a.ldx;
+    rp.b[c] = a.X + (int64_t)min(rb, a.m - 1) * a.ldx;
+    rp.va |= (ra < a.m) ? (1u << c) : 0u;
+    rp.vb |= (rb < a.m) ? (1u << c) : 0u;
   }
-
-  uint4 pa[CHUNKS], pb[CHUNKS];
-  auto fetch = [&](int64_t k0) {
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      pa[c] = load_chunk(pa_row[c], k0 + ch * 8, klast8);
-      pb[c] = load_chunk(pb_row[c], k0 + ch * 8, klast8);
-    }
-  };
-  // writes the fetched slab (tokens k0 ..) to LDS, zeroing what lies outside the matrix or the token range
-  auto stash = [&](uint16_t* as, uint16_t* bs, int64_t k0) {
-    const int64_t k = k0 + ch * 8;
-    const int nvalid = (int)max((int64_t)0, min((int64_t)8, kend - k));
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      uint4 xa = pa[c], xb = pb[c];
-      if (RAGGED) {
-        xa = mask_chunk(xa, ((va >> c) & 1u) ? nvalid : 0);
-        xb = mask_chunk(xb, ((vb >> c) & 1u) ? nvalid : 0);
-      } else {
-        xa = keep_if(((va >> c) & 1u) && nvalid == 8, xa);
-        xb = keep_if(((vb >> c) & 1u) && nvalid == 8, xb);
-      }
-      *reinterpret_cast<uint4*>(as + (r0 + 32 * c) * LDS_STRIDE + ch * 8) = xa;
-      *reinterpret_cast<uint4*>(bs + (r0 + 32 * c) * LDS_STRIDE + ch * 8) = xb;
-    }
-  };
-
-  int cur = 0;
-  fetch(kbeg);
-  stash(smem, smem + TM * LDS_STRIDE, kbeg);
-  __syncthreads();
+  // this thread's store position inside an LDS slab, and its operand read positions
+  const int st_off = r0 * LDS_STRIDE + ch * 8;
   const int l32 = lane & 31, lh = lane >> 5;
+  const int rdA = (wm * 128 + l32) * LDS_STRIDE + lh * 8;
+  const int rdB = TM * LDS_STRIDE + (wn * 128 + l32) * LDS_STRIDE + lh * 8;
+  const int64_t kch = ch * 8;
+
+  // The slab fetched into registers in iteration s is written to the other LDS stage at the end of the
+  // iteration and multiplied in iteration s + 1.  The fetch behind the last slab reads clamped addresses
+  // and is stashed as zeros.
+  Slab sl;
+  fetch_slab(sl, rp, kbeg + kch, klast8);
+  stash_slab<RAGGED>(sl, rp, smem + st_off, smem + TM * LDS_STRIDE + st_off, kbeg + kch, kend);
+  __syncthreads();
+  int cur = 0;
   for (int64_t k0 = kbeg; k0 < kend; k0 += BK) {
-    // unconditional: behind the last slab the fetch reads clamped addresses and the stash writes zeros
-    fetch(k0 + BK);
-    __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of, and its first use behind, the MFMA block
-    const uint16_t* as = smem + cur * STAGE + (wm * 128 + l32) * LDS_STRIDE + lh * 8;
-    const uint16_t* bs = smem + cur * STAGE + TM * LDS_STRIDE + (wn * 128 + l32) * LDS_STRIDE + lh * 8;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      uint4 fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const uint4*>(as + i * 32 * LDS_STRIDE + kk);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const uint4*>(bs + j * 32 * LDS_STRIDE + kk);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma<BF16>(fa[i], fb[j], acc[i][j]);
-    }
+    fetch_slab(sl, rp, k0 + BK + kch, klast8);
+    __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of, and the stash behind, the MFMA block
+    multiply_slab<BF16>(acc, smem + cur * STAGE + rdA, smem + cur * STAGE + rdB);
     __builtin_amdgcn_sched_barrier(0);
-    stash(smem + (cur ^ 1) * STAGE, smem + (cur ^ 1) * STAGE + TM * LDS_STRIDE, k0 + BK);
-    __syncthreads();
     cur ^= 1;
+    stash_slab<RAGGED>(sl, rp, smem + cur * STAGE + st_off, smem + cur * STAGE + TM * LDS_STRIDE + st_off,
+                       k0 + BK + kch, kend);
+    __syncthreads();
   }
 
   // Accumulator register v of lane l holds C[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32] of its 32 x 32 tile.
