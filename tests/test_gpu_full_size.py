@@ -1,0 +1,161 @@
+"""Parity at BASELINE config 2 (LLaMA-7B q_proj shape, 4096 x 4096, 131072 tokens), in the launch
+configuration bench.py times: same generators, same call sequence, same sizes.
+
+The oracle cannot run the whole 4096 x 4096 x 131072 pass in seconds, so each stage is checked on
+outputs the oracle can compute one by one (sampled Gram rows, sampled SBA candidates, sampled rows of the
+sweep in the row-independent mask scope) or through identities that hold at any size.  Stage inputs that
+are results of an earlier stage are computed by the ORACLE (from a token subset where the full set would
+take minutes), never taken from the HIP path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as orc
+from paper_2405_14917_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+CFG = synth.CONFIGS["C2"]
+MARGIN = 1e-6
+
+
+@pytest.fixture(scope="module")
+def slim():
+    from paper_2405_14917_amd import binding
+    s = binding.Slim("cuda:0")
+    yield s
+    s.close()
+
+
+@pytest.fixture(scope="module")
+def layer():
+    """W, X on the host (fp16) and on the device, plus the oracle's inverse for a token subset."""
+    W = synth.make_weights(CFG)
+    chunks = [synth.activation_chunk(CFG, c) for c in range(synth.n_chunks(CFG))]
+    Xd = torch.empty((CFG.m, CFG.t), dtype=torch.float16, device="cuda")
+    for c, xc in enumerate(chunks):
+        Xd[:, c * synth.CHUNK_TOKENS:c * synth.CHUNK_TOKENS + xc.shape[1]] = torch.from_numpy(xc).cuda()
+    # oracle-side second-order information from the first chunk only (seconds instead of minutes)
+    G0 = np.zeros((CFG.m, CFG.m))
+    orc.gram_accumulate(G0, chunks[0])
+    G32 = G0.astype(np.float32)
+    G32 = np.maximum(G32, G32.T)
+    t0 = chunks[0].shape[1]
+    U, d, lam = orc.hessian_inverse(G32.astype(np.float64), t0, CFG.percdamp)
+    _, grp, _ = orc.salience(W, d, CFG.beta)
+    return dict(W=W, chunks=chunks, Wd=torch.from_numpy(W).cuda(), Xd=Xd, G32=G32, t0=t0, U=U, d=d, lam=lam, grp=grp)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def test_gram_sampled_rows(slim, layer):
+    G = torch.zeros((CFG.m, CFG.m), dtype=torch.float32, device="cuda")
+    nt = slim.hessian_accumulate(layer["Xd"], G, 0)          # one call over all tokens, as bench.py does
+    assert nt == CFG.t
+    Gg = host(G).astype(np.float64)
+    assert np.array_equal(Gg, Gg.T)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([rng.integers(0, CFG.m, 12), synth.outlier_activation_channels(CFG)[:4]]))
+    ref = np.zeros((rows.size, CFG.m))
+    diag = np.zeros(CFG.m)
+    for xc in layer["chunks"]:
+        x = xc.astype(np.float64)
+        ref += x[rows] @ x.T
+        diag += np.einsum("ij,ij->i", x, x)
+    assert np.allclose(np.diag(Gg), diag, rtol=2e-5)
+    scale = np.sqrt(np.outer(diag[rows], diag))
+    err = np.max(np.abs(Gg[rows] - ref) / scale)
+    print("full-size gram: max scaled error on %d sampled rows %.3e" % (rows.size, err))
+    assert err < 2e-6 * np.sqrt(CFG.t / 512)
+
+
+def test_inverse_full_size(slim, layer):
+    U, d = slim.hessian_inverse(dev(layer["G32"]), layer["t0"], CFG.percdamp)
+    U, d = host(U), host(d)
+    assert np.all(np.tril(U, -1) == 0.0)
+    assert np.linalg.norm(U - layer["U"]) / np.linalg.norm(layer["U"]) < 1e-9
+    assert np.allclose(d, layer["d"], rtol=1e-8)
+
+
+def test_salience_full_size(slim, layer):
+    col, grp, _ = slim.salience(layer["Wd"], dev(layer["d"]), CFG.beta)
+    assert np.allclose(host(grp), layer["grp"], rtol=1e-11)
+
+
+def test_sba_sampled_candidates(slim, layer):
+    Xs_d = layer["Xd"][:, :2048]
+    bits, p_star, obj = slim.sba_allocate(layer["Wd"], dev(layer["grp"]), CFG.beta, CFG.N, Xs_d)
+    k = CFG.k
+    assert obj.shape == (k // 2 + 1,)
+    W = layer["W"].astype(np.float64)
+    Xs = layer["chunks"][0][:, :2048].astype(np.float64)
+    order = np.argsort(layer["grp"], kind="stable")
+    Y = Xs.T @ W.T
+    for p in sorted({0, k // 4, p_star, k // 2}):
+        Wp = orc.rtn_fakequant_fast(W, orc.bits_for_p(order, k, CFG.N, p), CFG.beta)
+        ref = orc.softmax_kl(Y, Xs.T @ Wp.T)
+        assert obj[p] == pytest.approx(ref, rel=1e-9), "objective of candidate %d" % p
+    assert p_star == int(np.argmin(obj))
+    gap = np.sort(obj)[1] - np.sort(obj)[0]
+    if gap > MARGIN * obj.min():
+        assert np.array_equal(host(bits), orc.bits_for_p(order, k, CFG.N, p_star))
+    b = host(bits).astype(int)
+    assert b.sum() == CFG.N * k and (b == CFG.N - 1).sum() == (b == CFG.N + 1).sum() == p_star
+
+
+def _alloc_bits():
+    k = CFG.k
+    bits = np.full(k, 2, dtype=np.uint8)
+    bits[[3, 9, 17, 30]] = 1
+    bits[[0, 12, 21, 27]] = 3
+    return bits
+
+
+def test_sweep_sampled_rows_and_identities(slim, layer):
+    from paper_2405_14917_amd import binding
+    bits = _alloc_bits()
+    Ud, W = dev(layer["U"]), layer["W"]
+    # (1) row-independent mask scope: the oracle reproduces sampled rows one by one
+    rows = np.random.default_rng(1).choice(CFG.n, 48, replace=False)
+    out = slim.gptq_quantize(layer["Wd"], Ud, dev(bits), CFG.beta, params=binding.make_params(mask_scope=orc.SCOPE_ROW),
+                             want_what=torch.float64)
+    ref = orc.gptq_quantize(W[rows], layer["U"], bits, CFG.beta, orc.tau_grid(), scope=orc.SCOPE_ROW)
+    ok = (ref["round_margin"].min(axis=1) > MARGIN) & (ref["sqc_margin"].min(axis=1) > MARGIN)
+    assert ok.mean() > 0.9
+    codes = host(out["codes"])[rows]
+    assert np.array_equal(codes[ok], ref["codes"][ok])
+    What = host(out["What"])[rows]
+    assert np.linalg.norm(What[ok] - ref["What"][ok]) / np.linalg.norm(ref["What"][ok]) < 1e-10
+    assert np.allclose(host(out["scale"])[rows][ok], ref["scale"][ok], rtol=1e-12)
+    # (2) default block-wide scope: identities that hold at any size
+    out = slim.gptq_quantize(layer["Wd"], Ud, dev(bits), CFG.beta, want_what=torch.float64, want_sum_e2=True)
+    codes, What = host(out["codes"]), host(out["What"])
+    scale, zero = host(out["scale"]), host(out["zero"])
+    assert codes.max() <= 7 and all(codes[:, g * 128:(g + 1) * 128].max() < 2 ** int(bits[g]) for g in range(CFG.k))
+    deq = np.repeat(scale, CFG.beta, axis=1) * (codes - np.repeat(zero, CFG.beta, axis=1))
+    assert np.allclose(What, deq, rtol=1e-15, atol=0)
+    Hd = 2.0 / layer["t0"] * layer["G32"].astype(np.float64) + layer["lam"] * np.eye(CFG.m)
+    dW = W.astype(np.float64) - What
+    assert host(out["sum_e2"])[0] == pytest.approx(float(np.sum((dW @ Hd) * dW)), rel=1e-7)
+    # the compensated result beats round-to-nearest on the same grids in the layer-output error
+    rtn = np.empty_like(What)
+    Wf = W.astype(np.float64)
+    for g in range(CFG.k):
+        s, z = scale[:, g:g + 1], zero[:, g:g + 1]
+        blk = Wf[:, g * 128:(g + 1) * 128]
+        q = (blk >= 0).astype(np.float64) if bits[g] == 1 else np.clip(np.rint(blk / s) + z, 0, 2 ** int(bits[g]) - 1)
+        rtn[:, g * 128:(g + 1) * 128] = s * (q - z)
+    G = layer["G32"].astype(np.float64)
+    assert orc.reconstruction_error(W, What, G) < orc.reconstruction_error(W, rtn, G)
+    # (3) packing of these codes, bit for bit
+    packed, gbits, row_off, m_star = slim.pack(out["codes"], dev(bits), CFG.beta)
+    po, go, ro, mo = orc.pack_fast(codes, bits, CFG.beta)
+    assert m_star == mo == CFG.m * CFG.N // 32
+    assert np.array_equal(host(row_off), ro) and np.array_equal(host(gbits).view(np.uint32), go)
+    assert np.array_equal(host(packed).view(np.uint32), po)
