@@ -246,6 +246,117 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   }
 }
 
+__device__ __forceinline__ void stash_plain(const Slab& s, uint16_t* as, uint16_t* bs) {
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    *reinterpret_cast<uint4*>(as + 32 * c * LDS_STRIDE) = s.a[c];
+    *reinterpret_cast<uint4*>(bs + 32 * c * LDS_STRIDE) = s.b[c];
+  }
+}
+
+// Interior fast path: every tile is complete (m a multiple of 256) and every split covers whole slabs, so
+// nothing is masked.  Addresses are a uniform base pointer that advances per slab plus constant 32-bit
+// lane offsets; one register stage; the whole iteration is ONE scheduling region in which the global loads
+// of the next slab, the LDS operand reads and the LDS writes are slotted between the 64 MFMAs (a wavefront
+// that is alone on its SIMD issues only about one instruction per 8 cycles, so anything issued outside the
+// shadow of the matrix pipe costs its full issue time).
+template <bool BF16>
+__global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
+  extern __shared__ __align__(16) uint16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int split = blockIdx.x % a.S;
+  int bi, bj;
+  decode_tile(blockIdx.x / a.S, bi, bj);
+  const int rowA0 = bi * TM, rowB0 = bj * TM;
+  const int64_t kbeg = (int64_t)split * a.kchunk;
+  const int64_t kend = min(a.t, kbeg + a.kchunk);
+  constexpr int STAGE = 2 * TM * LDS_STRIDE;
+  float16v acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int r0 = tid >> 3, ch = tid & 7;
+  unsigned off[CHUNKS];
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) off[c] = (unsigned)((int64_t)(r0 + 32 * c) * a.ldx * 2 + ch * 16);
+  const char* baseA = reinterpret_cast<const char*>(a.X + (int64_t)rowA0 * a.ldx + kbeg);
+  const char* baseB = reinterpret_cast<const char*>(a.X + (int64_t)rowB0 * a.ldx + kbeg);
+  const int st_off = r0 * LDS_STRIDE + ch * 8;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int rdA = (wm * 128 + l32) * LDS_STRIDE + lh * 8;
+  const int rdB = TM * LDS_STRIDE + (wn * 128 + l32) * LDS_STRIDE + lh * 8;
+  Slab sl;
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    sl.a[c] = *reinterpret_cast<const uint4*>(baseA + off[c]);
+    sl.b[c] = *reinterpret_cast<const uint4*>(baseB + off[c]);
+  }
+  stash_plain(sl, smem + st_off, smem + TM * LDS_STRIDE + st_off);
+  __syncthreads();
+  int cur = 0;
+  const int64_t nslab = (kend - kbeg) / BK;
+  for (int64_t it = 0; it < nslab; ++it) {
+    // the fetch behind the last slab re-reads the last slab (stays in bounds); its data is never multiplied
+    const int64_t adv = (it + 1 < nslab) ? BK * 2 : 0;
+    baseA += adv;
+    baseB += adv;
+    const uint16_t* as = smem + cur * STAGE + rdA;
+    const uint16_t* bs = smem + cur * STAGE + rdB;
+    uint16_t* was = smem + (cur ^ 1) * STAGE + st_off;
+    uint16_t* wbs = was + TM * LDS_STRIDE;
+    Frags f0, f1;
+    load_frags(f0, as, bs, 0);
+    load_frags(f1, as, bs, 16);
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      sl.a[c] = *reinterpret_cast<const uint4*>(baseA + off[c]);
+      sl.b[c] = *reinterpret_cast<const uint4*>(baseB + off[c]);
+    }
+    mfma_block<BF16>(acc, f0);
+    load_frags(f0, as, bs, 32);
+    mfma_block<BF16>(acc, f1);
+    load_frags(f1, as, bs, 48);
+    mfma_block<BF16>(acc, f0);
+    stash_plain(sl, was, wbs);
+    mfma_block<BF16>(acc, f1);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
+    __syncthreads();
+    cur ^= 1;
+  }
+  float* P = a.P + (int64_t)split * a.m * a.m;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = rowA0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int col = rowB0 + wn * 128 + j * 32 + l32;
+        P[(int64_t)row * a.m + col] = acc[i][j][v];
+      }
+    }
+  }
+}
+
 // G[i][j] += sum_s P[s][i][j] for every (i, j) of an upper tile pair; mirrored into the lower triangle.
 __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ P, int S, int m, float* __restrict__ G,
                                                    int64_t ldg) {
@@ -299,10 +410,14 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.P = static_cast<float*>(slim_ws_alloc(ctx, pbytes));
 
   const bool ragged = (t_c % 8) != 0;
-  const void* variants[4] = {reinterpret_cast<const void*>(gram_kernel<false, false>),
+  // fast path: complete tiles, whole slabs in every split, lane offsets inside 32 bits
+  const bool full = (m % TM == 0) && (t_c % BK == 0) && (kchunk * S == t_c) && ((int64_t)(TM - 1) * ldx * 2 + 128 < (int64_t(1) << 32));
+  const void* variants[6] = {reinterpret_cast<const void*>(gram_kernel<false, false>),
                              reinterpret_cast<const void*>(gram_kernel<false, true>),
                              reinterpret_cast<const void*>(gram_kernel<true, false>),
-                             reinterpret_cast<const void*>(gram_kernel<true, true>)};
+                             reinterpret_cast<const void*>(gram_kernel<true, true>),
+                             reinterpret_cast<const void*>(gram_kernel_full<false>),
+                             reinterpret_cast<const void*>(gram_kernel_full<true>)};
   static bool attr_done = false;
   if (!attr_done) {
     for (const void* f : variants)
@@ -311,12 +426,16 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   }
   const dim3 grid(tiles * S), block(NTHREADS);
   if (x_dtype == SLIM_BF16) {
-    if (ragged)
+    if (full)
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel_full<true>), grid, block, kSmemBytes, a);
+    else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
   } else {
-    if (ragged)
+    if (full)
+      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel_full<false>), grid, block, kSmemBytes, a);
+    else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
