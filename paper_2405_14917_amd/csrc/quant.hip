@@ -23,7 +23,7 @@ namespace {
 
 using namespace slimdev;
 
-constexpr int SQC_ROWS = 8;       // rows per workgroup in sqc_search
+constexpr int SQC_ROWS = 4;       // rows per workgroup in sqc_search
 constexpr int SQC_THREADS = 256;
 constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
 constexpr int SWEEP_WAVES = 16;   // rows (= wavefronts) per workgroup in gptq_sweep
@@ -206,23 +206,35 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
     double L = 0.0;
     if (sign_mode) {
       const double ta = tc * rp[r * 4 + 2];
-      for (int j = 0; j < beta; ++j) {
-        const double v = w[j];
-        const double err = v - (v >= 0.0 ? ta : -ta);
-        L += o[j] * err * err;
+      double L1 = 0.0;
+      for (int j = 0; j < beta; j += 2) {
+        const double v0 = w[j], v1 = w[j + 1];
+        const double e0 = v0 - (v0 >= 0.0 ? ta : -ta);
+        const double e1 = v1 - (v1 >= 0.0 ? ta : -ta);
+        L = fma(o[j] * e0, e0, L);
+        L1 = fma(o[j + 1] * e1, e1, L1);
       }
+      L += L1;
     } else {
       // The loss is continuous across a rounding tie (both neighbouring codes are equally far), so the
       // candidate losses may use a reciprocal; the codes themselves are decided with a true division.
       const double delta = tc * rp[r * 4 + 0];
       const double rdelta = 1.0 / delta;
       const double z = rp[r * 4 + 1];
-      for (int j = 0; j < beta; ++j) {
-        const double v = w[j];
-        const double q = fmin(fmax(rint(v * rdelta) + z, 0.0), qmax);
-        const double err = v - delta * (q - z);
-        L += o[j] * err * err;
+      // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), -z, qmax - z): one add and one subtract less per
+      // element; two accumulators shorten the dependent chain
+      const double lo = -z, hi = qmax - z;
+      double L1 = 0.0;
+      for (int j = 0; j < beta; j += 2) {
+        const double v0 = w[j], v1 = w[j + 1];
+        const double q0 = fmin(fmax(rint(v0 * rdelta), lo), hi);
+        const double q1 = fmin(fmax(rint(v1 * rdelta), lo), hi);
+        const double e0 = fma(-delta, q0, v0);
+        const double e1 = fma(-delta, q1, v1);
+        L = fma(o[j] * e0, e0, L);
+        L1 = fma(o[j + 1] * e1, e1, L1);
       }
+      L += L1;
     }
     loss[r * ncand + c] = L;
   }
@@ -289,25 +301,29 @@ struct SweepArgs {
   int what_f64;
 };
 
-template <int EPL>
+// The per-step dependent chain is what bounds this kernel (a dependent fp64 instruction costs about 32
+// cycles): broadcast w_j -> multiply by 1/s -> round -> clamp -> error -> scale -> update.  Everything else
+// (the next row of U and the next reciprocal from LDS, the code and error bookkeeping) is kept off that chain.
+template <int EPL, bool SIGN>
 __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
-  extern __shared__ __align__(16) double Us[];   // [beta][beta], then [beta] reciprocals of the diagonal
+  extern __shared__ __align__(16) double Us[];   // [beta + 1][beta] (last row padding), then [beta + 64] reciprocals
   const int beta = a.beta;
-  double* rdiag = Us + beta * beta;
+  double* rdiag = Us + (beta + 1) * beta + 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int idx = tid; idx < beta * beta; idx += SWEEP_WAVES * 64) {
+  for (int idx = tid; idx < (beta + 1) * beta + 64; idx += SWEEP_WAVES * 64) {
     const int j = idx / beta, l = idx - j * beta;
-    Us[idx] = (l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
+    Us[idx] = (j < beta && l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
   }
-  for (int j = tid; j < beta; j += SWEEP_WAVES * 64) rdiag[j] = 1.0 / a.U[(int64_t)j * a.ldu + j];
+  for (int j = tid; j < beta + 64; j += SWEEP_WAVES * 64) rdiag[j] = (j < beta) ? 1.0 / a.U[(int64_t)j * a.ldu + j] : 0.0;
   __syncthreads();
   const int row = blockIdx.x * SWEEP_WAVES + wave;
   if (row >= a.n) return;
 
-  const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
   const double qmax = (double)((1 << a.bits) - 1);
   const double s = a.scale[(int64_t)row * a.sz_stride];
   const double z = a.zero[(int64_t)row * a.sz_stride];
+  const double rs = 1.0 / s;
+  const double lo = -z, hi = qmax - z;           // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), lo, hi)
 
   double w[EPL], ev[EPL], qv[EPL];
   double* wr = a.W + (int64_t)row * a.ldw;
@@ -319,30 +335,46 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
     qv[r] = 0.0;
   }
   double e2 = 0.0;
+  // row j of U and 1 / U_jj for the current step, fetched one step ahead (lanes beyond beta read padding)
+  double u[EPL], rd = rdiag[0];
+#pragma unroll
+  for (int r = 0; r < EPL; ++r) u[r] = Us[r * 64 + lane];
 #pragma unroll
   for (int r = 0; r < EPL; ++r) {
     const int jend = min(64, beta - r * 64);
     for (int jj = 0; jj < jend; ++jj) {
       const int j = r * 64 + jj;
+      double un[EPL];
+      const double rdn = rdiag[j + 1];
+#pragma unroll
+      for (int r2 = 0; r2 < EPL; ++r2) un[r2] = Us[(j + 1) * beta + r2 * 64 + lane];
       const double wj = read_lane_f64(w[r], jj);
-      double q;
-      if (sign_mode) {
-        q = (wj >= 0.0) ? 1.0 : 0.0;
+      double qz;                                 // q - z
+      if (SIGN) {
+        qz = (wj >= 0.0) ? 0.5 : -0.5;
       } else {
-        q = fmin(fmax(rint(wj / s) + z, 0.0), qmax);
+        // The code is rint(wj / s) with a true division.  wj * (1 / s) lies within a few ulps of the quotient,
+        // so unless it is that close to a rounding tie it rounds the same way; only then is the division done
+        // (a real branch: the asm keeps the compiler from computing the quotient speculatively).
+        double x = wj * rs;
+        const double fr = fabs(__builtin_amdgcn_fract(x) - 0.5);
+        if (fr <= 8.0 * 2.220446049250313e-16 * fmax(fabs(x), 1.0)) {
+          x = wj / s;
+          asm volatile("" : "+v"(x));
+        }
+        qz = fmin(fmax(rint(x), lo), hi);
       }
-      const double what = s * (q - z);
-      const double e = (wj - what) * rdiag[j];   // the error is a continuous quantity: reciprocal is fine
-      e2 += e * e;
+      const double e = fma(-s, qz, wj) * rd;     // (w_j - s (q - z)) / U_jj; continuous, so a reciprocal is fine
+#pragma unroll
+      for (int r2 = r; r2 < EPL; ++r2) w[r2] = fma(-e, u[r2], w[r2]);
+      e2 = fma(e, e, e2);
       if (lane == jj) {
         ev[r] = e;
-        qv[r] = q;
+        qv[r] = qz + z;
       }
+      rd = rdn;
 #pragma unroll
-      for (int r2 = r; r2 < EPL; ++r2) {
-        const int c = r2 * 64 + lane;
-        if (c < beta) w[r2] -= e * Us[j * beta + c];
-      }
+      for (int r2 = 0; r2 < EPL; ++r2) u[r2] = un[r2];
     }
   }
 #pragma unroll
@@ -509,10 +541,12 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
 
-  const size_t sweep_smem = sizeof(double) * ((size_t)beta * beta + beta);
+  const size_t sweep_smem = sizeof(double) * ((size_t)(beta + 1) * beta + 64 + beta + 64);
   if (sweep_smem > 64 * 1024) {
-    static bool done = false;
-    st = allow_big_lds(ctx, gptq_sweep<2>, done);
+    static bool done0 = false, done1 = false;
+    st = allow_big_lds(ctx, gptq_sweep<2, false>, done0);
+    if (st != SLIM_OK) return st;
+    st = allow_big_lds(ctx, gptq_sweep<2, true>, done1);
     if (st != SLIM_OK) return st;
   }
 
@@ -562,10 +596,18 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
                           : static_cast<void*>(static_cast<float*>(What) + b0);
     }
     const dim3 sgrid(slim_cdiv(n, SWEEP_WAVES)), sblock(SWEEP_WAVES * 64);
-    if (beta <= 64)
-      SLIM_LAUNCH(ctx, "gptq_sweep", gptq_sweep<1>, sgrid, sblock, sweep_smem, s);
-    else
-      SLIM_LAUNCH(ctx, "gptq_sweep", gptq_sweep<2>, sgrid, sblock, sweep_smem, s);
+    const bool sign = (gb[g] == 1 && prm.q1_mode == SLIM_Q1_SIGN);
+    if (beta <= 64) {
+      if (sign)
+        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<1, true>), sgrid, sblock, sweep_smem, s);
+      else
+        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<1, false>), sgrid, sblock, sweep_smem, s);
+    } else {
+      if (sign)
+        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, true>), sgrid, sblock, sweep_smem, s);
+      else
+        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, false>), sgrid, sblock, sweep_smem, s);
+    }
 
     const int rest = m - b0 - beta;
     if (rest > 0) {
