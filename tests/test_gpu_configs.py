@@ -1,0 +1,87 @@
+"""The other BASELINE configurations (3, 4, 5) as parity cases, at reduced sizes that keep what makes each of
+them different: config 3 -- heavy-tailed weights and activations, m = 11 x 128 (not a multiple of the Gram
+tile, an odd number of groups, a non-power-of-two number of diagonal blocks), N = 2 and N = 3; config 4 --
+structured salient weight channels, widths {2, 3, 4}; config 5 -- many more rows than columns.  The whole
+HIP pass runs on its own intermediate results and is compared with the whole oracle pass."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as orc
+from paper_2405_14917_amd import synth
+
+pytestmark = pytest.mark.gpu
+MARGIN = 1e-6
+
+CASES = {
+    "C3-N2": (synth.scaled(synth.CONFIGS["C3"], n=192, m=1408, t=6144), 2),
+    "C3-N3": (synth.scaled(synth.CONFIGS["C3"], n=192, m=1408, t=6144), 3),
+    "C4": (synth.scaled(synth.CONFIGS["C4"], n=432, m=640, t=4096), 3),
+    "C5": (synth.scaled(synth.CONFIGS["C5"], n=1792, m=512, t=4104), 2),
+}
+
+
+@pytest.fixture(scope="module")
+def slim():
+    from paper_2405_14917_amd import binding
+    s = binding.Slim("cuda:0")
+    yield s
+    s.close()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_reduced_config(slim, name):
+    cfg, N = CASES[name]
+    W = synth.make_weights(cfg)
+    X = synth.make_activations(cfg, correlated=True)
+    t_sba = min(2048, cfg.t) // 4 * 4
+    ref = orc.slim_layer(W, [X], cfg.beta, N, t_sba=t_sba)
+
+    Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+    G = torch.zeros((cfg.m, cfg.m), dtype=torch.float32, device="cuda")
+    # two chunks, the second one ragged for config 5 (4104 tokens)
+    half = (cfg.t // 2) // 8 * 8
+    nt = slim.hessian_accumulate(Xd[:, :half], G, 0)
+    nt = slim.hessian_accumulate(Xd[:, half:], G, nt)
+    assert nt == cfg.t
+    Gg = host(G).astype(np.float64)
+    scale = np.sqrt(np.outer(np.diag(ref["G"]), np.diag(ref["G"])))
+    assert np.max(np.abs(Gg - ref["G"]) / scale) < 2e-6 * np.sqrt(cfg.t / 512)
+
+    U, d = slim.hessian_inverse(G, nt, cfg.percdamp)
+    assert np.linalg.norm(host(U) - ref["U"]) / np.linalg.norm(ref["U"]) < 1e-3    # fp32 Gram in, fp64 after
+    _, grp, _ = slim.salience(Wd, d, cfg.beta)
+    assert np.allclose(host(grp), ref["group_sal"], rtol=1e-3)
+    bits, p_star, obj = slim.sba_allocate(Wd, grp, cfg.beta, N, Xd[:, :t_sba])
+    order_ok = np.array_equal(np.argsort(host(grp), kind="stable"), np.argsort(ref["group_sal"], kind="stable"))
+    if order_ok:
+        assert np.allclose(obj, ref["obj_curve"], rtol=1e-8)
+        if ref["sba_margin"] > MARGIN:
+            assert p_star == ref["p_star"] and np.array_equal(host(bits), ref["bits"])
+    b = host(bits).astype(int)
+    assert set(b.tolist()) <= {N - 1, N, N + 1} and b.sum() == N * cfg.k
+
+    out = slim.gptq_quantize(Wd, U, bits, cfg.beta, want_what=torch.float64)
+    packed, gbits, row_off, m_star = slim.pack(out["codes"], bits, cfg.beta)
+    assert m_star == cfg.m * N // 32
+    c2, b2 = orc.unpack(host(packed).view(np.uint32), host(gbits).view(np.uint32), cfg.beta, cfg.k)
+    assert np.array_equal(c2, host(out["codes"])) and np.array_equal(b2, host(bits))
+    if np.array_equal(host(bits), ref["bits"]):
+        rec = orc.reconstruction_error(W, host(out["What"]), ref["G"])
+        print("%s: p*=%d codes equal %.4f recon gpu %.5e oracle %.5e" %
+              (name, p_star, (host(out["codes"]) == ref["codes"]).mean(), rec, ref["recon"]))
+        assert abs(rec - ref["recon"]) <= 0.01 * ref["recon"]
+
+    # the sweep on the ORACLE's second-order information and bits: code for code
+    chk = slim.gptq_quantize(Wd, torch.from_numpy(np.ascontiguousarray(ref["U"])).cuda(),
+                             torch.from_numpy(ref["bits"]).cuda(), cfg.beta, want_what=torch.float64)
+    ok = (ref["round_margin"].min(axis=1) > MARGIN) & (ref["sqc_margin"].min(axis=1) > MARGIN)
+    assert ok.mean() > 0.9
+    assert np.array_equal(host(chk["codes"])[ok], ref["codes"][ok])
+    fro = np.linalg.norm(host(chk["What"]) - ref["What"]) / np.linalg.norm(ref["What"])
+    assert fro < 1e-3
