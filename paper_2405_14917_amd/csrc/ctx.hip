@@ -41,6 +41,13 @@ void* slim_ws_alloc(slim_ctx* ctx, size_t bytes) {
   return p;
 }
 
+slim_status slim_ensure_side(slim_ctx* ctx) {
+  if (ctx->side) return SLIM_OK;
+  SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+  for (hipEvent_t& e : ctx->ev) SLIM_HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  return SLIM_OK;
+}
+
 void slim_prof_begin(slim_ctx* ctx, const char* name) {
   slim_prof_pending p;
   p.name = name;
@@ -117,6 +124,12 @@ slim_status slim_destroy(slim_ctx* ctx) {
     if (p.stop) (void)hipEventDestroy(p.stop);
   }
   for (hipEvent_t ev : ctx->free_events) (void)hipEventDestroy(ev);
+  if (ctx->side) {
+    (void)hipStreamSynchronize(ctx->side);
+    for (hipEvent_t e : ctx->ev)
+      if (e) (void)hipEventDestroy(e);
+    (void)hipStreamDestroy(ctx->side);
+  }
   if (ctx->ws) (void)hipFree(ctx->ws);
   if (ctx->tau_default) (void)hipFree(ctx->tau_default);
   if (ctx->dflags) (void)hipFree(ctx->dflags);

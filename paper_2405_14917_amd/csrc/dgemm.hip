@@ -3,104 +3,95 @@
 // (Alg. 1 line 2), the rank-beta trailing update of the GPTQ sweep (Alg. 1 line 12) and the layer
 // outputs of the SBA objective (Eq. 4).
 //
-// Tiling: one 256-thread workgroup (4 wavefronts, 2 x 2) owns a 128 x 128 tile of C; every wavefront
-// owns 64 x 64 of it as 4 x 4 MFMA tiles of 16 x 16 (128 accumulator registers per lane).  K advances
-// in slabs of 16 through two LDS buffers (k-major, so that the 16 lanes that feed one k-slice of an
-// MFMA operand read 16 consecutive doubles); the next slab is fetched into registers while the
-// current one is multiplied, one barrier per slab.
+// Tiling: one 256-thread workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of C (128 x 128, or 64 x 64
+// for problems too small to give every CU a big tile); every wavefront owns a quarter of it as MFMA tiles
+// of 16 x 16.  K advances in slabs of 16 through two LDS buffers (k-major, so that the 16 lanes that feed
+// one k-slice of an MFMA operand read 16 consecutive doubles); the next slab is fetched into registers
+// while the current one is multiplied, one barrier per slab.
 #include "slim_internal.h"
 
 namespace {
 
 typedef double double4v __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 16, NTHREADS = 256;
+constexpr int BK = 16, NTHREADS = 256;
 
+template <int BM, int BN>
 struct Prefetch {
-  double2 a[4];
-  double2 b[4];
+  double2 a[BM / 32];
+  double2 b[BN / 32];
   unsigned va, vb;   // bit j set: element pair j is inside the matrix and the K range
 };
 
 // Loads are branch-free: an out-of-range element is read from a clamped (valid) address and replaced by
 // zero only when it is written to LDS, so that the loads of the next slab stay in flight while the current
 // slab is multiplied.
-template <int TRANS_B>
-__device__ __forceinline__ void load_global(const slim_gemm_desc& d, int row0, int col0, int k0, int kend,
-                                            int tid, Prefetch& p) {
-  p.va = 0;
-  p.vb = 0;
-  // A slab: 128 rows x 16 k.  Thread -> (row, half of the k range), 4 x 16 bytes contiguous in k.
-  {
-    const int r = tid >> 1, kh = (tid & 1) * 8;
-    const int row = row0 + r;
-    const bool rv = row < d.M;
-    const double* src = d.A + (int64_t)min(row, d.M - 1) * d.lda;
+//
+// Operand slab stored "rows x 16 k" in memory (A, or B when it is given as N x K): thread -> (row, part of
+// the k range); R rows need R * 16 doubles = R / 32 double2 per thread.
+template <int R>
+__device__ __forceinline__ void load_rows_k(const double* base, int64_t ld, int nrows, int K, int row0, int k0,
+                                            int kend, int tid, double2* out, unsigned& valid) {
+  constexpr int PER = R / 32;                 // double2 per thread
+  constexpr int TPR = 8 / PER;                // threads per row
+  const int r = tid / TPR, kh = (tid % TPR) * (2 * PER);
+  const int row = row0 + r;
+  const bool rv = row < nrows;
+  const double* src = base + (int64_t)min(row, nrows - 1) * ld;
+  valid = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = k0 + kh + 2 * j;
-      p.a[j] = *reinterpret_cast<const double2*>(src + min(k, d.K - 2));
-      p.va |= (rv && k < kend) ? (1u << j) : 0u;
-    }
-  }
-  if (TRANS_B) {
-    // B stored N x K: same pattern as A with n in the role of the row
-    const int r = tid >> 1, kh = (tid & 1) * 8;
-    const int col = col0 + r;
-    const bool cv = col < d.N;
-    const double* src = d.B + (int64_t)min(col, d.N - 1) * d.ldb;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = k0 + kh + 2 * j;
-      p.b[j] = *reinterpret_cast<const double2*>(src + min(k, d.K - 2));
-      p.vb |= (cv && k < kend) ? (1u << j) : 0u;
-    }
-  } else {
-    // B stored K x N: thread -> (k, 8 consecutive n)
-    const int kk = tid >> 4, n0 = (tid & 15) * 8;
-    const int k = k0 + kk;
-    const bool kv = k < kend;
-    const double* src = d.B + (int64_t)min(k, d.K - 1) * d.ldb;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = col0 + n0 + 2 * j;
-      p.b[j] = *reinterpret_cast<const double2*>(src + min(col, d.N - 2));
-      p.vb |= (kv && col < d.N) ? (1u << j) : 0u;
-    }
+  for (int j = 0; j < PER; ++j) {
+    const int k = k0 + kh + 2 * j;
+    out[j] = *reinterpret_cast<const double2*>(src + min(k, K - 2));
+    valid |= (rv && k < kend) ? (1u << j) : 0u;
   }
 }
 
-template <int TRANS_B>
-__device__ __forceinline__ void store_lds(double* As, double* Bs, int tid, const Prefetch& p) {
-  {
-    const int r = tid >> 1, kh = (tid & 1) * 8;
+template <int R>
+__device__ __forceinline__ void store_rows_k(double* S, int tid, const double2* in, unsigned valid) {
+  constexpr int PER = R / 32;
+  constexpr int TPR = 8 / PER;
+  const int r = tid / TPR, kh = (tid % TPR) * (2 * PER);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool v = (p.va >> j) & 1u;
-      As[(kh + 2 * j) * BM + r] = v ? p.a[j].x : 0.0;
-      As[(kh + 2 * j + 1) * BM + r] = v ? p.a[j].y : 0.0;
-    }
-  }
-  if (TRANS_B) {
-    const int r = tid >> 1, kh = (tid & 1) * 8;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool v = (p.vb >> j) & 1u;
-      Bs[(kh + 2 * j) * BN + r] = v ? p.b[j].x : 0.0;
-      Bs[(kh + 2 * j + 1) * BN + r] = v ? p.b[j].y : 0.0;
-    }
-  } else {
-    const int kk = tid >> 4, n0 = (tid & 15) * 8;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const bool v = (p.vb >> j) & 1u;
-      *reinterpret_cast<double2*>(&Bs[kk * BN + n0 + 2 * j]) = make_double2(v ? p.b[j].x : 0.0, v ? p.b[j].y : 0.0);
-    }
+  for (int j = 0; j < PER; ++j) {
+    const bool v = (valid >> j) & 1u;
+    S[(kh + 2 * j) * R + r] = v ? in[j].x : 0.0;
+    S[(kh + 2 * j + 1) * R + r] = v ? in[j].y : 0.0;
   }
 }
 
-template <int TRANS_B>
+// B given as K x N: thread -> (k, consecutive n)
+template <int BN>
+__device__ __forceinline__ void load_k_cols(const double* base, int64_t ld, int N, int K, int col0, int k0, int kend,
+                                            int tid, double2* out, unsigned& valid) {
+  constexpr int PER = BN / 32;
+  const int kk = tid >> 4, n0 = (tid & 15) * (2 * PER);
+  const int k = k0 + kk;
+  const bool kv = k < kend;
+  const double* src = base + (int64_t)min(k, K - 1) * ld;
+  valid = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const int col = col0 + n0 + 2 * j;
+    out[j] = *reinterpret_cast<const double2*>(src + min(col, N - 2));
+    valid |= (kv && col < N) ? (1u << j) : 0u;
+  }
+}
+
+template <int BN>
+__device__ __forceinline__ void store_k_cols(double* S, int tid, const double2* in, unsigned valid) {
+  constexpr int PER = BN / 32;
+  const int kk = tid >> 4, n0 = (tid & 15) * (2 * PER);
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const bool v = (valid >> j) & 1u;
+    *reinterpret_cast<double2*>(&S[kk * BN + n0 + 2 * j]) = make_double2(v ? in[j].x : 0.0, v ? in[j].y : 0.0);
+  }
+}
+
+template <int TRANS_B, int BM, int BN>
 __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, double* smem) {
+  constexpr int MI = BM / 32, NJ = BN / 32;   // MFMA tiles per wavefront along M and N
   const int tiles_n = (d.N + BN - 1) / BN;
   const int tiles_m = (d.M + BM - 1) / BM;
   if (pid >= tiles_m * tiles_n) return;
@@ -121,69 +112,85 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   // accesses in the LDS address space)
   constexpr int STAGE = BK * BM + BK * BN;
 
-  double4v acc[4][4];
+  double4v acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = double4v{0.0, 0.0, 0.0, 0.0};
+    for (int j = 0; j < NJ; ++j) acc[i][j] = double4v{0.0, 0.0, 0.0, 0.0};
 
-  Prefetch pf;
+  Prefetch<BM, BN> pf;
+  auto fetch = [&](int k0) {
+    load_rows_k<BM>(d.A, d.lda, d.M, d.K, row0, k0, kend, tid, pf.a, pf.va);
+    if (TRANS_B)
+      load_rows_k<BN>(d.B, d.ldb, d.N, d.K, col0, k0, kend, tid, pf.b, pf.vb);
+    else
+      load_k_cols<BN>(d.B, d.ldb, d.N, d.K, col0, k0, kend, tid, pf.b, pf.vb);
+  };
+  auto stash = [&](double* st) {
+    store_rows_k<BM>(st, tid, pf.a, pf.va);
+    if (TRANS_B)
+      store_rows_k<BN>(st + BK * BM, tid, pf.b, pf.vb);
+    else
+      store_k_cols<BN>(st + BK * BM, tid, pf.b, pf.vb);
+  };
+
   int cur = 0;
   if (kbeg < kend) {
-    load_global<TRANS_B>(d, row0, col0, kbeg, kend, tid, pf);
-    store_lds<TRANS_B>(smem, smem + BK * BM, tid, pf);
+    fetch(kbeg);
+    stash(smem);
   }
   __syncthreads();
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
     // unconditional (the slab behind the last one is all zeros read from clamped addresses): one basic
     // block per iteration keeps the accumulators in place across the loop
-    load_global<TRANS_B>(d, row0, col0, k0 + BK, kend, tid, pf);
+    fetch(k0 + BK);
     __builtin_amdgcn_sched_barrier(0);   // keep the fetch ahead of, and its first use behind, the MFMA block
-    const double* as = smem + cur * STAGE + wm * 64 + l16;
-    const double* bs = smem + cur * STAGE + BK * BM + wn * 64 + l16;
+    const double* as = smem + cur * STAGE + wm * (BM / 2) + l16;
+    const double* bs = smem + cur * STAGE + BK * BM + wn * (BN / 2) + l16;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 4) {
-      double a[4], b[4];
+      double a[MI], b[NJ];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = as[(kk + lk) * BM + i * 16];
+      for (int i = 0; i < MI; ++i) a[i] = as[(kk + lk) * BM + i * 16];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = bs[(kk + lk) * BN + j * 16];
+      for (int j = 0; j < NJ; ++j) b[j] = bs[(kk + lk) * BN + j * 16];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    store_lds<TRANS_B>(smem + (cur ^ 1) * STAGE, smem + (cur ^ 1) * STAGE + BK * BM, tid, pf);
+    stash(smem + (cur ^ 1) * STAGE);
     __syncthreads();
     cur ^= 1;
   }
 
   // Epilogue.  Accumulator register v of lane l holds C[4 * v + l / 16][l % 16] of its 16 x 16 tile.
-  // The old values of C are fetched 16 at a time (clamped addresses, no branches) before any store, so
-  // that the read-modify-write costs one memory round trip per 16 rows instead of one per element.
+  // The old values of C are fetched a row of MFMA tiles at a time (clamped addresses, no branches) before
+  // any store, so that the read-modify-write costs one memory round trip per 16 rows instead of one per
+  // element.
   const double alpha = d.alpha, beta = d.beta;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    double cold[4][4];
+  for (int i = 0; i < MI; ++i) {
+    double cold[4][NJ];
     if (beta != 0.0) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int row = min(row0 + wm * 64 + i * 16 + 4 * v + lk, d.M - 1);
+        const int row = min(row0 + wm * (BM / 2) + i * 16 + 4 * v + lk, d.M - 1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int col = min(col0 + wn * 64 + j * 16 + l16, d.N - 1);
+        for (int j = 0; j < NJ; ++j) {
+          const int col = min(col0 + wn * (BN / 2) + j * 16 + l16, d.N - 1);
           cold[v][j] = d.C[(int64_t)row * d.ldc + col];
         }
       }
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const int row = row0 + wm * 64 + i * 16 + 4 * v + lk;
+      const int row = row0 + wm * (BM / 2) + i * 16 + 4 * v + lk;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int col = col0 + wn * 64 + j * 16 + l16;
+      for (int j = 0; j < NJ; ++j) {
+        const int col = col0 + wn * (BN / 2) + j * 16 + l16;
         double r = alpha * acc[i][j][v];
         if (beta != 0.0) r += beta * cold[v][j];
         if (row < d.M && col < d.N) {
@@ -195,20 +202,25 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   }
 }
 
-template <int TRANS_B>
+template <int TRANS_B, int BM, int BN>
 __global__ __launch_bounds__(NTHREADS) void dgemm_kernel(slim_gemm_desc d) {
   extern __shared__ __align__(16) double smem[];
-  gemm_body<TRANS_B>(d, blockIdx.x, smem);
+  gemm_body<TRANS_B, BM, BN>(d, blockIdx.x, smem);
 }
 
-template <int TRANS_B>
+template <int TRANS_B, int BM, int BN>
 __global__ __launch_bounds__(NTHREADS) void dgemm_batched_kernel(const slim_gemm_desc* descs) {
   extern __shared__ __align__(16) double smem[];
   const slim_gemm_desc d = descs[blockIdx.y];
-  gemm_body<TRANS_B>(d, blockIdx.x, smem);
+  gemm_body<TRANS_B, BM, BN>(d, blockIdx.x, smem);
 }
 
-constexpr size_t kSmemBytes = size_t(2) * (BK * BM + BK * BN) * sizeof(double);
+constexpr size_t smem_bytes(int bm, int bn) { return size_t(2) * (BK * bm + BK * bn) * sizeof(double); }
+
+// 64 x 64 tiles when 128 x 128 tiles would leave most of the 256 CUs without work
+bool use_small_tiles(int M, int N, int count) {
+  return (int64_t)slim_cdiv(M, 128) * slim_cdiv(N, 128) * count < 192;
+}
 
 slim_status check_desc(slim_ctx* ctx, const slim_gemm_desc& d) {
   SLIM_REQUIRE(ctx, d.M >= 0 && d.N >= 0 && d.K >= 0, "dgemm: negative size");
@@ -226,21 +238,37 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
   slim_status st = check_desc(ctx, d);
   if (st != SLIM_OK) return st;
   if (d.M == 0 || d.N == 0) return SLIM_OK;
-  const int tiles = slim_cdiv(d.M, BM) * slim_cdiv(d.N, BN);
+  if (use_small_tiles(d.M, d.N, 1)) {
+    const int tiles = slim_cdiv(d.M, 64) * slim_cdiv(d.N, 64);
+    if (trans_b)
+      SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 64, 64>), dim3(tiles), dim3(NTHREADS), smem_bytes(64, 64), d);
+    else
+      SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 64, 64>), dim3(tiles), dim3(NTHREADS), smem_bytes(64, 64), d);
+    return SLIM_OK;
+  }
+  const int tiles = slim_cdiv(d.M, 128) * slim_cdiv(d.N, 128);
   if (trans_b)
-    SLIM_LAUNCH(ctx, name, dgemm_kernel<1>, dim3(tiles), dim3(NTHREADS), kSmemBytes, d);
+    SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 128, 128>), dim3(tiles), dim3(NTHREADS), smem_bytes(128, 128), d);
   else
-    SLIM_LAUNCH(ctx, name, dgemm_kernel<0>, dim3(tiles), dim3(NTHREADS), kSmemBytes, d);
+    SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 128, 128>), dim3(tiles), dim3(NTHREADS), smem_bytes(128, 128), d);
   return SLIM_OK;
 }
 
 slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs_dev,
                                int count, int max_M, int max_N) {
   if (count == 0 || max_M == 0 || max_N == 0) return SLIM_OK;
-  const int tiles = slim_cdiv(max_M, BM) * slim_cdiv(max_N, BN);
+  if (use_small_tiles(max_M, max_N, count)) {
+    const int tiles = slim_cdiv(max_M, 64) * slim_cdiv(max_N, 64);
+    if (trans_b)
+      SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<1, 64, 64>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
+    else
+      SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<0, 64, 64>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
+    return SLIM_OK;
+  }
+  const int tiles = slim_cdiv(max_M, 128) * slim_cdiv(max_N, 128);
   if (trans_b)
-    SLIM_LAUNCH(ctx, name, dgemm_batched_kernel<1>, dim3(tiles, count), dim3(NTHREADS), kSmemBytes, descs_dev);
+    SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<1, 128, 128>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
   else
-    SLIM_LAUNCH(ctx, name, dgemm_batched_kernel<0>, dim3(tiles, count), dim3(NTHREADS), kSmemBytes, descs_dev);
+    SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<0, 128, 128>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
   return SLIM_OK;
 }

@@ -217,7 +217,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   std::vector<Level> levels;
 
   const size_t bytes_A = slim_ws_round(sizeof(double) * (size_t)m * m);
-  const size_t bytes_P = slim_ws_round(sizeof(double) * (size_t)m * NB);
+  const size_t bytes_P = slim_ws_round(sizeof(double) * (size_t)m * NB * 2);   // two panels (double buffer)
   const size_t bytes_part = slim_ws_round(sizeof(double) * (size_t)parts * m);
   const size_t bytes_desc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * nblk + 8));
   slim_status st = slim_ws_reserve(ctx, 2 * bytes_A + bytes_P + bytes_part + bytes_desc + 256);
@@ -299,10 +299,32 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
                                      hipMemcpyHostToDevice, ctx->stream));
   }
 
-  // ---- factorisation from the bottom-right corner upwards
+  // ---- factorisation from the bottom-right corner upwards, with one block of lookahead:
+  //   main stream : diag(J) -> panel(J) -> update of block column J-1 only -> diag(J-1) -> ...
+  //   side stream : the bulk of the symmetric update of block J (all columns left of block J-1)
+  // The bulk update therefore runs while the next diagonal block is being factored.  Events order the two
+  // streams: the bulk of block J starts after panel(J); the main stream touches block column J-2 (and
+  // reuses the panel buffer of block J) only after the bulk of block J has finished.
+  st = slim_ensure_side(ctx);
+  if (st != SLIM_OK) return st;
+  hipStream_t s0 = ctx->stream, s1 = ctx->side;
+  hipEvent_t ev_fork = ctx->ev[0];
+  hipEvent_t ev_panel[2] = {ctx->ev[1], ctx->ev[2]};
+  hipEvent_t ev_bulk[2] = {ctx->ev[3], ctx->ev[4]};
+  bool bulk_issued[2] = {false, false};
+  SLIM_HIP_TRY(ctx, hipEventRecord(ev_fork, s0));
+  SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_fork, 0));
+  struct StreamSwap {
+    slim_ctx* c;
+    hipStream_t keep;
+    StreamSwap(slim_ctx* cc, hipStream_t s) : c(cc), keep(cc->stream) { c->stream = s; }
+    ~StreamSwap() { c->stream = keep; }
+  };
   for (int blk = nblk - 1; blk >= 0; --blk) {
     const int j0 = blk * NB;
     const int nbk = std::min(NB, m - j0);
+    const int pb = blk & 1;
+    double* Pb = P + (size_t)pb * m * NB;
     SLIM_LAUNCH(ctx, "inv_chol_diag", chol_diag, dim3(1), dim3(1024), 0, A + (int64_t)j0 * lda + j0, lda, nbk,
                 U + (int64_t)j0 * ldu + j0, ldu, flag, j0);
     if (j0 == 0) break;
@@ -311,7 +333,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
     d.lda = lda;
     d.B = U + (int64_t)j0 * ldu + j0;   // V_JJ, used transposed
     d.ldb = ldu;
-    d.C = P;
+    d.C = Pb;
     d.ldc = NB;
     d.C2 = A + j0;                      // the panel of R replaces the panel of A
     d.ldc2 = lda;
@@ -323,23 +345,42 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
     d.beta = 0.0;
     st = slim_dgemm(ctx, "inv_panel_dgemm", 1, d);
     if (st != SLIM_OK) return st;
-    d.A = P;
+    SLIM_HIP_TRY(ctx, hipEventRecord(ev_panel[pb], s0));
+    // block column J-1 was last written by the bulk update of block J+1
+    if (bulk_issued[pb ^ 1]) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_bulk[pb ^ 1], 0));
+    const int jn = j0 - NB;             // first column of block J-1 (j0 is a multiple of NB here)
+    d.A = Pb;
     d.lda = NB;
-    d.B = P;
+    d.B = Pb + (size_t)jn * NB;         // rows of the panel that belong to block J-1
     d.ldb = NB;
-    d.C = A;
+    d.C = A + jn;
     d.ldc = lda;
     d.C2 = nullptr;
     d.ldc2 = 0;
     d.M = j0;
-    d.N = j0;
+    d.N = NB;
     d.K = nbk;
-    d.flags = SLIM_GEMM_UPPER_ONLY;
+    d.flags = 0;
     d.alpha = -1.0;
     d.beta = 1.0;
-    st = slim_dgemm(ctx, "inv_syrk_dgemm", 1, d);
+    st = slim_dgemm(ctx, "inv_syrk_next_dgemm", 1, d);
     if (st != SLIM_OK) return st;
+    if (jn > 0) {
+      StreamSwap swap(ctx, s1);
+      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_panel[pb], 0));
+      d.B = Pb;
+      d.C = A;
+      d.M = jn;
+      d.N = jn;
+      d.flags = SLIM_GEMM_UPPER_ONLY;
+      st = slim_dgemm(ctx, "inv_syrk_dgemm", 1, d);
+      if (st != SLIM_OK) return st;
+      SLIM_HIP_TRY(ctx, hipEventRecord(ev_bulk[pb], s1));
+      bulk_issued[pb] = true;
+    }
   }
+  for (int i = 0; i < 2; ++i)
+    if (bulk_issued[i]) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_bulk[i], 0));
 
   // ---- triangular inverse U = R^-1: two batched GEMM launches per level
   if (!descs.empty()) {

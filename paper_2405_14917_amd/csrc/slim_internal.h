@@ -38,6 +38,9 @@ struct slim_ctx {
   int ncand_default = 0;
   int* dflags = nullptr;          // device, 64 ints (pivot failures, counters)
   char* hpin = nullptr;           // pinned host staging, SLIM_HPIN_BYTES
+  // side stream (default priority) and events for work that overlaps with the main stream inside one call
+  hipStream_t side = nullptr;
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   // profiling
   bool prof = false;
   std::vector<slim_prof_pending> pending;
@@ -55,6 +58,9 @@ slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...);
 slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes);
 void* slim_ws_alloc(slim_ctx* ctx, size_t bytes);
 inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255); }
+
+// Creates the side stream and its events on first use.
+slim_status slim_ensure_side(slim_ctx* ctx);
 
 // Profiling hooks used by SLIM_LAUNCH.
 void slim_prof_begin(slim_ctx* ctx, const char* name);
