@@ -74,9 +74,14 @@ def algorithmic_work(name, cfg, launches_per_step):
     if name == "sba_output_dgemm":
         return "mfma", "mfma_f64", 2.0 * n * m * ts
     if name == "sba_update_dgemm":
-        return "mfma", "mfma_f64", 2.0 * n * beta * ts
+        return "mfma", "mfma_f64", 4.0 * n * beta * ts
     if name == "gptq_trailing_dgemm":
-        return "mfma", "mfma_f64", float(n) * beta * beta * k * (k - 1) / max(launches_per_step, 1)
+        return "mfma", "mfma_f64", float(n) * beta * beta * (k - 1) * (k - 2) / max(launches_per_step, 1)
+    if name == "gptq_next_dgemm":
+        return "mfma", "mfma_f64", 2.0 * n * beta * beta
+    if name == "inv_syrk_next_dgemm":
+        tot = sum(2.0 * j0 * 64 * min(64, m - j0) for j0 in range(64, m, 64))
+        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
     if name == "inv_syrk_dgemm":
         tot = sum(float(j0) * (j0 + 1) * min(64, m - j0) for j0 in range(64, m, 64))
         return "mfma", "mfma_f64", tot / max(launches_per_step, 1)

@@ -4,15 +4,15 @@
 // layer outputs are carried incrementally:
 //   sba_rank        stable ascending rank of the k group saliences (one workgroup, counting sort by
 //                   comparison; NaN ranks last) -> order[]
-//   sba_fakequant   per (row, group), one wavefront: Eq. 1 / Eq. 2 round-to-nearest at the three widths;
-//                   stores W_N and the two differences D_lo = W_{N-1} - W_N, D_hi = W_{N+1} - W_N
+//   sba_fakequant   per (row, group), one wavefront: Eq. 1 / Eq. 2 round-to-nearest at width N and at the one
+//                   other width the group can take; stores W_N and the difference, the latter in search order
 //   dgemm           Y^T = W X_s and Y_0^T = W_N X_s     (n x t_s, fp64 matrix cores)
 //   for p = 0 .. floor(k/2):
 //     kl_partial / kl_finalize   obj[p] = sum_tokens KL(softmax(Y_t) || softmax(Y_p,t)); the softmax runs
 //                   over the n outputs of a token, i.e. down a column of the transposed outputs, so
 //                   consecutive lanes read consecutive tokens
-//     dgemm x 2     Y_{p+1}^T = Y_p^T + D_lo[:, g_lo] X_s[g_lo, :] + D_hi[:, g_hi] X_s[g_hi, :]
-//                   (descriptors built on the device from order[], no host round trip)
+//     dgemm         Y_{p+1}^T = Y_p^T + [D_lo(g_lo) | D_hi(g_hi)] [X_s(g_lo) ; X_s(g_hi)]  (rank 2 beta; the
+//                   operands were laid out in search order on the device, no host round trip)
 //   sba_finalize    first minimum of obj, bit vector of p*
 #include "slim_device.h"
 #include "slim_internal.h"
@@ -24,7 +24,8 @@ using namespace slimdev;
 constexpr int KL_TOK = 64;     // tokens per workgroup
 constexpr int KL_PART = 5;     // doubles per (part, token): max y, sum exp y, max q, sum exp q, weighted diff
 
-__global__ __launch_bounds__(256) void sba_rank(const double* __restrict__ sal, int k, int* __restrict__ order) {
+__global__ __launch_bounds__(256) void sba_rank(const double* __restrict__ sal, int k, int* __restrict__ order,
+                                                int* __restrict__ rank_of) {
   for (int g = threadIdx.x; g < k; g += 256) {
     double v = sal[g];
     if (v != v) v = INFINITY;
@@ -35,6 +36,7 @@ __global__ __launch_bounds__(256) void sba_rank(const double* __restrict__ sal, 
       rank += (u < v || (u == v && h < g)) ? 1 : 0;
     }
     order[rank] = g;
+    rank_of[g] = rank;
   }
 }
 
@@ -70,10 +72,13 @@ __device__ __forceinline__ double rtn_apply(const RtnParams& p, double w) {
   return p.delta0 * (q - p.z);
 }
 
-// one wavefront per (row, group); grid = ceil(n * k / 4) workgroups of 4 wavefronts
+// one wavefront per (row, group); grid = ceil(n * k / 4) workgroups of 4 wavefronts.
+// W_N goes to WN in the natural layout.  The difference to the other width a group can take is stored in
+// "search order": column block r (2 beta wide) of Dcat holds [W_{N-1} - W_N of the r-th least salient group |
+// W_{N+1} - W_N of the r-th most salient group], so that step r of the search is ONE rank-2beta update.
 __global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ W, int n, int m, int beta, int N,
-                                                     int q1_mode, double* __restrict__ WN, double* __restrict__ Dlo,
-                                                     double* __restrict__ Dhi) {
+                                                     int q1_mode, const int* __restrict__ rank_of, int pmax,
+                                                     double* __restrict__ WN, double* __restrict__ Dcat) {
   const int lane = threadIdx.x & 63;
   const int k = m / beta;
   const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -90,45 +95,30 @@ __global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ 
   mn = wave_min(mn);
   mx = wave_max(mx);
   sabs = wave_sum(sabs) / (double)beta;
-  const RtnParams pl = rtn_params(mn, mx, sabs, N - 1, q1_mode);
   const RtnParams pn = rtn_params(mn, mx, sabs, N, q1_mode);
-  const RtnParams ph = rtn_params(mn, mx, sabs, N + 1, q1_mode);
+  const int pos = rank_of[g];
+  const bool low = pos < pmax, high = pos >= k - pmax;
+  const RtnParams po = rtn_params(mn, mx, sabs, low ? N - 1 : N + 1, q1_mode);
+  const int64_t dbase = (int64_t)row * m + (low ? (int64_t)pos * 2 * beta : (int64_t)(k - 1 - pos) * 2 * beta + beta);
   for (int c = lane; c < beta; c += 64) {
     const double v = W[base + c];
     const double wn = rtn_apply(pn, v);
     WN[base + c] = wn;
-    Dlo[base + c] = rtn_apply(pl, v) - wn;
-    Dhi[base + c] = rtn_apply(ph, v) - wn;
+    if (low || high) Dcat[dbase + c] = rtn_apply(po, v) - wn;
   }
 }
 
-// device-built descriptors of the incremental updates: for step p (going from p to p+1 demoted/promoted
-// groups) two rank-beta products into the running outputs Yc
-__global__ __launch_bounds__(256) void sba_build_descs(const int* __restrict__ order, int k, int pmax, int n, int m,
-                                                       int beta, int64_t ts, const double* Dlo, const double* Dhi,
-                                                       const double* X64, double* Yc, slim_gemm_desc* descs) {
-  for (int p = threadIdx.x; p < pmax; p += 256) {
-    const int glo = order[p], ghi = order[k - 1 - p];
-    for (int h = 0; h < 2; ++h) {
-      const int g = h ? ghi : glo;
-      slim_gemm_desc d;
-      d.A = (h ? Dhi : Dlo) + (int64_t)g * beta;
-      d.lda = m;
-      d.B = X64 + (int64_t)g * beta * ts;
-      d.ldb = ts;
-      d.C = Yc;
-      d.ldc = ts;
-      d.C2 = nullptr;
-      d.ldc2 = 0;
-      d.M = n;
-      d.N = (int)ts;
-      d.K = beta;
-      d.flags = 0;
-      d.alpha = 1.0;
-      d.beta = 1.0;
-      descs[2 * p + h] = d;
-    }
-  }
+// rows of X_s in search order: row block r (2 beta rows) = [rows of the r-th least salient group ; rows of the
+// r-th most salient group]
+__global__ __launch_bounds__(256) void sba_gather_x(const double* __restrict__ X64, int64_t ts, int beta, int k,
+                                                    const int* __restrict__ order, double* __restrict__ Xcat) {
+  const int r = blockIdx.y >> 1, h = blockIdx.y & 1;
+  const int g = h ? order[k - 1 - r] : order[r];
+  const int64_t total = (int64_t)beta * ts;
+  const double* src = X64 + (int64_t)g * beta * ts;
+  double* dst = Xcat + ((int64_t)r * 2 + h) * beta * ts;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 2; i < total; i += (int64_t)gridDim.x * 512)
+    *reinterpret_cast<double2*>(dst + i) = *reinterpret_cast<const double2*>(src + i);
 }
 
 // grid (ceil(ts / 64), parts): 64 tokens x 4 row lanes per workgroup; part r owns rows [r*rpp, (r+1)*rpp)
@@ -274,36 +264,34 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   const size_t bX = slim_ws_round(sizeof(double) * (size_t)m * t_s);
   const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
   const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);
-  const size_t bDesc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * pmax + 2));
   const int kl_blocks = slim_cdiv(t_s, 256);
   const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
-  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(k + 1));
-  slim_status st = slim_ws_reserve(ctx, 4 * bW + bX + 2 * bY + bPart + bDesc + bObj + bOrd + 256);
+  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * k + 2));
+  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + bPart + bObj + bOrd + 256);
   if (st != SLIM_OK) return st;
   double* W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
   double* WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
-  double* Dlo = static_cast<double*>(slim_ws_alloc(ctx, bW));
-  double* Dhi = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  double* Dcat = static_cast<double*>(slim_ws_alloc(ctx, bW));
   double* X64 = static_cast<double*>(slim_ws_alloc(ctx, bX));
+  double* Xcat = static_cast<double*>(slim_ws_alloc(ctx, bX));
   double* Yt = static_cast<double*>(slim_ws_alloc(ctx, bY));
   double* Yc = static_cast<double*>(slim_ws_alloc(ctx, bY));
   double* partial = static_cast<double*>(slim_ws_alloc(ctx, bPart));
-  slim_gemm_desc* descs = static_cast<slim_gemm_desc*>(slim_ws_alloc(ctx, bDesc));
   double* obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
   double* block_sums = obj + (pmax + 2);
   int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
+  int* rank_of = order + (k + 1);
   int* pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
 
-  SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order);
+  SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order, rank_of);
   st = slim_widen_f64(ctx, "sba_widen_w", W, w_dtype, n, m, ldw, W64, (int64_t)m);
   if (st != SLIM_OK) return st;
   st = slim_widen_f64(ctx, "sba_widen_x", X_s, x_dtype, m, (int)t_s, ldxs, X64, t_s);
   if (st != SLIM_OK) return st;
   SLIM_LAUNCH(ctx, "sba_fakequant", sba_fakequant, dim3(slim_cdiv((int64_t)n * k, 4)), dim3(256), 0, W64, n, m, beta, N,
-              prm.q1_mode, WN, Dlo, Dhi);
+              prm.q1_mode, rank_of, pmax, WN, Dcat);
   if (pmax > 0)
-    SLIM_LAUNCH(ctx, "sba_build_descs", sba_build_descs, dim3(1), dim3(256), 0, order, k, pmax, n, m, beta, t_s, Dlo, Dhi,
-                X64, Yc, descs);
+    SLIM_LAUNCH(ctx, "sba_gather_x", sba_gather_x, dim3(64, 2 * pmax), dim3(256), 0, X64, t_s, beta, k, order, Xcat);
 
   slim_gemm_desc d;
   d.A = W64;
@@ -333,9 +321,23 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
     SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
                 block_sums + (int64_t)p * kl_blocks);
     if (p < pmax) {
-      st = slim_dgemm_batched(ctx, "sba_update_dgemm", 0, descs + 2 * p, 1, n, (int)t_s);
-      if (st != SLIM_OK) return st;
-      st = slim_dgemm_batched(ctx, "sba_update_dgemm", 0, descs + 2 * p + 1, 1, n, (int)t_s);
+      // Y_{p+1}^T = Y_p^T + [D_lo | D_hi]_p [X_lo ; X_hi]_p : one rank-2beta update
+      slim_gemm_desc u;
+      u.A = Dcat + (int64_t)p * 2 * beta;
+      u.lda = m;
+      u.B = Xcat + (int64_t)p * 2 * beta * t_s;
+      u.ldb = t_s;
+      u.C = Yc;
+      u.ldc = t_s;
+      u.C2 = nullptr;
+      u.ldc2 = 0;
+      u.M = n;
+      u.N = (int)t_s;
+      u.K = 2 * beta;
+      u.flags = 0;
+      u.alpha = 1.0;
+      u.beta = 1.0;
+      st = slim_dgemm(ctx, "sba_update_dgemm", 0, u);
       if (st != SLIM_OK) return st;
     }
   }
