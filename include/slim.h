@@ -51,7 +51,7 @@ enum { SLIM_WEIGHT_MASK_MEAN = 0, SLIM_WEIGHT_UNIFORM = 1, SLIM_WEIGHT_ELEMENT =
 enum { SLIM_Q1_SIGN = 0, SLIM_Q1_AFFINE = 1 };
 enum { SLIM_SCOPE_BLOCK = 0, SLIM_SCOPE_ROW = 1 };
 enum { SLIM_SAL_HINV_DIAG = 0, SLIM_SAL_CHOL_DIAG = 1 };
-enum { SLIM_OBJ_KL = 0 };
+enum { SLIM_OBJ_KL = 0, SLIM_OBJ_MSE = 1 };
 
 typedef struct slim_params {
   /* SQC loss weights (Eq. 5, Alg. 2 SQC lines 13-15):
@@ -126,7 +126,8 @@ slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int 
  *   groups get N-1 bits, the p most salient N+1, the rest N; the original W is fake-quantised per
  *   (row, group) with the default parameters of Eq. 1 (Eq. 2 for width 1) and the objective is
  *   sum over the t_s tokens of KL(softmax(x W^T) || softmax(x W_p^T)), softmax over the n outputs.
- *   The smallest p attaining the minimum is kept.
+ *   The smallest p attaining the minimum is kept.  objective = SLIM_OBJ_MSE replaces the KL divergence by the
+ *   squared error of the same outputs, || x W^T - x W_p^T ||_F^2 (the loss of Eq. 3; the variant of App. D).
  *   X_s       m x t_s (F16/BF16), tokens contiguous, the calibration tokens used by the objective
  *   bits      device, k bytes: the chosen width of every group
  *   p_star    host
@@ -150,7 +151,7 @@ slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, 
  *   hinv_diag_blk  beta values of [H^-1]_jj for the block's columns, needed by SLIM_WEIGHT_ELEMENT only
  *   tau       ncand candidates (device), or NULL for the default grid (then ncand is ignored)
  *   scale, zero  n doubles each;  cand_idx  n ints or NULL
- *   beta in {32, 64, 128, 256}; bits in 1..4.
+ *   beta in {32, 64, 128, 256, 512}; bits in 1..4.
  */
 slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, int n, int beta, int bits,
                                const double* omega, const double* hinv_diag_blk, const slim_params* params,
@@ -164,7 +165,9 @@ slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, i
  *   W         n x m, F16/BF16/F32, read only; the working copy (fp64) lives in the workspace
  *   U         from slim_hessian_inverse (fp64, upper triangular, zero below the diagonal)
  *   bits      device, k bytes, every value in 1..4
- *   gptq_block  must equal beta (the lazy-update block is the group)
+ *   beta        32, 64, 128, 256 or 512
+ *   gptq_block  columns swept between two trailing updates: beta, or 128 for wider groups (groups wider than
+ *               128 columns are always swept in 128-column blocks; the result does not depend on it)
  *   hinv_diag needed by SLIM_WEIGHT_ELEMENT only, else may be NULL
  *   codes     n x m bytes (ld = m);  scale, zero  n x k doubles (ld = k)
  *   What      optional dequantised weights n x m (ld = m) in what_dtype (F32 or F64), or NULL

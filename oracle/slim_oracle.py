@@ -40,6 +40,7 @@ WEIGHT_MASK_MEAN, WEIGHT_UNIFORM, WEIGHT_ELEMENT = 0, 1, 2
 Q1_SIGN, Q1_AFFINE = 0, 1
 SCOPE_BLOCK, SCOPE_ROW = 0, 1
 SAL_HINV_DIAG, SAL_CHOL_DIAG = 0, 1
+OBJ_KL, OBJ_MSE = 0, 1
 
 
 def tau_grid(lam: float = 0.1, n: int = 50) -> np.ndarray:
@@ -189,7 +190,7 @@ def bits_for_p(order: np.ndarray, k: int, N: int, p: int) -> np.ndarray:
 
 
 def sba_allocate(W: np.ndarray, group_sal: np.ndarray, beta: int, N: int, Xs: np.ndarray,
-                 q1_mode: int = Q1_SIGN):
+                 q1_mode: int = Q1_SIGN, objective: int = OBJ_KL):
     """Returns (bits[k] uint8, p_star, obj_curve[k//2 + 1], margin).
 
     Groups are ranked by salience (stable ascending sort: ties keep the lower group index
@@ -198,7 +199,9 @@ def sba_allocate(W: np.ndarray, group_sal: np.ndarray, beta: int, N: int, Xs: np
     of that p and the objective is KL(softmax(x W^T) || softmax(x W_p^T)) summed over the
     tokens of Xs (shape (m, t_s), channels x tokens).  The first p that attains the
     minimum wins (strict '<' in Alg. 2 line 12).  margin = relative gap between the best
-    and the second-best objective."""
+    and the second-best objective.  objective = OBJ_MSE replaces the KL divergence by the
+    squared error of the same layer outputs, || x W^T - x W_p^T ||_F^2 (the loss of Eq. 3; the
+    variant the paper compares against in App. D)."""
     W = np.asarray(W, dtype=np.float64)
     n, m = W.shape
     k = m // beta
@@ -209,7 +212,8 @@ def sba_allocate(W: np.ndarray, group_sal: np.ndarray, beta: int, N: int, Xs: np
     obj = np.empty(pmax + 1, dtype=np.float64)
     for p in range(pmax + 1):
         Wp = rtn_fakequant_fast(W, bits_for_p(order, k, N, p), beta, q1_mode)
-        obj[p] = softmax_kl(Y, Xs.T @ Wp.T)
+        Yp = Xs.T @ Wp.T
+        obj[p] = softmax_kl(Y, Yp) if objective == OBJ_KL else float(np.sum((Y - Yp) ** 2))
     p_star = int(np.argmin(obj))            # numpy returns the first minimum
     rest = np.delete(obj, p_star)
     margin = float("inf") if rest.size == 0 else float((rest.min() - obj[p_star]) / max(abs(obj[p_star]), 1e-300))

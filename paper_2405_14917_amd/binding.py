@@ -20,7 +20,7 @@ WEIGHT_MASK_MEAN, WEIGHT_UNIFORM, WEIGHT_ELEMENT = 0, 1, 2
 Q1_SIGN, Q1_AFFINE = 0, 1
 SCOPE_BLOCK, SCOPE_ROW = 0, 1
 SAL_HINV_DIAG, SAL_CHOL_DIAG = 0, 1
-OBJ_KL = 0
+OBJ_KL, OBJ_MSE = 0, 1
 
 _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32, torch.float64: F64}
 

@@ -406,7 +406,7 @@ slim_status allow_big_lds(slim_ctx* ctx, K kernel, bool& done) {
   return SLIM_OK;
 }
 
-bool beta_supported(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256; }
+bool beta_supported(int beta) { return beta == 32 || beta == 64 || beta == 128 || beta == 256 || beta == 512; }
 
 slim_status launch_stats_and_sqc(slim_ctx* ctx, SqcArgs a, double* stat_partial) {
   const bool need_block_stats =
@@ -453,7 +453,7 @@ extern "C" slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int
   SLIM_REQUIRE(ctx, n > 0 && ldw >= beta, "slim_sqc_calibrate: need n > 0 and ldw >= beta");
   SLIM_REQUIRE(ctx, bits >= 1 && bits <= 4, "slim_sqc_calibrate: bits must be in 1..4 (got %d)", bits);
   if (!beta_supported(beta))
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sqc_calibrate: beta must be 32, 64, 128 or 256 (got %d)", beta);
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sqc_calibrate: beta must be 32, 64, 128, 256 or 512 (got %d)", beta);
   if (!tau) {
     tau = ctx->tau_default;
     ncand = ctx->ncand_default;
@@ -498,10 +498,13 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_gptq_quantize: need n, m > 0 and beta | m");
   SLIM_REQUIRE(ctx, ldw >= m && ldw % 4 == 0 && ldu >= m && ldu % 2 == 0, "slim_gptq_quantize: bad leading dimension");
   SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(U), "slim_gptq_quantize: misaligned pointer");
-  if (!beta_supported(beta) || beta > 128)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: beta must be 32, 64 or 128 (got %d)", beta);
-  if (gptq_block != beta)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: gptq_block must equal beta");
+  if (!beta_supported(beta))
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: beta must be 32, 64, 128, 256 or 512 (got %d)", beta);
+  // The sweep works on blocks of at most 128 columns (the beta x beta block of U has to fit in LDS); wider
+  // groups are swept in 128-column blocks with a trailing update between them, which gives the same result.
+  const int SB = std::min(beta, 128);
+  if (gptq_block != beta && gptq_block != SB)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: gptq_block must be beta%s", beta > 128 ? " or 128" : "");
   if (w_dtype != SLIM_F16 && w_dtype != SLIM_BF16 && w_dtype != SLIM_F32)
     return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_gptq_quantize: W must be F16, BF16 or F32");
   if (What && what_dtype != SLIM_F32 && what_dtype != SLIM_F64)
@@ -527,12 +530,12 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   }
 
   const int nstat = slim_cdiv(n, STAT_ROWS);
-  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * beta) +
+  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * SB) +
                       slim_ws_round(sizeof(double) * 2 * nstat) + slim_ws_round(sizeof(double) * n);
   st = slim_ws_reserve(ctx, need);
   if (st != SLIM_OK) return st;
   double* Wc = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * m));
-  double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * beta));
+  double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * SB));
   double* stat_partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * 2 * nstat));
   double* row_e2 = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * n));
 
@@ -541,7 +544,7 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
 
-  const size_t sweep_smem = sizeof(double) * ((size_t)(beta + 1) * beta + 64 + beta + 64);
+  const size_t sweep_smem = sizeof(double) * ((size_t)(SB + 1) * SB + 64 + SB + 64);
   if (sweep_smem > 64 * 1024) {
     static bool done0 = false, done1 = false;
     st = allow_big_lds(ctx, gptq_sweep<2, false>, done0);
@@ -550,33 +553,36 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
     if (st != SLIM_OK) return st;
   }
 
-  for (int g = 0; g < k; ++g) {
-    const int b0 = g * beta;
-    SqcArgs a;
-    a.W = Wc + b0;
-    a.ldw = m;
-    a.n = n;
-    a.beta = beta;
-    a.bits = gb[g];
-    a.omega = nullptr;
-    a.dblk = hinv_diag ? hinv_diag + b0 : nullptr;
-    a.weight_mode = prm.sqc_weight_mode;
-    a.scope = prm.mask_scope;
-    a.q1_mode = prm.q1_mode;
-    a.tau = tau;
-    a.ncand = ncand;
-    a.scale = scale + g;
-    a.zero = zero + g;
-    a.out_stride = k;
-    a.cand_idx = nullptr;
-    st = launch_stats_and_sqc(ctx, a, stat_partial);
-    if (st != SLIM_OK) return st;
+  for (int sb = 0; sb < m / SB; ++sb) {
+    const int b0 = sb * SB;
+    const int g = b0 / beta;
+    if (b0 % beta == 0) {
+      SqcArgs a;
+      a.W = Wc + b0;
+      a.ldw = m;
+      a.n = n;
+      a.beta = beta;
+      a.bits = gb[g];
+      a.omega = nullptr;
+      a.dblk = hinv_diag ? hinv_diag + b0 : nullptr;
+      a.weight_mode = prm.sqc_weight_mode;
+      a.scope = prm.mask_scope;
+      a.q1_mode = prm.q1_mode;
+      a.tau = tau;
+      a.ncand = ncand;
+      a.scale = scale + g;
+      a.zero = zero + g;
+      a.out_stride = k;
+      a.cand_idx = nullptr;
+      st = launch_stats_and_sqc(ctx, a, stat_partial);
+      if (st != SLIM_OK) return st;
+    }
 
     SweepArgs s;
     s.W = Wc + b0;
     s.ldw = m;
     s.n = n;
-    s.beta = beta;
+    s.beta = SB;
     s.bits = gb[g];
     s.q1_mode = prm.q1_mode;
     s.U = U + (int64_t)b0 * ldu + b0;
@@ -597,7 +603,7 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
     }
     const dim3 sgrid(slim_cdiv(n, SWEEP_WAVES)), sblock(SWEEP_WAVES * 64);
     const bool sign = (gb[g] == 1 && prm.q1_mode == SLIM_Q1_SIGN);
-    if (beta <= 64) {
+    if (SB <= 64) {
       if (sign)
         SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<1, true>), sgrid, sblock, sweep_smem, s);
       else
@@ -609,20 +615,20 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
         SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, false>), sgrid, sblock, sweep_smem, s);
     }
 
-    const int rest = m - b0 - beta;
+    const int rest = m - b0 - SB;
     if (rest > 0) {
       slim_gemm_desc d;
       d.A = E;
-      d.lda = beta;
-      d.B = U + (int64_t)b0 * ldu + (b0 + beta);
+      d.lda = SB;
+      d.B = U + (int64_t)b0 * ldu + (b0 + SB);
       d.ldb = ldu;
-      d.C = Wc + (b0 + beta);
+      d.C = Wc + (b0 + SB);
       d.ldc = m;
       d.C2 = nullptr;
       d.ldc2 = 0;
       d.M = n;
       d.N = rest;
-      d.K = beta;
+      d.K = SB;
       d.flags = 0;
       d.alpha = -1.0;
       d.beta = 1.0;

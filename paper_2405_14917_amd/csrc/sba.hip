@@ -166,6 +166,44 @@ __global__ __launch_bounds__(256) void kl_partial(const double* __restrict__ Y, 
   }
 }
 
+// squared-error objective: per (part, token) the sum over the part's rows of (y - q)^2, stored in slot 4 of the
+// same partial layout so that the fixed-order reductions are shared
+__global__ __launch_bounds__(256) void mse_partial(const double* __restrict__ Y, const double* __restrict__ Q, int n,
+                                                   int64_t ts, int rows_per_part, double* __restrict__ partial) {
+  __shared__ double red[4][KL_TOK];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * KL_TOK + tx;
+  const int r0 = blockIdx.y * rows_per_part;
+  const int r1 = min(n, r0 + rows_per_part);
+  double a = 0.0;
+  if (t < ts) {
+    for (int r = r0 + ty; r < r1; r += 4) {
+      const double dlt = Y[(int64_t)r * ts + t] - Q[(int64_t)r * ts + t];
+      a = fma(dlt, dlt, a);
+    }
+  }
+  red[ty][tx] = a;
+  __syncthreads();
+  if (ty == 0 && t < ts) partial[((int64_t)blockIdx.y * ts + t) * KL_PART + 4] = ((red[0][tx] + red[1][tx]) + red[2][tx]) + red[3][tx];
+}
+
+// one thread per token: sums the row parts of its token; every workgroup of 256 tokens writes its sum
+__global__ __launch_bounds__(256) void mse_finalize(const double* __restrict__ partial, int parts, int64_t ts,
+                                                    double* __restrict__ block_sums) {
+  __shared__ double red[256];
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  double acc = 0.0;
+  if (t < ts)
+    for (int p = 0; p < parts; ++p) acc += partial[((int64_t)p * ts + t) * KL_PART + 4];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
+}
+
 // one thread per token: merges the row parts of its token; every workgroup of 256 tokens writes its sum
 __global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
                                                    double* __restrict__ block_sums) {
@@ -250,8 +288,7 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
                "slim_sba_allocate: t_s and ldxs must be positive multiples of 4");
   SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(X_s), "slim_sba_allocate: misaligned pointer");
   SLIM_REQUIRE(ctx, prm.q1_mode == 0 || prm.q1_mode == 1, "slim_sba_allocate: unknown q1_mode");
-  if (objective != SLIM_OBJ_KL)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sba_allocate: only the KL objective is built");
+  SLIM_REQUIRE(ctx, objective == SLIM_OBJ_KL || objective == SLIM_OBJ_MSE, "slim_sba_allocate: unknown objective %d", objective);
   if (w_dtype == SLIM_F64 || x_dtype == SLIM_F64 || x_dtype == SLIM_F32)
     return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sba_allocate: W must be F16/BF16/F32 and X_s F16/BF16");
   const int k = m / beta;
@@ -317,9 +354,15 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
 
   const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
   for (int p = 0; p <= pmax; ++p) {
-    SLIM_LAUNCH(ctx, "sba_kl_partial", kl_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
-    SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
-                block_sums + (int64_t)p * kl_blocks);
+    if (objective == SLIM_OBJ_KL) {
+      SLIM_LAUNCH(ctx, "sba_kl_partial", kl_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
+      SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
+                  block_sums + (int64_t)p * kl_blocks);
+    } else {
+      SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
+      SLIM_LAUNCH(ctx, "sba_mse_finalize", mse_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
+                  block_sums + (int64_t)p * kl_blocks);
+    }
     if (p < pmax) {
       // Y_{p+1}^T = Y_p^T + [D_lo | D_hi]_p [X_lo ; X_hi]_p : one rank-2beta update
       slim_gemm_desc u;

@@ -168,6 +168,21 @@ def test_sba_allocate(slim, N, beta, m, ts):
     assert set(b.tolist()) <= {N - 1, N, N + 1} and b.sum() == N * (m // beta)
 
 
+def test_sba_mse_objective(slim):
+    from paper_2405_14917_amd import binding
+    W, X = small_layer(31, n=72, m=512, t=1024, beta=64)
+    G = np.zeros((512, 512))
+    orc.gram_accumulate(G, X)
+    _, do, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
+    _, grp_o, _ = orc.salience(W, do, 64)
+    Xs = np.ascontiguousarray(X[:, :256])
+    bits_o, p_o, obj_o, margin = orc.sba_allocate(W, grp_o, 64, 3, Xs, objective=orc.OBJ_MSE)
+    bits, p_star, obj = slim.sba_allocate(dev(W), dev(grp_o), 64, 3, dev(Xs), objective=binding.OBJ_MSE)
+    assert np.allclose(obj, obj_o, rtol=1e-10)
+    if margin > MARGIN:
+        assert p_star == p_o and np.array_equal(host(bits), bits_o)
+
+
 def test_sba_ties_keep_lower_group_first(slim):
     W, X = small_layer(21, n=40, m=256, t=512, beta=64)
     gs = np.array([2.0, 1.0, 1.0, 2.0])
@@ -179,7 +194,7 @@ def test_sba_ties_keep_lower_group_first(slim):
 
 
 # ------------------------------------------------------------------------------------------ a5 + a6
-@pytest.mark.parametrize("beta", [32, 64, 128, 256])
+@pytest.mark.parametrize("beta", [32, 64, 128, 256, 512])
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_sqc_calibrate(slim, beta, bits):
     from paper_2405_14917_amd import binding
@@ -266,7 +281,7 @@ def _gptq_case(slim, W, X, bits, beta, params=None, okw=None):
     return out_o, out
 
 
-@pytest.mark.parametrize("beta,n,m", [(64, 96, 256), (128, 130, 512), (32, 50, 160)])
+@pytest.mark.parametrize("beta,n,m", [(64, 96, 256), (128, 130, 512), (32, 50, 160), (256, 70, 768), (512, 40, 1024)])
 def test_gptq_quantize(slim, beta, n, m):
     W, X = small_layer(beta + n, n=n, m=m, t=4 * m, beta=beta)
     k = m // beta
@@ -356,6 +371,9 @@ def test_invalid_arguments_are_rejected(slim):
     with pytest.raises(binding.SlimError) as ei:
         slim.gptq_quantize(W, U, dev(np.array([2, 2], dtype=np.uint8)), 64, gptq_block=128)
     assert ei.value.status == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.SlimError) as ei:
+        slim.gptq_quantize(W, U, dev(np.array([2, 2, 2, 2], dtype=np.uint8)), 48)
+    assert ei.value.status == binding.ERR_INVALID_ARG or ei.value.status == binding.ERR_UNSUPPORTED
     with pytest.raises(binding.SlimError) as ei:
         slim.sba_allocate(W, dev(np.ones(2)), 64, 5, dev(np.zeros((128, 64), dtype=np.float16)))
     assert ei.value.status == binding.ERR_INVALID_ARG

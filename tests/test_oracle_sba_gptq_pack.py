@@ -104,6 +104,20 @@ def test_sba_objective_zero_when_quantisation_is_exact():
     assert orc.softmax_kl(X.T @ W.T, X.T @ W.T) == 0.0
 
 
+def test_sba_mse_objective_is_the_trace_form():
+    # Eq. 3: || x W^T - x W_p^T ||^2 = tr(dW (X X^T) dW^T), evaluated here without forming the outputs
+    N, beta = 3, 8
+    W, X, U, d, gs = _small_layer(14)
+    k = W.shape[1] // beta
+    bits, p_star, obj, _ = orc.sba_allocate(W, gs, beta, N, X, objective=orc.OBJ_MSE)
+    order = np.argsort(gs, kind="stable")
+    G = X @ X.T
+    for p in range(k // 2 + 1):
+        dW = W - orc.rtn_fakequant(W, orc.bits_for_p(order, k, N, p), beta)
+        assert obj[p] == pytest.approx(np.trace(dW @ G @ dW.T), rel=1e-10)
+    assert p_star == int(np.argmin(obj)) and bits.astype(int).sum() == N * k
+
+
 def test_sba_stable_ties():
     # equal salience: the lower group index ranks first (is demoted first)
     rng = np.random.default_rng(13)
