@@ -81,13 +81,15 @@ def algorithmic_work(name, cfg, launches_per_step):
         return "mfma", "mfma_f64", 4.0 * n * beta * ts
     if name == "gptq_trailing_dgemm":
         return "mfma", "mfma_f64", float(n) * beta * beta * (k - 1) * (k - 2) / max(launches_per_step, 1)
-    if name == "gptq_next_dgemm":
-        return "mfma", "mfma_f64", 2.0 * n * beta * beta
-    if name == "inv_syrk_next_dgemm":
-        tot = sum(2.0 * j0 * 64 * min(64, m - j0) for j0 in range(64, m, 64))
+    if name == "inv_window_dgemm":
+        # rank-64 update of the columns between the start of the group of block J-1 and block J, rows above J-1
+        tot = sum(2.0 * (j0 - 64) * (j0 - ((j0 // 64 - 1) // 4) * 256) * min(64, m - j0) for j0 in range(128, m, 64))
+        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
+    if name == "inv_group_next_dgemm":
+        tot = sum(2.0 * g0 * 256 * (min(m, g0 + 256) - g0 - 64) for g0 in range(256, m, 256) if min(m, g0 + 256) - g0 > 64)
         return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
     if name == "inv_syrk_dgemm":
-        tot = sum(float(j0) * (j0 + 1) * min(64, m - j0) for j0 in range(64, m, 64))
+        tot = sum(float(g0 - 256) * (g0 - 255) * (min(m, g0 + 256) - g0) for g0 in range(512, m, 256))
         return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
     if name == "inv_trtri_dgemm":
         return "mfma", "mfma_f64", float(m) ** 3 / 3.0 / max(launches_per_step, 1)

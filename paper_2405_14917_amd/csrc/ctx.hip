@@ -44,6 +44,7 @@ void* slim_ws_alloc(slim_ctx* ctx, size_t bytes) {
 slim_status slim_ensure_side(slim_ctx* ctx) {
   if (ctx->side) return SLIM_OK;
   SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+  SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking));
   for (hipEvent_t& e : ctx->ev) SLIM_HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return SLIM_OK;
 }
@@ -129,6 +130,10 @@ slim_status slim_destroy(slim_ctx* ctx) {
     for (hipEvent_t e : ctx->ev)
       if (e) (void)hipEventDestroy(e);
     (void)hipStreamDestroy(ctx->side);
+    if (ctx->side2) {
+      (void)hipStreamSynchronize(ctx->side2);
+      (void)hipStreamDestroy(ctx->side2);
+    }
   }
   if (ctx->ws) (void)hipFree(ctx->ws);
   if (ctx->tau_default) (void)hipFree(ctx->tau_default);

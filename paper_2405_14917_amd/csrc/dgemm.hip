@@ -232,6 +232,19 @@ slim_status check_desc(slim_ctx* ctx, const slim_gemm_desc& d) {
   return SLIM_OK;
 }
 
+// LDS request that lets only one workgroup of the launch live on a CU (160 KiB per CU)
+constexpr size_t ONE_PER_CU_BYTES = 88 * 1024;
+
+template <typename K>
+slim_status allow_lds(slim_ctx* ctx, K kernel, bool& done) {
+  if (!done) {
+    SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)ONE_PER_CU_BYTES));
+    done = true;
+  }
+  return SLIM_OK;
+}
+
 }  // namespace
 
 slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc& d) {
@@ -247,10 +260,17 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
     return SLIM_OK;
   }
   const int tiles = slim_cdiv(d.M, 128) * slim_cdiv(d.N, 128);
+  size_t lds = smem_bytes(128, 128);
+  if (d.flags & SLIM_GEMM_ONE_PER_CU) {
+    static bool done0 = false, done1 = false;
+    st = trans_b ? allow_lds(ctx, dgemm_kernel<1, 128, 128>, done1) : allow_lds(ctx, dgemm_kernel<0, 128, 128>, done0);
+    if (st != SLIM_OK) return st;
+    lds = ONE_PER_CU_BYTES;
+  }
   if (trans_b)
-    SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 128, 128>), dim3(tiles), dim3(NTHREADS), smem_bytes(128, 128), d);
+    SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 128, 128>), dim3(tiles), dim3(NTHREADS), lds, d);
   else
-    SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 128, 128>), dim3(tiles), dim3(NTHREADS), smem_bytes(128, 128), d);
+    SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 128, 128>), dim3(tiles), dim3(NTHREADS), lds, d);
   return SLIM_OK;
 }
 

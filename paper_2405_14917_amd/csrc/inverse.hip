@@ -6,10 +6,14 @@
 // inverse, (2/3) m^3 flops instead of (4/3) m^3:
 //
 //   1. widen:   A = (2 / n_tokens) G + lambda I,  lambda = percdamp * mean(diag(2 / n_tokens G))
-//   2. for the diagonal blocks J = last .. first (64 columns each):
-//        chol_diag   A_JJ = R_JJ R_JJ^T in LDS by one workgroup, plus V_JJ = R_JJ^-1 (written into U)
-//        panel       R[0:J, J] = A[0:J, J] V_JJ^T                    (fp64 MFMA GEMM)
-//        update      A[0:J, 0:J] -= R[0:J, J] R[0:J, J]^T, upper tiles only   (fp64 MFMA GEMM)
+//   2. for the diagonal blocks J = last .. first (64 columns each; four of them form a group):
+//        chol_step   one workgroup: applies the last pending rank-64 update to A_JJ itself, factors
+//                    A_JJ = R_JJ R_JJ^T in LDS and inverts R_JJ (V_JJ, written into U)
+//        panel       R[0:J, J] = A[0:J, J] V_JJ^T                            (fp64 MFMA GEMM)
+//        update      rank-64 update of the columns between the start of block J-1's group and block J
+//        group update  rank-256 updates of everything further left, once per group
+//      The factorisation of the diagonal blocks and the GEMMs form two chains on two streams that only
+//      meet two steps apart, see the schedule at the call site.
 //   3. triangular inverse by recursive doubling: ranges of 2^l diagonal blocks that are already inverted
 //      are merged pairwise, U12 = -U11 (R12 U22); all pairs of a level form one batched GEMM launch.
 //   4. hinv_diag_j = sum_i U_ij^2.
@@ -17,6 +21,8 @@
 #include "slim_internal.h"
 
 namespace {
+
+using slimdev::read_lane_f64;
 
 constexpr int NB = 64;          // diagonal block
 
@@ -65,105 +71,239 @@ __device__ __forceinline__ double fast_rcp(double x) {
   return r;
 }
 
-// One workgroup (16 wavefronts) factors the nbk x nbk diagonal block at A (upper triangle valid) as R R^T
-// with R upper triangular, from the last column to the first, writes R back (zero below the diagonal) and
-// its inverse V into Vout.  A non-positive pivot is recorded in flag[0] (1-based global column) and
-// replaced by 1.
+typedef double double4v __attribute__((ext_vector_type(4)));
+
+struct CholArgs {
+  const double* A;       // A[j0][j0]: the diagonal block (upper triangle valid)
+  int64_t lda;
+  int nbk;               // width of this block (64, less for a ragged last block)
+  int nprev;             // width of block J+1 whose rank-64 update is still pending on this block (0: none)
+  const double* Vprev;   // V of block J+1 (in U)
+  double* Vout;          // V of this block (in U)
+  int64_t ldv;
+  int* flag;
+  int col_base;
+};
+
+
+// One workgroup (16 wavefronts) per diagonal block:
+//   prologue   (nprev > 0)  Rn = A[J, J+1] V_{J+1}^T and A_JJ -= Rn Rn^T on the matrix cores: the update
+//              with the panel of block J+1 restricted to this block, so that this kernel does not have to
+//              wait for the GEMMs of block J+1
+//   factor     A_JJ = R R^T with R upper triangular, from the last column to the first, and in its shadow
+//   invert     V = R^-1, written to Vout (zeros below the diagonal)
+// A non-positive pivot is recorded in flag[0] (1-based global column); the outputs are then meaningless.
 //
-// A lone wavefront issues roughly one instruction every 8 cycles on this chip, so the kernel is built to
-// execute few instructions per elimination step: lane = row, wavefront w owns columns w, w+16, w+32, w+48
-// in four registers.  The pivot column therefore sits in ONE register of ONE wavefront and is broadcast
-// with a single 64-lane LDS store; which columns still take part in a step is known statically (register
-// index) or per wavefront (scalar), never per lane.  Entries below the diagonal are never read.
-__global__ __launch_bounds__(1024) void chol_diag(double* __restrict__ A, int64_t lda, int nbk, double* __restrict__ Vout,
-                                                  int64_t ldv, int* __restrict__ flag, int col_base) {
+// With a_j the column of pivot j at the time it is eliminated, p_j its diagonal entry and s_j = a_j / p_j,
+// R = [s_j] diag(sqrt p_j), and R^-1 = diag(1 / sqrt p_j) E where E results from the identity by the row
+// operations row_i -= s_j[i] row_j (i < j) in the order of the elimination.  E has columns, a column c is only
+// touched by pivots j <= c, i.e. once the column c of A is finished: the wavefronts that are done factoring
+// carry the inverse, the others the factorisation, and no separate inversion pass is needed.
+//
+// A lone wavefront issues an instruction every ~8 cycles and a dependent fp64 one every ~32, and an LDS
+// write -> barrier -> read costs ~200 cycles, so the elimination is blocked by four columns: lane = row,
+// wavefront w owns columns 4w .. 4w+3 of A and of E in registers.  The owner of the current four columns reads
+// their 4 x 4 diagonal block with lane reads, runs its elimination on wavefront-uniform values (the serial
+// chain: four reciprocals and the pivot updates between them), finishes the four columns, and publishes them
+// and the s_j through LDS once; the other wavefronts apply a rank-4 update to their columns of A or E:
+// 16 barriers instead of 128.  Entries of A below the diagonal are never read as values that matter.
+__global__ __launch_bounds__(1024) void chol_step(CholArgs g) {
   constexpr int LD = NB + 1;
-  __shared__ double Rs[NB * LD];       // the block (row-major), later R, later V
-  __shared__ double cb[2][NB];         // broadcast column, double buffered
-  __shared__ double diag[NB], rdiag[NB];
+  extern __shared__ __align__(16) double sm[];
+  double* Rs = sm;                 // [64][LD] staging: the block, then A[J, J+1], then Rn; later 1 / sqrt(pivot)
+  double* Xs = sm + NB * LD;       // [64][LD] staging: V_{J+1}, then Rn Rn^T; then the broadcast buffers; then V
+  double* cbA = Xs;                // [2][4][64] published columns
+  double* cbS = Xs + 512;          // [2][4][64] the same divided by their pivots, zero at and below the pivot
+  double* cbE = Xs + 1024;         // [2][4][64] combinations of the latter that drive the inverse
+  double* rsq = Rs;                // [64]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  // coalesced load (lane = column), identity padding of a ragged block
-  for (int r = w; r < NB; r += 16) {
-    double v = (r == lane) ? 1.0 : 0.0;
-    if (r < nbk && lane < nbk) v = (lane >= r) ? A[(int64_t)r * lda + lane] : 0.0;
-    Rs[r * LD + lane] = v;
+  const int nbk = g.nbk, np = g.nprev;
+  const int prior_flag = g.flag[0];
+  // every global load is issued up front, coalesced (lane = column): the block (identity padding of a ragged
+  // one), and for the prologue A[J, J+1] and V_{J+1} (zero padding)
+  double ld_d[4], ld_a[4], ld_v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = w + 16 * i;
+    ld_d[i] = (r == lane) ? 1.0 : 0.0;
+    if (r < nbk && lane < nbk) ld_d[i] = (lane >= r) ? g.A[(int64_t)r * g.lda + lane] : 0.0;
+    ld_a[i] = 0.0;
+    ld_v[i] = 0.0;
+    if (np > 0) {
+      if (lane < np) ld_a[i] = g.A[(int64_t)r * g.lda + NB + lane];
+      if (r < np && lane < np && lane >= r) ld_v[i] = g.Vprev[(int64_t)r * g.ldv + lane];
+    }
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) Rs[(w + 16 * i) * LD + lane] = ld_d[i];
   __syncthreads();
-  double a[4], b[4];
+  double a[4], e[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    a[q] = Rs[lane * LD + w + 16 * q];
-    b[q] = (lane == w + 16 * q) ? 1.0 : 0.0;
+    a[q] = Rs[lane * LD + 4 * w + q];
+    e[q] = (lane == 4 * w + q) ? 1.0 : 0.0;
   }
-  // ---- factorisation: after step j, column j holds R[:, j] * R[j][j] (scaled afterwards)
+  if (np > 0) {
+    // Rn = A[J, J+1] V^T, then A_JJ -= Rn Rn^T, as 16 x 16 MFMA tiles.  Operand lane (l16, lk) feeds row / column
+    // l16 at k = 16 lk + s in step s (any assignment of k works as long as both operands share it); result
+    // register v is row 4 v + lk, column l16 of the tile.
+    const int l16 = lane & 15, lk = lane >> 4;
+    __syncthreads();
 #pragma unroll
-  for (int qj = 3; qj >= 0; --qj) {
-    for (int wj = 15; wj >= 0; --wj) {
-      const int j = 16 * qj + wj;
-      double* c = cb[j & 1];
-      if (w == wj) c[lane] = a[qj];
+    for (int i = 0; i < 4; ++i) {
+      Rs[(w + 16 * i) * LD + lane] = ld_a[i];
+      Xs[(w + 16 * i) * LD + lane] = ld_v[i];
+    }
+    __syncthreads();
+    {
+      // tile (ti, tj); V[c][k] = 0 for k < c, so tile column tj needs k >= 16 tj only: lane groups lk >= tj.
+      // Wavefronts that share a SIMD (w mod 4) get different tj, which balances the work.
+      const int ti = w & 3, tj = w >> 2;
+      double4v acc = {0.0, 0.0, 0.0, 0.0};
+      const double* ap = Rs + (16 * ti + l16) * LD + 16 * lk;
+      const double* bp = Xs + (16 * tj + l16) * LD + 16 * lk;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[s], bp[s], acc, 0, 0, 0);
       __syncthreads();
-      double piv = c[j];
-      if (!(piv > 0.0)) {                                 // uniform over the workgroup, rare
-        if (tid == 0 && j < nbk && flag[0] == 0) flag[0] = col_base + j + 1;
-        piv = 1.0;
-        if (w == wj && lane == j) a[qj] = 1.0;            // keep the sanitised pivot for the scaling pass
-      }
-      const double s = c[lane] * fast_rcp(piv);           // a[i][j] / pivot for this lane's row
-      // columns of registers below qj are all left of j; register qj itself only in wavefronts left of wj
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (q < qj) a[q] -= s * c[w + 16 * q];
+      for (int v = 0; v < 4; ++v) Rs[(16 * ti + 4 * v + lk) * LD + 16 * tj + l16] = acc[v];
+    }
+    __syncthreads();
+    if (w < 10) {
+      // the ten tiles on and above the diagonal, dealt round the SIMDs
+      const int ti = (w < 4) ? 0 : ((w < 7) ? 1 : ((w < 9) ? 2 : 3));
+      const int tj = (w < 4) ? w : ((w < 7) ? w - 3 : ((w < 9) ? w - 5 : 3));
+      double4v acc = {0.0, 0.0, 0.0, 0.0};
+      const double* ap = Rs + (16 * ti + l16) * LD + 16 * lk;
+      const double* bp = Rs + (16 * tj + l16) * LD + 16 * lk;
+#pragma unroll
+      for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[s], bp[s], acc, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Xs[(16 * ti + 4 * v + lk) * LD + 16 * tj + l16] = acc[v];
+    }
+    __syncthreads();
+    // below the diagonal Xs still holds entries of V: finite, and never used as values that matter
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a[q] -= Xs[lane * LD + 4 * w + q];
+  }
+  __syncthreads();   // Rs and Xs are free from here on
+  int bad = 0;       // owner only: a non-positive pivot in this lane's column
+
+  // E lags one step behind: in step wj the wavefronts right of the owner apply the row operations of the
+  // pivots of step wj+1, whose owner prepared them after its barrier, off the critical path.
+  auto e_update = [&](const double* bE, int jp) {
+    double sp[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sp[r] = bE[r * 64 + lane];
+#pragma unroll
+    for (int q2 = 0; q2 < 4; ++q2) {
+      const double x0 = read_lane_f64(e[q2], jp), x1 = read_lane_f64(e[q2], jp + 1);
+      const double x2 = read_lane_f64(e[q2], jp + 2), x3 = read_lane_f64(e[q2], jp + 3);
+      e[q2] = fma(-sp[0], x0, fma(-sp[1], x1, fma(-sp[2], x2, fma(-sp[3], x3, e[q2]))));
+    }
+  };
+  for (int wj = 15; wj >= 0; --wj) {
+    double* bA = cbA + (wj & 1) * 256;
+    double* bS = cbS + (wj & 1) * 256;
+    const int jb = 4 * wj;
+    double pj = 1.0, sv0 = 0.0, sv1 = 0.0, sv2 = 0.0, sv3 = 0.0;
+    if (w == wj) {
+      // the 4 x 4 diagonal block of the owner's columns: D_rc = a[c] at row jb + r  (r <= c), uniform values
+      const double D33 = read_lane_f64(a[3], jb + 3), D23 = read_lane_f64(a[3], jb + 2);
+      const double D13 = read_lane_f64(a[3], jb + 1), D03 = read_lane_f64(a[3], jb + 0);
+      const double D22 = read_lane_f64(a[2], jb + 2), D12 = read_lane_f64(a[2], jb + 1);
+      const double D02 = read_lane_f64(a[2], jb + 0), D11 = read_lane_f64(a[1], jb + 1);
+      const double D01 = read_lane_f64(a[1], jb + 0), D00 = read_lane_f64(a[0], jb + 0);
+      // elimination of the block on uniform values; the chain is r3 -> p2 -> r2 -> p1 -> r1 -> p0 -> r0
+      const double r3 = fast_rcp(D33);
+      const double p2 = fma(-(D23 * D23), r3, D22);
+      const double E12 = fma(-(D13 * D23), r3, D12);       // entries after pivot 3
+      const double E02 = fma(-(D03 * D23), r3, D02);
+      const double E11 = fma(-(D13 * D13), r3, D11);
+      const double E01 = fma(-(D03 * D13), r3, D01);
+      const double E00 = fma(-(D03 * D03), r3, D00);
+      const double r2 = fast_rcp(p2);
+      const double p1 = fma(-(E12 * E12), r2, E11);
+      const double F01 = fma(-(E02 * E12), r2, E01);       // entries after pivot 2
+      const double F00 = fma(-(E02 * E02), r2, E00);
+      const double r1 = fast_rcp(p1);
+      const double p0 = fma(-(F01 * F01), r1, F00);
+      const double r0 = fast_rcp(p0);
+      // the four columns as they stand when they are eliminated, and s_j = a_j / p_j
+      const double s3 = a[3] * r3;
+      a[2] = fma(-s3, D23, a[2]);
+      const double s2 = a[2] * r2;
+      a[1] = fma(-s2, E12, fma(-s3, D13, a[1]));
+      const double s1 = a[1] * r1;
+      a[0] = fma(-s1, F01, fma(-s2, E02, fma(-s3, D03, a[0])));
+      const double s0 = a[0] * r0;
+      // rows at and below the pivot take no part in the row operations
+      sv0 = (lane < jb + 0) ? s0 : 0.0;
+      sv1 = (lane < jb + 1) ? s1 : 0.0;
+      sv2 = (lane < jb + 2) ? s2 : 0.0;
+      sv3 = (lane < jb + 3) ? s3 : 0.0;
+      bA[0 * 64 + lane] = a[0];
+      bA[1 * 64 + lane] = a[1];
+      bA[2 * 64 + lane] = a[2];
+      bA[3 * 64 + lane] = a[3];
+      bS[0 * 64 + lane] = sv0;
+      bS[1 * 64 + lane] = sv1;
+      bS[2 * 64 + lane] = sv2;
+      bS[3 * 64 + lane] = sv3;
+      pj = (lane == jb + 3) ? D33 : ((lane == jb + 2) ? p2 : ((lane == jb + 1) ? p1 : p0));
+    }
+    __syncthreads();
+    if (w < wj) {
+      // factorisation: rank-4 update of this wavefront's columns of A
+      double s4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) s4[q] = bS[q * 64 + lane];
+#pragma unroll
+      for (int q = 3; q >= 0; --q) {
+        const double2 c01 = *reinterpret_cast<const double2*>(&bA[q * 64 + 4 * w]);
+        const double2 c23 = *reinterpret_cast<const double2*>(&bA[q * 64 + 4 * w + 2]);
+        a[0] = fma(-s4[q], c01.x, a[0]);
+        a[1] = fma(-s4[q], c01.y, a[1]);
+        a[2] = fma(-s4[q], c23.x, a[2]);
+        a[3] = fma(-s4[q], c23.y, a[3]);
       }
-      if (w < wj) a[qj] -= s * c[w + 16 * qj];
+    } else if (w == wj) {
+      // Off the chain.  With x_r the entries of a column of E in the pivot rows before this block's row
+      // operations, the rows the four operations use are
+      //   y3 = x3, y2 = x2 - t32 y3, y1 = x1 - t31 y3 - t21 y2, y0 = x0 - t30 y3 - t20 y2 - t10 y1,  t_qr = s_q[jb+r],
+      // and every row i loses sum_q s_q[i] y_q = sum_r s'_r[i] x_r; the s'_r are published for the next step.
+      const double t32 = read_lane_f64(sv3, jb + 2), t31 = read_lane_f64(sv3, jb + 1), t30 = read_lane_f64(sv3, jb);
+      const double t21 = read_lane_f64(sv2, jb + 1), t20 = read_lane_f64(sv2, jb), t10 = read_lane_f64(sv1, jb);
+      const double L13 = fma(t21, t32, -t31);
+      const double L02 = fma(t10, t21, -t20);
+      const double L03 = fma(-t10, L13, fma(t20, t32, -t30));
+      double* bE = cbE + (wj & 1) * 256;
+      bE[0 * 64 + lane] = sv0;
+      bE[1 * 64 + lane] = fma(-t10, sv0, sv1);
+      bE[2 * 64 + lane] = fma(L02, sv0, fma(-t21, sv1, sv2));
+      bE[3 * 64 + lane] = fma(L03, sv0, fma(L13, sv1, fma(-t32, sv2, sv3)));
+      if (lane >= jb && lane < jb + 4) {
+        rsq[lane] = 1.0 / sqrt(pj);                        // for the final scaling
+        if (!(pj > 0.0) && lane < nbk) bad = 1;
+      }
+    } else {
+      e_update(cbE + ((wj + 1) & 1) * 256, jb + 4);
     }
   }
-  // ---- scale: R[i][j] = a[i][j] / sqrt(a[j][j]); zeros below the diagonal; R goes to LDS
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    if (lane == w + 16 * q) {
-      const double d = sqrt(a[q]);
-      diag[lane] = d;
-      rdiag[lane] = 1.0 / d;
-    }
   __syncthreads();
+  e_update(cbE, 0);   // the pivots of the last step (columns 0 .. 3) act on every column
+  // the first failure in elimination order is kept: the highest column of the first block that fails
+  if (bad && prior_flag == 0) atomicMax(g.flag, g.col_base + lane + 1);
+  __syncthreads();   // every wavefront is done with the broadcast buffers, which V now overwrites
+  const double rs = rsq[lane];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int cq = w + 16 * q;
-    a[q] = (lane < cq) ? a[q] * rdiag[cq] : ((lane == cq) ? diag[cq] : 0.0);
-    Rs[lane * LD + cq] = a[q];
-  }
+  for (int q = 0; q < 4; ++q) Xs[lane * LD + 4 * w + q] = e[q] * rs;
   __syncthreads();
   for (int r = w; r < NB; r += 16)
-    if (r < nbk && lane < nbk) A[(int64_t)r * lda + lane] = Rs[r * LD + lane];
-  // ---- inverse: V R = I, columns from left to right.  Column c of V is final once the columns left of it
-  //      have been eliminated; it is broadcast and subtracted from the columns to its right.
-#pragma unroll
-  for (int qc = 0; qc < 4; ++qc) {
-    for (int wc = 0; wc < 16; ++wc) {
-      const int cc = 16 * qc + wc;
-      double* c = cb[cc & 1];
-      if (w == wc) {
-        b[qc] *= rdiag[cc];
-        c[lane] = b[qc];
-      }
-      __syncthreads();
-      const double v = c[lane];
-      const double* rrow = Rs + cc * LD;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (q > qc) b[q] -= v * rrow[w + 16 * q];
-      }
-      if (w > wc) b[qc] -= v * rrow[w + 16 * qc];
-    }
-  }
-  __syncthreads();   // every wavefront is done reading R from LDS
-#pragma unroll
-  for (int q = 0; q < 4; ++q) Rs[lane * LD + w + 16 * q] = b[q];
-  __syncthreads();
-  for (int r = w; r < NB; r += 16)
-    if (r < nbk && lane < nbk) Vout[(int64_t)r * ldv + lane] = (lane >= r) ? Rs[r * LD + lane] : 0.0;
+    if (r < nbk && lane < nbk) g.Vout[(int64_t)r * g.ldv + lane] = (lane >= r) ? Xs[r * LD + lane] : 0.0;
 }
+
+constexpr size_t CHOL_LDS = sizeof(double) * 2 * NB * (NB + 1);
 
 // partial column sums of squares of the upper triangle of U: grid (ceil(m/64), parts); part p owns 256 rows
 __global__ __launch_bounds__(256) void colsumsq_upper(const double* __restrict__ U, int64_t ldu, int m,
@@ -216,15 +356,15 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   struct Level { int first, count, maxM, maxN; };
   std::vector<Level> levels;
 
+  // A: the matrix being factored (upper triangle), later the scratch of the triangular inverse.
+  // R: the factor, panel by panel (only the blocks above the diagonal are ever written or read).
   const size_t bytes_A = slim_ws_round(sizeof(double) * (size_t)m * m);
-  const size_t bytes_P = slim_ws_round(sizeof(double) * (size_t)m * NB * 2);   // two panels (double buffer)
   const size_t bytes_part = slim_ws_round(sizeof(double) * (size_t)parts * m);
   const size_t bytes_desc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * nblk + 8));
-  slim_status st = slim_ws_reserve(ctx, 2 * bytes_A + bytes_P + bytes_part + bytes_desc + 256);
+  slim_status st = slim_ws_reserve(ctx, 2 * bytes_A + bytes_part + bytes_desc + 256);
   if (st != SLIM_OK) return st;
   double* A = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
-  double* T = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
-  double* P = static_cast<double*>(slim_ws_alloc(ctx, bytes_P));
+  double* R = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
   double* partial = static_cast<double*>(slim_ws_alloc(ctx, bytes_part));
   slim_gemm_desc* descs_dev = static_cast<slim_gemm_desc*>(slim_ws_alloc(ctx, bytes_desc));
   double* lam = static_cast<double*>(slim_ws_alloc(ctx, 256));
@@ -244,12 +384,12 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       const int64_t mid = lo + sz, hi = std::min<int64_t>(lo + 2 * sz, m);
       const int a = (int)sz, b = (int)(hi - mid);
       slim_gemm_desc d;
-      // T12 = R12 * U22
-      d.A = A + lo * lda + mid;
+      // T12 = R12 * U22 (into the scratch, at the position of the block)
+      d.A = R + lo * lda + mid;
       d.lda = lda;
       d.B = U + mid * ldu + mid;
       d.ldb = ldu;
-      d.C = T + lo * lda + mid;
+      d.C = A + lo * lda + mid;
       d.ldc = lda;
       d.C2 = nullptr;
       d.ldc2 = 0;
@@ -270,7 +410,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   // second product of every pair: U12 = -U11 * T12
   for (int i = 0; i < n_first; ++i) {
     const slim_gemm_desc& t = descs[i];
-    const int64_t off = t.C - T;   // element offset of the (lo, mid) block
+    const int64_t off = t.C - A;   // element offset of the (lo, mid) block
     const int64_t lo = off / lda, mid = off % lda;
     slim_gemm_desc d;
     d.A = U + lo * ldu + lo;
@@ -299,88 +439,161 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
                                      hipMemcpyHostToDevice, ctx->stream));
   }
 
-  // ---- factorisation from the bottom-right corner upwards, with one block of lookahead:
-  //   main stream : diag(J) -> panel(J) -> update of block column J-1 only -> diag(J-1) -> ...
-  //   side stream : the bulk of the symmetric update of block J (all columns left of block J-1)
-  // The bulk update therefore runs while the next diagonal block is being factored.  Events order the two
-  // streams: the bulk of block J starts after panel(J); the main stream touches block column J-2 (and
-  // reuses the panel buffer of block J) only after the bulk of block J has finished.
+  // ---- factorisation from the bottom-right corner upwards.  Blocks of 64 columns, groups of GRP blocks;
+  //      "the window of block K" = the columns from the start of the group of block K-1 up to block K.
+  //   s0 (caller's stream)  step(J): the diagonal-block kernel; it applies the update with panel J+1 to A_JJ
+  //                         itself, so it depends on step(J+1) and on the GEMMs of block J+2 only
+  //   s1  gemm(K):          panel R[0:K, K] = A[0:K, K] V_KK^T
+  //                         A[rows above block K-1, window of K] -= R[.., K] R[window, K]^T        (rank 64)
+  //                         and, when K is the second block of its group G (all other panels of G are done):
+  //                         A[0:G, columns of group G-1] -= the panels of G except the first block's
+  //   s2  far(G):           A[left of group G-1]^2 -= all panels of G, upper tiles only            (rank 256)
+  // Every element of A thus receives each panel's contribution exactly once: from far() if it lies two or more
+  // groups to the left, from the group update if one group to the left (the first block's panel comes through
+  // that block's window), from a window update inside the group, and from the diagonal kernel for the
+  // neighbouring diagonal block.  gemm(K) runs while step(K-1) runs; step(K-2) waits for it.
   st = slim_ensure_side(ctx);
   if (st != SLIM_OK) return st;
-  hipStream_t s0 = ctx->stream, s1 = ctx->side;
+  {
+    static bool done = false;
+    if (!done) {
+      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(chol_step),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)CHOL_LDS));
+      done = true;
+    }
+  }
+  constexpr int GRP = 4;
+  hipStream_t s0 = ctx->stream, s1 = ctx->side, s2 = ctx->side2;
   hipEvent_t ev_fork = ctx->ev[0];
-  hipEvent_t ev_panel[2] = {ctx->ev[1], ctx->ev[2]};
-  hipEvent_t ev_bulk[2] = {ctx->ev[3], ctx->ev[4]};
-  bool bulk_issued[2] = {false, false};
+  hipEvent_t* ev_step = &ctx->ev[1];   // ring of 4
+  hipEvent_t* ev_gemm = &ctx->ev[5];   // ring of 4
+  hipEvent_t* ev_far = &ctx->ev[9];    // ring of 2
   SLIM_HIP_TRY(ctx, hipEventRecord(ev_fork, s0));
   SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_fork, 0));
+  SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s2, ev_fork, 0));
   struct StreamSwap {
     slim_ctx* c;
     hipStream_t keep;
     StreamSwap(slim_ctx* cc, hipStream_t s) : c(cc), keep(cc->stream) { c->stream = s; }
     ~StreamSwap() { c->stream = keep; }
   };
-  for (int blk = nblk - 1; blk >= 0; --blk) {
-    const int j0 = blk * NB;
+  bool far_issued = false;
+  int last_far_slot = 0;
+  for (int J = nblk - 1; J >= 0; --J) {
+    const int j0 = J * NB;
     const int nbk = std::min(NB, m - j0);
-    const int pb = blk & 1;
-    double* Pb = P + (size_t)pb * m * NB;
-    SLIM_LAUNCH(ctx, "inv_chol_diag", chol_diag, dim3(1), dim3(1024), 0, A + (int64_t)j0 * lda + j0, lda, nbk,
-                U + (int64_t)j0 * ldu + j0, ldu, flag, j0);
-    if (j0 == 0) break;
-    slim_gemm_desc d;
-    d.A = A + j0;                       // A[0:j0, j0:j0+nbk]
-    d.lda = lda;
-    d.B = U + (int64_t)j0 * ldu + j0;   // V_JJ, used transposed
-    d.ldb = ldu;
-    d.C = Pb;
-    d.ldc = NB;
-    d.C2 = A + j0;                      // the panel of R replaces the panel of A
-    d.ldc2 = lda;
-    d.M = j0;
-    d.N = nbk;
-    d.K = nbk;
-    d.flags = 0;
-    d.alpha = 1.0;
-    d.beta = 0.0;
-    st = slim_dgemm(ctx, "inv_panel_dgemm", 1, d);
-    if (st != SLIM_OK) return st;
-    SLIM_HIP_TRY(ctx, hipEventRecord(ev_panel[pb], s0));
-    // block column J-1 was last written by the bulk update of block J+1
-    if (bulk_issued[pb ^ 1]) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_bulk[pb ^ 1], 0));
-    const int jn = j0 - NB;             // first column of block J-1 (j0 is a multiple of NB here)
-    d.A = Pb;
-    d.lda = NB;
-    d.B = Pb + (size_t)jn * NB;         // rows of the panel that belong to block J-1
-    d.ldb = NB;
-    d.C = A + jn;
-    d.ldc = lda;
-    d.C2 = nullptr;
-    d.ldc2 = 0;
-    d.M = j0;
-    d.N = NB;
-    d.K = nbk;
-    d.flags = 0;
-    d.alpha = -1.0;
-    d.beta = 1.0;
-    st = slim_dgemm(ctx, "inv_syrk_next_dgemm", 1, d);
-    if (st != SLIM_OK) return st;
-    if (jn > 0) {
+    // ---- s0: diagonal block
+    if (J + 2 <= nblk - 1) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_gemm[(J + 2) & 3], 0));
+    CholArgs ca;
+    ca.A = A + (int64_t)j0 * lda + j0;
+    ca.lda = lda;
+    ca.nbk = nbk;
+    ca.nprev = (J < nblk - 1) ? std::min(NB, m - (j0 + NB)) : 0;
+    ca.Vprev = U + (int64_t)(j0 + NB) * ldu + (j0 + NB);
+    ca.Vout = U + (int64_t)j0 * ldu + j0;
+    ca.ldv = ldu;
+    ca.flag = flag;
+    ca.col_base = j0;
+    SLIM_LAUNCH(ctx, "inv_chol_diag", chol_step, dim3(1), dim3(1024), CHOL_LDS, ca);
+    if (J == 0) break;
+    SLIM_HIP_TRY(ctx, hipEventRecord(ev_step[J & 3], s0));
+
+    // ---- s1: GEMMs of block J
+    const int G = J / GRP;                          // group of block J
+    const int g0 = G * GRP * NB;                    // first column of the group
+    const int g1 = std::min(m, g0 + GRP * NB);      // one past its last column
+    const int wstart = ((J - 1) / GRP) * GRP * NB;  // window: from the start of the group of block J-1 ...
+    const int jn = j0 - NB;                         // ... to block J; rows above block J-1 take part
+    {
       StreamSwap swap(ctx, s1);
-      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_panel[pb], 0));
-      d.B = Pb;
+      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_step[J & 3], 0));
+      slim_gemm_desc d;
+      d.A = A + j0;                       // A[0:j0, j0:j0+nbk]
+      d.lda = lda;
+      d.B = U + (int64_t)j0 * ldu + j0;   // V_JJ, used transposed
+      d.ldb = ldu;
+      d.C = R + j0;
+      d.ldc = lda;
+      d.C2 = nullptr;
+      d.ldc2 = 0;
+      d.M = j0;
+      d.N = nbk;
+      d.K = nbk;
+      d.flags = 0;
+      d.alpha = 1.0;
+      d.beta = 0.0;
+      st = slim_dgemm(ctx, "inv_panel_dgemm", 1, d);
+      if (st != SLIM_OK) return st;
+      if (jn > 0) {
+        // the window of the first block of a group lies in the group to the left, which far() of the group
+        // before this one also writes
+        if (wstart < g0 && far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_far[last_far_slot], 0));
+        d.A = R + j0;                               // rows 0 .. jn of the panel
+        d.lda = lda;
+        d.B = R + (int64_t)wstart * lda + j0;       // rows of the panel that belong to the window
+        d.ldb = lda;
+        d.C = A + wstart;
+        d.ldc = lda;
+        d.M = jn;
+        d.N = j0 - wstart;
+        d.K = nbk;
+        d.alpha = -1.0;
+        d.beta = 1.0;
+        st = slim_dgemm(ctx, "inv_window_dgemm", 1, d);
+        if (st != SLIM_OK) return st;
+      }
+      if (J == G * GRP + 1 && g0 > 0) {
+        // every panel of the group except the first block's is complete: bring the group to the left up to date
+        const int gp = g0 - GRP * NB;               // first column of the group to the left
+        if (far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_far[last_far_slot], 0));
+        d.A = R + j0;                               // R[0:g0, j0:g1]
+        d.lda = lda;
+        d.B = R + (int64_t)gp * lda + j0;
+        d.ldb = lda;
+        d.C = A + gp;
+        d.ldc = lda;
+        d.M = g0;
+        d.N = g0 - gp;
+        d.K = g1 - j0;
+        d.alpha = -1.0;
+        d.beta = 1.0;
+        st = slim_dgemm(ctx, "inv_group_next_dgemm", 1, d);
+        if (st != SLIM_OK) return st;
+      }
+      SLIM_HIP_TRY(ctx, hipEventRecord(ev_gemm[J & 3], s1));
+    }
+    // ---- s2: everything two or more groups to the left, once all panels of the group exist
+    if (J == G * GRP && g0 - GRP * NB > 0) {
+      StreamSwap swap(ctx, s2);
+      const int gp = g0 - GRP * NB;
+      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s2, ev_gemm[J & 3], 0));
+      slim_gemm_desc d;
+      d.A = R + g0;                                 // R[0:gp, g0:g1]
+      d.lda = lda;
+      d.B = R + g0;
+      d.ldb = lda;
       d.C = A;
-      d.M = jn;
-      d.N = jn;
-      d.flags = SLIM_GEMM_UPPER_ONLY;
+      d.ldc = lda;
+      d.C2 = nullptr;
+      d.ldc2 = 0;
+      d.M = gp;
+      d.N = gp;
+      d.K = g1 - g0;
+      // While this update is short next to the four diagonal steps it runs beside, it takes one workgroup slot
+      // per CU and so leaves room for their kernels; a large one is throughput-bound and takes the whole chip.
+      d.flags = SLIM_GEMM_UPPER_ONLY | (gp <= 4096 ? SLIM_GEMM_ONE_PER_CU : 0);
+      d.alpha = -1.0;
+      d.beta = 1.0;
       st = slim_dgemm(ctx, "inv_syrk_dgemm", 1, d);
       if (st != SLIM_OK) return st;
-      SLIM_HIP_TRY(ctx, hipEventRecord(ev_bulk[pb], s1));
-      bulk_issued[pb] = true;
+      last_far_slot ^= 1;
+      SLIM_HIP_TRY(ctx, hipEventRecord(ev_far[last_far_slot], s2));
+      far_issued = true;
     }
   }
-  for (int i = 0; i < 2; ++i)
-    if (bulk_issued[i]) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_bulk[i], 0));
+  // the triangular inverse reads every panel of R and overwrites A
+  if (nblk > 1) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_gemm[1 & 3], 0));
+  if (far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_far[last_far_slot], 0));
 
   // ---- triangular inverse U = R^-1: two batched GEMM launches per level
   if (!descs.empty()) {

@@ -25,6 +25,8 @@ struct slim_prof_pending {
   hipEvent_t start, stop;
 };
 
+constexpr int SLIM_NUM_EVENTS = 16;
+
 struct slim_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
@@ -38,9 +40,9 @@ struct slim_ctx {
   int ncand_default = 0;
   int* dflags = nullptr;          // device, 64 ints (pivot failures, counters)
   char* hpin = nullptr;           // pinned host staging, SLIM_HPIN_BYTES
-  // side stream (default priority) and events for work that overlaps with the main stream inside one call
-  hipStream_t side = nullptr;
-  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  // side streams (default priority) and events for work that overlaps with the main stream inside one call
+  hipStream_t side = nullptr, side2 = nullptr;
+  hipEvent_t ev[SLIM_NUM_EVENTS] = {};
   // profiling
   bool prof = false;
   std::vector<slim_prof_pending> pending;
@@ -59,7 +61,7 @@ slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes);
 void* slim_ws_alloc(slim_ctx* ctx, size_t bytes);
 inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255); }
 
-// Creates the side stream and its events on first use.
+// Creates the side streams and their events on first use.
 slim_status slim_ensure_side(slim_ctx* ctx);
 
 // Profiling hooks used by SLIM_LAUNCH.
@@ -102,8 +104,11 @@ inline int slim_cdiv(int64_t a, int64_t b) { return static_cast<int>((a + b - 1)
 //   flags: SLIM_GEMM_UPPER_ONLY skips output tiles that lie entirely below the diagonal (M == N).
 //          SLIM_GEMM_A_UPPER / SLIM_GEMM_B_UPPER declare A (M x K, square) / op(B) (K x N, square) upper
 //          triangular with zeros below the diagonal so that the K range can be cut.
+//          SLIM_GEMM_ONE_PER_CU makes the launch ask for so much LDS that a CU holds one workgroup of it: for
+//          bulk work on a side stream that must leave registers and LDS to a latency-critical chain of
+//          small kernels on another stream.
 // K and N even, all pointers 16-byte aligned, leading dimensions even.
-enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4 };
+enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4, SLIM_GEMM_ONE_PER_CU = 8 };
 struct slim_gemm_desc {
   const double* A;
   const double* B;
