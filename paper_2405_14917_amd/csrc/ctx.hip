@@ -100,6 +100,8 @@ slim_status slim_create(slim_ctx** out, void* hip_stream) {
   };
   hipError_t e = hipGetDevice(&ctx->device);
   if (e != hipSuccess) return bail(e, "hipGetDevice");
+  e = hipDeviceGetAttribute(&ctx->num_cus, hipDeviceAttributeMultiprocessorCount, ctx->device);
+  if (e != hipSuccess) return bail(e, "hipDeviceGetAttribute");
   e = hipMalloc(reinterpret_cast<void**>(&ctx->tau_default), SLIM_MAX_CAND * sizeof(double));
   if (e != hipSuccess) return bail(e, "hipMalloc(tau)");
   e = hipMalloc(reinterpret_cast<void**>(&ctx->dflags), 64 * sizeof(int));

@@ -13,8 +13,14 @@
 //  * Split-K: workgroup id = tile * S + s.  Workgroups are dealt round-robin to the 8 XCDs, so with S a
 //    multiple of 8 every XCD works on one token range and the slab of X that all of its tiles share
 //    stays in that XCD's L2.
-//  * Each split writes its partial tile to a scratch buffer; a second kernel adds the partials to G in
-//    a fixed order (deterministic, no floating-point atomics) and mirrors the upper triangle.
+//  * Every workgroup writes its partial 256 x 256 tile to a slot of a scratch buffer; a second kernel adds the
+//    slots of a tile to G in a fixed order (deterministic, no floating-point atomics) and mirrors the upper
+//    triangle.
+//  * Balance: workgroups run one per CU in rounds of as many as the chip has CUs.  When the last round would be
+//    at most half full, the tiles in it are split further along K so that it is full of shorter workgroups
+//    (a 4096-wide Gram matrix has 136 tiles: 4.25 rounds of work instead of 5 rounds of time).
+#include <algorithm>
+
 #include "slim_internal.h"
 
 namespace {
@@ -37,8 +43,41 @@ struct GramArgs {
   int64_t t;           // tokens in this chunk
   int64_t kchunk;      // tokens per split (multiple of BK)
   int S;               // number of splits
-  float* P;            // partials: [S][m][m]
+  int n_main;          // workgroups that take a whole split of their tile: ids 0 .. n_main-1 = tile * S + split
+  int tiles_main;      // tiles handled that way; the tiles behind them are split `f` ways more
+  int f;               // sub-splits per split of a tail tile
+  int64_t subchunk;    // tokens per sub-split (multiple of BK)
+  float* P;            // partial tiles: [slot][TM][TM]
 };
+
+// Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  Workgroup ids
+// keep `split` as the fastest index everywhere, so that with S a multiple of 8 the XCD (id mod 8) of a
+// workgroup is determined by its token range.  The slots of one tile are contiguous.
+struct WorkItem {
+  int tile;
+  int64_t kbeg, kend;
+  int64_t slot;
+};
+__device__ __forceinline__ WorkItem decode_work(const GramArgs& a, int id) {
+  WorkItem w;
+  if (id < a.n_main) {
+    w.tile = id / a.S;
+    const int split = id - w.tile * a.S;
+    w.kbeg = (int64_t)split * a.kchunk;
+    w.kend = min(a.t, w.kbeg + a.kchunk);
+    w.slot = id;
+  } else {
+    const int j = id - a.n_main;
+    const int split = j % a.S, q = j / a.S;
+    const int sub = q % a.f, tt = q / a.f;
+    w.tile = a.tiles_main + tt;
+    const int64_t k0 = (int64_t)split * a.kchunk;
+    w.kbeg = k0 + (int64_t)sub * a.subchunk;
+    w.kend = min(a.t, min(k0 + a.kchunk, w.kbeg + a.subchunk));
+    w.slot = (int64_t)a.n_main + ((int64_t)tt * a.S + split) * a.f + sub;
+  }
+  return w;
+}
 
 __device__ __forceinline__ void decode_tile(int t, int& bi, int& bj) {
   int j = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
@@ -171,12 +210,11 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int split = blockIdx.x % a.S;
+  const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(blockIdx.x / a.S, bi, bj);
+  decode_tile(wk.tile, bi, bj);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
-  const int64_t kbeg = (int64_t)split * a.kchunk;
-  const int64_t kend = min(a.t, kbeg + a.kchunk);
+  const int64_t kbeg = wk.kbeg, kend = wk.kend;
   const int64_t klast8 = ((a.t - 1) / 8) * 8;   // start of the last (possibly partial) 8-token chunk
 
   // LDS stage s: A slab at smem + s * STAGE, B slab TM * LDS_STRIDE behind it
@@ -230,17 +268,17 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   }
 
   // Accumulator register v of lane l holds C[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32] of its 32 x 32 tile.
-  float* P = a.P + (int64_t)split * a.m * a.m;
+  float* P = a.P + wk.slot * (TM * TM);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int row = rowA0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-      if (row >= a.m) continue;
+      const int rl = wm * 128 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+      if (rowA0 + rl >= a.m) continue;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int col = rowB0 + wn * 128 + j * 32 + l32;
-        if (col < a.m) P[(int64_t)row * a.m + col] = acc[i][j][v];
+        const int cl = wn * 128 + j * 32 + l32;
+        if (rowB0 + cl < a.m) P[rl * TM + cl] = acc[i][j][v];
       }
     }
   }
@@ -265,12 +303,11 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int split = blockIdx.x % a.S;
+  const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(blockIdx.x / a.S, bi, bj);
+  decode_tile(wk.tile, bi, bj);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
-  const int64_t kbeg = (int64_t)split * a.kchunk;
-  const int64_t kend = min(a.t, kbeg + a.kchunk);
+  const int64_t kbeg = wk.kbeg, kend = wk.kend;
   constexpr int STAGE = 2 * TM * LDS_STRIDE;
   float16v acc[4][4];
 #pragma unroll
@@ -342,33 +379,44 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
     __syncthreads();
     cur ^= 1;
   }
-  float* P = a.P + (int64_t)split * a.m * a.m;
+  float* P = a.P + wk.slot * (TM * TM);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int row = rowA0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+      const int rl = wm * 128 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int col = rowB0 + wn * 128 + j * 32 + l32;
-        P[(int64_t)row * a.m + col] = acc[i][j][v];
-      }
+      for (int j = 0; j < 4; ++j) P[rl * TM + wn * 128 + j * 32 + l32] = acc[i][j][v];
     }
   }
 }
 
-// G[i][j] += sum_s P[s][i][j] for every (i, j) of an upper tile pair; mirrored into the lower triangle.
-__global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ P, int S, int m, float* __restrict__ G,
-                                                   int64_t ldg) {
+// G[i][j] += the sum over the slots of the tile (in slot order) for every (i, j) of an upper tile pair;
+// mirrored into the lower triangle.
+__global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict__ G, int64_t ldg) {
+  const int tile = blockIdx.x;
   int bi, bj;
-  decode_tile(blockIdx.x, bi, bj);
+  decode_tile(tile, bi, bj);
   const int row0 = bi * TM, col0 = bj * TM;
-  const int r = row0 + blockIdx.y * 4 + (threadIdx.x >> 6);
-  if (r >= m) return;
-  for (int c = col0 + (threadIdx.x & 63); c < min(m, col0 + TM); c += 64) {
+  const int rl = blockIdx.y * 4 + (threadIdx.x >> 6);
+  const int r = row0 + rl;
+  if (r >= a.m) return;
+  int64_t base;
+  int count;
+  if (tile < a.tiles_main) {
+    base = (int64_t)tile * a.S;
+    count = a.S;
+  } else {
+    base = (int64_t)a.n_main + (int64_t)(tile - a.tiles_main) * a.S * a.f;
+    count = a.S * a.f;
+  }
+  const float* __restrict__ P = a.P + base * (TM * TM) + rl * TM;
+  for (int cl = threadIdx.x & 63; cl < TM; cl += 64) {
+    const int c = col0 + cl;
+    if (c >= a.m) break;
     if (bi == bj && c < r) continue;
     float s = 0.f;
-    for (int p = 0; p < S; ++p) s += P[((int64_t)p * m + r) * m + c];
+    for (int p = 0; p < count; ++p) s += P[(int64_t)p * (TM * TM) + cl];
     G[(int64_t)r * ldg + c] += s;
     if (c != r) G[(int64_t)c * ldg + r] += s;
   }
@@ -397,9 +445,6 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   const int64_t kchunk = ((iters + S - 1) / S) * BK;
   S = (int)((t_c + kchunk - 1) / kchunk);
 
-  const size_t pbytes = sizeof(float) * (size_t)S * m * m;
-  slim_status st = slim_ws_reserve(ctx, slim_ws_round(pbytes));
-  if (st != SLIM_OK) return st;
   GramArgs a;
   a.X = static_cast<const uint16_t*>(X);
   a.ldx = ldx;
@@ -407,11 +452,40 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.t = t_c;
   a.kchunk = kchunk;
   a.S = S;
+  // the tiles of a last round that is at most half full are split f ways more
+  const int ncu = ctx->num_cus > 0 ? ctx->num_cus : 256;
+  const int64_t n_items = (int64_t)tiles * S;
+  const int64_t nsl = kchunk / BK;
+  int tail_tiles = 0, f = 1;
+  const int r = (int)(n_items % ncu);
+  if (n_items > ncu && r >= S && 2 * r <= ncu) {
+    tail_tiles = r / S;
+    f = (int)std::min<int64_t>(ncu / (tail_tiles * S), nsl);
+    if (f < 2) {
+      tail_tiles = 0;
+      f = 1;
+    }
+  }
+  int64_t subchunk = kchunk;
+  if (tail_tiles > 0) {
+    subchunk = ((nsl + f - 1) / f) * BK;
+    f = (int)((kchunk + subchunk - 1) / subchunk);   // every sub-split non-empty
+  }
+  a.tiles_main = tiles - tail_tiles;
+  a.n_main = a.tiles_main * S;
+  a.f = f;
+  a.subchunk = subchunk;
+  const int64_t nwg = (int64_t)a.n_main + (int64_t)tail_tiles * S * f;
+
+  const size_t pbytes = sizeof(float) * (size_t)nwg * TM * TM;
+  slim_status st = slim_ws_reserve(ctx, slim_ws_round(pbytes));
+  if (st != SLIM_OK) return st;
   a.P = static_cast<float*>(slim_ws_alloc(ctx, pbytes));
 
   const bool ragged = (t_c % 8) != 0;
   // fast path: complete tiles, whole slabs in every split, lane offsets inside 32 bits
-  const bool full = (m % TM == 0) && (t_c % BK == 0) && (kchunk * S == t_c) && ((int64_t)(TM - 1) * ldx * 2 + 128 < (int64_t(1) << 32));
+  const bool full = (m % TM == 0) && (t_c % BK == 0) && (kchunk * S == t_c) &&
+                    ((int64_t)(TM - 1) * ldx * 2 + 128 < (int64_t(1) << 32));
   const void* variants[6] = {reinterpret_cast<const void*>(gram_kernel<false, false>),
                              reinterpret_cast<const void*>(gram_kernel<false, true>),
                              reinterpret_cast<const void*>(gram_kernel<true, false>),
@@ -420,11 +494,11 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
                              reinterpret_cast<const void*>(gram_kernel_full<true>)};
   static bool attr_done = false;
   if (!attr_done) {
-    for (const void* f : variants)
-      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
+    for (const void* fn : variants)
+      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
     attr_done = true;
   }
-  const dim3 grid(tiles * S), block(NTHREADS);
+  const dim3 grid((unsigned)nwg), block(NTHREADS);
   if (x_dtype == SLIM_BF16) {
     if (full)
       SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel_full<true>), grid, block, kSmemBytes, a);
@@ -440,7 +514,7 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
     else
       SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
   }
-  SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, TM / 4), dim3(256), 0, a.P, S, m, G, ldg);
+  SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, TM / 4), dim3(256), 0, a, G, ldg);
   *n_tokens += t_c;
   return SLIM_OK;
 }

@@ -30,6 +30,7 @@ constexpr int SLIM_NUM_EVENTS = 16;
 struct slim_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
+  int num_cus = 0;                // compute units of the device
   char err[512] = {0};
   // grow-only device workspace with a bump pointer that every entry point resets
   char* ws = nullptr;

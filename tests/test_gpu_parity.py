@@ -51,7 +51,9 @@ def small_layer(seed, n=96, m=256, t=640, beta=64, correlated=True, w_dtype=np.f
 
 
 # ------------------------------------------------------------------------------------------ a1
-@pytest.mark.parametrize("m,t,chunks", [(256, 512, 1), (264, 500, 2), (520, 1100, 3), (8, 8, 1), (256, 64 * 40, 1)])
+# the last two cases have 36 tiles x 8 splits = 288 workgroups: the 32 of the last round are split further along K
+@pytest.mark.parametrize("m,t,chunks", [(256, 512, 1), (264, 500, 2), (520, 1100, 3), (8, 8, 1), (256, 64 * 40, 1),
+                                        (1800, 2000, 1), (2048, 2044, 1)])
 def test_hessian_accumulate(slim, m, t, chunks):
     rng = np.random.default_rng(m + t)
     X = (rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]).astype(np.float16)
