@@ -80,7 +80,13 @@ def algorithmic_work(name, cfg, launches_per_step):
     if name == "sba_update_dgemm":
         return "mfma", "mfma_f64", 4.0 * n * beta * ts
     if name == "gptq_trailing_dgemm":
-        return "mfma", "mfma_f64", float(n) * beta * beta * (k - 1) * (k - 2) / max(launches_per_step, 1)
+        # rank-512 update of the columns behind each window of 512 columns
+        tot = sum(2.0 * n * (min(m, w0 + 512) - w0) * (m - min(m, w0 + 512)) for w0 in range(0, m, 512))
+        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
+    if name == "gptq_window_dgemm":
+        sb = min(beta, 128)
+        tot = sum(2.0 * n * sb * (min(m, (b0 // 512) * 512 + 512) - b0 - sb) for b0 in range(0, m, sb))
+        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
     if name == "inv_window_dgemm":
         # rank-64 update of the columns between the start of the group of block J-1 and block J, rows above J-1
         tot = sum(2.0 * (j0 - 64) * (j0 - ((j0 // 64 - 1) // 4) * 256) * min(64, m - j0) for j0 in range(128, m, 64))

@@ -294,7 +294,8 @@ struct SweepArgs {
   int64_t sz_stride;
   uint8_t* codes;        // pointer to codes[0][b0]
   int64_t ldc;
-  double* E;             // n x beta, ld = beta
+  double* E;             // n x beta block of the error matrix
+  int64_t lde;
   double* row_e2;        // n running sums of e^2
   void* What;            // pointer to What[0][b0] or null
   int64_t ldwh;
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
     const int c = r * 64 + lane;
     if (c < beta) {
       a.codes[(int64_t)row * a.ldc + c] = (uint8_t)qv[r];
-      a.E[(int64_t)row * beta + c] = ev[r];
+      a.E[(int64_t)row * a.lde + c] = ev[r];
       if (a.What) {
         const double what = s * (qv[r] - z);
         if (a.what_f64)
@@ -530,12 +531,19 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   }
 
   const int nstat = slim_cdiv(n, STAT_ROWS);
-  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * SB) +
+  // Trailing updates (Alg. 1 line 12) in two levels: inside a window of WINC columns every swept block updates
+  // the rest of the window at once (rank SB); the columns behind the window receive the whole window's errors in
+  // one rank-WINC update when its last block is done.  A rank-128 update of everything behind each block moves
+  // 16 bytes of W per 32 flops and is bound by memory; this way most of the work has four times that intensity.
+  // WINC is a multiple of every supported group size, so a group never straddles a window and the calibration at
+  // a group's first column sees columns that have received every earlier block's update.
+  const int WINC = 512;
+  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * WINC) +
                       slim_ws_round(sizeof(double) * 2 * nstat) + slim_ws_round(sizeof(double) * n);
   st = slim_ws_reserve(ctx, need);
   if (st != SLIM_OK) return st;
   double* Wc = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * m));
-  double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * SB));
+  double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * WINC));
   double* stat_partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * 2 * nstat));
   double* row_e2 = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * n));
 
@@ -556,6 +564,7 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   for (int sb = 0; sb < m / SB; ++sb) {
     const int b0 = sb * SB;
     const int g = b0 / beta;
+    const int w0 = (b0 / WINC) * WINC, w1 = std::min(m, w0 + WINC);   // the window of this block
     if (b0 % beta == 0) {
       SqcArgs a;
       a.W = Wc + b0;
@@ -592,7 +601,8 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
     s.sz_stride = k;
     s.codes = codes + b0;
     s.ldc = m;
-    s.E = E;
+    s.E = E + (b0 - w0);
+    s.lde = WINC;
     s.row_e2 = row_e2;
     s.What = nullptr;
     s.ldwh = m;
@@ -615,23 +625,32 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
         SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, false>), sgrid, sblock, sweep_smem, s);
     }
 
-    const int rest = m - b0 - SB;
-    if (rest > 0) {
-      slim_gemm_desc d;
-      d.A = E;
-      d.lda = SB;
+    slim_gemm_desc d;
+    d.C2 = nullptr;
+    d.ldc2 = 0;
+    d.M = n;
+    d.flags = 0;
+    d.alpha = -1.0;
+    d.beta = 1.0;
+    d.lda = WINC;
+    d.ldb = ldu;
+    d.ldc = m;
+    if (b0 + SB < w1) {
+      // the rest of the window
+      d.A = E + (b0 - w0);
       d.B = U + (int64_t)b0 * ldu + (b0 + SB);
-      d.ldb = ldu;
       d.C = Wc + (b0 + SB);
-      d.ldc = m;
-      d.C2 = nullptr;
-      d.ldc2 = 0;
-      d.M = n;
-      d.N = rest;
+      d.N = w1 - (b0 + SB);
       d.K = SB;
-      d.flags = 0;
-      d.alpha = -1.0;
-      d.beta = 1.0;
+      st = slim_dgemm(ctx, "gptq_window_dgemm", 0, d);
+      if (st != SLIM_OK) return st;
+    } else if (w1 < m) {
+      // last block of the window: everything behind it
+      d.A = E;
+      d.B = U + (int64_t)w0 * ldu + w1;
+      d.C = Wc + w1;
+      d.N = m - w1;
+      d.K = w1 - w0;
       st = slim_dgemm(ctx, "gptq_trailing_dgemm", 0, d);
       if (st != SLIM_OK) return st;
     }
