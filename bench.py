@@ -106,8 +106,8 @@ def algorithmic_work(name, cfg, launches_per_step):
         return "alu", "alu_f64", 9.0 * cfg.ncand * n * beta          # ~9 fp64 operations per weight and candidate
     if name == "gptq_sweep":
         return "alu", "alu_f64", float(n) * beta * beta              # rank-1 updates inside the group
-    if name == "sba_kl_partial":
-        return "hbm", "hbm", 2.0 * 8 * n * ts
+    if name == "sba_kl_step":
+        return "hbm", "hbm", 2.0 * 8 * n * ts      # one pass over P and the candidate's outputs
     if name == "salience_colsumsq":
         return "hbm", "hbm", 2.0 * n * m
     if name == "pack_codes":

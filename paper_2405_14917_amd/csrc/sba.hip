@@ -7,10 +7,15 @@
 //   sba_fakequant   per (row, group), one wavefront: Eq. 1 / Eq. 2 round-to-nearest at width N and at the one
 //                   other width the group can take; stores W_N and the difference, the latter in search order
 //   dgemm           Y^T = W X_s and Y_0^T = W_N X_s     (n x t_s, fp64 matrix cores)
+//   kl_ref_*        once: per token the maximum M_t and log-sum-exp of the reference outputs; Y is then overwritten
+//                   by P = softmax(Y) and B_t = sum_i P_i log P_i is kept
 //   for p = 0 .. floor(k/2):
-//     kl_partial / kl_finalize   obj[p] = sum_tokens KL(softmax(Y_t) || softmax(Y_p,t)); the softmax runs
-//                   over the n outputs of a token, i.e. down a column of the transposed outputs, so
-//                   consecutive lanes read consecutive tokens
+//     kl_step / kl_finalize   obj[p] = sum_tokens KL(softmax(Y_t) || softmax(Y_p,t))
+//                   = sum_t [ B_t - (sum_i P_i q_i - lse(q)) ]: ONE pass over P and Y_p per candidate, with the
+//                   reference maximum M_t as the shift of the exponentials (Y_p differs from Y by quantisation
+//                   noise, so M_t is as good a shift as the maximum of Y_p itself).  The softmax runs over the n
+//                   outputs of a token, i.e. down a column of the transposed outputs, so consecutive lanes read
+//                   consecutive tokens
 //     dgemm         Y_{p+1}^T = Y_p^T + [D_lo(g_lo) | D_hi(g_hi)] [X_s(g_lo) ; X_s(g_hi)]  (rank 2 beta; the
 //                   operands were laid out in search order on the device, no host round trip)
 //   sba_finalize    first minimum of obj, bit vector of p*
@@ -22,7 +27,7 @@ namespace {
 using namespace slimdev;
 
 constexpr int KL_TOK = 64;     // tokens per workgroup
-constexpr int KL_PART = 5;     // doubles per (part, token): max y, sum exp y, max q, sum exp q, weighted diff
+constexpr int KL_PART = 5;     // doubles per (part, token): max y, sum exp y, sum P log P, sum exp q, sum P q (or squared error)
 
 __global__ __launch_bounds__(256) void sba_rank(const double* __restrict__ sal, int k, int* __restrict__ order,
                                                 int* __restrict__ rank_of) {
@@ -121,49 +126,147 @@ __global__ __launch_bounds__(256) void sba_gather_x(const double* __restrict__ X
     *reinterpret_cast<double2*>(dst + i) = *reinterpret_cast<const double2*>(src + i);
 }
 
-// grid (ceil(ts / 64), parts): 64 tokens x 4 row lanes per workgroup; part r owns rows [r*rpp, (r+1)*rpp)
-__global__ __launch_bounds__(256) void kl_partial(const double* __restrict__ Y, const double* __restrict__ Q, int n,
-                                                  int64_t ts, int rows_per_part, double* __restrict__ partial) {
-  __shared__ double red[5][4][KL_TOK];
+// ---- reference side, once per call ----------------------------------------------------------------
+// grid (ceil(ts / 64), parts): 64 tokens x 4 row lanes per workgroup; part r owns rows [r*rpp, (r+1)*rpp).
+// per (part, token): max y and sum exp(y - max)
+__global__ __launch_bounds__(256) void kl_ref_partial(const double* __restrict__ Y, int n, int64_t ts, int rows_per_part,
+                                                      double* __restrict__ partial) {
+  __shared__ double red[2][4][KL_TOK];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int64_t t = (int64_t)blockIdx.x * KL_TOK + tx;
   const int r0 = blockIdx.y * rows_per_part;
   const int r1 = min(n, r0 + rows_per_part);
   const bool live = t < ts;
-  double my = -INFINITY, mq = -INFINITY;
-  if (live) {
-    for (int r = r0 + ty; r < r1; r += 4) {
-      my = fmax(my, Y[(int64_t)r * ts + t]);
-      mq = fmax(mq, Q[(int64_t)r * ts + t]);
-    }
-  }
+  double my = -INFINITY;
+  if (live)
+    for (int r = r0 + ty; r < r1; r += 4) my = fmax(my, Y[(int64_t)r * ts + t]);
   red[0][ty][tx] = my;
-  red[1][ty][tx] = mq;
   __syncthreads();
   my = fmax(fmax(red[0][0][tx], red[0][1][tx]), fmax(red[0][2][tx], red[0][3][tx]));
-  mq = fmax(fmax(red[1][0][tx], red[1][1][tx]), fmax(red[1][2][tx], red[1][3][tx]));
-  double zy = 0.0, zq = 0.0, a = 0.0;
-  if (live && my > -INFINITY) {
-    for (int r = r0 + ty; r < r1; r += 4) {
-      const double y = Y[(int64_t)r * ts + t], q = Q[(int64_t)r * ts + t];
-      const double ey = exp(y - my);
-      zy += ey;
-      zq += exp(q - mq);
-      a += ey * (y - q);
-    }
-  }
-  red[2][ty][tx] = zy;
-  red[3][ty][tx] = zq;
-  red[4][ty][tx] = a;
+  double zy = 0.0;
+  if (live && my > -INFINITY)
+    for (int r = r0 + ty; r < r1; r += 4) zy += exp(Y[(int64_t)r * ts + t] - my);
+  red[1][ty][tx] = zy;
   __syncthreads();
   if (ty == 0 && live) {
     double* o = partial + ((int64_t)blockIdx.y * ts + t) * KL_PART;
     o[0] = my;
-    o[1] = ((red[2][0][tx] + red[2][1][tx]) + red[2][2][tx]) + red[2][3][tx];
-    o[2] = mq;
-    o[3] = ((red[3][0][tx] + red[3][1][tx]) + red[3][2][tx]) + red[3][3][tx];
-    o[4] = ((red[4][0][tx] + red[4][1][tx]) + red[4][2][tx]) + red[4][3][tx];
+    o[1] = ((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx];
   }
+}
+
+// one thread per token: merges the parts into tok[t] = {M_t, lse_t}
+__global__ __launch_bounds__(256) void kl_ref_merge(const double* __restrict__ partial, int parts, int64_t ts,
+                                                    double* __restrict__ tok) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= ts) return;
+  double M = -INFINITY;
+  for (int p = 0; p < parts; ++p) M = fmax(M, partial[((int64_t)p * ts + t) * KL_PART]);
+  double Z = 0.0;
+  for (int p = 0; p < parts; ++p) {
+    const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
+    Z += o[1] * exp(o[0] - M);
+  }
+  tok[2 * t] = M;
+  tok[2 * t + 1] = M + log(Z);
+}
+
+// Y <- P = exp(Y - lse); per (part, token) the partial sum of P log P goes to slot 2
+__global__ __launch_bounds__(256) void kl_ref_softmax(double* __restrict__ Y, int n, int64_t ts, int rows_per_part,
+                                                      const double* __restrict__ tok, double* __restrict__ partial) {
+  __shared__ double red[4][KL_TOK];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * KL_TOK + tx;
+  const int r0 = blockIdx.y * rows_per_part;
+  const int r1 = min(n, r0 + rows_per_part);
+  double b = 0.0;
+  if (t < ts) {
+    const double lse = tok[2 * t + 1];
+    for (int r = r0 + ty; r < r1; r += 4) {
+      const double lp = Y[(int64_t)r * ts + t] - lse;
+      const double pr = exp(lp);
+      Y[(int64_t)r * ts + t] = pr;
+      b = fma(pr, lp, b);
+    }
+  }
+  red[ty][tx] = b;
+  __syncthreads();
+  if (ty == 0 && t < ts)
+    partial[((int64_t)blockIdx.y * ts + t) * KL_PART + 2] = ((red[0][tx] + red[1][tx]) + red[2][tx]) + red[3][tx];
+}
+
+// one thread per token: B_t = sum_i P_i log P_i (fixed order over the parts) into tok2[t]
+__global__ __launch_bounds__(256) void kl_ref_entropy(const double* __restrict__ partial, int parts, int64_t ts,
+                                                      double* __restrict__ tokB) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= ts) return;
+  double b = 0.0;
+  for (int p = 0; p < parts; ++p) b += partial[((int64_t)p * ts + t) * KL_PART + 2];
+  tokB[t] = b;
+}
+
+// ---- per candidate -------------------------------------------------------------------------------------
+// per (part, token): sum exp(q - M_t) and sum P q over the part's rows, one pass
+__global__ __launch_bounds__(256) void kl_step(const double* __restrict__ P, const double* __restrict__ Q, int n,
+                                               int64_t ts, int rows_per_part, const double* __restrict__ tok,
+                                               double* __restrict__ partial) {
+  __shared__ double red[2][4][KL_TOK];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t t = (int64_t)blockIdx.x * KL_TOK + tx;
+  const int r0 = blockIdx.y * rows_per_part;
+  const int r1 = min(n, r0 + rows_per_part);
+  double z0 = 0.0, z1 = 0.0, a0 = 0.0, a1 = 0.0;
+  if (t < ts) {
+    const double M = tok[2 * t];
+    int r = r0 + ty;
+    for (; r + 4 < r1; r += 8) {
+      const double q0 = Q[(int64_t)r * ts + t], q1 = Q[(int64_t)(r + 4) * ts + t];
+      const double p0 = P[(int64_t)r * ts + t], p1 = P[(int64_t)(r + 4) * ts + t];
+      z0 += exp(q0 - M);
+      z1 += exp(q1 - M);
+      a0 = fma(p0, q0, a0);
+      a1 = fma(p1, q1, a1);
+    }
+    if (r < r1) {
+      const double q0 = Q[(int64_t)r * ts + t];
+      z0 += exp(q0 - M);
+      a0 = fma(P[(int64_t)r * ts + t], q0, a0);
+    }
+  }
+  red[0][ty][tx] = z0 + z1;
+  red[1][ty][tx] = a0 + a1;
+  __syncthreads();
+  if (ty == 0 && t < ts) {
+    double* o = partial + ((int64_t)blockIdx.y * ts + t) * KL_PART;
+    o[3] = ((red[0][0][tx] + red[0][1][tx]) + red[0][2][tx]) + red[0][3][tx];
+    o[4] = ((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx];
+  }
+}
+
+// one thread per token: KL_t = B_t - (sum P q - (M_t + log sum exp(q - M_t))); every workgroup of 256 tokens
+// writes its sum
+__global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
+                                                   const double* __restrict__ tok, const double* __restrict__ tokB,
+                                                   double* __restrict__ block_sums) {
+  __shared__ double red[256];
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  double acc = 0.0;
+  if (t < ts) {
+    double Z = 0.0, A = 0.0;
+    for (int p = 0; p < parts; ++p) {
+      const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
+      Z += o[3];
+      A += o[4];
+    }
+    acc = tokB[t] - (A - (tok[2 * t] + log(Z)));
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
 }
 
 // squared-error objective: per (part, token) the sum over the part's rows of (y - q)^2, stored in slot 4 of the
@@ -195,39 +298,6 @@ __global__ __launch_bounds__(256) void mse_finalize(const double* __restrict__ p
   double acc = 0.0;
   if (t < ts)
     for (int p = 0; p < parts; ++p) acc += partial[((int64_t)p * ts + t) * KL_PART + 4];
-  red[threadIdx.x] = acc;
-  __syncthreads();
-  for (int st = 128; st > 0; st >>= 1) {
-    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
-}
-
-// one thread per token: merges the row parts of its token; every workgroup of 256 tokens writes its sum
-__global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
-                                                   double* __restrict__ block_sums) {
-  __shared__ double red[256];
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  double acc = 0.0;
-  if (t < ts) {
-    double My = -INFINITY, Mq = -INFINITY;
-    for (int p = 0; p < parts; ++p) {
-      const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
-      My = fmax(My, o[0]);
-      Mq = fmax(Mq, o[2]);
-    }
-    double Zy = 0.0, Zq = 0.0, A = 0.0;
-    for (int p = 0; p < parts; ++p) {
-      const double* o = partial + ((int64_t)p * ts + t) * KL_PART;
-      const double sy = exp(o[0] - My), sq = exp(o[2] - Mq);
-      Zy += o[1] * sy;
-      A += o[4] * sy;
-      Zq += o[3] * sq;
-    }
-    // KL_t = sum_i P_i ((y_i - lse_y) - (q_i - lse_q)) = A / Zy - lse_y + lse_q
-    acc = A / Zy - (My + log(Zy)) + (Mq + log(Zq));
-  }
   red[threadIdx.x] = acc;
   __syncthreads();
   for (int st = 128; st > 0; st >>= 1) {
@@ -304,7 +374,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   const int kl_blocks = slim_cdiv(t_s, 256);
   const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
   const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * k + 2));
-  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + bPart + bObj + bOrd + 256);
+  const size_t bTok = slim_ws_round(sizeof(double) * 3 * (size_t)t_s);
+  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + bPart + bObj + bOrd + bTok + 256);
   if (st != SLIM_OK) return st;
   double* W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
   double* WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
@@ -319,6 +390,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
   int* rank_of = order + (k + 1);
   int* pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
+  double* tok = static_cast<double*>(slim_ws_alloc(ctx, bTok));   // per token {max, log-sum-exp} of the reference
+  double* tokB = tok + 2 * t_s;                                   // per token sum P log P
 
   SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order, rank_of);
   st = slim_widen_f64(ctx, "sba_widen_w", W, w_dtype, n, m, ldw, W64, (int64_t)m);
@@ -353,10 +426,17 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   if (st != SLIM_OK) return st;
 
   const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
+  if (objective == SLIM_OBJ_KL) {
+    // reference side once: per-token maximum and log-sum-exp, then Y^T becomes P = softmax over the outputs
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_partial, kgrid, dim3(256), 0, Yt, n, t_s, rpp, partial);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_merge, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tok);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_softmax, kgrid, dim3(256), 0, Yt, n, t_s, rpp, tok, partial);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_entropy, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tokB);
+  }
   for (int p = 0; p <= pmax; ++p) {
     if (objective == SLIM_OBJ_KL) {
-      SLIM_LAUNCH(ctx, "sba_kl_partial", kl_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
-      SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
+      SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial);
+      SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tok, tokB,
                   block_sums + (int64_t)p * kl_blocks);
     } else {
       SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
