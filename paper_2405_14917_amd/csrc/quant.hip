@@ -23,7 +23,7 @@ namespace {
 
 using namespace slimdev;
 
-constexpr int SQC_ROWS = 4;       // rows per workgroup in sqc_search
+constexpr int SQC_CPT = 4;        // candidates per thread in sqc_search
 constexpr int SQC_THREADS = 256;
 constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
 constexpr int SWEEP_WAVES = 16;   // rows (= wavefronts) per workgroup in gptq_sweep
@@ -70,6 +70,7 @@ struct SqcArgs {
   int weight_mode, scope, q1_mode;
   const double* tau;
   int ncand;
+  int rows_per_wg;       // rows of the block one workgroup calibrates
   double* scale;         // element i at scale[i * out_stride]
   double* zero;
   int64_t out_stride;
@@ -95,14 +96,15 @@ __device__ __forceinline__ void minmax_params(double wmin, double wmax, int bits
 __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
   extern __shared__ __align__(16) double smem[];
   const int beta = a.beta, ncand = a.ncand;
-  double* wrow = smem;                            // [SQC_ROWS][beta]
-  double* om = wrow + SQC_ROWS * beta;            // [SQC_ROWS][beta]
-  double* loss = om + SQC_ROWS * beta;            // [SQC_ROWS][ncand]
-  double* rp = loss + SQC_ROWS * ncand;           // [SQC_ROWS][4]: delta0, z, alpha, unused
-  double* red = rp + SQC_ROWS * 4;                // [256] + 2
+  const int RW = a.rows_per_wg;
+  double* wrow = smem;                            // [RW][beta]
+  double* om = wrow + RW * beta;                  // [RW][beta]
+  double* loss = om + RW * beta;                  // [RW][ncand]
+  double* rp = loss + RW * ncand;                 // [RW][4]: delta0, z, alpha, unused
+  double* red = rp + RW * 4;                      // [256] + 2
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r0 = blockIdx.x * SQC_ROWS;
-  const int rows = min(SQC_ROWS, a.n - r0);
+  const int r0 = blockIdx.x * RW;
+  const int rows = min(RW, a.n - r0);
   const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
   const bool need_mask = (a.omega == nullptr && a.weight_mode == SLIM_WEIGHT_MASK_MEAN);
 
@@ -114,21 +116,15 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
       s1 += a.stat_partial[2 * p];
       s2 += a.stat_partial[2 * p + 1];
     }
-    red[tid] = s1;
-    __syncthreads();
-    for (int s = SQC_THREADS / 2; s > 0; s >>= 1) {
-      if (tid < s) red[tid] += red[tid + s];
-      __syncthreads();
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (lane == 0) {
+      red[2 * wave] = s1;
+      red[2 * wave + 1] = s2;
     }
-    const double S1 = red[0];
     __syncthreads();
-    red[tid] = s2;
-    __syncthreads();
-    for (int s = SQC_THREADS / 2; s > 0; s >>= 1) {
-      if (tid < s) red[tid] += red[tid + s];
-      __syncthreads();
-    }
-    const double S2 = red[0];
+    const double S1 = ((red[0] + red[2]) + red[4]) + red[6];
+    const double S2 = ((red[1] + red[3]) + red[5]) + red[7];
     const double cnt = (double)a.n * (double)beta;
     const double m1 = S1 / cnt;
     const double var = fmax(S2 / cnt - m1 * m1, 0.0);
@@ -196,47 +192,65 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
   }
   __syncthreads();
 
-  // every (row, candidate) pair is one thread
+  // A pair of neighbouring lanes takes SQC_CPT consecutive candidates of one row, each lane half of the row's
+  // weights: a weight and its loss weight are read from LDS once for four candidates, the four losses form
+  // independent dependency chains, and there are enough wavefronts to hide the latency of the fp64 pipeline.
   const double qmax = (double)((1 << a.bits) - 1);
-  for (int s = tid; s < rows * ncand; s += SQC_THREADS) {
-    const int r = s / ncand, c = s - r * ncand;
-    const double* w = wrow + r * beta;
-    const double* o = om + r * beta;
-    const double tc = a.tau[c];
-    double L = 0.0;
-    if (sign_mode) {
-      const double ta = tc * rp[r * 4 + 2];
-      double L1 = 0.0;
-      for (int j = 0; j < beta; j += 2) {
-        const double v0 = w[j], v1 = w[j + 1];
-        const double e0 = v0 - (v0 >= 0.0 ? ta : -ta);
-        const double e1 = v1 - (v1 >= 0.0 ? ta : -ta);
-        L = fma(o[j] * e0, e0, L);
-        L1 = fma(o[j + 1] * e1, e1, L1);
-      }
-      L += L1;
-    } else {
-      // The loss is continuous across a rounding tie (both neighbouring codes are equally far), so the
-      // candidate losses may use a reciprocal; the codes themselves are decided with a true division.
-      const double delta = tc * rp[r * 4 + 0];
-      const double rdelta = 1.0 / delta;
-      const double z = rp[r * 4 + 1];
-      // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), -z, qmax - z): one add and one subtract less per
-      // element; two accumulators shorten the dependent chain
-      const double lo = -z, hi = qmax - z;
-      double L1 = 0.0;
-      for (int j = 0; j < beta; j += 2) {
-        const double v0 = w[j], v1 = w[j + 1];
-        const double q0 = fmin(fmax(rint(v0 * rdelta), lo), hi);
-        const double q1 = fmin(fmax(rint(v1 * rdelta), lo), hi);
-        const double e0 = fma(-delta, q0, v0);
-        const double e1 = fma(-delta, q1, v1);
-        L = fma(o[j] * e0, e0, L);
-        L1 = fma(o[j + 1] * e1, e1, L1);
-      }
-      L += L1;
+  const int tpr = (ncand + SQC_CPT - 1) / SQC_CPT;      // lane pairs per row
+  const int hb = beta / 2;
+  for (int s0 = 0; s0 < 2 * rows * tpr; s0 += SQC_THREADS) {
+    const int s = s0 + tid;
+    const bool live = s < 2 * rows * tpr;
+    const int item = min(s, 2 * rows * tpr - 1) >> 1, half = s & 1;
+    const int r = item / tpr, c0 = (item - r * tpr) * SQC_CPT;
+    const double* w = wrow + r * beta + half * hb;
+    const double* o = om + r * beta + half * hb;
+    double L[SQC_CPT], dl[SQC_CPT], rd[SQC_CPT];
+#pragma unroll
+    for (int i = 0; i < SQC_CPT; ++i) {
+      const double tc = a.tau[min(c0 + i, ncand - 1)];
+      L[i] = 0.0;
+      // SIGN: the level tau * alpha; otherwise the step tau * delta0 and its reciprocal.  The loss is continuous
+      // across a rounding tie (both neighbouring codes are equally far), so the candidate losses may use a
+      // reciprocal; the codes themselves are decided with a true division.
+      dl[i] = tc * (sign_mode ? rp[r * 4 + 2] : rp[r * 4 + 0]);
+      rd[i] = 1.0 / dl[i];
     }
-    loss[r * ncand + c] = L;
+    if (sign_mode) {
+      for (int j = 0; j < hb; ++j) {
+        const double v = w[j], oj = o[j];
+#pragma unroll
+        for (int i = 0; i < SQC_CPT; ++i) {
+          const double e = v - (v >= 0.0 ? dl[i] : -dl[i]);
+          L[i] = fma(oj * e, e, L[i]);
+        }
+      }
+    } else {
+      // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), -z, qmax - z): one add and one subtract less per element
+      const double z = rp[r * 4 + 1];
+      const double lo = -z, hi = qmax - z;
+      for (int j = 0; j < hb; j += 2) {
+        const double2 v2 = *reinterpret_cast<const double2*>(w + j);
+        const double2 o2 = *reinterpret_cast<const double2*>(o + j);
+#pragma unroll
+        for (int i = 0; i < SQC_CPT; ++i) {
+          const double q0 = fmin(fmax(rint(v2.x * rd[i]), lo), hi);
+          const double e0 = fma(-dl[i], q0, v2.x);
+          L[i] = fma(o2.x * e0, e0, L[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < SQC_CPT; ++i) {
+          const double q1 = fmin(fmax(rint(v2.y * rd[i]), lo), hi);
+          const double e1 = fma(-dl[i], q1, v2.y);
+          L[i] = fma(o2.y * e1, e1, L[i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < SQC_CPT; ++i) {
+      const double other = shfl_xor_f64(L[i], 1);          // the other half of the row, from the neighbouring lane
+      if (live && half == 0 && c0 + i < ncand) loss[r * ncand + c0 + i] = L[i] + other;
+    }
   }
   __syncthreads();
 
@@ -276,8 +290,14 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
   }
 }
 
-size_t sqc_smem_bytes(int beta, int ncand) {
-  return sizeof(double) * ((size_t)2 * SQC_ROWS * beta + (size_t)SQC_ROWS * ncand + SQC_ROWS * 4 + SQC_THREADS + 2);
+// rows per workgroup: as many as fill the 256 threads with (row, four candidates, half row) items, 16 at most
+int sqc_rows_per_wg(int ncand) {
+  const int tpr = (ncand + SQC_CPT - 1) / SQC_CPT;
+  return std::max(1, std::min(16, SQC_THREADS / (2 * tpr)));
+}
+
+size_t sqc_smem_bytes(int beta, int ncand, int rows) {
+  return sizeof(double) * ((size_t)2 * rows * beta + (size_t)rows * ncand + rows * 4 + SQC_THREADS + 2);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -419,14 +439,15 @@ slim_status launch_stats_and_sqc(slim_ctx* ctx, SqcArgs a, double* stat_partial)
     a.stat_partial = stat_partial;
     SLIM_LAUNCH(ctx, "sqc_block_stats", block_stats, dim3(a.nstat), dim3(256), 0, a.W, a.ldw, a.n, a.beta, stat_partial);
   }
-  const size_t smem = sqc_smem_bytes(a.beta, a.ncand);
+  a.rows_per_wg = sqc_rows_per_wg(a.ncand);
+  const size_t smem = sqc_smem_bytes(a.beta, a.ncand, a.rows_per_wg);
   if (smem > 160 * 1024) return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "sqc: beta * ncand too large for LDS");
   if (smem > 64 * 1024) {
     static bool done = false;
     slim_status st = allow_big_lds(ctx, sqc_search, done);
     if (st != SLIM_OK) return st;
   }
-  SLIM_LAUNCH(ctx, "sqc_search", sqc_search, dim3(slim_cdiv(a.n, SQC_ROWS)), dim3(SQC_THREADS), smem, a);
+  SLIM_LAUNCH(ctx, "sqc_search", sqc_search, dim3(slim_cdiv(a.n, a.rows_per_wg)), dim3(SQC_THREADS), smem, a);
   return SLIM_OK;
 }
 
