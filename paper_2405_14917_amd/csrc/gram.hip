@@ -284,20 +284,82 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   }
 }
 
-__device__ __forceinline__ void stash_plain(const Slab& s, uint16_t* as, uint16_t* bs) {
+// ---- interior fast path -----------------------------------------------------------------------------
+// Every tile is complete (m a multiple of 256) and every split covers whole slabs, so nothing is masked.
+//
+// A wavefront that is alone on its SIMD pays the full issue time of every instruction that does not fit in the
+// shadow of the matrix pipe, and measured on this kernel the global loads and the LDS stores of the operand
+// slabs together cost as much again as a third of the MFMA time.  So the slabs go from memory to LDS directly
+// (global_load_lds_dwordx4): one instruction per 1 KiB instead of a load plus a store, no registers in between,
+// and a whole iteration for the data to arrive (the loads of slab s+1 are issued before the MFMAs of slab s).
+//
+// A direct load writes the 64 lanes' 16 bytes to consecutive LDS addresses, so rows cannot be padded: a row
+// of a slab is exactly 128 bytes, and 8 lanes x 8 rows of a wavefront form one contiguous KiB.  Bank conflicts
+// of the operand reads are avoided by a swizzle instead, applied on the global side: position p (16-byte unit)
+// of row r holds the tokens of chunk p ^ ((r >> 1) & 7).  Sixteen lanes that read the same chunk of sixteen
+// consecutive rows then hit sixteen different groups of four banks.
+constexpr int FROW = BK;                                               // halves per LDS row
+constexpr size_t kSmemFull = size_t(2) * 2 * TM * FROW * sizeof(uint16_t);   // two stages of A and B slabs
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+// One direct load: the 64 lanes' 16 bytes at gbase + voff (uniform 64-bit base, 32-bit lane offset) go to the
+// LDS bytes lds_addr + 16 * lane.  Written as asm so that the compiler neither computes 64-bit lane addresses
+// for it nor makes later LDS reads of the other stage wait for it; completion is awaited explicitly (vmcnt).
+__device__ __forceinline__ void direct_load(unsigned lds_addr, unsigned voff, const char* gbase) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(gbase)
+               : "m0");
+#else
+  (void)lds_addr, (void)voff, (void)gbase;
+#endif
+}
+
+// operand fragments of K step s: `ap` / `bp` already point at this lane's row and swizzled chunk
+__device__ __forceinline__ void load_frags_full(Frags& f, const uint16_t* ap, const uint16_t* bp) {
 #pragma unroll
-  for (int c = 0; c < CHUNKS; ++c) {
-    *reinterpret_cast<uint4*>(as + 32 * c * LDS_STRIDE) = s.a[c];
-    *reinterpret_cast<uint4*>(bs + 32 * c * LDS_STRIDE) = s.b[c];
+  for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const uint4*>(ap + i * 32 * FROW);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const uint4*>(bp + j * 32 * FROW);
+}
+
+// One K step of the fast path in a fixed issue order: its 16 MFMAs, after every second one an operand read of
+// the next K step (into the other fragment set), after every third MFMA of the first three K steps a direct
+// load of the next slab.  The loads are spread out because the four wavefronts of a CU together must not ask
+// the vector memory path for more than it moves (64 bytes per cycle): bunched up, they stall the wavefront at
+// issue and the matrix pipe behind it; the last K step is left free so that the last load has time to land.
+template <bool BF16, int S>
+__device__ __forceinline__ void kstep_full(float16v (&acc)[4][4], const Frags& cf, Frags& nf, const uint16_t* nap,
+                                           const uint16_t* nbp, unsigned ldsn, const unsigned (&off)[CHUNKS],
+                                           const char* baseA, const char* baseB) {
+  constexpr unsigned OPB_BYTES = TM * FROW * 2, CHUNK_BYTES = 32 * FROW * 2;
+#pragma unroll
+  for (int m = 0; m < 16; ++m) {
+    acc[m >> 2][m & 3] = mfma<BF16>(cf.a[m >> 2], cf.b[m & 3], acc[m >> 2][m & 3]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (S < 3 && (m & 1) == 0) {
+      const int q = m >> 1;
+      if (q < 4)
+        nf.a[q] = *reinterpret_cast<const uint4*>(nap + q * 32 * FROW);
+      else
+        nf.b[q - 4] = *reinterpret_cast<const uint4*>(nbp + (q - 4) * 32 * FROW);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const int gm = 16 * S + m;             // index of this MFMA in the iteration
+    if (gm % 3 == 1 && gm / 3 < 2 * CHUNKS) {
+      const int d = gm / 3, c = d >> 1;
+      if (d & 1)
+        direct_load(ldsn + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
+      else
+        direct_load(ldsn + c * CHUNK_BYTES, off[c], baseA);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 }
 
-// Interior fast path: every tile is complete (m a multiple of 256) and every split covers whole slabs, so
-// nothing is masked.  Addresses are a uniform base pointer that advances per slab plus constant 32-bit
-// lane offsets; one register stage; the whole iteration is ONE scheduling region in which the global loads
-// of the next slab, the LDS operand reads and the LDS writes are slotted between the 64 MFMAs (a wavefront
-// that is alone on its SIMD issues only about one instruction per 8 cycles, so anything issued outside the
-// shadow of the matrix pipe costs its full issue time).
 template <bool BF16>
 __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
@@ -308,7 +370,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   decode_tile(wk.tile, bi, bj);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
-  constexpr int STAGE = 2 * TM * LDS_STRIDE;
+  constexpr int STAGE = 2 * TM * FROW;    // halves per stage: A slab, then B slab
   float16v acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -316,23 +378,36 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // global side: this lane fetches, for c = 0 .. 7, row r0 + 32 c, chunk ch ^ swizzle(row)
   const int r0 = tid >> 3, ch = tid & 7;
+  const int gch = ch ^ ((r0 >> 1) & 7);       // ((r0 + 32 c) >> 1) & 7 == (r0 >> 1) & 7
   unsigned off[CHUNKS];
 #pragma unroll
-  for (int c = 0; c < CHUNKS; ++c) off[c] = (unsigned)((int64_t)(r0 + 32 * c) * a.ldx * 2 + ch * 16);
+  for (int c = 0; c < CHUNKS; ++c) off[c] = (unsigned)((int64_t)(r0 + 32 * c) * a.ldx * 2 + gch * 16);
   const char* baseA = reinterpret_cast<const char*>(a.X + (int64_t)rowA0 * a.ldx + kbeg);
   const char* baseB = reinterpret_cast<const char*>(a.X + (int64_t)rowB0 * a.ldx + kbeg);
-  const int st_off = r0 * LDS_STRIDE + ch * 8;
+  // LDS side: load c of this wavefront fills rows 32 c + 8 wave .. + 8 of a slab (1 KiB)
+  const int wrow = 8 * wave * FROW;
+  // operand reads: lane (l32, lh) reads row l32 (+ 32 i) of its wavefront's half, chunk 2 s + lh of K step s
   const int l32 = lane & 31, lh = lane >> 5;
-  const int rdA = (wm * 128 + l32) * LDS_STRIDE + lh * 8;
-  const int rdB = TM * LDS_STRIDE + (wn * 128 + l32) * LDS_STRIDE + lh * 8;
-  Slab sl;
+  const int xm = (l32 >> 1) & 7;
+  const int rdA = (wm * 128 + l32) * FROW, rdB = TM * FROW + (wn * 128 + l32) * FROW;
+  int pos[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) pos[s] = ((2 * s + lh) ^ xm) * 8;
+
+  // LDS byte address of this wavefront's first destination row in stage 0
+  const unsigned lds0 = (unsigned)__builtin_amdgcn_readfirstlane(
+      (int)((unsigned)(uintptr_t)((__attribute__((address_space(3))) uint16_t*)smem) + (unsigned)wrow * 2));
+  constexpr unsigned STAGE_BYTES = STAGE * 2, OPB_BYTES = TM * FROW * 2, CHUNK_BYTES = 32 * FROW * 2;
+
+  // prologue: slab 0 into stage 0
 #pragma unroll
   for (int c = 0; c < CHUNKS; ++c) {
-    sl.a[c] = *reinterpret_cast<const uint4*>(baseA + off[c]);
-    sl.b[c] = *reinterpret_cast<const uint4*>(baseB + off[c]);
+    direct_load(lds0 + c * CHUNK_BYTES, off[c], baseA);
+    direct_load(lds0 + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
   }
-  stash_plain(sl, smem + st_off, smem + TM * LDS_STRIDE + st_off);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   int cur = 0;
   const int64_t nslab = (kend - kbeg) / BK;
@@ -343,39 +418,15 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
     baseB += adv;
     const uint16_t* as = smem + cur * STAGE + rdA;
     const uint16_t* bs = smem + cur * STAGE + rdB;
-    uint16_t* was = smem + (cur ^ 1) * STAGE + st_off;
-    uint16_t* wbs = was + TM * LDS_STRIDE;
+    const unsigned ldsn = lds0 + (unsigned)(cur ^ 1) * STAGE_BYTES;
     Frags f0, f1;
-    load_frags(f0, as, bs, 0);
-    load_frags(f1, as, bs, 16);
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-      sl.a[c] = *reinterpret_cast<const uint4*>(baseA + off[c]);
-      sl.b[c] = *reinterpret_cast<const uint4*>(baseB + off[c]);
-    }
-    mfma_block<BF16>(acc, f0);
-    load_frags(f0, as, bs, 32);
-    mfma_block<BF16>(acc, f1);
-    load_frags(f1, as, bs, 48);
-    mfma_block<BF16>(acc, f0);
-    stash_plain(sl, was, wbs);
-    mfma_block<BF16>(acc, f1);
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-    }
+    load_frags_full(f0, as + pos[0], bs + pos[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    kstep_full<BF16, 0>(acc, f0, f1, as + pos[1], bs + pos[1], ldsn, off, baseA, baseB);
+    kstep_full<BF16, 1>(acc, f1, f0, as + pos[2], bs + pos[2], ldsn, off, baseA, baseB);
+    kstep_full<BF16, 2>(acc, f0, f1, as + pos[3], bs + pos[3], ldsn, off, baseA, baseB);
+    kstep_full<BF16, 3>(acc, f1, f0, as, bs, ldsn, off, baseA, baseB);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the slab for the next iteration has landed in LDS
     __syncthreads();
     cur ^= 1;
   }
@@ -501,14 +552,14 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   const dim3 grid((unsigned)nwg), block(NTHREADS);
   if (x_dtype == SLIM_BF16) {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel_full<true>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel_full<true>), grid, block, kSmemFull, a);
     else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
   } else {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel_full<false>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel_full<false>), grid, block, kSmemFull, a);
     else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
     else
