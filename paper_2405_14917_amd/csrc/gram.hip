@@ -79,12 +79,41 @@ __device__ __forceinline__ WorkItem decode_work(const GramArgs& a, int id) {
   return w;
 }
 
-__device__ __forceinline__ void decode_tile(int t, int& bi, int& bj) {
+// position t in the upper triangle of a square grid, column by column: (bi <= bj)
+__device__ __forceinline__ void decode_triangle(int t, int& bi, int& bj) {
   int j = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
   while ((j + 1) * (j + 2) / 2 <= t) ++j;
   while (j * (j + 1) / 2 > t) --j;
   bj = j;
   bi = t - j * (j + 1) / 2;
+}
+
+// Tile index -> tile (bi <= bj) of the upper triangle of an nt x nt grid.  Tiles are numbered supertile by
+// supertile (SUPER x SUPER tiles, the supertiles column by column over the triangle): the ~32 workgroups that
+// run at the same time on one XCD then cover a compact square of tiles that needs 2 x SUPER row blocks of X
+// per slab instead of one plus one per tile, and most of their operand loads hit in that XCD's L2.
+constexpr int SUPER = 6;
+__device__ __forceinline__ void decode_tile(int t, int nt, int& bi, int& bj) {
+  const int ns = (nt + SUPER - 1) / SUPER;
+  for (int J = 0; J < ns; ++J) {
+    const int w = min(SUPER, nt - J * SUPER);          // columns of tiles in supertile column J
+    for (int I = 0; I <= J; ++I) {
+      const int cnt = (I < J) ? SUPER * w : w * (w + 1) / 2;
+      if (t < cnt) {
+        if (I < J) {
+          bi = I * SUPER + t % SUPER;
+          bj = J * SUPER + t / SUPER;
+        } else {
+          decode_triangle(t, bi, bj);
+          bi += I * SUPER;
+          bj += J * SUPER;
+        }
+        return;
+      }
+      t -= cnt;
+    }
+  }
+  bi = bj = 0;   // not reached for t < nt (nt + 1) / 2
 }
 
 // 8 consecutive 16-bit elements of one row starting at token k, read branch-free from a clamped (valid)
@@ -212,7 +241,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(wk.tile, bi, bj);
+  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
   const int64_t klast8 = ((a.t - 1) / 8) * 8;   // start of the last (possibly partial) 8-token chunk
@@ -367,7 +396,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(wk.tile, bi, bj);
+  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
   constexpr int STAGE = 2 * TM * FROW;    // halves per stage: A slab, then B slab
@@ -447,7 +476,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
 __global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict__ G, int64_t ldg) {
   const int tile = blockIdx.x;
   int bi, bj;
-  decode_tile(tile, bi, bj);
+  decode_tile(tile, (a.m + TM - 1) / TM, bi, bj);
   const int row0 = bi * TM, col0 = bj * TM;
   const int rl = blockIdx.y * 4 + (threadIdx.x >> 6);
   const int r = row0 + rl;
