@@ -27,8 +27,9 @@ from paper_2405_14917_amd import binding, synth
 PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e12}
 # HBM bytes per launch measured with two `rocprofv3 --pmc` runs of this command (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for the 64 MiB copy below (FETCH_SIZE reads 32 MiB for it: factor 2.0;
-# WRITE_SIZE reads 64 MiB: factor 1.0); see profiles/gram_C2_hbm_traffic.md.  Keyed by (config, kernel).
-TRAFFIC_BYTES = {("C2", "gram_mfma_f16"): 2.0 * 3.068e6 * 1024 + 1.0 * 2.785e5 * 1024}
+# WRITE_SIZE reads 64 MiB: factor 1.0); see profiles/dgemm_gram_C2_hbm_traffic.md.  Keyed by (config, kernel).
+TRAFFIC_BYTES = {("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.309e5 * 1024 + 1.0 * 6.758e4 * 1024,
+                 ("C2", "gram_kernel_full<false>"): 2.0 * 2.592e6 * 1024 + 1.0 * 3.277e5 * 1024}
 T_SBA = 2048
 
 
@@ -200,30 +201,49 @@ def main():
         job.step()
     prof = slim.profile_collect()
     slim.profile_enable(False)
-    kernels = {}
-    for name, (ms, cnt) in prof.items():
-        kernels[name] = {"ms_per_step": ms / args.profile_steps, "launches_per_step": cnt / args.profile_steps,
-                         "avg_us": 1e3 * ms / cnt}
+    # A profiling entry is named "<step>" or "<step>@<kernel function>" (launch sites that choose among several
+    # kernel functions say which one ran).  `kernels` is keyed by step; the roofline is given for the kernel
+    # FUNCTION with the largest share of the GPU time, under the name rocprofv3 lists it by, so that its average
+    # duration can be compared with the rocprofv3 summary of the same command (profiles/).
+    kernels, functions = {}, {}
+    for full, (ms, cnt) in prof.items():
+        step, _, fn = full.partition("@")
+        k = kernels.setdefault(step, {"ms": 0.0, "cnt": 0, "parts": []})
+        k["ms"] += ms
+        k["cnt"] += cnt
+        k["parts"].append((fn or step, ms, cnt))
+    for step, k in kernels.items():
+        k["ms_per_step"] = k["ms"] / args.profile_steps
+        k["launches_per_step"] = k["cnt"] / args.profile_steps
+        k["avg_us"] = 1e3 * k["ms"] / k["cnt"]
+        bound, peak_key, work = algorithmic_work(step, cfg, k["launches_per_step"])
+        k["bound"], k["peak_key"], k["work_per_step"] = bound, peak_key, work * k["launches_per_step"]
+        for fn, ms, cnt in k["parts"]:
+            f = functions.setdefault(fn, {"ms": 0.0, "cnt": 0, "work": 0.0, "bound": bound, "peak_key": peak_key})
+            f["ms"] += ms
+            f["cnt"] += cnt
+            # a step that ran on several kernel functions is credited to them in proportion to their time
+            f["work"] += k["work_per_step"] * args.profile_steps * (ms / k["ms"] if k["ms"] > 0 else 0.0)
     roofline = None
-    if kernels:
-        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-        bound, peak_key, work = algorithmic_work(dom, cfg, kernels[dom]["launches_per_step"])
-        avg_s = kernels[dom]["avg_us"] * 1e-6
-        achieved = work / avg_s
-        unit = {"mfma": "TFLOP/s", "alu": "TFLOP/s", "hbm": "GB/s"}[bound]
-        div = 1e9 if bound == "hbm" else 1e12
-        roofline = {"kernel": dom, "bound": bound, "achieved": achieved / div, "peak": PEAK[peak_key] / div,
-                    "unit": unit, "frac": achieved / PEAK[peak_key], "traffic": TRAFFIC_BYTES.get((cfg.name, dom)),
-                    "avg_us": kernels[dom]["avg_us"], "ms_per_step": kernels[dom]["ms_per_step"]}
-    # the other rooflines the metric names, for the record
+    rated = {fn: f for fn, f in functions.items() if f["work"] > 0}
+    if rated:
+        dom = max(rated, key=lambda fn: rated[fn]["ms"])
+        f = rated[dom]
+        achieved = f["work"] / (f["ms"] * 1e-3)
+        unit = {"mfma": "TFLOP/s", "alu": "TFLOP/s", "hbm": "GB/s"}[f["bound"]]
+        div = 1e9 if f["bound"] == "hbm" else 1e12
+        roofline = {"kernel": dom, "bound": f["bound"], "achieved": achieved / div, "peak": PEAK[f["peak_key"]] / div,
+                    "unit": unit, "frac": achieved / PEAK[f["peak_key"]], "traffic": TRAFFIC_BYTES.get((cfg.name, dom)),
+                    "avg_us": 1e3 * f["ms"] / f["cnt"], "launches_per_step": f["cnt"] / args.profile_steps,
+                    "ms_per_step": f["ms"] / args.profile_steps}
+    # the other rooflines the metric names, for the record (per step of the path)
     others = {}
-    for name in kernels:
-        b, pk, wk = algorithmic_work(name, cfg, kernels[name]["launches_per_step"])
-        if wk > 0:
-            others[name] = {"ms_per_step": round(kernels[name]["ms_per_step"], 4), "bound": b,
-                            "frac": round(wk / (kernels[name]["avg_us"] * 1e-6) / PEAK[pk], 4)}
+    for name, k in kernels.items():
+        if k["work_per_step"] > 0:
+            others[name] = {"ms_per_step": round(k["ms_per_step"], 4), "bound": k["bound"],
+                            "frac": round(k["work_per_step"] / (k["ms_per_step"] * 1e-3) / PEAK[k["peak_key"]], 4)}
         else:
-            others[name] = {"ms_per_step": round(kernels[name]["ms_per_step"], 4)}
+            others[name] = {"ms_per_step": round(k["ms_per_step"], 4)}
 
     line = {
         "metric": "weights_quantized_per_s", "value": cfg.n * cfg.m / (ms_per_step * 1e-3), "unit": "weights/s",

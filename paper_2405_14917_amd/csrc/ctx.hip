@@ -1,4 +1,7 @@
 // Context, error reporting, workspace and per-kernel event timing of libslim.
+#include <mutex>
+#include <set>
+
 #include "slim_internal.h"
 
 slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...) {
@@ -47,6 +50,13 @@ slim_status slim_ensure_side(slim_ctx* ctx) {
   SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking));
   for (hipEvent_t& e : ctx->ev) SLIM_HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return SLIM_OK;
+}
+
+const char* slim_prof_name(const char* step, const char* kernel_function) {
+  static std::mutex mu;
+  static std::set<std::string> names;   // node-based: the strings never move
+  std::lock_guard<std::mutex> lock(mu);
+  return names.insert(std::string(step) + "@" + kernel_function).first->c_str();
 }
 
 void slim_prof_begin(slim_ctx* ctx, const char* name) {

@@ -254,9 +254,11 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
   if (use_small_tiles(d.M, d.N, 1)) {
     const int tiles = slim_cdiv(d.M, 64) * slim_cdiv(d.N, 64);
     if (trans_b)
-      SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 64, 64>), dim3(tiles), dim3(NTHREADS), smem_bytes(64, 64), d);
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 64, 64>"), (dgemm_kernel<1, 64, 64>), dim3(tiles),
+                  dim3(NTHREADS), smem_bytes(64, 64), d);
     else
-      SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 64, 64>), dim3(tiles), dim3(NTHREADS), smem_bytes(64, 64), d);
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<0, 64, 64>"), (dgemm_kernel<0, 64, 64>), dim3(tiles),
+                  dim3(NTHREADS), smem_bytes(64, 64), d);
     return SLIM_OK;
   }
   const int tiles = slim_cdiv(d.M, 128) * slim_cdiv(d.N, 128);
@@ -268,9 +270,11 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
     lds = ONE_PER_CU_BYTES;
   }
   if (trans_b)
-    SLIM_LAUNCH(ctx, name, (dgemm_kernel<1, 128, 128>), dim3(tiles), dim3(NTHREADS), lds, d);
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 128, 128>"), (dgemm_kernel<1, 128, 128>), dim3(tiles),
+                dim3(NTHREADS), lds, d);
   else
-    SLIM_LAUNCH(ctx, name, (dgemm_kernel<0, 128, 128>), dim3(tiles), dim3(NTHREADS), lds, d);
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<0, 128, 128>"), (dgemm_kernel<0, 128, 128>), dim3(tiles),
+                dim3(NTHREADS), lds, d);
   return SLIM_OK;
 }
 
@@ -280,15 +284,19 @@ slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, con
   if (use_small_tiles(max_M, max_N, count)) {
     const int tiles = slim_cdiv(max_M, 64) * slim_cdiv(max_N, 64);
     if (trans_b)
-      SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<1, 64, 64>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_batched_kernel<1, 64, 64>"), (dgemm_batched_kernel<1, 64, 64>),
+                  dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
     else
-      SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<0, 64, 64>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_batched_kernel<0, 64, 64>"), (dgemm_batched_kernel<0, 64, 64>),
+                  dim3(tiles, count), dim3(NTHREADS), smem_bytes(64, 64), descs_dev);
     return SLIM_OK;
   }
   const int tiles = slim_cdiv(max_M, 128) * slim_cdiv(max_N, 128);
   if (trans_b)
-    SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<1, 128, 128>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_batched_kernel<1, 128, 128>"), (dgemm_batched_kernel<1, 128, 128>),
+                dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
   else
-    SLIM_LAUNCH(ctx, name, (dgemm_batched_kernel<0, 128, 128>), dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_batched_kernel<0, 128, 128>"), (dgemm_batched_kernel<0, 128, 128>),
+                dim3(tiles, count), dim3(NTHREADS), smem_bytes(128, 128), descs_dev);
   return SLIM_OK;
 }

@@ -581,18 +581,18 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   const dim3 grid((unsigned)nwg), block(NTHREADS);
   if (x_dtype == SLIM_BF16) {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel_full<true>), grid, block, kSmemFull, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel_full<true>", (gram_kernel_full<true>), grid, block, kSmemFull, a);
     else if (ragged)
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, true>", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
     else
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, false>", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
   } else {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel_full<false>), grid, block, kSmemFull, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel_full<false>", (gram_kernel_full<false>), grid, block, kSmemFull, a);
     else if (ragged)
-      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, true>", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
     else
-      SLIM_LAUNCH(ctx, "gram_mfma_f16", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, false>", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
   }
   SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, TM / 4), dim3(256), 0, a, G, ldg);
   *n_tokens += t_c;

@@ -65,6 +65,10 @@ inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255);
 // Creates the side streams and their events on first use.
 slim_status slim_ensure_side(slim_ctx* ctx);
 
+// Returns a pointer to a process-lifetime copy of "<step>@<kernel function>", the form of a profiling entry's
+// name for launch sites that choose among several kernel functions.
+const char* slim_prof_name(const char* step, const char* kernel_function);
+
 // Profiling hooks used by SLIM_LAUNCH.
 void slim_prof_begin(slim_ctx* ctx, const char* name);
 void slim_prof_end(slim_ctx* ctx);
