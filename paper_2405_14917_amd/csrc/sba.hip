@@ -245,10 +245,13 @@ __global__ __launch_bounds__(256) void kl_step(const double* __restrict__ P, con
 
 // one thread per token: KL_t = B_t - (sum P q - (M_t + log sum exp(q - M_t))); every workgroup of 256 tokens
 // writes its sum
-__global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial, int parts, int64_t ts,
-                                                   const double* __restrict__ tok, const double* __restrict__ tokB,
-                                                   double* __restrict__ block_sums) {
+__global__ __launch_bounds__(256) void kl_finalize(const double* __restrict__ partial_all, int64_t pstride, int parts,
+                                                   int64_t ts, const double* __restrict__ tok,
+                                                   const double* __restrict__ tokB, double* __restrict__ block_sums_all,
+                                                   int nblocks) {
   __shared__ double red[256];
+  const double* partial = partial_all + (int64_t)blockIdx.y * pstride;       // blockIdx.y = candidate
+  double* block_sums = block_sums_all + (int64_t)blockIdx.y * nblocks;
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   double acc = 0.0;
   if (t < ts) {
@@ -291,9 +294,11 @@ __global__ __launch_bounds__(256) void mse_partial(const double* __restrict__ Y,
 }
 
 // one thread per token: sums the row parts of its token; every workgroup of 256 tokens writes its sum
-__global__ __launch_bounds__(256) void mse_finalize(const double* __restrict__ partial, int parts, int64_t ts,
-                                                    double* __restrict__ block_sums) {
+__global__ __launch_bounds__(256) void mse_finalize(const double* __restrict__ partial_all, int64_t pstride, int parts,
+                                                    int64_t ts, double* __restrict__ block_sums_all, int nblocks) {
   __shared__ double red[256];
+  const double* partial = partial_all + (int64_t)blockIdx.y * pstride;       // blockIdx.y = candidate
+  double* block_sums = block_sums_all + (int64_t)blockIdx.y * nblocks;
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   double acc = 0.0;
   if (t < ts)
@@ -370,12 +375,12 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   const size_t bW = slim_ws_round(sizeof(double) * (size_t)n * m);
   const size_t bX = slim_ws_round(sizeof(double) * (size_t)m * t_s);
   const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
-  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);
+  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);   // per candidate
   const int kl_blocks = slim_cdiv(t_s, 256);
   const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
   const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * k + 2));
   const size_t bTok = slim_ws_round(sizeof(double) * 3 * (size_t)t_s);
-  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + bPart + bObj + bOrd + bTok + 256);
+  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + (size_t)(pmax + 1) * bPart + bObj + bOrd + bTok + 256);
   if (st != SLIM_OK) return st;
   double* W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
   double* WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
@@ -384,7 +389,8 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   double* Xcat = static_cast<double*>(slim_ws_alloc(ctx, bX));
   double* Yt = static_cast<double*>(slim_ws_alloc(ctx, bY));
   double* Yc = static_cast<double*>(slim_ws_alloc(ctx, bY));
-  double* partial = static_cast<double*>(slim_ws_alloc(ctx, bPart));
+  double* partial = static_cast<double*>(slim_ws_alloc(ctx, (size_t)(pmax + 1) * bPart));
+  const int64_t pstride = (int64_t)(bPart / sizeof(double));   // every candidate keeps its partials until the end
   double* obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
   double* block_sums = obj + (pmax + 2);
   int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
@@ -434,15 +440,10 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
     SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_entropy, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tokB);
   }
   for (int p = 0; p <= pmax; ++p) {
-    if (objective == SLIM_OBJ_KL) {
-      SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial);
-      SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tok, tokB,
-                  block_sums + (int64_t)p * kl_blocks);
-    } else {
-      SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial);
-      SLIM_LAUNCH(ctx, "sba_mse_finalize", mse_finalize, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s,
-                  block_sums + (int64_t)p * kl_blocks);
-    }
+    if (objective == SLIM_OBJ_KL)
+      SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial + p * pstride);
+    else
+      SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial + p * pstride);
     if (p < pmax) {
       // Y_{p+1}^T = Y_p^T + [D_lo | D_hi]_p [X_lo ; X_hi]_p : one rank-2beta update
       slim_gemm_desc u;
@@ -464,6 +465,13 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
       if (st != SLIM_OK) return st;
     }
   }
+  // the per-token merges of all candidates in one launch (grid.y = candidate)
+  if (objective == SLIM_OBJ_KL)
+    SLIM_LAUNCH(ctx, "sba_kl_finalize", kl_finalize, dim3(kl_blocks, pmax + 1), dim3(256), 0, partial, pstride, parts, t_s,
+                tok, tokB, block_sums, kl_blocks);
+  else
+    SLIM_LAUNCH(ctx, "sba_mse_finalize", mse_finalize, dim3(kl_blocks, pmax + 1), dim3(256), 0, partial, pstride, parts,
+                t_s, block_sums, kl_blocks);
   SLIM_LAUNCH(ctx, "sba_finalize", sba_finalize, dim3(1), dim3(256), 0, block_sums, kl_blocks, obj, pmax, order, k, N,
               bits, pstar_dev);
 
