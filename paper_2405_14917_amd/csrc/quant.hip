@@ -322,15 +322,75 @@ struct SweepArgs {
   int what_f64;
 };
 
-// The per-step dependent chain is what bounds this kernel (a dependent fp64 instruction costs about 32
-// cycles): broadcast w_j -> multiply by 1/s -> round -> clamp -> error -> scale -> update.  Everything else
-// (the next row of U and the next reciprocal from LDS, the code and error bookkeeping) is kept off that chain.
+// fmax / fmin without the canonicalisation of the operands that the compiler would add in front of every use
+// (the operands here are never signalling NaNs)
+__device__ __forceinline__ double vmax_f64(double a, double b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  double r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+#else
+  return a > b ? a : b;
+#endif
+}
+__device__ __forceinline__ double vmin_f64(double a, double b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  double r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+#else
+  return a < b ? a : b;
+#endif
+}
+
+// One step of the sweep: column j (lane jj of register set r) with row `u` of U and 1 / U_jj = rd.
+// With four wavefronts per SIMD the kernel is bound by the number of instructions it issues per step, so the
+// step is kept short: the error and the code go to LDS with one store each (every lane holds the same value)
+// instead of being selected into the owning lane's registers, the tie check is a subtraction and a compare.
+template <int EPL, bool SIGN>
+__device__ __forceinline__ void sweep_step(double (&w)[EPL], int r, int jj, const double (&u)[EPL], double rd, double s,
+                                           double rs, double z, double lo, double hi, double& e2, double* eb, uint8_t* qb,
+                                           int j) {
+  const double wj = read_lane_f64(w[r], jj);
+  double qz;                                   // q - z
+  if (SIGN) {
+    qz = (wj >= 0.0) ? 0.5 : -0.5;
+  } else {
+    // The code is rint(wj / s) with a true division.  wj * (1 / s) lies within a few ulps of the quotient, so
+    // unless it is that close to a rounding tie it rounds the same way; only then (practically never) is the
+    // division done (a real branch: the asm keeps the compiler from computing the quotient speculatively).
+    // Codes are clamped to a few units around zero, so 1e-7 is far above a few ulps of any x that matters.
+    double x = wj * rs;
+    double xr = rint(x);
+    if (fabs(x - xr) > 0.5 - 1e-7) {
+      x = wj / s;
+      asm volatile("" : "+v"(x));
+      xr = rint(x);
+    }
+    qz = vmin_f64(vmax_f64(xr, lo), hi);
+  }
+  const double e = fma(-s, qz, wj) * rd;       // (w_j - s (q - z)) / U_jj; continuous, so a reciprocal is fine
+#pragma unroll
+  for (int r2 = 0; r2 < EPL; ++r2)
+    if (r2 >= r) w[r2] = fma(-e, u[r2], w[r2]);
+  e2 = fma(e, e, e2);
+  eb[j] = e;
+  qb[j] = (uint8_t)(int)(qz + z);
+}
+
+// The per-step dependent chain and the number of instructions per step bound this kernel (a dependent fp64
+// instruction costs about 32 cycles): broadcast w_j -> multiply by 1/s -> round -> clamp -> error -> scale ->
+// update.  The next row of U and the next reciprocal come from LDS one step ahead; two steps per loop iteration
+// so that the two register sets of the look-ahead swap roles instead of being copied.
 template <int EPL, bool SIGN>
 __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
-  extern __shared__ __align__(16) double Us[];   // [beta + 1][beta] (last row padding), then [beta + 64] reciprocals
+  // [beta + 1][beta] (last row padding), [beta + 64] reciprocals, then per wavefront beta errors and beta codes
+  extern __shared__ __align__(16) double Us[];
   const int beta = a.beta;
   double* rdiag = Us + (beta + 1) * beta + 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  double* eb = rdiag + beta + 64 + wave * beta;
+  uint8_t* qb = reinterpret_cast<uint8_t*>(rdiag + beta + 64 + SWEEP_WAVES * beta) + wave * beta;
   for (int idx = tid; idx < (beta + 1) * beta + 64; idx += SWEEP_WAVES * 64) {
     const int j = idx / beta, l = idx - j * beta;
     Us[idx] = (j < beta && l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
@@ -346,66 +406,44 @@ __global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
   const double rs = 1.0 / s;
   const double lo = -z, hi = qmax - z;           // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), lo, hi)
 
-  double w[EPL], ev[EPL], qv[EPL];
+  double w[EPL];
   double* wr = a.W + (int64_t)row * a.ldw;
 #pragma unroll
   for (int r = 0; r < EPL; ++r) {
     const int c = r * 64 + lane;
     w[r] = (c < beta) ? wr[c] : 0.0;
-    ev[r] = 0.0;
-    qv[r] = 0.0;
   }
   double e2 = 0.0;
   // row j of U and 1 / U_jj for the current step, fetched one step ahead (lanes beyond beta read padding)
-  double u[EPL], rd = rdiag[0];
+  double u0[EPL], u1[EPL], rd0 = rdiag[0], rd1;
 #pragma unroll
-  for (int r = 0; r < EPL; ++r) u[r] = Us[r * 64 + lane];
+  for (int r = 0; r < EPL; ++r) u0[r] = Us[r * 64 + lane];
 #pragma unroll
   for (int r = 0; r < EPL; ++r) {
-    const int jend = min(64, beta - r * 64);
-    for (int jj = 0; jj < jend; ++jj) {
+    const int jend = min(64, beta - r * 64);     // even: beta is a multiple of 32
+    for (int jj = 0; jj < jend; jj += 2) {
       const int j = r * 64 + jj;
-      double un[EPL];
-      const double rdn = rdiag[j + 1];
+      rd1 = rdiag[j + 1];
 #pragma unroll
-      for (int r2 = 0; r2 < EPL; ++r2) un[r2] = Us[(j + 1) * beta + r2 * 64 + lane];
-      const double wj = read_lane_f64(w[r], jj);
-      double qz;                                 // q - z
-      if (SIGN) {
-        qz = (wj >= 0.0) ? 0.5 : -0.5;
-      } else {
-        // The code is rint(wj / s) with a true division.  wj * (1 / s) lies within a few ulps of the quotient,
-        // so unless it is that close to a rounding tie it rounds the same way; only then is the division done
-        // (a real branch: the asm keeps the compiler from computing the quotient speculatively).
-        double x = wj * rs;
-        const double fr = fabs(__builtin_amdgcn_fract(x) - 0.5);
-        if (fr <= 8.0 * 2.220446049250313e-16 * fmax(fabs(x), 1.0)) {
-          x = wj / s;
-          asm volatile("" : "+v"(x));
-        }
-        qz = fmin(fmax(rint(x), lo), hi);
-      }
-      const double e = fma(-s, qz, wj) * rd;     // (w_j - s (q - z)) / U_jj; continuous, so a reciprocal is fine
+      for (int r2 = 0; r2 < EPL; ++r2) u1[r2] = Us[(j + 1) * beta + r2 * 64 + lane];
+      sweep_step<EPL, SIGN>(w, r, jj, u0, rd0, s, rs, z, lo, hi, e2, eb, qb, j);
+      rd0 = rdiag[j + 2];
 #pragma unroll
-      for (int r2 = r; r2 < EPL; ++r2) w[r2] = fma(-e, u[r2], w[r2]);
-      e2 = fma(e, e, e2);
-      if (lane == jj) {
-        ev[r] = e;
-        qv[r] = qz + z;
-      }
-      rd = rdn;
-#pragma unroll
-      for (int r2 = 0; r2 < EPL; ++r2) u[r2] = un[r2];
+      for (int r2 = 0; r2 < EPL; ++r2) u0[r2] = Us[(j + 2) * beta + r2 * 64 + lane];
+      sweep_step<EPL, SIGN>(w, r, jj + 1, u1, rd1, s, rs, z, lo, hi, e2, eb, qb, j + 1);
     }
   }
+  // each lane picks up the errors and codes of its own columns (written by its own wavefront)
 #pragma unroll
   for (int r = 0; r < EPL; ++r) {
     const int c = r * 64 + lane;
     if (c < beta) {
-      a.codes[(int64_t)row * a.ldc + c] = (uint8_t)qv[r];
-      a.E[(int64_t)row * a.lde + c] = ev[r];
+      const double ev = eb[c];
+      const double qv = (double)qb[c];
+      a.codes[(int64_t)row * a.ldc + c] = qb[c];
+      a.E[(int64_t)row * a.lde + c] = ev;
       if (a.What) {
-        const double what = s * (qv[r] - z);
+        const double what = s * (qv - z);
         if (a.what_f64)
           static_cast<double*>(a.What)[(int64_t)row * a.ldwh + c] = what;
         else
@@ -573,7 +611,8 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
 
-  const size_t sweep_smem = sizeof(double) * ((size_t)(SB + 1) * SB + 64 + SB + 64);
+  const size_t sweep_smem = sizeof(double) * ((size_t)(SB + 1) * SB + 64 + SB + 64 + (size_t)SWEEP_WAVES * SB) +
+                            (size_t)SWEEP_WAVES * SB;
   if (sweep_smem > 64 * 1024) {
     static bool done0 = false, done1 = false;
     st = allow_big_lds(ctx, gptq_sweep<2, false>, done0);
