@@ -11,10 +11,11 @@
 //   sqc_search    one workgroup per 8 rows: row min/max/mean|w|, loss weights, then every
 //                 (row, candidate) pair is one thread that walks the row's beta weights in LDS;
 //                 wavefront argmin with ties to the lower candidate index
-//   gptq_sweep    one wavefront per row, the row's beta weights in registers, the beta x beta block
-//                 of U in LDS; beta serial steps of quantise -> error -> rank-1 update of the row
+//   gptq_sweep4   four rows per wavefront (16 lanes each), the row's beta weights in registers, the
+//                 beta x beta block of U in LDS; beta serial steps of quantise -> error -> rank-1 update
 //   dgemm         W[:, later] -= E_b U[b, later] on the fp64 matrix cores
 #include <algorithm>
+#include <utility>
 
 #include "slim_device.h"
 #include "slim_internal.h"
@@ -26,7 +27,6 @@ using namespace slimdev;
 constexpr int SQC_CPT = 4;        // candidates per thread in sqc_search
 constexpr int SQC_THREADS = 256;
 constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
-constexpr int SWEEP_WAVES = 16;   // rows (= wavefronts) per workgroup in gptq_sweep
 
 // ------------------------------------------------------------------------------------------
 // Shifted first and second moments of an n x beta block, one partial pair per slab of STAT_ROWS rows.
@@ -301,7 +301,7 @@ size_t sqc_smem_bytes(int beta, int ncand, int rows) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Column sweep of one group.  One wavefront per row; lane l holds columns l, l + 64, ... of the group.
+// Column sweep of one group: arguments and helpers.
 // ------------------------------------------------------------------------------------------
 struct SweepArgs {
   double* W;             // working copy, pointer to the block's first column
@@ -320,6 +320,7 @@ struct SweepArgs {
   void* What;            // pointer to What[0][b0] or null
   int64_t ldwh;
   int what_f64;
+  int sets;              // sets of rows each wavefront sweeps one after the other
 };
 
 // fmax / fmin without the canonicalisation of the operands that the compiler would add in front of every use
@@ -343,115 +344,243 @@ __device__ __forceinline__ double vmin_f64(double a, double b) {
 #endif
 }
 
-// One step of the sweep: column j (lane jj of register set r) with row `u` of U and 1 / U_jj = rd.
-// With four wavefronts per SIMD the kernel is bound by the number of instructions it issues per step, so the
-// step is kept short: the error and the code go to LDS with one store each (every lane holds the same value)
-// instead of being selected into the owning lane's registers, the tie check is a subtraction and a compare.
-template <int EPL, bool SIGN>
-__device__ __forceinline__ void sweep_step(double (&w)[EPL], int r, int jj, const double (&u)[EPL], double rd, double s,
-                                           double rs, double z, double lo, double hi, double& e2, double* eb, uint8_t* qb,
-                                           int j) {
-  const double wj = read_lane_f64(w[r], jj);
-  double qz;                                   // q - z
+// ------------------------------------------------------------------------------------------
+// The sweep itself, four rows per wavefront.  Most instructions of a step work on values that are the same for
+// every lane of a row (the current weight, its code, the error), so a wavefront that carried one row would
+// spend 64 lanes on them.  Here a row takes 16 lanes (one DPP row): lane l of a row holds columns
+// l, l + 16, ... of the group, v_mov_b32_dpp row_newbcast hands the current column to the 16 lanes of each row,
+// and the scalar work of a step serves four rows at once.  The steps are unrolled completely (the DPP lane is
+// an immediate), so every LDS offset is a constant.  Row j of the U block keeps only the columns from the start
+// of its 16-column segment on, which halves the block in LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int SWEEP4_RPW = 4;   // rows per wavefront
+
+// offset of row 16 k + jj of the packed U block (rows of segment k' hold BETA - 16 k' entries)
+__host__ __device__ constexpr int sweep4_row_off(int beta, int k, int jj) {
+  return 16 * k * beta - 128 * k * (k - 1) + jj * (beta - 16 * k);
+}
+
+template <int N>
+__device__ __forceinline__ double bcast_row16(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, 0x150 + N, 0xf, 0xf, true);   // row_newbcast:N, every lane written
+  hi = __builtin_amdgcn_update_dpp(0, hi, 0x150 + N, 0xf, 0xf, true);
+  return __hiloint2double(hi, lo);
+}
+
+template <int BETA>
+struct Sweep4 {
+  static constexpr int NK = BETA / 16;
+  double w[NK];          // the row's weights: w[k] is column 16 k + l16
+  double u[NK];          // row j of U / U_jj for the current step (entries k >= j / 16)
+  double wj;             // the current column's weight, the same in the row's 16 lanes
+  double rd;             // 1 / U_jj
+  double ujn;            // U_{j,j+1} / U_jj
+  double s, rs, z, lo, hi, e2;
+  const double* Ub;      // packed, row-scaled U block
+  const double* rdiag;
+  // Index bases kept in registers (opaque to the compiler), so that every LDS read of the unrolled steps is one of
+  // these plus an immediate offset below 64 KiB: 0 and HI for the reads that are the same in every lane, l16 and
+  // l16 + HI for a lane's own columns.
+  static constexpr int HI = 4096;
+  int u0, uh, l0, lh;
+  template <int OFF> __device__ __forceinline__ double uni() const {
+    return OFF < HI ? Ub[u0 + OFF] : Ub[uh + (OFF - HI)];
+  }
+  // index of entry OFF of the packed block plus the lane's own column offset
+  template <int OFF> __device__ __forceinline__ int mine() const { return OFF < HI ? l0 + OFF : lh + (OFF - HI); }
+  double* eb;            // this row's beta errors
+  uint8_t* qb;           // this row's beta codes
+};
+
+// One step.  A lone wavefront per SIMD is bound by the chain of dependent fp64 instructions from one column's
+// weight to the next one's (each costs some 32 cycles), so the chain is kept to
+//   w_j -> * 1/s -> round -> max -> min -> d = w_j - s (q - z) -> w_{j+1} = bcast(w[j+1]) - d U'_{j,j+1}:
+// the rows of U are stored divided by their diagonal element (U' = U / U_jj, so the update is w -= d U' and the
+// error e = d / U_jj is formed beside the chain), the next column's weight is updated by itself from a broadcast
+// taken before this step's update, and the tie check is evaluated beside the clamp and acted on afterwards.
+template <int BETA, bool SIGN, int K, int JJ>
+__device__ __forceinline__ void sweep4_step(Sweep4<BETA>& st) {
+  constexpr int NK = BETA / 16, J = 16 * K + JJ;
+  constexpr int K1 = (J + 1) / 16, JJ1 = (J + 1) % 16;
+  // the next step's row of U' and reciprocal, fetched ahead of this step's arithmetic
+  double un[NK];
+  double rdn = 0.0, ujnn = 0.0, wpre = 0.0;
+  if constexpr (J + 1 < BETA) {
+    constexpr int off = sweep4_row_off(BETA, K1, JJ1);
+#pragma unroll
+    for (int k2 = K1; k2 < NK; ++k2) un[k2] = st.Ub[st.template mine<off>() + (k2 - K1) * 16];
+    rdn = st.rdiag[st.u0 + J + 1];
+    if constexpr (J + 2 < BETA) ujnn = st.template uni<off + JJ1 + 1>();   // U'_{j+1,j+2}
+    wpre = bcast_row16<JJ1>(st.w[K1]);                         // w_{j+1} before this step's update
+  }
+  const double wj = st.wj;
+  double qz, d;                                // q - z and w_j - s (q - z)
   if (SIGN) {
     qz = (wj >= 0.0) ? 0.5 : -0.5;
+    d = fma(-st.s, qz, wj);
   } else {
     // The code is rint(wj / s) with a true division.  wj * (1 / s) lies within a few ulps of the quotient, so
     // unless it is that close to a rounding tie it rounds the same way; only then (practically never) is the
     // division done (a real branch: the asm keeps the compiler from computing the quotient speculatively).
     // Codes are clamped to a few units around zero, so 1e-7 is far above a few ulps of any x that matters.
-    double x = wj * rs;
-    double xr = rint(x);
+    const double x = wj * st.rs;
+    const double xr = rint(x);
+    qz = vmin_f64(vmax_f64(xr, st.lo), st.hi);
+    d = fma(-st.s, qz, wj);
     if (fabs(x - xr) > 0.5 - 1e-7) {
-      x = wj / s;
-      asm volatile("" : "+v"(x));
-      xr = rint(x);
+      double xd = wj / st.s;
+      asm volatile("" : "+v"(xd));
+      qz = vmin_f64(vmax_f64(rint(xd), st.lo), st.hi);
+      d = fma(-st.s, qz, wj);
     }
-    qz = vmin_f64(vmax_f64(xr, lo), hi);
   }
-  const double e = fma(-s, qz, wj) * rd;       // (w_j - s (q - z)) / U_jj; continuous, so a reciprocal is fine
+  if constexpr (J + 1 < BETA) st.wj = fma(-d, st.ujn, wpre);
 #pragma unroll
-  for (int r2 = 0; r2 < EPL; ++r2)
-    if (r2 >= r) w[r2] = fma(-e, u[r2], w[r2]);
-  e2 = fma(e, e, e2);
-  eb[j] = e;
-  qb[j] = (uint8_t)(int)(qz + z);
+  for (int k2 = K; k2 < NK; ++k2) {
+    st.w[k2] = fma(-d, st.u[k2], st.w[k2]);
+    // Later segments' weights are not read for many steps; without this the compiler sinks their updates down to
+    // the first use and keeps every step's d and row of U alive (in scratch) until then.
+    asm volatile("" : "+v"(st.w[k2]));
+  }
+  const double e = d * st.rd;
+  st.e2 = fma(e, e, st.e2);
+  asm volatile("" : "+v"(st.e2));              // same: keep the running sum here, not every error until the end
+  st.eb[J] = e;
+  st.qb[J] = (uint8_t)(int)(qz + st.z);
+  if constexpr (J + 1 < BETA) {
+#pragma unroll
+    for (int k2 = K1; k2 < NK; ++k2) st.u[k2] = un[k2];
+    st.rd = rdn;
+    st.ujn = ujnn;
+  }
+  // The steps are one long straight line; left alone, the scheduler hoists the LDS reads of many steps to the
+  // top and runs out of registers.
+  __builtin_amdgcn_sched_barrier(0);
 }
 
-// The per-step dependent chain and the number of instructions per step bound this kernel (a dependent fp64
-// instruction costs about 32 cycles): broadcast w_j -> multiply by 1/s -> round -> clamp -> error -> scale ->
-// update.  The next row of U and the next reciprocal come from LDS one step ahead; two steps per loop iteration
-// so that the two register sets of the look-ahead swap roles instead of being copied.
-template <int EPL, bool SIGN>
-__global__ __launch_bounds__(SWEEP_WAVES * 64) void gptq_sweep(SweepArgs a) {
-  // [beta + 1][beta] (last row padding), [beta + 64] reciprocals, then per wavefront beta errors and beta codes
+template <int BETA, bool SIGN, int K, int... JJ>
+__device__ __forceinline__ void sweep4_segment(Sweep4<BETA>& st, std::integer_sequence<int, JJ...>) {
+  (sweep4_step<BETA, SIGN, K, JJ>(st), ...);
+}
+template <int BETA, bool SIGN, int... K>
+__device__ __forceinline__ void sweep4_all(Sweep4<BETA>& st, std::integer_sequence<int, K...>) {
+  (sweep4_segment<BETA, SIGN, K>(st, std::make_integer_sequence<int, 16>{}), ...);
+}
+
+// LDS of gptq_sweep4: packed U block, reciprocals of its diagonal, then per row BETA errors and BETA codes
+size_t sweep4_smem_bytes(int beta, int waves) {
+  const int rows = waves * SWEEP4_RPW;
+  const size_t packed = (size_t)sweep4_row_off(beta, beta / 16, 0);
+  return sizeof(double) * (packed + beta + (size_t)rows * beta) + (size_t)rows * beta;
+}
+
+template <int BETA, bool SIGN>
+__global__ __launch_bounds__(1024) void gptq_sweep4(SweepArgs a) {
+  constexpr int NK = BETA / 16, PACKED = sweep4_row_off(BETA, NK, 0);
   extern __shared__ __align__(16) double Us[];
-  const int beta = a.beta;
-  double* rdiag = Us + (beta + 1) * beta + 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  double* eb = rdiag + beta + 64 + wave * beta;
-  uint8_t* qb = reinterpret_cast<uint8_t*>(rdiag + beta + 64 + SWEEP_WAVES * beta) + wave * beta;
-  for (int idx = tid; idx < (beta + 1) * beta + 64; idx += SWEEP_WAVES * 64) {
-    const int j = idx / beta, l = idx - j * beta;
-    Us[idx] = (j < beta && l >= j) ? a.U[(int64_t)j * a.ldu + l] : 0.0;   // only the upper triangle is meaningful
-  }
-  for (int j = tid; j < beta + 64; j += SWEEP_WAVES * 64) rdiag[j] = (j < beta) ? 1.0 / a.U[(int64_t)j * a.ldu + j] : 0.0;
+  const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63, wave = tid >> 6;
+  const int rows_per_wg = (nthreads >> 6) * SWEEP4_RPW;
+  double* rdiag = Us + PACKED;
+  double* ebase = rdiag + BETA;
+  uint8_t* qbase = reinterpret_cast<uint8_t*>(ebase + rows_per_wg * BETA);
+  for (int j = tid; j < BETA; j += nthreads) rdiag[j] = 1.0 / a.U[(int64_t)j * a.ldu + j];
   __syncthreads();
-  const int row = blockIdx.x * SWEEP_WAVES + wave;
-  if (row >= a.n) return;
-
-  const double qmax = (double)((1 << a.bits) - 1);
-  const double s = a.scale[(int64_t)row * a.sz_stride];
-  const double z = a.zero[(int64_t)row * a.sz_stride];
-  const double rs = 1.0 / s;
-  const double lo = -z, hi = qmax - z;           // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), lo, hi)
-
-  double w[EPL];
-  double* wr = a.W + (int64_t)row * a.ldw;
+  // The packed block, two columns at a time: only the upper triangle is meaningful, and each row is divided by
+  // its diagonal element.  Six loads are in flight per thread before the first is used (the block comes from L2,
+  // and with few wavefronts per workgroup the fill would otherwise be a string of round trips).
+  constexpr int FILL = 6;
+  for (int i0 = tid; i0 < PACKED / 2; i0 += FILL * nthreads) {
+    double2 v[FILL];
+    int jrow[FILL], col[FILL];
 #pragma unroll
-  for (int r = 0; r < EPL; ++r) {
-    const int c = r * 64 + lane;
-    w[r] = (c < beta) ? wr[c] : 0.0;
-  }
-  double e2 = 0.0;
-  // row j of U and 1 / U_jj for the current step, fetched one step ahead (lanes beyond beta read padding)
-  double u0[EPL], u1[EPL], rd0 = rdiag[0], rd1;
+    for (int q = 0; q < FILL; ++q) {
+      const int e = 2 * (i0 + q * nthreads);       // index in the packed block
+      v[q] = make_double2(0.0, 0.0);
+      if (e < PACKED) {
+        int k = 0;
 #pragma unroll
-  for (int r = 0; r < EPL; ++r) u0[r] = Us[r * 64 + lane];
-#pragma unroll
-  for (int r = 0; r < EPL; ++r) {
-    const int jend = min(64, beta - r * 64);     // even: beta is a multiple of 32
-    for (int jj = 0; jj < jend; jj += 2) {
-      const int j = r * 64 + jj;
-      rd1 = rdiag[j + 1];
-#pragma unroll
-      for (int r2 = 0; r2 < EPL; ++r2) u1[r2] = Us[(j + 1) * beta + r2 * 64 + lane];
-      sweep_step<EPL, SIGN>(w, r, jj, u0, rd0, s, rs, z, lo, hi, e2, eb, qb, j);
-      rd0 = rdiag[j + 2];
-#pragma unroll
-      for (int r2 = 0; r2 < EPL; ++r2) u0[r2] = Us[(j + 2) * beta + r2 * 64 + lane];
-      sweep_step<EPL, SIGN>(w, r, jj + 1, u1, rd1, s, rs, z, lo, hi, e2, eb, qb, j + 1);
+        for (int kk = 1; kk < NK; ++kk) k += (e >= sweep4_row_off(BETA, kk, 0)) ? 1 : 0;
+        const int width = BETA - 16 * k, r = e - sweep4_row_off(BETA, k, 0);
+        const int jj = r / width;
+        jrow[q] = 16 * k + jj;
+        col[q] = r - jj * width;                   // column within the segment's range, even
+        v[q] = *reinterpret_cast<const double2*>(a.U + (int64_t)jrow[q] * a.ldu + 16 * k + col[q]);
+      }
     }
-  }
-  // each lane picks up the errors and codes of its own columns (written by its own wavefront)
 #pragma unroll
-  for (int r = 0; r < EPL; ++r) {
-    const int c = r * 64 + lane;
-    if (c < beta) {
-      const double ev = eb[c];
-      const double qv = (double)qb[c];
-      a.codes[(int64_t)row * a.ldc + c] = qb[c];
-      a.E[(int64_t)row * a.lde + c] = ev;
-      if (a.What) {
-        const double what = s * (qv - z);
-        if (a.what_f64)
-          static_cast<double*>(a.What)[(int64_t)row * a.ldwh + c] = what;
-        else
-          static_cast<float*>(a.What)[(int64_t)row * a.ldwh + c] = (float)what;
+    for (int q = 0; q < FILL; ++q) {
+      const int e = 2 * (i0 + q * nthreads);
+      if (e < PACKED) {
+        const double rd = rdiag[jrow[q]];
+        const int jj = jrow[q] & 15;
+        double2 o;
+        o.x = (col[q] >= jj) ? v[q].x * rd : 0.0;
+        o.y = (col[q] + 1 >= jj) ? v[q].y * rd : 0.0;
+        *reinterpret_cast<double2*>(Us + e) = o;
       }
     }
   }
-  if (lane == 0) a.row_e2[row] += e2;
+  __syncthreads();
+
+  // No barrier below.  With more rows than one round of workgroups holds, a wavefront sweeps several sets of rows
+  // in turn and the workgroup's copy of the U block serves them all.
+  const int g = lane >> 4, l16 = lane & 15;
+  const int rl = wave * SWEEP4_RPW + g;            // row within the workgroup's current set
+  for (int set = 0; set < a.sets; ++set) {
+    const int row0 = (blockIdx.x * a.sets + set) * rows_per_wg;
+    const int row = row0 + rl;
+    if (row0 + wave * SWEEP4_RPW >= a.n) break;
+    const bool valid = row < a.n;                    // rows past the end compute on zeros and store nothing
+
+    Sweep4<BETA> st;
+    const double qmax = (double)((1 << a.bits) - 1);
+    st.s = valid ? a.scale[(int64_t)row * a.sz_stride] : 1.0;
+    st.z = valid ? a.zero[(int64_t)row * a.sz_stride] : 0.0;
+    st.rs = 1.0 / st.s;
+    st.lo = -st.z;                                   // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), lo, hi)
+    st.hi = qmax - st.z;
+    st.e2 = 0.0;
+    st.Ub = Us;
+    st.rdiag = rdiag;
+    st.u0 = 0;
+    st.uh = Sweep4<BETA>::HI;
+    st.l0 = l16;
+    st.lh = l16 + Sweep4<BETA>::HI;
+    asm volatile("" : "+v"(st.u0), "+v"(st.uh), "+v"(st.l0), "+v"(st.lh));
+    st.eb = ebase + rl * BETA;
+    st.qb = qbase + rl * BETA;
+    const double* wr = a.W + (int64_t)row * a.ldw;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) st.w[k] = valid ? wr[16 * k + l16] : 0.0;
+#pragma unroll
+    for (int k = 0; k < NK; ++k) st.u[k] = Us[l16 + 16 * k];
+    st.rd = rdiag[0];
+    st.ujn = Us[1];
+    st.wj = bcast_row16<0>(st.w[0]);
+    asm volatile("" : "+v"(st.lo));                  // opaque, or -z is formed again in every step
+    sweep4_all<BETA, SIGN>(st, std::make_integer_sequence<int, NK>{});
+
+    // each lane picks up the errors and codes of its own columns (written by its own wavefront)
+    if (valid) {
+#pragma unroll
+      for (int k = 0; k < NK; ++k) {
+        const int c = 16 * k + l16;
+        const double ev = st.eb[c];
+        const uint8_t code = st.qb[c];
+        a.codes[(int64_t)row * a.ldc + c] = code;
+        a.E[(int64_t)row * a.lde + c] = ev;
+        if (a.What) {
+          const double what = st.s * ((double)code - st.z);
+          if (a.what_f64)
+            static_cast<double*>(a.What)[(int64_t)row * a.ldwh + c] = what;
+          else
+            static_cast<float*>(a.What)[(int64_t)row * a.ldwh + c] = (float)what;
+        }
+      }
+      if (l16 == 0) a.row_e2[row] += st.e2;
+    }
+  }
 }
 
 // Kernels that may need more than the default 64 KiB of dynamic LDS opt in once per process.
@@ -611,13 +740,18 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
 
-  const size_t sweep_smem = sizeof(double) * ((size_t)(SB + 1) * SB + 64 + SB + 64 + (size_t)SWEEP_WAVES * SB) +
-                            (size_t)SWEEP_WAVES * SB;
+  // Rows per workgroup of the sweep: as few as fill the chip, so that small layers spread over every compute
+  // unit and large ones share each workgroup's copy of the U block among more rows.
+  int sweep_waves = 4;
+  while (sweep_waves < 16 && slim_cdiv(n, sweep_waves * SWEEP4_RPW) > ctx->num_cus) sweep_waves *= 2;
+  const int sweep_rows = sweep_waves * SWEEP4_RPW;
+  const int sweep_sets = std::min(8, slim_cdiv(n, sweep_rows * ctx->num_cus));
+  const size_t sweep_smem = sweep4_smem_bytes(SB, sweep_waves);
   if (sweep_smem > 64 * 1024) {
     static bool done0 = false, done1 = false;
-    st = allow_big_lds(ctx, gptq_sweep<2, false>, done0);
+    st = allow_big_lds(ctx, gptq_sweep4<128, false>, done0);
     if (st != SLIM_OK) return st;
-    st = allow_big_lds(ctx, gptq_sweep<2, true>, done1);
+    st = allow_big_lds(ctx, gptq_sweep4<128, true>, done1);
     if (st != SLIM_OK) return st;
   }
 
@@ -671,19 +805,23 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
       s.What = s.what_f64 ? static_cast<void*>(static_cast<double*>(What) + b0)
                           : static_cast<void*>(static_cast<float*>(What) + b0);
     }
-    const dim3 sgrid(slim_cdiv(n, SWEEP_WAVES)), sblock(SWEEP_WAVES * 64);
+    s.sets = sweep_sets;
+    const dim3 sgrid(slim_cdiv(n, sweep_rows * sweep_sets)), sblock(sweep_waves * 64);
     const bool sign = (gb[g] == 1 && prm.q1_mode == SLIM_Q1_SIGN);
-    if (SB <= 64) {
-      if (sign)
-        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<1, true>), sgrid, sblock, sweep_smem, s);
-      else
-        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<1, false>), sgrid, sblock, sweep_smem, s);
-    } else {
-      if (sign)
-        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, true>), sgrid, sblock, sweep_smem, s);
-      else
-        SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep<2, false>), sgrid, sblock, sweep_smem, s);
-    }
+#define SLIM_SWEEP4(B)                                                                           \
+  do {                                                                                           \
+    if (sign)                                                                                    \
+      SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep4<B, true>), sgrid, sblock, sweep_smem, s);      \
+    else                                                                                         \
+      SLIM_LAUNCH(ctx, "gptq_sweep", (gptq_sweep4<B, false>), sgrid, sblock, sweep_smem, s);     \
+  } while (0)
+    if (SB == 32)
+      SLIM_SWEEP4(32);
+    else if (SB == 64)
+      SLIM_SWEEP4(64);
+    else
+      SLIM_SWEEP4(128);
+#undef SLIM_SWEEP4
 
     slim_gemm_desc d;
     d.C2 = nullptr;

@@ -293,6 +293,15 @@ def test_gptq_quantize(slim, beta, n, m):
     _gptq_case(slim, W, X, bits, beta)
 
 
+# many rows: the sweep puts more rows into a workgroup (5000: 32, with a last workgroup of 8) and, beyond one round
+# of workgroups, lets each wavefront sweep several sets of rows in turn (20000: 64 rows x 2 sets, ragged)
+@pytest.mark.parametrize("beta,n,m", [(128, 5000, 256), (128, 20000, 128), (32, 20000, 64)])
+def test_gptq_quantize_many_rows(slim, beta, n, m):
+    W, X = small_layer(n + m, n=n, m=m, t=4 * m, beta=beta)
+    bits = np.array([2, 3, 4, 2][: m // beta], dtype=np.uint8)
+    _gptq_case(slim, W, X, bits, beta)
+
+
 def test_gptq_modes_and_fp32_weights(slim):
     from paper_2405_14917_amd import binding
     W, X = small_layer(77, n=64, m=256, t=1024, beta=64, w_dtype=np.float32)
