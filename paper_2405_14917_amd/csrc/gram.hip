@@ -472,15 +472,19 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
 }
 
 // G[i][j] += the sum over the slots of the tile (in slot order) for every (i, j) of an upper tile pair;
-// mirrored into the lower triangle.
+// mirrored into the lower triangle.  One workgroup per 64 x 64 block of a tile: 16-byte reads of the slots,
+// the block itself added to G row by row, its transpose through LDS, so that both sides are written in whole rows.
+constexpr int RB = 64;
 __global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict__ G, int64_t ldg) {
+  __shared__ float T[RB][RB + 1];
   const int tile = blockIdx.x;
+  const int si = blockIdx.y / (TM / RB), sj = blockIdx.y % (TM / RB);
   int bi, bj;
   decode_tile(tile, (a.m + TM - 1) / TM, bi, bj);
-  const int row0 = bi * TM, col0 = bj * TM;
-  const int rl = blockIdx.y * 4 + (threadIdx.x >> 6);
-  const int r = row0 + rl;
-  if (r >= a.m) return;
+  if (bi == bj && si > sj) return;                 // below the diagonal: written as the mirror of the block above it
+  const int row0 = bi * TM + si * RB, col0 = bj * TM + sj * RB;
+  if (row0 >= a.m || col0 >= a.m) return;
+  const bool diag = (bi == bj && si == sj);
   int64_t base;
   int count;
   if (tile < a.tiles_main) {
@@ -490,15 +494,67 @@ __global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict
     base = (int64_t)a.n_main + (int64_t)(tile - a.tiles_main) * a.S * a.f;
     count = a.S * a.f;
   }
-  const float* __restrict__ P = a.P + base * (TM * TM) + rl * TM;
-  for (int cl = threadIdx.x & 63; cl < TM; cl += 64) {
-    const int c = col0 + cl;
-    if (c >= a.m) break;
-    if (bi == bj && c < r) continue;
-    float s = 0.f;
-    for (int p = 0; p < count; ++p) s += P[(int64_t)p * (TM * TM) + cl];
-    G[(int64_t)r * ldg + c] += s;
-    if (c != r) G[(int64_t)c * ldg + r] += s;
+  // thread -> rows tr, tr + 16, tr + 32, tr + 48 of the block, columns tc .. tc + 3
+  const int tr = threadIdx.x >> 4, tc = (threadIdx.x & 15) * 4;
+  const float* __restrict__ P = a.P + base * (TM * TM) + (int64_t)(si * RB + tr) * TM + sj * RB + tc;
+  float4 acc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = 0; p < count; ++p) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(P + (int64_t)p * (TM * TM) + q * 16 * TM);
+      acc[q].x += v.x;
+      acc[q].y += v.y;
+      acc[q].z += v.z;
+      acc[q].w += v.w;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    T[tr + 16 * q][tc + 0] = acc[q].x;
+    T[tr + 16 * q][tc + 1] = acc[q].y;
+    T[tr + 16 * q][tc + 2] = acc[q].z;
+    T[tr + 16 * q][tc + 3] = acc[q].w;
+  }
+  __syncthreads();
+  const bool vec = (ldg % 4 == 0) && !diag;        // m is a multiple of 8, so a group of 4 is inside or outside
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int y = tr + 16 * q;
+    // the block: G[row0 + y][col0 + tc ..]
+    if (row0 + y < a.m && col0 + tc < a.m) {
+      float* g = G + (int64_t)(row0 + y) * ldg + col0 + tc;
+      if (vec) {
+        float4 o = *reinterpret_cast<float4*>(g);
+        o.x += acc[q].x;
+        o.y += acc[q].y;
+        o.z += acc[q].z;
+        o.w += acc[q].w;
+        *reinterpret_cast<float4*>(g) = o;
+      } else {
+        const float e[4] = {acc[q].x, acc[q].y, acc[q].z, acc[q].w};
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          if (!diag || tc + x >= y) g[x] += e[x];
+      }
+    }
+    // its mirror: G[col0 + y][row0 + tc ..] gets T[tc ..][y]
+    if (col0 + y < a.m && row0 + tc < a.m) {
+      float* g = G + (int64_t)(col0 + y) * ldg + row0 + tc;
+      if (vec) {
+        float4 o = *reinterpret_cast<float4*>(g);
+        o.x += T[tc + 0][y];
+        o.y += T[tc + 1][y];
+        o.z += T[tc + 2][y];
+        o.w += T[tc + 3][y];
+        *reinterpret_cast<float4*>(g) = o;
+      } else {
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          if (!diag || y > tc + x) g[x] += T[tc + x][y];
+      }
+    }
   }
 }
 
@@ -594,7 +650,7 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
     else
       SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, false>", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
   }
-  SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, TM / 4), dim3(256), 0, a, G, ldg);
+  SLIM_LAUNCH(ctx, "gram_reduce", gram_reduce, dim3(tiles, (TM / RB) * (TM / RB)), dim3(256), 0, a, G, ldg);
   *n_tokens += t_c;
   return SLIM_OK;
 }
