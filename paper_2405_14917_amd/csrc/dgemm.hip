@@ -8,6 +8,8 @@
 // of 16 x 16.  K advances in slabs of 16 through two LDS buffers (k-major, so that the 16 lanes that feed
 // one k-slice of an MFMA operand read 16 consecutive doubles); the next slab is fetched into registers
 // while the current one is multiplied, one barrier per slab.
+#include <algorithm>
+
 #include "slim_internal.h"
 
 namespace {
@@ -346,6 +348,31 @@ __global__ __launch_bounds__(NTHREADS) void dgemm_batched_kernel(const slim_gemm
   gemm_body<TRANS_B, BM, BN>(d, blockIdx.x, smem);
 }
 
+// Persistent form for bulk work beside a latency-critical chain on another stream: fewer workgroups than CUs, each
+// taking tiles in turn, with an LDS request that lets nothing else of any size share their CUs.  The CUs it leaves
+// out stay free for the chain's kernels.  With SLIM_GEMM_UPPER_ONLY (M == N) only the tiles on or above the
+// diagonal are enumerated.
+template <int TRANS_B, int BM, int BN>
+__global__ __launch_bounds__(NTHREADS) void dgemm_reserved_kernel(slim_gemm_desc d) {
+  extern __shared__ __align__(16) double smem[];
+  const int tiles_n = (d.N + BN - 1) / BN, tiles_m = (d.M + BM - 1) / BM;
+  if (d.flags & SLIM_GEMM_UPPER_ONLY) {
+    const int nt = tiles_n;                       // square: tiles_m == tiles_n
+    const int total = nt * (nt + 1) / 2;
+    for (int u = blockIdx.x; u < total; u += gridDim.x) {
+      // row bi holds the nt - bi tiles bj >= bi; rows before it hold bi * nt - bi (bi - 1) / 2
+      int bi = (int)((2.0f * nt + 1.0f - sqrtf((2.0f * nt + 1.0f) * (2.0f * nt + 1.0f) - 8.0f * u)) * 0.5f);
+      bi = max(0, min(bi, nt - 1));
+      while (bi > 0 && bi * nt - bi * (bi - 1) / 2 > u) --bi;
+      while (bi + 1 < nt && (bi + 1) * nt - (bi + 1) * bi / 2 <= u) ++bi;
+      const int bj = bi + (u - (bi * nt - bi * (bi - 1) / 2));
+      gemm_body<TRANS_B, BM, BN>(d, bi * tiles_n + bj, smem);
+    }
+  } else {
+    for (int pid = blockIdx.x; pid < tiles_m * tiles_n; pid += gridDim.x) gemm_body<TRANS_B, BM, BN>(d, pid, smem);
+  }
+}
+
 constexpr size_t smem_bytes(int bm, int bn) { return size_t(2) * (BK * bm + BK * bn) * sizeof(double); }
 
 // 64 x 64 tiles when 128 x 128 tiles would leave most of the 256 CUs without work
@@ -363,8 +390,10 @@ slim_status check_desc(slim_ctx* ctx, const slim_gemm_desc& d) {
   return SLIM_OK;
 }
 
-// LDS request that lets only one workgroup of the launch live on a CU (160 KiB per CU)
-constexpr size_t ONE_PER_CU_BYTES = 88 * 1024;
+// The persistent form asks for all of a CU's LDS (160 KiB), so nothing else shares its CUs, and leaves RESERVED_CUS
+// of them alone: room for the chain's own kernels and the small products it waits for.
+constexpr size_t ONE_PER_CU_BYTES = 160 * 1024;
+constexpr int RESERVED_CUS = 32;
 
 template <typename K>
 slim_status allow_lds(slim_ctx* ctx, K kernel, bool& done) {
@@ -393,12 +422,26 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
     return SLIM_OK;
   }
   const int tiles = slim_cdiv(d.M, 128) * slim_cdiv(d.N, 128);
-  size_t lds = smem_bytes(128, 128);
+  const size_t lds = smem_bytes(128, 128);
   if (d.flags & SLIM_GEMM_ONE_PER_CU) {
     static bool done0 = false, done1 = false;
-    st = trans_b ? allow_lds(ctx, dgemm_kernel<1, 128, 128>, done1) : allow_lds(ctx, dgemm_kernel<0, 128, 128>, done0);
+    st = trans_b ? allow_lds(ctx, dgemm_reserved_kernel<1, 128, 128>, done1)
+                 : allow_lds(ctx, dgemm_reserved_kernel<0, 128, 128>, done0);
     if (st != SLIM_OK) return st;
-    lds = ONE_PER_CU_BYTES;
+    int work = tiles;
+    if (d.flags & SLIM_GEMM_UPPER_ONLY) {
+      SLIM_REQUIRE(ctx, d.M == d.N, "dgemm: SLIM_GEMM_UPPER_ONLY needs a square result");
+      const int nt = slim_cdiv(d.N, 128);
+      work = nt * (nt + 1) / 2;
+    }
+    const int wgs = std::max(1, std::min(work, ctx->num_cus - RESERVED_CUS));
+    if (trans_b)
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_reserved_kernel<1, 128, 128>"), (dgemm_reserved_kernel<1, 128, 128>),
+                  dim3(wgs), dim3(NTHREADS), ONE_PER_CU_BYTES, d);
+    else
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_reserved_kernel<0, 128, 128>"), (dgemm_reserved_kernel<0, 128, 128>),
+                  dim3(wgs), dim3(NTHREADS), ONE_PER_CU_BYTES, d);
+    return SLIM_OK;
   }
   if (trans_b)
     SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 128, 128>"), (dgemm_kernel<1, 128, 128>), dim3(tiles),

@@ -579,8 +579,8 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       d.M = gp;
       d.N = gp;
       d.K = g1 - g0;
-      // While this update is short next to the four diagonal steps it runs beside, it takes one workgroup slot
-      // per CU and so leaves room for their kernels; a large one is throughput-bound and takes the whole chip.
+      // While this update is short next to the four diagonal steps it runs beside, it runs as a persistent
+      // kernel that leaves some CUs to their kernels; a large one is throughput-bound and takes the whole chip.
       d.flags = SLIM_GEMM_UPPER_ONLY | (gp <= 4096 ? SLIM_GEMM_ONE_PER_CU : 0);
       d.alpha = -1.0;
       d.beta = 1.0;

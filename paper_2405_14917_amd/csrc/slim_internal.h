@@ -109,9 +109,9 @@ inline int slim_cdiv(int64_t a, int64_t b) { return static_cast<int>((a + b - 1)
 //   flags: SLIM_GEMM_UPPER_ONLY skips output tiles that lie entirely below the diagonal (M == N).
 //          SLIM_GEMM_A_UPPER / SLIM_GEMM_B_UPPER declare A (M x K, square) / op(B) (K x N, square) upper
 //          triangular with zeros below the diagonal so that the K range can be cut.
-//          SLIM_GEMM_ONE_PER_CU makes the launch ask for so much LDS that a CU holds one workgroup of it: for
-//          bulk work on a side stream that must leave registers and LDS to a latency-critical chain of
-//          small kernels on another stream.
+//          SLIM_GEMM_ONE_PER_CU runs the product as a persistent kernel on all but a few CUs, one workgroup per
+//          CU, with an LDS request that lets nothing else share those CUs: for bulk work on a side stream next to
+//          a latency-critical chain of small kernels on other streams, which then finds the remaining CUs free.
 // K and N even, all pointers 16-byte aligned, leading dimensions even.
 enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4, SLIM_GEMM_ONE_PER_CU = 8 };
 struct slim_gemm_desc {
