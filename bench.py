@@ -46,7 +46,11 @@ def resident_inputs(cfg):
 
 
 class Pass:
-    """The hot path over one resident layer; all buffers are allocated once, outside the timed region."""
+    """The hot path over one resident layer; all buffers are allocated once, outside the timed region.
+
+    Two library contexts on two streams: the half of the bit allocation that needs neither the Hessian nor the
+    salience (the reference outputs and the outputs of the all-N-bit weights, two n x m x t_s products) is enqueued
+    on the second stream before the inverse, whose chain of small kernels leaves most of the chip idle."""
 
     def __init__(self, slim, cfg, W, X):
         self.slim, self.cfg, self.W, self.X = slim, cfg, W, X
@@ -55,17 +59,34 @@ class Pass:
         self.U = torch.empty((m, m), dtype=torch.float64, device="cuda")
         self.d = torch.empty(m, dtype=torch.float64, device="cuda")
         self.Xs = X[:, : min(T_SBA, cfg.t)]
+        self.main = torch.cuda.current_stream()
+        self.side = torch.cuda.Stream()
+        with torch.cuda.stream(self.side):
+            self.slim_sba = binding.Slim("cuda:0")
+
+    def contexts(self):
+        return [self.slim, self.slim_sba]
 
     def step(self):
-        cfg, s = self.cfg, self.slim
+        cfg, s, s2 = self.cfg, self.slim, self.slim_sba
         self.G.zero_()
         nt = s.hessian_accumulate(self.X, self.G, 0)
+        self.side.wait_stream(self.main)               # the Gram kernel has the chip to itself
+        s2.sba_prepare(self.W, cfg.beta, cfg.N, self.Xs)
         s.hessian_inverse(self.G, nt, cfg.percdamp, U=self.U, hinv_diag=self.d)
         _, grp, _ = s.salience(self.W, self.d, cfg.beta)
-        bits, p_star, _ = s.sba_allocate(self.W, grp, cfg.beta, cfg.N, self.Xs)
+        self.side.wait_stream(self.main)
+        with torch.cuda.stream(self.side):
+            bits, p_star, _ = s2.sba_allocate(self.W, grp, cfg.beta, cfg.N, self.Xs)
+        grp.record_stream(self.side)
+        bits.record_stream(self.main)
+        self.main.wait_stream(self.side)
         out = s.gptq_quantize(self.W, self.U, bits, cfg.beta)
         packed, gbits, row_off, m_star = s.pack(out["codes"], bits, cfg.beta, packed_rows=cfg.m * (cfg.N + 1) // 32)
         return p_star, m_star
+
+    def close(self):
+        self.slim_sba.close()
 
 
 def algorithmic_work(name, cfg, launches_per_step):
@@ -77,7 +98,8 @@ def algorithmic_work(name, cfg, launches_per_step):
     if name.startswith("gram_mfma"):
         return "mfma", "mfma_f16", float(m) * (m + 1) * t / launches_per_step
     if name == "sba_output_dgemm":
-        return "mfma", "mfma_f64", 2.0 * n * m * ts
+        # two products per step (reference outputs, outputs of the all-N-bit weights), in one launch or two
+        return "mfma", "mfma_f64", 2.0 * (2.0 * n * m * ts) / max(launches_per_step, 1)
     if name == "sba_update_dgemm":
         return "mfma", "mfma_f64", 4.0 * n * beta * ts
     if name == "gptq_trailing_dgemm":
@@ -195,12 +217,17 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # per-kernel durations with HIP events on the library's stream, in extra steps of the same job
-    slim.profile_enable(True)
-    slim.profile_reset()
+    for c in job.contexts():
+        c.profile_enable(True)
+        c.profile_reset()
     for _ in range(args.profile_steps):
         job.step()
-    prof = slim.profile_collect()
-    slim.profile_enable(False)
+    prof = {}
+    for c in job.contexts():
+        for full, (ms, cnt) in c.profile_collect().items():
+            a = prof.get(full, (0.0, 0))
+            prof[full] = (a[0] + ms, a[1] + cnt)
+        c.profile_enable(False)
     # A profiling entry is named "<step>" or "<step>@<kernel function>" (launch sites that choose among several
     # kernel functions say which one ran).  `kernels` is keyed by step; the roofline is given for the kernel
     # FUNCTION with the largest share of the GPU time, under the name rocprofv3 lists it by, so that its average
@@ -262,6 +289,7 @@ def main():
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:
         line["cpu_baseline"] = None
+    job.close()
     slim.close()
     print(json.dumps(line))
 

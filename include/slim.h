@@ -139,6 +139,19 @@ slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, 
                               slim_dtype x_dtype, int64_t t_s, int64_t ldxs, const slim_params* params,
                               uint8_t* bits, int* p_star, double* obj_curve);
 
+/* Optional first half of slim_sba_allocate (Eq. 4): everything of the objective that does not depend on the
+ * ranking of the groups - the reference outputs x W^T and their softmax statistics, and the outputs of the weights
+ * with every group at N bits - is computed and kept in the context's workspace.  It needs neither the Hessian nor
+ * the salience, so a caller with a second context on a second stream can run it beside slim_hessian_inverse
+ * (a chain of small kernels that leaves most of the chip idle; the products here leave some CUs to it).
+ * Asynchronous, no host output.  The next call on this context must be slim_sba_allocate with the same W, X_s,
+ * shapes, N, objective and params, which then only ranks, searches and finishes; with any other argument, or after
+ * any other call on the context, slim_sba_allocate computes everything itself.  W and X_s must not change in
+ * between.  The result of slim_sba_allocate is bit for bit the same either way. */
+slim_status slim_sba_prepare(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw, int beta,
+                             int N, int objective, const void* X_s, slim_dtype x_dtype, int64_t t_s, int64_t ldxs,
+                             const slim_params* params);
+
 /* ---------------------------------------------------------------------------------------------
  * a5 + a6  3-sigma mask and Salience-Weighted Quantizer Calibration on ONE n x beta block of
  * current weights (Sec. 3.3.2; Eq. 5; Alg. 1 line 8; Alg. 2 SQC).

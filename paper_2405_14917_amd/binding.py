@@ -28,7 +28,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32, torch.float
 EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
-    "slim_sba_allocate", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack",
+    "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -75,6 +75,8 @@ def load() -> ctypes.CDLL:
                                   c_int, c_void_p, c_void_p, c_void_p]
     lib.slim_sba_allocate.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_i64, c_void_p, c_int, c_int, c_int,
                                       c_void_p, c_int, c_i64, c_i64, P(SlimParams), c_void_p, P(c_int), P(c_double)]
+    lib.slim_sba_prepare.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_i64, c_int, c_int, c_int, c_void_p,
+                                     c_int, c_i64, c_i64, P(SlimParams)]
     lib.slim_sqc_calibrate.argtypes = [c_void_p, c_void_p, c_i64, c_int, c_int, c_int, c_void_p, c_void_p,
                                        P(SlimParams), c_void_p, c_int, c_void_p, c_void_p, c_void_p]
     lib.slim_gptq_quantize.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_i64, c_void_p, c_i64, c_void_p,
@@ -194,6 +196,16 @@ class Slim:
         return col, grp, elem
 
     # ---- a4
+    def sba_prepare(self, W: torch.Tensor, beta: int, N: int, Xs: torch.Tensor, params: Optional[SlimParams] = None,
+                    objective: int = OBJ_KL) -> None:
+        """Enqueues the part of sba_allocate that needs no salience; the next call on this context must be
+        sba_allocate with the same W, Xs, beta, N, params and objective."""
+        _need_cuda(W, Xs)
+        n, m = W.shape
+        self._check(self.lib.slim_sba_prepare(self.ctx, _ptr(W), _DT[W.dtype], n, m, W.stride(0), beta, N, objective,
+                                              _ptr(Xs), _DT[Xs.dtype], Xs.shape[1], Xs.stride(0),
+                                              ctypes.byref(params) if params is not None else None))
+
     def sba_allocate(self, W: torch.Tensor, group_sal: torch.Tensor, beta: int, N: int, Xs: torch.Tensor,
                      params: Optional[SlimParams] = None, objective: int = OBJ_KL):
         """Returns (bits uint8 device tensor (k,), p_star, obj_curve numpy (k//2+1,))."""

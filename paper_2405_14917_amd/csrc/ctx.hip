@@ -16,6 +16,7 @@ slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...) {
 
 slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes) {
   ctx->ws_off = 0;
+  ctx->sba_prep.valid = false;    // whoever reserves is about to overwrite what a prepare call left
   if (bytes <= ctx->ws_bytes) return SLIM_OK;
   // the old buffer may still be in use by work enqueued earlier
   SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));

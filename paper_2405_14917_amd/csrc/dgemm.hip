@@ -158,11 +158,13 @@ __device__ __forceinline__ void k_loop_edge(const slim_gemm_desc& d, int row0, i
 // follow behind the next ones, and the LDS reads of each k-step of 4 are issued one step ahead.  No clamps and
 // no selects: the global pointers just advance by a slab (and stop at the last one, which is then fetched and
 // stored again without being used).
-template <int TRANS_B, int BM, int BN>
+// NT threads: NT / 64 wavefronts, two along N and the rest along M.
+template <int TRANS_B, int BM, int BN, int NT = NTHREADS>
 __device__ __forceinline__ void k_loop_fast(const slim_gemm_desc& d, int row0, int col0, int kbeg, int kend,
-                                            double* smem, double4v (&acc)[BM / 32][BN / 32]) {
-  constexpr int MI = BM / 32, NJ = BN / 32;
-  constexpr int PA = BM / 32, PB = BN / 32;          // double2 per thread and slab
+                                            double* smem, double4v (&acc)[BM / (NT / 128) / 16][BN / 32]) {
+  constexpr int WM = NT / 128;                       // wavefronts along M
+  constexpr int MI = BM / WM / 16, NJ = BN / 32;
+  constexpr int PA = BM * 8 / NT, PB = BN * 8 / NT;  // double2 per thread and slab
   constexpr int STAGE = BK * BM + BK * BN;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -175,8 +177,8 @@ __device__ __forceinline__ void k_loop_fast(const slim_gemm_desc& d, int row0, i
   const double* pa = d.A + (int64_t)(row0 + ra) * d.lda + kbeg + kha;
   const int sa = kha * BM + ra;
   // B: as A when given N x K; else (K x N) thread -> (k, 2 * PB consecutive columns)
-  constexpr int TB = 8 / PB;
-  const int rb = TRANS_B ? tid / TB : tid >> 4, khb = TRANS_B ? (tid % TB) * (2 * PB) : (tid & 15) * (2 * PB);
+  constexpr int TB = 8 / PB, TK = NT / 16;           // threads per row (N x K) or per k (K x N)
+  const int rb = TRANS_B ? tid / TB : tid / TK, khb = TRANS_B ? (tid % TB) * (2 * PB) : (tid % TK) * (2 * PB);
   const double* pb = TRANS_B ? d.B + (int64_t)(col0 + rb) * d.ldb + kbeg + khb
                              : d.B + (int64_t)(kbeg + rb) * d.ldb + col0 + khb;
   const int64_t stepb = TRANS_B ? (int64_t)BK : (int64_t)BK * d.ldb;
@@ -218,7 +220,7 @@ __device__ __forceinline__ void k_loop_fast(const slim_gemm_desc& d, int row0, i
   __syncthreads();
 
   for (int it = 0; it < nslabs; ++it) {
-    const double* as = smem + (it & 1) * STAGE + wm * (BM / 2) + l16;
+    const double* as = smem + (it & 1) * STAGE + wm * (BM / WM) + l16;
     const double* bs = smem + (it & 1) * STAGE + BK * BM + wn * (BN / 2) + l16;
     double* other = smem + ((it & 1) ^ 1) * STAGE;
     // the registers hold slab it + 1; the loads below fetch slab min(it + 2, nslabs - 1)
@@ -373,6 +375,49 @@ __global__ __launch_bounds__(NTHREADS) void dgemm_reserved_kernel(slim_gemm_desc
   }
 }
 
+// The same for products without edges (M a multiple of 256, N of 128, K of 16, no flags): 512 threads per
+// workgroup on a 256 x 128 tile, so that the one workgroup a CU holds still gives every SIMD two wavefronts.
+// Up to two products share a launch: their tiles are numbered through, which evens out the last round.
+struct WidePair {
+  slim_gemm_desc d[2];
+  int count;
+};
+template <int TRANS_B>
+__global__ __launch_bounds__(512) void dgemm_reserved_wide_kernel(WidePair w) {
+  constexpr int BM = 256, BN = 128, NT = 512, MI = 4, NJ = 4;
+  extern __shared__ __align__(16) double smem[];
+  const int tiles0 = (w.d[0].M / BM) * (w.d[0].N / BN);
+  const int tiles = tiles0 + (w.count > 1 ? (w.d[1].M / BM) * (w.d[1].N / BN) : 0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lk = lane >> 4;
+  for (int unit = blockIdx.x; unit < tiles; unit += gridDim.x) {
+    const slim_gemm_desc& d = unit < tiles0 ? w.d[0] : w.d[1];
+    const int pid = unit < tiles0 ? unit : unit - tiles0;
+    const int tiles_n = d.N / BN;
+    const int row0 = (pid / tiles_n) * BM, col0 = (pid % tiles_n) * BN;
+    double4v acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[i][j] = double4v{0.0, 0.0, 0.0, 0.0};
+    k_loop_fast<TRANS_B, BM, BN, NT>(d, row0, col0, 0, d.K, smem, acc);
+    // accumulator register v of lane l holds C[4 * v + l / 16][l % 16] of its 16 x 16 tile
+    const double alpha = d.alpha, beta = d.beta;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        double* crow = d.C + (int64_t)(row0 + wm * 64 + i * 16 + 4 * v + lk) * d.ldc + col0 + wn * 64 + l16;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          double r = alpha * acc[i][j][v];
+          if (beta != 0.0) r += beta * crow[j * 16];
+          crow[j * 16] = r;
+        }
+      }
+  }
+}
+
 constexpr size_t smem_bytes(int bm, int bn) { return size_t(2) * (BK * bm + BK * bn) * sizeof(double); }
 
 // 64 x 64 tiles when 128 x 128 tiles would leave most of the 256 CUs without work
@@ -449,6 +494,49 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
   else
     SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<0, 128, 128>"), (dgemm_kernel<0, 128, 128>), dim3(tiles),
                 dim3(NTHREADS), lds, d);
+  return SLIM_OK;
+}
+
+// Half of the chip: next to a factorisation, whose own bulk updates want whole CUs too, this has measured best.
+int slim_dgemm_reserved_cus(const slim_ctx* ctx) { return std::max(1, ctx->num_cus / 2); }
+
+slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count) {
+  if (count < 1 || count > 2) return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "dgemm: one or two products per reserved launch");
+  bool wide = true;
+  int tiles = 0;
+  for (int i = 0; i < count; ++i) {
+    const slim_gemm_desc& d = descs[i];
+    slim_status st = check_desc(ctx, d);
+    if (st != SLIM_OK) return st;
+    wide = wide && d.flags == 0 && d.M > 0 && d.N > 0 && d.M % 256 == 0 && d.N % 128 == 0 && d.K % 16 == 0 && d.K > 0 && !d.C2;
+    if (wide) tiles += (d.M / 256) * (d.N / 128);
+  }
+  if (!wide) {
+    for (int i = 0; i < count; ++i) {
+      slim_gemm_desc d = descs[i];
+      d.flags |= SLIM_GEMM_ONE_PER_CU;
+      slim_status st = slim_dgemm(ctx, name, trans_b, d);
+      if (st != SLIM_OK) return st;
+    }
+    return SLIM_OK;
+  }
+  static bool wide0 = false, wide1 = false;
+  slim_status st = trans_b ? allow_lds(ctx, dgemm_reserved_wide_kernel<1>, wide1) : allow_lds(ctx, dgemm_reserved_wide_kernel<0>, wide0);
+  if (st != SLIM_OK) return st;
+  // as many rounds as the CUs that may be used need, and then no more workgroups than fill those rounds
+  const int usable = slim_dgemm_reserved_cus(ctx);
+  const int rounds = slim_cdiv(tiles, usable);
+  const int wgs = slim_cdiv(tiles, rounds);
+  WidePair w;
+  w.d[0] = descs[0];
+  w.d[1] = descs[count - 1];
+  w.count = count;
+  if (trans_b)
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_reserved_wide_kernel<1>"), (dgemm_reserved_wide_kernel<1>), dim3(wgs),
+                dim3(512), ONE_PER_CU_BYTES, w);
+  else
+    SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_reserved_wide_kernel<0>"), (dgemm_reserved_wide_kernel<0>), dim3(wgs),
+                dim3(512), ONE_PER_CU_BYTES, w);
   return SLIM_OK;
 }
 

@@ -19,6 +19,8 @@
 //     dgemm         Y_{p+1}^T = Y_p^T + [D_lo(g_lo) | D_hi(g_hi)] [X_s(g_lo) ; X_s(g_hi)]  (rank 2 beta; the
 //                   operands were laid out in search order on the device, no host round trip)
 //   sba_finalize    first minimum of obj, bit vector of p*
+#include <algorithm>
+
 #include "slim_device.h"
 #include "slim_internal.h"
 
@@ -81,9 +83,11 @@ __device__ __forceinline__ double rtn_apply(const RtnParams& p, double w) {
 // W_N goes to WN in the natural layout.  The difference to the other width a group can take is stored in
 // "search order": column block r (2 beta wide) of Dcat holds [W_{N-1} - W_N of the r-th least salient group |
 // W_{N+1} - W_N of the r-th most salient group], so that step r of the search is ONE rank-2beta update.
+// `parts` selects what is written: FQ_WN (needs no ranking), FQ_DCAT, or both.
+enum { FQ_WN = 1, FQ_DCAT = 2 };
 __global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ W, int n, int m, int beta, int N,
                                                      int q1_mode, const int* __restrict__ rank_of, int pmax,
-                                                     double* __restrict__ WN, double* __restrict__ Dcat) {
+                                                     double* __restrict__ WN, double* __restrict__ Dcat, int parts) {
   const int lane = threadIdx.x & 63;
   const int k = m / beta;
   const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -101,6 +105,10 @@ __global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ 
   mx = wave_max(mx);
   sabs = wave_sum(sabs) / (double)beta;
   const RtnParams pn = rtn_params(mn, mx, sabs, N, q1_mode);
+  if (!(parts & FQ_DCAT)) {
+    for (int c = lane; c < beta; c += 64) WN[base + c] = rtn_apply(pn, W[base + c]);
+    return;
+  }
   const int pos = rank_of[g];
   const bool low = pos < pmax, high = pos >= k - pmax;
   const RtnParams po = rtn_params(mn, mx, sabs, low ? N - 1 : N + 1, q1_mode);
@@ -108,7 +116,7 @@ __global__ __launch_bounds__(256) void sba_fakequant(const double* __restrict__ 
   for (int c = lane; c < beta; c += 64) {
     const double v = W[base + c];
     const double wn = rtn_apply(pn, v);
-    WN[base + c] = wn;
+    if (parts & FQ_WN) WN[base + c] = wn;
     if (low || high) Dcat[dbase + c] = rtn_apply(po, v) - wn;
   }
 }
@@ -347,74 +355,87 @@ __global__ __launch_bounds__(256) void sba_finalize(const double* __restrict__ b
 
 }  // namespace
 
-extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
-                                         const double* group_sal, int beta, int N, int objective, const void* X_s,
-                                         slim_dtype x_dtype, int64_t t_s, int64_t ldxs, const slim_params* params,
-                                         uint8_t* bits, int* p_star, double* obj_curve) {
-  if (!ctx) return SLIM_ERR_INVALID_ARG;
-  slim_params prm;
-  slim_default_params(&prm);
-  if (params) prm = *params;
-  SLIM_REQUIRE(ctx, W && group_sal && X_s && bits && p_star, "slim_sba_allocate: null pointer");
-  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_sba_allocate: need n, m > 0 and beta | m");
-  SLIM_REQUIRE(ctx, N == 2 || N == 3, "slim_sba_allocate: N must be 2 or 3 (got %d)", N);
-  SLIM_REQUIRE(ctx, beta % 4 == 0 && ldw >= m && ldw % 4 == 0, "slim_sba_allocate: beta and ldw must be multiples of 4");
-  SLIM_REQUIRE(ctx, t_s > 0 && t_s % 4 == 0 && ldxs >= t_s && ldxs % 4 == 0,
-               "slim_sba_allocate: t_s and ldxs must be positive multiples of 4");
-  SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(X_s), "slim_sba_allocate: misaligned pointer");
-  SLIM_REQUIRE(ctx, prm.q1_mode == 0 || prm.q1_mode == 1, "slim_sba_allocate: unknown q1_mode");
-  SLIM_REQUIRE(ctx, objective == SLIM_OBJ_KL || objective == SLIM_OBJ_MSE, "slim_sba_allocate: unknown objective %d", objective);
-  if (w_dtype == SLIM_F64 || x_dtype == SLIM_F64 || x_dtype == SLIM_F32)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sba_allocate: W must be F16/BF16/F32 and X_s F16/BF16");
-  const int k = m / beta;
-  const int pmax = k / 2;
-  SLIM_REQUIRE(ctx, (size_t)(pmax + 2) * sizeof(double) <= (size_t)SLIM_HPIN_BYTES, "slim_sba_allocate: too many groups");
+namespace {
 
-  const int rpp = 256;                                  // rows per part of the KL reduction
-  const int parts = slim_cdiv(n, rpp);
+// The workspace of slim_sba_allocate; slim_sba_prepare fills the part of it that does not depend on the ranking.
+struct SbaWorkspace {
+  int k, pmax, rpp, parts, kl_blocks;
+  int64_t pstride;
+  double *W64, *WN, *Dcat, *X64, *Xcat, *Yt, *Yc, *partial, *obj, *block_sums, *tok, *tokB;
+  int *order, *rank_of, *pstar_dev;
+};
+
+slim_status sba_workspace(slim_ctx* ctx, int n, int m, int beta, int64_t t_s, SbaWorkspace& w) {
+  w.k = m / beta;
+  w.pmax = w.k / 2;
+  w.rpp = 256;                                          // rows per part of the KL reduction
+  w.parts = slim_cdiv(n, w.rpp);
+  w.kl_blocks = slim_cdiv(t_s, 256);
   const size_t bW = slim_ws_round(sizeof(double) * (size_t)n * m);
   const size_t bX = slim_ws_round(sizeof(double) * (size_t)m * t_s);
   const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
-  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);   // per candidate
-  const int kl_blocks = slim_cdiv(t_s, 256);
-  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
-  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * k + 2));
+  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)w.parts * t_s * KL_PART);   // per candidate
+  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(w.pmax + 2) * (size_t)(w.kl_blocks + 1));
+  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * w.k + 2));
   const size_t bTok = slim_ws_round(sizeof(double) * 3 * (size_t)t_s);
-  slim_status st = slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + (size_t)(pmax + 1) * bPart + bObj + bOrd + bTok + 256);
+  slim_status st =
+      slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + (size_t)(w.pmax + 1) * bPart + bObj + bOrd + bTok + 256);
   if (st != SLIM_OK) return st;
-  double* W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
-  double* WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
-  double* Dcat = static_cast<double*>(slim_ws_alloc(ctx, bW));
-  double* X64 = static_cast<double*>(slim_ws_alloc(ctx, bX));
-  double* Xcat = static_cast<double*>(slim_ws_alloc(ctx, bX));
-  double* Yt = static_cast<double*>(slim_ws_alloc(ctx, bY));
-  double* Yc = static_cast<double*>(slim_ws_alloc(ctx, bY));
-  double* partial = static_cast<double*>(slim_ws_alloc(ctx, (size_t)(pmax + 1) * bPart));
-  const int64_t pstride = (int64_t)(bPart / sizeof(double));   // every candidate keeps its partials until the end
-  double* obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
-  double* block_sums = obj + (pmax + 2);
-  int* order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
-  int* rank_of = order + (k + 1);
-  int* pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
-  double* tok = static_cast<double*>(slim_ws_alloc(ctx, bTok));   // per token {max, log-sum-exp} of the reference
-  double* tokB = tok + 2 * t_s;                                   // per token sum P log P
+  w.W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  w.WN = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  w.Dcat = static_cast<double*>(slim_ws_alloc(ctx, bW));
+  w.X64 = static_cast<double*>(slim_ws_alloc(ctx, bX));
+  w.Xcat = static_cast<double*>(slim_ws_alloc(ctx, bX));
+  w.Yt = static_cast<double*>(slim_ws_alloc(ctx, bY));
+  w.Yc = static_cast<double*>(slim_ws_alloc(ctx, bY));
+  w.partial = static_cast<double*>(slim_ws_alloc(ctx, (size_t)(w.pmax + 1) * bPart));
+  w.pstride = (int64_t)(bPart / sizeof(double));        // every candidate keeps its partials until the end
+  w.obj = static_cast<double*>(slim_ws_alloc(ctx, bObj));
+  w.block_sums = w.obj + (w.pmax + 2);
+  w.order = static_cast<int*>(slim_ws_alloc(ctx, bOrd));
+  w.rank_of = w.order + (w.k + 1);
+  w.pstar_dev = static_cast<int*>(slim_ws_alloc(ctx, 256));
+  w.tok = static_cast<double*>(slim_ws_alloc(ctx, bTok));   // per token {max, log-sum-exp} of the reference
+  w.tokB = w.tok + 2 * t_s;                                 // per token sum P log P
+  return SLIM_OK;
+}
 
-  SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order, rank_of);
-  st = slim_widen_f64(ctx, "sba_widen_w", W, w_dtype, n, m, ldw, W64, (int64_t)m);
-  if (st != SLIM_OK) return st;
-  st = slim_widen_f64(ctx, "sba_widen_x", X_s, x_dtype, m, (int)t_s, ldxs, X64, t_s);
-  if (st != SLIM_OK) return st;
-  SLIM_LAUNCH(ctx, "sba_fakequant", sba_fakequant, dim3(slim_cdiv((int64_t)n * k, 4)), dim3(256), 0, W64, n, m, beta, N,
-              prm.q1_mode, rank_of, pmax, WN, Dcat);
-  if (pmax > 0)
-    SLIM_LAUNCH(ctx, "sba_gather_x", sba_gather_x, dim3(64, 2 * pmax), dim3(256), 0, X64, t_s, beta, k, order, Xcat);
+slim_status sba_check(slim_ctx* ctx, const char* fn, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                      int beta, int N, int objective, const void* X_s, slim_dtype x_dtype, int64_t t_s, int64_t ldxs,
+                      const slim_params& prm) {
+  SLIM_REQUIRE(ctx, W && X_s, "%s: null pointer", fn);
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "%s: need n, m > 0 and beta | m", fn);
+  SLIM_REQUIRE(ctx, N == 2 || N == 3, "%s: N must be 2 or 3 (got %d)", fn, N);
+  SLIM_REQUIRE(ctx, beta % 4 == 0 && ldw >= m && ldw % 4 == 0, "%s: beta and ldw must be multiples of 4", fn);
+  SLIM_REQUIRE(ctx, t_s > 0 && t_s % 4 == 0 && ldxs >= t_s && ldxs % 4 == 0,
+               "%s: t_s and ldxs must be positive multiples of 4", fn);
+  SLIM_REQUIRE(ctx, slim_aligned16(W) && slim_aligned16(X_s), "%s: misaligned pointer", fn);
+  SLIM_REQUIRE(ctx, prm.q1_mode == 0 || prm.q1_mode == 1, "%s: unknown q1_mode", fn);
+  SLIM_REQUIRE(ctx, objective == SLIM_OBJ_KL || objective == SLIM_OBJ_MSE, "%s: unknown objective %d", fn, objective);
+  if (w_dtype == SLIM_F64 || x_dtype == SLIM_F64 || x_dtype == SLIM_F32)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "%s: W must be F16/BF16/F32 and X_s F16/BF16", fn);
+  SLIM_REQUIRE(ctx, (size_t)(m / beta / 2 + 2) * sizeof(double) <= (size_t)SLIM_HPIN_BYTES, "%s: too many groups", fn);
+  return SLIM_OK;
+}
 
+// The part of the objective that does not depend on the ranking (Eq. 4): W and X_s in fp64, the all-N-bit weights,
+// the reference outputs Y^T = W X_s and the outputs of the all-N-bit weights, and for the KL objective the reference
+// softmax with its per-token statistics.  `beside_chain` runs the two products in the form that leaves CUs free.
+slim_status sba_rank_independent(slim_ctx* ctx, const SbaWorkspace& w, const void* W, slim_dtype w_dtype, int n, int m,
+                                 int64_t ldw, int beta, int N, int objective, const void* X_s, slim_dtype x_dtype,
+                                 int64_t t_s, int64_t ldxs, int q1_mode, bool beside_chain) {
+  slim_status st = slim_widen_f64(ctx, "sba_widen_w", W, w_dtype, n, m, ldw, w.W64, (int64_t)m);
+  if (st != SLIM_OK) return st;
+  st = slim_widen_f64(ctx, "sba_widen_x", X_s, x_dtype, m, (int)t_s, ldxs, w.X64, t_s);
+  if (st != SLIM_OK) return st;
+  SLIM_LAUNCH(ctx, "sba_fakequant", sba_fakequant, dim3(slim_cdiv((int64_t)n * w.k, 4)), dim3(256), 0, w.W64, n, m, beta,
+              N, q1_mode, nullptr, w.pmax, w.WN, nullptr, FQ_WN);
   slim_gemm_desc d;
-  d.A = W64;
+  d.A = w.W64;
   d.lda = m;
-  d.B = X64;
+  d.B = w.X64;
   d.ldb = t_s;
-  d.C = Yt;
+  d.C = w.Yt;
   d.ldc = t_s;
   d.C2 = nullptr;
   d.ldc2 = 0;
@@ -424,21 +445,121 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   d.flags = 0;
   d.alpha = 1.0;
   d.beta = 0.0;
-  st = slim_dgemm(ctx, "sba_output_dgemm", 0, d);
-  if (st != SLIM_OK) return st;
-  d.A = WN;
-  d.C = Yc;
-  st = slim_dgemm(ctx, "sba_output_dgemm", 0, d);
-  if (st != SLIM_OK) return st;
-
-  const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
+  slim_gemm_desc pair[2] = {d, d};
+  pair[1].A = w.WN;
+  pair[1].C = w.Yc;
+  // Beside the inverse only as many rows of the two products run (persistent, on part of the chip) as take about
+  // as long as the inverse does; the rest follows in the ordinary form, which wants the whole chip.  The inverse
+  // is modelled as its chain of m / 64 diagonal steps of 45 us plus m^3 / 3 flops of triangular inversion at
+  // 50 TFLOP/s, the persistent form at 85 % of the matrix cores of its CUs.
+  int rows_beside = 0;
+  if (beside_chain && n % 256 == 0 && t_s % 128 == 0 && m % 16 == 0) {
+    const double t_inv = (m / 64) * 45e-6 + (double)m * m * m / 3.0 / 50e12;
+    const int cus = slim_dgemm_reserved_cus(ctx);
+    const double rate = 0.85 * 78.6e12 * cus / std::max(1, ctx->num_cus);
+    const int64_t tiles_per_block = 2 * (t_s / 128);            // of 256 rows, both products
+    int64_t tiles_fit = (int64_t)(rate * t_inv / (2.0 * 256 * 128 * m));
+    tiles_fit = (tiles_fit / cus) * cus;                          // whole rounds
+    rows_beside = (int)std::min<int64_t>(n, std::max<int64_t>(tiles_fit / tiles_per_block, 0) * 256);
+  }
+  if (rows_beside > 0) {
+    slim_gemm_desc part[2] = {pair[0], pair[1]};
+    part[0].M = part[1].M = rows_beside;
+    st = slim_dgemm_reserved(ctx, "sba_output_dgemm", 0, part, 2);
+    if (st != SLIM_OK) return st;
+  }
+  if (rows_beside < n) {
+    for (slim_gemm_desc g : pair) {
+      g.A += (int64_t)rows_beside * g.lda;
+      g.C += (int64_t)rows_beside * g.ldc;
+      g.M = n - rows_beside;
+      st = slim_dgemm(ctx, "sba_output_dgemm", 0, g);
+      if (st != SLIM_OK) return st;
+    }
+  }
   if (objective == SLIM_OBJ_KL) {
     // reference side once: per-token maximum and log-sum-exp, then Y^T becomes P = softmax over the outputs
-    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_partial, kgrid, dim3(256), 0, Yt, n, t_s, rpp, partial);
-    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_merge, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tok);
-    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_softmax, kgrid, dim3(256), 0, Yt, n, t_s, rpp, tok, partial);
-    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_entropy, dim3(kl_blocks), dim3(256), 0, partial, parts, t_s, tokB);
+    const dim3 kgrid(slim_cdiv(t_s, KL_TOK), w.parts);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_partial, kgrid, dim3(256), 0, w.Yt, n, t_s, w.rpp, w.partial);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_merge, dim3(w.kl_blocks), dim3(256), 0, w.partial, w.parts, t_s, w.tok);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_softmax, kgrid, dim3(256), 0, w.Yt, n, t_s, w.rpp, w.tok, w.partial);
+    SLIM_LAUNCH(ctx, "sba_kl_ref", kl_ref_entropy, dim3(w.kl_blocks), dim3(256), 0, w.partial, w.parts, t_s, w.tokB);
   }
+  return SLIM_OK;
+}
+
+}  // namespace
+
+extern "C" slim_status slim_sba_prepare(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                                        int beta, int N, int objective, const void* X_s, slim_dtype x_dtype,
+                                        int64_t t_s, int64_t ldxs, const slim_params* params) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  slim_params prm;
+  slim_default_params(&prm);
+  if (params) prm = *params;
+  slim_status st = sba_check(ctx, "slim_sba_prepare", W, w_dtype, n, m, ldw, beta, N, objective, X_s, x_dtype, t_s, ldxs, prm);
+  if (st != SLIM_OK) return st;
+  SbaWorkspace w;
+  st = sba_workspace(ctx, n, m, beta, t_s, w);
+  if (st != SLIM_OK) return st;
+  st = sba_rank_independent(ctx, w, W, w_dtype, n, m, ldw, beta, N, objective, X_s, x_dtype, t_s, ldxs, prm.q1_mode, true);
+  if (st != SLIM_OK) return st;
+  slim_sba_prepared& r = ctx->sba_prep;
+  r.W = W;
+  r.X_s = X_s;
+  r.ws = ctx->ws;
+  r.w_dtype = w_dtype;
+  r.x_dtype = x_dtype;
+  r.n = n;
+  r.m = m;
+  r.beta = beta;
+  r.N = N;
+  r.objective = objective;
+  r.q1_mode = prm.q1_mode;
+  r.ldw = ldw;
+  r.t_s = t_s;
+  r.ldxs = ldxs;
+  r.valid = true;
+  return SLIM_OK;
+}
+
+extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                                         const double* group_sal, int beta, int N, int objective, const void* X_s,
+                                         slim_dtype x_dtype, int64_t t_s, int64_t ldxs, const slim_params* params,
+                                         uint8_t* bits, int* p_star, double* obj_curve) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  slim_params prm;
+  slim_default_params(&prm);
+  if (params) prm = *params;
+  SLIM_REQUIRE(ctx, group_sal && bits && p_star, "slim_sba_allocate: null pointer");
+  slim_status st = sba_check(ctx, "slim_sba_allocate", W, w_dtype, n, m, ldw, beta, N, objective, X_s, x_dtype, t_s, ldxs, prm);
+  if (st != SLIM_OK) return st;
+  // a preceding slim_sba_prepare with the same arguments has left the rank-independent part in the workspace
+  const slim_sba_prepared r = ctx->sba_prep;
+  const bool prepared = r.valid && r.W == W && r.X_s == X_s && r.w_dtype == (int)w_dtype && r.x_dtype == (int)x_dtype &&
+                        r.n == n && r.m == m && r.beta == beta && r.N == N && r.objective == objective &&
+                        r.q1_mode == prm.q1_mode && r.ldw == ldw && r.t_s == t_s && r.ldxs == ldxs;
+  SbaWorkspace w;
+  st = sba_workspace(ctx, n, m, beta, t_s, w);
+  if (st != SLIM_OK) return st;
+  const int k = w.k, pmax = w.pmax, rpp = w.rpp, parts = w.parts, kl_blocks = w.kl_blocks;
+  const int64_t pstride = w.pstride;
+  double *W64 = w.W64, *WN = w.WN, *Dcat = w.Dcat, *X64 = w.X64, *Xcat = w.Xcat, *Yt = w.Yt, *Yc = w.Yc;
+  double *partial = w.partial, *obj = w.obj, *block_sums = w.block_sums, *tok = w.tok, *tokB = w.tokB;
+  int *order = w.order, *rank_of = w.rank_of, *pstar_dev = w.pstar_dev;
+
+  const bool reuse = prepared && r.ws == ctx->ws;       // (the workspace was not reallocated in between)
+  if (!reuse) {
+    st = sba_rank_independent(ctx, w, W, w_dtype, n, m, ldw, beta, N, objective, X_s, x_dtype, t_s, ldxs, prm.q1_mode, false);
+    if (st != SLIM_OK) return st;
+  }
+  SLIM_LAUNCH(ctx, "sba_rank", sba_rank, dim3(1), dim3(256), 0, group_sal, k, order, rank_of);
+  SLIM_LAUNCH(ctx, "sba_fakequant", sba_fakequant, dim3(slim_cdiv((int64_t)n * k, 4)), dim3(256), 0, W64, n, m, beta, N,
+              prm.q1_mode, rank_of, pmax, WN, Dcat, FQ_DCAT);
+  if (pmax > 0)
+    SLIM_LAUNCH(ctx, "sba_gather_x", sba_gather_x, dim3(64, 2 * pmax), dim3(256), 0, X64, t_s, beta, k, order, Xcat);
+
+  const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
   for (int p = 0; p <= pmax; ++p) {
     if (objective == SLIM_OBJ_KL)
       SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial + p * pstride);

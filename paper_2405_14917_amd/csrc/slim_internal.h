@@ -27,6 +27,16 @@ struct slim_prof_pending {
 
 constexpr int SLIM_NUM_EVENTS = 16;
 
+// What slim_sba_prepare left in the workspace: valid until the next call that uses the workspace.
+struct slim_sba_prepared {
+  bool valid = false;
+  const void* W = nullptr;
+  const void* X_s = nullptr;
+  const char* ws = nullptr;       // workspace base the results live in
+  int w_dtype = 0, x_dtype = 0, n = 0, m = 0, beta = 0, N = 0, objective = 0, q1_mode = 0;
+  int64_t ldw = 0, t_s = 0, ldxs = 0;
+};
+
 struct slim_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
@@ -44,6 +54,7 @@ struct slim_ctx {
   // side streams (default priority) and events for work that overlaps with the main stream inside one call
   hipStream_t side = nullptr, side2 = nullptr;
   hipEvent_t ev[SLIM_NUM_EVENTS] = {};
+  slim_sba_prepared sba_prep;
   // profiling
   bool prof = false;
   std::vector<slim_prof_pending> pending;
@@ -125,6 +136,12 @@ struct slim_gemm_desc {
   double alpha, beta;
 };
 slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc& d);
+// One or two products (host descriptors) beside a latency-critical chain on other streams: persistent workgroups
+// on all but a few CUs, as with SLIM_GEMM_ONE_PER_CU, in one launch.
+slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count);
+// CUs such a launch occupies when every product is edge-free (M % 256 == 0, N % 128 == 0, K % 16 == 0, no flags):
+// it then works on 256 x 128 tiles, one workgroup per CU.
+int slim_dgemm_reserved_cus(const slim_ctx* ctx);
 // Batched form: `descs` is a device array of `count` descriptors; max_M / max_N bound the grid.
 slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs_dev,
                                int count, int max_M, int max_N);

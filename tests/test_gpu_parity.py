@@ -170,6 +170,51 @@ def test_sba_allocate(slim, N, beta, m, ts):
     assert set(b.tolist()) <= {N - 1, N, N + 1} and b.sum() == N * (m // beta)
 
 
+def test_sba_prepare_then_allocate_equals_allocate(slim):
+    """The rank-independent half run ahead (on a second context and stream, beside the inverse) changes nothing."""
+    from paper_2405_14917_amd import binding
+    beta, m, n, ts = 64, 512, 384, 256
+    W, X = small_layer(77, n=n, m=m, t=1024, beta=beta)
+    Wd, Xd = dev(W), dev(X)
+    G = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+    nt = slim.hessian_accumulate(Xd, G, 0)
+    Xs = Xd[:, :ts]
+    U, d = slim.hessian_inverse(G, nt, 0.01)
+    _, grp, _ = slim.salience(Wd, d, beta)
+    bits0, p0, obj0 = slim.sba_allocate(Wd, grp, beta, 2, Xs)
+    # prepared on the same context
+    slim.sba_prepare(Wd, beta, 2, Xs)
+    bits1, p1, obj1 = slim.sba_allocate(Wd, grp, beta, 2, Xs)
+    assert p1 == p0 and np.array_equal(host(bits1), host(bits0)) and np.array_equal(obj1, obj0)
+    # prepared on a second context and stream while the first one inverts
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        slim2 = binding.Slim("cuda:0")
+    side.wait_stream(main)
+    with torch.cuda.stream(side):
+        slim2.sba_prepare(Wd, beta, 2, Xs)
+    U2, d2 = slim.hessian_inverse(G, nt, 0.01)
+    _, grp2, _ = slim.salience(Wd, d2, beta)
+    side.wait_stream(main)
+    with torch.cuda.stream(side):
+        bits2, p2, obj2 = slim2.sba_allocate(Wd, grp2, beta, 2, Xs)
+    main.wait_stream(side)
+    assert p2 == p0 and np.array_equal(host(bits2), host(bits0)) and np.array_equal(obj2, obj0)
+    assert np.array_equal(host(U2), host(U))
+    # a prepare whose arguments do not match is ignored (the call computes everything itself) ...
+    slim2.sba_prepare(Wd, beta, 3, Xs)
+    with torch.cuda.stream(side):
+        bits3, p3, obj3 = slim2.sba_allocate(Wd, grp2, beta, 2, Xs)
+    assert p3 == p0 and np.array_equal(host(bits3), host(bits0)) and np.array_equal(obj3, obj0)
+    # ... and so is one followed by another call on the context
+    slim.sba_prepare(Wd, beta, 2, Xs)
+    slim.salience(Wd, d, beta)
+    bits4, p4, obj4 = slim.sba_allocate(Wd, grp, beta, 2, Xs)
+    assert p4 == p0 and np.array_equal(host(bits4), host(bits0)) and np.array_equal(obj4, obj0)
+    slim2.close()
+
+
 def test_sba_mse_objective(slim):
     from paper_2405_14917_amd import binding
     W, X = small_layer(31, n=72, m=512, t=1024, beta=64)
