@@ -33,6 +33,7 @@ def hipcc() -> str:
 # The fp64 GEMM keeps its 128 accumulator registers in ordinary VGPRs (MFMA "VGPR form"): without this the
 # compiler shuttles them between the two register files on every K slab and halves the occupancy.
 EXTRA_FLAGS = {"dgemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "sba.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
                # gram.hip sets M0 in inline asm (destination of its direct-to-LDS loads) and says so in the clobber
                # list, which the compiler remarks on
                "gram.hip": ["-Wno-inline-asm"]}

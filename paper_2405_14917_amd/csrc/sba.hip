@@ -21,6 +21,7 @@
 //   sba_finalize    first minimum of obj, bit vector of p*
 #include <algorithm>
 
+#include "dgemm_device.h"
 #include "slim_device.h"
 #include "slim_internal.h"
 
@@ -357,8 +358,117 @@ __global__ __launch_bounds__(256) void sba_finalize(const double* __restrict__ b
 
 namespace {
 
+// ---- the whole search in one kernel -----------------------------------------------------------------
+// One workgroup per 128 x 128 tile of the outputs (rows x tokens) keeps the tile of the current candidate's
+// outputs in its accumulator registers from the first candidate to the last: per candidate it adds the tile's
+// terms of the objective (per token: sum exp(q - M) and sum P q over the tile's rows, or the squared error)
+// to the candidate's partials and then applies the rank-2beta update of the next candidate on the matrix cores
+// (the K loop of the fp64 GEMM).  The candidates' outputs never go back to memory: per candidate the kernel reads
+// the reference tile once and two thin operand slabs, where a GEMM launch per candidate reads and writes all
+// outputs and a second kernel reads them again.
+struct SearchArgs {
+  const double* Yc;        // n x ts outputs of the all-N-bit weights
+  const double* R;         // n x ts reference: P = softmax(Y) (KL) or Y (squared error)
+  const double* tok;       // per token {max, log-sum-exp} of the reference (KL)
+  const double* Dcat;      // n x m, column block p: the change of W from candidate p to p + 1
+  const double* Xcat;      // m x ts, row block p: the rows of X_s that change meets
+  double* partial;         // per candidate (stride pstride) [row block][token][KL_PART]
+  int64_t pstride, ts;
+  int n, m, beta, pmax;
+};
+
+constexpr int SEARCH_TILE = 128;
+constexpr size_t SEARCH_LDS = sizeof(double) * (2 * (slimgemm::BK * SEARCH_TILE * 2) + 4 * SEARCH_TILE);
+
+template <int OBJ>
+__global__ __launch_bounds__(256, 2) void sba_search_tile(SearchArgs a) {   // two wavefronts per SIMD
+  using namespace slimgemm;
+  constexpr int BM = SEARCH_TILE, BN = SEARCH_TILE, MI = 4, NJ = 4;
+  extern __shared__ __align__(16) double smem[];
+  double* red = smem + 2 * (BK * BM + BK * BN);        // [sum exp | sum P q][upper | lower 64 rows][128 tokens]
+  const int tiles_n = (int)(a.ts / BN);
+  const int bi = blockIdx.x / tiles_n, bj = blockIdx.x % tiles_n;
+  const int row0 = bi * BM, col0 = bj * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l16 = lane & 15, lk = lane >> 4;
+  // accumulator register v of tile (i, j) of this lane is row 16 i + 4 v + lk, column 16 j + l16 of the wavefront's
+  // 64 x 64 quarter
+  const int64_t ts = a.ts;
+  const int rbase = row0 + wm * 64 + lk, cbase = col0 + wn * 64 + l16;
+  double4v acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[i][j][v] = a.Yc[(int64_t)(rbase + 16 * i + 4 * v) * ts + cbase + 16 * j];
+  double Mt[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) Mt[j] = (OBJ == SLIM_OBJ_KL) ? a.tok[2 * (int64_t)(cbase + 16 * j)] : 0.0;
+
+  for (int p = 0; p <= a.pmax; ++p) {
+    double z[NJ], s[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) z[j] = s[j] = 0.0;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      // 16 reference values in flight at a time: all 64 would not leave room for two workgroups per CU
+      double ref[4][NJ];
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) ref[v][j] = a.R[(int64_t)(rbase + 16 * i + 4 * v) * ts + cbase + 16 * j];
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const double q = acc[i][j][v];
+          if (OBJ == SLIM_OBJ_KL) {
+            z[j] += exp(q - Mt[j]);
+            s[j] = fma(ref[v][j], q, s[j]);
+          } else {
+            const double dlt = ref[v][j] - q;
+            s[j] = fma(dlt, dlt, s[j]);
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the four lanes that share a token column, then the two wavefronts that do
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      z[j] += shfl_xor_f64(z[j], 16);
+      z[j] += shfl_xor_f64(z[j], 32);
+      s[j] += shfl_xor_f64(s[j], 16);
+      s[j] += shfl_xor_f64(s[j], 32);
+      if (lk == 0) {
+        red[(0 * 2 + wm) * BN + wn * 64 + 16 * j + l16] = z[j];
+        red[(1 * 2 + wm) * BN + wn * 64 + 16 * j + l16] = s[j];
+      }
+    }
+    __syncthreads();
+    if (tid < BN) {
+      double* o = a.partial + (int64_t)p * a.pstride + ((int64_t)bi * ts + col0 + tid) * KL_PART;
+      o[3] = red[0 * BN + tid] + red[1 * BN + tid];
+      o[4] = red[2 * BN + tid] + red[3 * BN + tid];
+    }
+    if (p == a.pmax) break;
+    // candidate p + 1: Y^T += [D_lo | D_hi]_p [X_lo ; X_hi]_p, a rank-2beta update of the tile
+    slim_gemm_desc d;
+    d.A = a.Dcat + (int64_t)p * 2 * a.beta;
+    d.lda = a.m;
+    d.B = a.Xcat + (int64_t)p * 2 * a.beta * ts;
+    d.ldb = ts;
+    k_loop_fast<0, BM, BN>(d, row0, col0, 0, 2 * a.beta, smem, acc);
+  }
+}
+
+}  // namespace
+
+namespace {
+
 // The workspace of slim_sba_allocate; slim_sba_prepare fills the part of it that does not depend on the ranking.
 struct SbaWorkspace {
+  bool fused;            // the search runs as one kernel over 128 x 128 output tiles
   int k, pmax, rpp, parts, kl_blocks;
   int64_t pstride;
   double *W64, *WN, *Dcat, *X64, *Xcat, *Yt, *Yc, *partial, *obj, *block_sums, *tok, *tokB;
@@ -368,7 +478,9 @@ struct SbaWorkspace {
 slim_status sba_workspace(slim_ctx* ctx, int n, int m, int beta, int64_t t_s, SbaWorkspace& w) {
   w.k = m / beta;
   w.pmax = w.k / 2;
-  w.rpp = 256;                                          // rows per part of the KL reduction
+  // The one-kernel search needs whole tiles and whole K slabs; its partials are per 128 rows.
+  w.fused = n % SEARCH_TILE == 0 && t_s % SEARCH_TILE == 0 && (2 * beta) % 16 == 0;
+  w.rpp = w.fused ? SEARCH_TILE : 256;                  // rows per part of the reduction over the outputs
   w.parts = slim_cdiv(n, w.rpp);
   w.kl_blocks = slim_cdiv(t_s, 256);
   const size_t bW = slim_ws_round(sizeof(double) * (size_t)n * m);
@@ -560,30 +672,63 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
     SLIM_LAUNCH(ctx, "sba_gather_x", sba_gather_x, dim3(64, 2 * pmax), dim3(256), 0, X64, t_s, beta, k, order, Xcat);
 
   const dim3 kgrid(slim_cdiv(t_s, KL_TOK), parts);
-  for (int p = 0; p <= pmax; ++p) {
-    if (objective == SLIM_OBJ_KL)
-      SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial + p * pstride);
-    else
-      SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial + p * pstride);
-    if (p < pmax) {
-      // Y_{p+1}^T = Y_p^T + [D_lo | D_hi]_p [X_lo ; X_hi]_p : one rank-2beta update
-      slim_gemm_desc u;
-      u.A = Dcat + (int64_t)p * 2 * beta;
-      u.lda = m;
-      u.B = Xcat + (int64_t)p * 2 * beta * t_s;
-      u.ldb = t_s;
-      u.C = Yc;
-      u.ldc = t_s;
-      u.C2 = nullptr;
-      u.ldc2 = 0;
-      u.M = n;
-      u.N = (int)t_s;
-      u.K = 2 * beta;
-      u.flags = 0;
-      u.alpha = 1.0;
-      u.beta = 1.0;
-      st = slim_dgemm(ctx, "sba_update_dgemm", 0, u);
-      if (st != SLIM_OK) return st;
+  if (w.fused) {
+    SearchArgs sa;
+    sa.Yc = Yc;
+    sa.R = Yt;
+    sa.tok = tok;
+    sa.Dcat = Dcat;
+    sa.Xcat = Xcat;
+    sa.partial = partial;
+    sa.pstride = pstride;
+    sa.ts = t_s;
+    sa.n = n;
+    sa.m = m;
+    sa.beta = beta;
+    sa.pmax = pmax;
+    static bool lds_kl = false, lds_mse = false;
+    const dim3 sgrid((n / SEARCH_TILE) * (int)(t_s / SEARCH_TILE));
+    if (objective == SLIM_OBJ_KL) {
+      if (!lds_kl) {
+        SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(sba_search_tile<SLIM_OBJ_KL>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)SEARCH_LDS));
+        lds_kl = true;
+      }
+      SLIM_LAUNCH(ctx, "sba_search", sba_search_tile<SLIM_OBJ_KL>, sgrid, dim3(256), SEARCH_LDS, sa);
+    } else {
+      if (!lds_mse) {
+        SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(sba_search_tile<SLIM_OBJ_MSE>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)SEARCH_LDS));
+        lds_mse = true;
+      }
+      SLIM_LAUNCH(ctx, "sba_search", sba_search_tile<SLIM_OBJ_MSE>, sgrid, dim3(256), SEARCH_LDS, sa);
+    }
+  } else {
+    for (int p = 0; p <= pmax; ++p) {
+      if (objective == SLIM_OBJ_KL)
+        SLIM_LAUNCH(ctx, "sba_kl_step", kl_step, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, tok, partial + p * pstride);
+      else
+        SLIM_LAUNCH(ctx, "sba_mse_partial", mse_partial, kgrid, dim3(256), 0, Yt, Yc, n, t_s, rpp, partial + p * pstride);
+      if (p < pmax) {
+        // Y_{p+1}^T = Y_p^T + [D_lo | D_hi]_p [X_lo ; X_hi]_p : one rank-2beta update
+        slim_gemm_desc u;
+        u.A = Dcat + (int64_t)p * 2 * beta;
+        u.lda = m;
+        u.B = Xcat + (int64_t)p * 2 * beta * t_s;
+        u.ldb = t_s;
+        u.C = Yc;
+        u.ldc = t_s;
+        u.C2 = nullptr;
+        u.ldc2 = 0;
+        u.M = n;
+        u.N = (int)t_s;
+        u.K = 2 * beta;
+        u.flags = 0;
+        u.alpha = 1.0;
+        u.beta = 1.0;
+        st = slim_dgemm(ctx, "sba_update_dgemm", 0, u);
+        if (st != SLIM_OK) return st;
+      }
     }
   }
   // the per-token merges of all candidates in one launch (grid.y = candidate)

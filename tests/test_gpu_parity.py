@@ -151,9 +151,12 @@ def test_salience(slim, dtype):
 
 
 # ------------------------------------------------------------------------------------------ a4
-@pytest.mark.parametrize("N,beta,m,ts", [(2, 64, 256, 128), (3, 32, 288, 64), (2, 128, 640, 132)])
-def test_sba_allocate(slim, N, beta, m, ts):
-    W, X = small_layer(10 + N + beta, n=72, m=m, t=max(ts, 4 * m) // 4 * 4, beta=beta)
+# n = 72 and t_s = 132 take the search with a GEMM launch and a reduction per candidate; the shapes with whole
+# 128 x 128 output tiles take the search in one kernel
+@pytest.mark.parametrize("N,beta,m,ts,n", [(2, 64, 256, 128, 72), (3, 32, 288, 64, 72), (2, 128, 640, 132, 72),
+                                           (2, 64, 512, 256, 384), (3, 32, 256, 128, 128), (2, 128, 1024, 128, 256)])
+def test_sba_allocate(slim, N, beta, m, ts, n):
+    W, X = small_layer(10 + N + beta, n=n, m=m, t=max(ts, 4 * m) // 4 * 4, beta=beta)
     G = np.zeros((m, m))
     orc.gram_accumulate(G, X)
     _, do, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
@@ -215,9 +218,10 @@ def test_sba_prepare_then_allocate_equals_allocate(slim):
     slim2.close()
 
 
-def test_sba_mse_objective(slim):
+@pytest.mark.parametrize("n", [72, 256])     # per-candidate launches / the search in one kernel
+def test_sba_mse_objective(slim, n):
     from paper_2405_14917_amd import binding
-    W, X = small_layer(31, n=72, m=512, t=1024, beta=64)
+    W, X = small_layer(31, n=n, m=512, t=1024, beta=64)
     G = np.zeros((512, 512))
     orc.gram_accumulate(G, X)
     _, do, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
