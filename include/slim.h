@@ -213,7 +213,9 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  * Per-kernel timing with HIP events on the context's stream (measurement aid, host only).
  * While enabled, every kernel launch of the library is bracketed by an event pair.
  * An entry is named after the step of the path ("sba_output_dgemm"), followed by "@" and the kernel function
- * where the launch site chooses among several ("...@dgemm_kernel<0, 128, 128>").
+ * where the launch site chooses among several ("...@dgemm_kernel<0, 128, 128>"), followed by "#side" for a launch
+ * on one of the context's internal side streams (such launches run beside the work on the context's own stream,
+ * so their durations overlap it rather than add to it).
  * slim_profile_collect synchronises, folds the pending pairs into per-kernel totals and returns
  * the number of distinct kernel names; slim_profile_entry reads entry i.
  */

@@ -53,6 +53,14 @@ slim_status slim_ensure_side(slim_ctx* ctx) {
   return SLIM_OK;
 }
 
+// "<name>#side": a launch on one of the context's side streams, beside the work on its main stream
+static const char* side_name(const char* name) {
+  static std::mutex mu;
+  static std::set<std::string> names;
+  std::lock_guard<std::mutex> lock(mu);
+  return names.insert(std::string(name) + "#side").first->c_str();
+}
+
 const char* slim_prof_name(const char* step, const char* kernel_function) {
   static std::mutex mu;
   static std::set<std::string> names;   // node-based: the strings never move
@@ -62,7 +70,7 @@ const char* slim_prof_name(const char* step, const char* kernel_function) {
 
 void slim_prof_begin(slim_ctx* ctx, const char* name) {
   slim_prof_pending p;
-  p.name = name;
+  p.name = ctx->on_side ? side_name(name) : name;
   for (hipEvent_t* ev : {&p.start, &p.stop}) {
     if (!ctx->free_events.empty()) {
       *ev = ctx->free_events.back();

@@ -474,8 +474,14 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   struct StreamSwap {
     slim_ctx* c;
     hipStream_t keep;
-    StreamSwap(slim_ctx* cc, hipStream_t s) : c(cc), keep(cc->stream) { c->stream = s; }
-    ~StreamSwap() { c->stream = keep; }
+    StreamSwap(slim_ctx* cc, hipStream_t s) : c(cc), keep(cc->stream) {
+      c->stream = s;
+      c->on_side = true;
+    }
+    ~StreamSwap() {
+      c->stream = keep;
+      c->on_side = false;
+    }
   };
   bool far_issued = false;
   int last_far_slot = 0;

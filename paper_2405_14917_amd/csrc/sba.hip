@@ -410,6 +410,13 @@ __global__ __launch_bounds__(256, 2) void sba_search_tile(SearchArgs a) {   // t
     double z[NJ], s[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) z[j] = s[j] = 0.0;
+    // The addresses of the reference tile are formed again for every candidate from this pointer (opaque to the
+    // compiler): kept across the K loop below they would cost 32 registers and spill.
+    const double* rtile = a.R + (int64_t)rbase * ts + cbase;
+    asm volatile("" : "+v"(rtile));
+    // (the condition always holds; as a block of its own this part is register-allocated apart from the K loop,
+    // and the kernel no longer spills)
+    if (a.n > 0)
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       // 16 reference values in flight at a time: all 64 would not leave room for two workgroups per CU
@@ -417,7 +424,7 @@ __global__ __launch_bounds__(256, 2) void sba_search_tile(SearchArgs a) {   // t
 #pragma unroll
       for (int v = 0; v < 4; ++v)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) ref[v][j] = a.R[(int64_t)(rbase + 16 * i + 4 * v) * ts + cbase + 16 * j];
+        for (int j = 0; j < NJ; ++j) ref[v][j] = rtile[(int64_t)(16 * i + 4 * v) * ts + 16 * j];
 #pragma unroll
       for (int v = 0; v < 4; ++v)
 #pragma unroll

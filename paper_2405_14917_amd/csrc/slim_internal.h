@@ -53,6 +53,7 @@ struct slim_ctx {
   char* hpin = nullptr;           // pinned host staging, SLIM_HPIN_BYTES
   // side streams (default priority) and events for work that overlaps with the main stream inside one call
   hipStream_t side = nullptr, side2 = nullptr;
+  bool on_side = false;           // `stream` temporarily names a side stream (profiling entries say so)
   hipEvent_t ev[SLIM_NUM_EVENTS] = {};
   slim_sba_prepared sba_prep;
   // profiling
