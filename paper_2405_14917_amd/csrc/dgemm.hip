@@ -373,6 +373,21 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
                   dim3(wgs), dim3(NTHREADS), ONE_PER_CU_BYTES, d);
     return SLIM_OK;
   }
+  // 128 x 128 tiles, two to a CU, or 128 x 64 tiles, three to a CU and a little less efficient each: whichever
+  // fills the rounds of workgroups better.  Cost of a form = rounds x (tile area x tiles per CU / efficiency).
+  const int cus = std::max(1, ctx->num_cus);
+  const int tiles_n64 = slim_cdiv(d.M, 128) * slim_cdiv(d.N, 64);
+  const double cost128 = slim_cdiv(tiles, 2 * cus) * (128.0 * 128.0 * 2 / 0.91);
+  const double cost64 = slim_cdiv(tiles_n64, 3 * cus) * (128.0 * 64.0 * 3 / 0.85);
+  if (!(d.flags & SLIM_GEMM_UPPER_ONLY) && cost64 < cost128) {
+    if (trans_b)
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 128, 64>"), (dgemm_kernel<1, 128, 64>), dim3(tiles_n64),
+                  dim3(NTHREADS), smem_bytes(128, 64), d);
+    else
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<0, 128, 64>"), (dgemm_kernel<0, 128, 64>), dim3(tiles_n64),
+                  dim3(NTHREADS), smem_bytes(128, 64), d);
+    return SLIM_OK;
+  }
   if (trans_b)
     SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 128, 128>"), (dgemm_kernel<1, 128, 128>), dim3(tiles),
                 dim3(NTHREADS), lds, d);
