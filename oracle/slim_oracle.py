@@ -18,6 +18,7 @@ beta along the input dimension; k = m / beta groups; target average width N):
   sqc_calibrate       Eq. 5, Alg. 2 (SQC)         tau grid search per (row, group)
   gptq_quantize       Alg. 1 lines 5-13           column-serial quantisation with compensation
   pack / unpack       App. B.2                    per-group bit-packing, group-bit array, offsets
+  dequant_matmul      App. B.2 (inference)        y = x dequant(W_int)^T straight from the packed tensors
 
 Readings taken where the paper is silent or inconsistent are stated at the
 function that needs them.  Pins (tests/test_oracle_*.py) tie each function to
@@ -546,6 +547,36 @@ def unpack(packed: np.ndarray, gbits: np.ndarray, beta: int, k: int) -> tuple:
                 codes[i, g * beta + r] = (stream >> (r * b)) & ((1 << b) - 1)
         off += nw
     return codes, bits
+
+
+def dequant_matmul(packed: np.ndarray, gbits: np.ndarray, row_off: np.ndarray, scale: np.ndarray,
+                   zero: np.ndarray, beta: int, X: np.ndarray) -> np.ndarray:
+    """The linear layer on the stored form (App. B.2, inference): the weights are dequantised group by group from
+    the packed integers, the group-width array and the start rows, W^_ij = scale[i, g] * (q_ij - zero[i, g]) with
+    g = j // beta (Eq. 1), and multiplied with the activations: Y = X W^^T for X of shape (t, m).  Plain float64.
+
+    Written against the stored tensors only: widths come from gbits, a group's words from row_off, the codes
+    from the bit stream of every (group, output row) - nothing from the quantiser's own outputs."""
+    n = packed.shape[1]
+    k = len(row_off) - 1
+    X = np.asarray(X, dtype=np.float64)
+    Y = np.zeros((X.shape[0], n))
+    for g in range(k):
+        b = ((int(gbits[g // 16]) >> (2 * (g % 16))) & 3) + 1
+        nw = int(row_off[g + 1]) - int(row_off[g])
+        assert nw * 32 == beta * b
+        words = packed[int(row_off[g]):int(row_off[g + 1]), :].astype(np.uint64)        # (nw, n)
+        q = np.zeros((n, beta))
+        for r in range(beta):
+            lo = r * b                       # element r occupies bits [r b, (r + 1) b) of the group's stream
+            w, sh = lo // 32, lo % 32
+            v = words[w] >> np.uint64(sh)
+            if sh + b > 32:
+                v = v | (words[w + 1] << np.uint64(32 - sh))
+            q[:, r] = (v & np.uint64((1 << b) - 1)).astype(np.float64)
+        Wg = scale[:, g][:, None] * (q - zero[:, g][:, None])                            # (n, beta)
+        Y += X[:, g * beta:(g + 1) * beta] @ Wg.T
+    return Y
 
 
 # ----------------------------------------------------------------------------------------

@@ -315,3 +315,48 @@ def test_pack_roundtrip_sizes_and_fast_form():
     bits17 = np.array([1] * 16 + [4], dtype=np.uint8)
     gb = orc.pack_fast(np.zeros((1, 17 * 32), np.uint8), bits17, 32)[1]
     assert gb.tolist() == [0, 3]
+
+
+# ----------------------------------------------------------------- inference on the stored form ------
+def test_dequant_matmul_worked_example_by_hand():
+    # one output row, one group of 32 two-bit codes 0,1,2,3 repeating (words 0xE4E4E4E4, see above),
+    # scale 0.5, zero 1: weights 0.5 * (q - 1) = -0.5, 0, 0.5, 1 repeating
+    packed = np.array([[0xE4E4E4E4], [0xE4E4E4E4]], dtype=np.uint32)
+    gbits = np.array([1], dtype=np.uint32)
+    row_off = np.array([0, 2], dtype=np.int32)
+    x = np.arange(32, dtype=np.float64)[None, :]
+    y = orc.dequant_matmul(packed, gbits, row_off, np.array([[0.5]]), np.array([[1.0]]), 32, x)
+    w = np.tile(np.array([-0.5, 0.0, 0.5, 1.0]), 8)
+    # per four activations 4i .. 4i+3: -0.5 (4i) + 0.5 (4i + 2) + (4i + 3) = 4i + 4; summed over i = 0 .. 7: 144
+    assert y.shape == (1, 1) and y[0, 0] == float(x[0] @ w) == 144.0
+    # a three-bit group: element 10 straddles the first two words
+    c3 = np.zeros((1, 32), dtype=np.uint8)
+    c3[0, 10] = 0b101
+    p3, g3, r3, _ = orc.pack(c3, np.array([3]), 32)
+    e10 = np.zeros((1, 32))
+    e10[0, 10] = 1.0
+    assert orc.dequant_matmul(p3, g3, r3, np.array([[2.0]]), np.array([[0.0]]), 32, e10)[0, 0] == 10.0
+
+
+def test_dequant_matmul_is_the_dense_product_with_the_dequantised_weights():
+    """Reduces to a library routine: X @ What^T with What from the quantiser itself, not from the stored form."""
+    rng = np.random.default_rng(41)
+    n, beta, k = 7, 32, 5
+    m = k * beta
+    W = rng.standard_normal((n, m)) * 0.05
+    X = rng.standard_normal((m, 4 * m)) * rng.lognormal(0, 1, m)[:, None]
+    G = np.zeros((m, m))
+    orc.gram_accumulate(G, X)
+    U, d, _ = orc.hessian_inverse(G, X.shape[1], 0.01)
+    bits = np.array([1, 2, 3, 4, 2], dtype=np.uint8)
+    out = orc.gptq_quantize(W, U, bits, beta, orc.tau_grid(), hinv_diag=d)
+    packed, gbits, row_off, _ = orc.pack(out["codes"], bits, beta)
+    Xin = rng.standard_normal((3, m))
+    Y = orc.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], beta, Xin)
+    assert np.allclose(Y, Xin @ out["What"].T, rtol=1e-12, atol=1e-12)
+    # linear in X, and a unit activation reads one column of the dequantised weights
+    assert np.allclose(orc.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], beta, 2.0 * Xin), 2.0 * Y)
+    e = np.zeros((1, m))
+    e[0, 3 * beta + 7] = 1.0
+    col = orc.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], beta, e)[0]
+    assert np.allclose(col, out["What"][:, 3 * beta + 7], rtol=1e-13, atol=0)
