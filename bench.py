@@ -83,7 +83,25 @@ class Pass:
         self.main.wait_stream(self.side)
         out = s.gptq_quantize(self.W, self.U, bits, cfg.beta)
         packed, gbits, row_off, m_star = s.pack(out["codes"], bits, cfg.beta, packed_rows=cfg.m * (cfg.N + 1) // 32)
+        self.stored = (packed, gbits, row_off, out["scale"], out["zero"])
         return p_star, m_star
+
+    def inference(self, tokens=1, reps=100):
+        """Not part of the step: the linear layer on the stored form of the last pass (App. B.2), `tokens`
+        activations at a time; returns microseconds per call and the bytes of the stored form it streams."""
+        packed, gbits, row_off, scale, zero = self.stored
+        x = self.X[:, :tokens].t().contiguous()
+        y = torch.empty((tokens, self.cfg.n), dtype=torch.float32, device="cuda")
+        for _ in range(5):
+            self.slim.dequant_matmul(packed, gbits, row_off, scale, zero, self.cfg.beta, x, Y=y)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            self.slim.dequant_matmul(packed, gbits, row_off, scale, zero, self.cfg.beta, x, Y=y)
+        e1.record()
+        torch.cuda.synchronize()
+        nbytes = packed.numel() * 4 + gbits.numel() * 4 + row_off.numel() * 4 + scale.numel() * 8 + zero.numel() * 8
+        return e0.elapsed_time(e1) * 1e3 / reps, nbytes
 
     def close(self):
         self.slim_sba.close()
@@ -293,6 +311,10 @@ def main():
         "roofline": roofline,
         "kernels": others,
     }
+    # beside the metric: the inference kernel of the stored form (next step of the path, not part of `value`)
+    us, nbytes = job.inference(tokens=1)
+    line["inference"] = {"kernel": "dequant_matmul", "tokens": 1, "us_per_call": us, "stored_bytes": nbytes,
+                         "GB_per_s": nbytes / us / 1e3, "frac_hbm": nbytes / (us * 1e-6) / PEAK["hbm"]}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:

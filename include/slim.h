@@ -210,6 +210,24 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
                       int* m_star);
 
 /* ---------------------------------------------------------------------------------------------
+ * n1  Linear layer on the stored form (App. B.2, inference; built from the list of next steps).
+ *   Y[t][i] = sum_j X[t][j] * scale[i][g] * (q_ij - zero[i][g]),   g = j / beta   (Eq. 1),
+ *   the codes q_ij decoded from packed / gbits / row_off exactly as slim_pack writes them.
+ *   packed   m_star x n words (ld = ldp >= n);  gbits ceil(k/16) words;  row_off k+1 ints   (device)
+ *   scale, zero   n x k doubles (ld = k), as written by slim_gptq_quantize                  (device)
+ *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
+ *   Y        t_x x n fp32 (ldy >= n), overwritten
+ *   beta     a multiple of 32 that divides m
+ * Arithmetic: codes and activations are exact in fp32; per (row, group) sum (q - z) x in fp32, times the scale
+ * rounded to fp32; the sums of group ranges are added in a fixed order (deterministic, no atomics).
+ * Uses the context's workspace for those partial sums.
+ */
+slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
+                                const int32_t* row_off, const double* scale, const double* zero, int n, int m,
+                                int beta, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx, float* Y,
+                                int64_t ldy);
+
+/* ---------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the context's stream (measurement aid, host only).
  * While enabled, every kernel launch of the library is bracketed by an event pair.
  * An entry is named after the step of the path ("sba_output_dgemm"), followed by "@" and the kernel function

@@ -28,7 +28,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32, torch.float
 EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
-    "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack",
+    "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.slim_gptq_quantize.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_i64, c_void_p, c_i64, c_void_p,
                                        c_int, c_int, P(SlimParams), c_void_p, c_void_p, c_int, c_void_p, c_void_p,
                                        c_void_p, c_void_p, c_int, c_void_p]
+    lib.slim_dequant_matmul.argtypes = [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
+                                        c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
     lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_void_p, c_i64, c_void_p,
                               c_void_p, P(c_int)]
     lib.slim_profile_enable.argtypes = [c_void_p, c_int]
@@ -274,6 +276,20 @@ class Slim:
         self._check(self.lib.slim_pack(self.ctx, _ptr(codes), n, m, codes.stride(0), _ptr(bits), beta, _ptr(packed), cap,
                                        _ptr(gbits), _ptr(row_off), ctypes.byref(m_star)))
         return packed[: m_star.value], gbits, row_off, int(m_star.value)
+
+    # ---- n1
+    def dequant_matmul(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,
+                       zero: torch.Tensor, beta: int, X: torch.Tensor, Y: Optional[torch.Tensor] = None):
+        """Y (t_x, n) float32 = X (t_x, m) float16 / bfloat16 times the dequantised weights, from the stored form."""
+        _need_cuda(packed, gbits, row_off, scale, zero, X)
+        n = packed.shape[1]
+        t_x, m = X.shape
+        assert scale.dtype == torch.float64 and zero.dtype == torch.float64 and scale.stride(0) == m // beta
+        Y = torch.empty((t_x, n), dtype=torch.float32, device=X.device) if Y is None else Y
+        self._check(self.lib.slim_dequant_matmul(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
+                                                 _ptr(scale), _ptr(zero), n, m, beta, _ptr(X), _DT[X.dtype], t_x,
+                                                 X.stride(0), _ptr(Y), Y.stride(0)))
+        return Y
 
     # ---- measurement aid
     def profile_enable(self, on: bool = True):

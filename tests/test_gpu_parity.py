@@ -409,6 +409,58 @@ def test_pack(slim, beta, n):
     assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
 
 
+# ------------------------------------------------------------------------------------------ n1
+# Tolerance: the kernel forms sum (q - z) x per (row, group) and the sum over the groups in fp32 (exact inputs), so
+# its error is bounded by a few m * 2^-24 times sum |x| |w| for that output; 1e-5 of that sum (m <= 1024 here) has
+# a safe margin.  The oracle is float64.
+@pytest.mark.parametrize("beta,n,m,t_x,dtype", [(128, 300, 512, 1, torch.float16), (32, 70, 160, 3, torch.float16),
+                                                (64, 520, 1024, 16, torch.bfloat16), (256, 64, 512, 5, torch.float16)])
+def test_dequant_matmul(slim, beta, n, m, t_x, dtype):
+    rng = np.random.default_rng(beta + n + t_x)
+    k = m // beta
+    allowed = [b for b in (1, 2, 3, 4) if (beta * b) % 32 == 0]
+    bits = rng.choice(allowed, size=k).astype(np.uint8)
+    bits[: min(k, 4)] = np.array([1, 2, 3, 4])[: min(k, 4)]              # every width at least once when k >= 4
+    codes = np.concatenate([rng.integers(0, 2 ** int(b), (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    scale = np.abs(rng.standard_normal((n, k))) * 0.01 + 1e-3
+    zero = np.stack([rng.integers(0, 2 ** int(b), n).astype(np.float64) for b in bits], axis=1)
+    zero[:, bits == 1] = 0.5                                              # the sign form of width 1
+    packed_o, gbits_o, row_off_o, m_star = orc.pack_fast(codes, bits, beta)
+    X = torch.from_numpy(rng.standard_normal((t_x, m))).to(dtype)
+    Y_o = orc.dequant_matmul(packed_o, gbits_o, row_off_o, scale, zero, beta, X.double().numpy())
+    # the stored form comes from the HIP path's own packing
+    packed, gbits, row_off, ms = slim.pack(dev(codes), dev(bits), beta)
+    assert ms == m_star and np.array_equal(host(packed).view(np.uint32), packed_o)
+    Y = host(slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, X.cuda()))
+    What = np.repeat(scale, beta, axis=1) * (codes - np.repeat(zero, beta, axis=1))
+    bound = np.abs(X.double().numpy()) @ np.abs(What).T
+    assert Y.shape == (t_x, n) and np.all(np.abs(Y - Y_o) <= 1e-5 * bound + 1e-30)
+    # a strided activation view and a caller-provided, wider output
+    Xw = torch.zeros((t_x, m + 8), dtype=dtype, device="cuda")
+    Xw[:, :m] = X.cuda()
+    Yw = torch.full((t_x, n + 3), -1.0, dtype=torch.float32, device="cuda")
+    slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, Xw[:, :m], Y=Yw[:, :n])
+    assert np.array_equal(host(Yw[:, :n]), Y) and np.all(host(Yw[:, n:]) == -1.0)
+
+
+def test_dequant_matmul_after_the_whole_pass(slim):
+    """The stored form of a quantised layer, multiplied with activations, is X What^T."""
+    W, X = small_layer(91, n=256, m=512, t=2048, beta=128)
+    G = torch.zeros((512, 512), dtype=torch.float32, device="cuda")
+    nt = slim.hessian_accumulate(dev(X), G, 0)
+    U, d = slim.hessian_inverse(G, nt, 0.01)
+    _, grp, _ = slim.salience(dev(W), d, 128)
+    bits, _, _ = slim.sba_allocate(dev(W), grp, 128, 2, dev(X)[:, :256])
+    out = slim.gptq_quantize(dev(W), U, bits, 128, want_what=torch.float64)
+    packed, gbits, row_off, _ = slim.pack(out["codes"], bits, 128)
+    Xin = dev(X)[:, 100:104].t().contiguous()                             # 4 tokens x m
+    Y = host(slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, Xin))
+    Xn, What = host(Xin).astype(np.float64), host(out["What"])
+    assert np.all(np.abs(Y - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
+    with pytest.raises(Exception):
+        slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, dev(X)[:, :17].t().contiguous())
+
+
 def test_pack_rejects_bad_input(slim):
     from paper_2405_14917_amd import binding
     codes = dev(np.zeros((8, 128), dtype=np.uint8))
