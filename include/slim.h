@@ -214,12 +214,14 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  *   Y[t][i] = sum_j X[t][j] * scale[i][g] * (q_ij - zero[i][g]),   g = j / beta   (Eq. 1),
  *   the codes q_ij decoded from packed / gbits / row_off exactly as slim_pack writes them.
  *   packed   m_star x n words (ld = ldp >= n);  gbits ceil(k/16) words;  row_off k+1 ints   (device)
- *   scale, zero   n x k doubles (ld = k), as written by slim_gptq_quantize                  (device)
+ *   scale, zero   n x k doubles (ld = k), as written by slim_gptq_quantize (device); every zero must be a
+ *            multiple of 1/2 in [0, 255] (Eq. 1 gives integers, the sign form of width 1 uses 1/2)
  *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
  *   Y        t_x x n fp32 (ldy >= n), overwritten
  *   beta     a multiple of 32 that divides m
- * Arithmetic: codes and activations are exact in fp32; per (row, group) sum (q - z) x in fp32, times the scale
- * rounded to fp32; the sums of group ranges are added in a fixed order (deterministic, no atomics).
+ * Arithmetic: codes and activations are exact; per (row, group) sum (q - z) x in fp32 (for fp16 activations on
+ * the matrix cores, with 2 (q - z) formed exactly in fp16), times the scale rounded to fp32; the sums of group
+ * ranges are added in a fixed order (deterministic, no atomics).
  * Uses the context's workspace for those partial sums.
  */
 slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,

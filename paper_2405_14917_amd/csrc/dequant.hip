@@ -138,9 +138,154 @@ __global__ __launch_bounds__(256) void dequant_reduce(const float* __restrict__ 
   Y[(int64_t)t * ldy + i] = s;
 }
 
+// ------------------------------------------------------------------------------------------------------
+// The same product on the matrix cores, for fp16 activations.  v_mfma_f32_32x32x16_f16 with the tokens as rows
+// of the first operand and the output rows of the layer as columns of the second: a lane then owns ONE output
+// row (its scale and zero are lane constants) and the 16 tokens of its accumulator registers.  The second
+// operand is 2 (q - z), formed exactly in fp16 from the packed codes without any conversion instruction: a code
+// q shifted left by one and OR-ed into the mantissa of 1024.0 is the fp16 number 1024 + 2 q, and subtracting
+// 1024 + 2 z (2 z is an integer: zeros are integers, or 1/2 for the sign form of width 1) leaves 2 (q - z);
+// the factor 1/2 goes into the scale.  Two codes are handled per instruction (packed fp16): the eight codes a
+// lane needs for one MFMA are first spread so that code j sits in the low and code j + 4 in the high half of a
+// register, and the activations are stored in LDS in that order (0 4 1 5 2 6 3 7) to match.  Products are exact
+// (11-bit by 6-bit), the sums are fp32 in the matrix core, the scale is applied per group in fp32.
+// With up to 32 tokens served by the same instructions, the kernel is a stream over the packed weights.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr int DM_WAVES = 4, DM_ROWS = 32 * DM_WAVES, DM_TOK = 32, DM_PAD = 8;
+
+// the 8 B-bit codes in the low bits of v -> four registers of packed fp16 pairs (1024 + 2 c_j, 1024 + 2 c_{j+4})
+template <int B>
+__device__ __forceinline__ void spread_codes(unsigned v, unsigned (&t)[4]) {
+  constexpr unsigned M2 = ((1u << B) - 1u) << 1;
+  const unsigned u = (B == 4) ? v : ((v & ((1u << (4 * B)) - 1u)) | ((v >> (4 * B)) << 16));
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const unsigned sh = (B * j >= 1) ? (u >> (B * j - 1)) : (u << 1);
+    t[j] = (sh & (M2 | (M2 << 16))) | 0x64006400u;
+  }
+}
+
+// One sub-block of SUB codes (SUB / 16 MFMA steps) of one group: `w` holds the NW = SUB * B / 32 words of the lane's
+// output row; xs points at the lane's token row of the activation tile, at this sub-block's first column.
+template <int B, int SUB>
+__device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[SUB * B / 32], int h, half2v zz,
+                                                  const _Float16* xs, float16v acc) {
+  constexpr int NW = SUB * B / 32;
+#pragma unroll
+  for (int st = 0; st < SUB / 16; ++st) {
+    // unit 2 st + h of the stream: 8 codes = 8 B bits starting at bit 8 B (2 st + h)
+    unsigned v0, v1;                                 // the unit for h = 0 and for h = 1
+    auto unit_bits = [&](int unit) -> unsigned {
+      const int bit = 8 * B * unit, wi = bit / 32, sh = bit % 32;
+      if (sh + 8 * B <= 32) return w[wi] >> sh;
+      const uint64_t two = (uint64_t)w[wi] | ((uint64_t)w[(wi + 1 < NW) ? wi + 1 : wi] << 32);
+      return (unsigned)(two >> sh);
+    };
+    v0 = unit_bits(2 * st);
+    v1 = unit_bits(2 * st + 1);
+    unsigned t[4];
+    spread_codes<B>(h ? v1 : v0, t);
+    half8v bfrag;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const half2v d = *reinterpret_cast<const half2v*>(&t[j]) - zz;
+      bfrag[2 * j] = d[0];
+      bfrag[2 * j + 1] = d[1];
+    }
+    const half8v afrag = *reinterpret_cast<const half8v*>(xs + 16 * st + 8 * h);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag, bfrag, acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+template <int B>
+__device__ __forceinline__ float16v group_mfma(const DqArgs& a, int row, int base, int h, half2v zz,
+                                               const _Float16* xs, float16v acc) {
+  const uint32_t* p = a.packed + (int64_t)base * a.ldp + row;
+  if (a.beta >= 128) {
+    for (int sb = 0; sb < a.beta / 128; ++sb) {
+      unsigned w[4 * B];
+#pragma unroll
+      for (int wi = 0; wi < 4 * B; ++wi) w[wi] = p[(int64_t)(sb * 4 * B + wi) * a.ldp];
+      acc = subblock_mfma<B, 128>(w, h, zz, xs + 128 * sb, acc);
+    }
+  } else if (a.beta == 64) {
+    unsigned w[2 * B];
+#pragma unroll
+    for (int wi = 0; wi < 2 * B; ++wi) w[wi] = p[(int64_t)wi * a.ldp];
+    acc = subblock_mfma<B, 64>(w, h, zz, xs, acc);
+  } else {
+    unsigned w[B];
+#pragma unroll
+    for (int wi = 0; wi < B; ++wi) w[wi] = p[(int64_t)wi * a.ldp];
+    acc = subblock_mfma<B, 32>(w, h, zz, xs, acc);
+  }
+  return acc;
+}
+
+__global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
+  extern __shared__ __align__(16) _Float16 xh[];   // [DM_TOK][beta + DM_PAD], columns of every 8 in the order 0 4 1 5 2 6 3 7
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int ldxs = a.beta + DM_PAD;
+  const int row = min(blockIdx.x * DM_ROWS + wave * 32 + l32, a.n - 1);    // clamped: rows past the end are not stored
+  const int g0 = blockIdx.y * a.gper, g1 = min(a.k, g0 + a.gper);
+  float y[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) y[v] = 0.f;
+  const uint16_t* X = static_cast<const uint16_t*>(a.X);
+  for (int g = g0; g < g1; ++g) {
+    __syncthreads();
+    for (int idx = tid; idx < DM_TOK * (a.beta / 8); idx += 64 * DM_WAVES) {
+      const int t = idx / (a.beta / 8), c = idx - t * (a.beta / 8);
+      uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+      if (t < a.t_x) raw = *reinterpret_cast<const uint4*>(X + (int64_t)t * a.ldx + (int64_t)g * a.beta + 8 * c);
+      // halves 0..7 of the chunk are (raw.x lo, hi), (raw.y lo, hi), ...; stored as 0 4 1 5 2 6 3 7
+      uint4 o;
+      o.x = (raw.x & 0xffffu) | (raw.z << 16);
+      o.y = (raw.x >> 16) | (raw.z & 0xffff0000u);
+      o.z = (raw.y & 0xffffu) | (raw.w << 16);
+      o.w = (raw.y >> 16) | (raw.w & 0xffff0000u);
+      *reinterpret_cast<uint4*>(xh + t * ldxs + 8 * c) = o;
+    }
+    __syncthreads();
+    const int b = (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + 1;
+    const int base = a.row_off[g];
+    const double sd = a.scale[(int64_t)row * a.k + g], zd = a.zero[(int64_t)row * a.k + g];
+    const _Float16 zc = (_Float16)(float)(1024.0 + 2.0 * zd);             // exact: 2 z is an integer below 1024
+    half2v zz;
+    zz[0] = zc;
+    zz[1] = zc;
+    float16v acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const _Float16* xs = xh + l32 * ldxs;
+    switch (b) {                                   // the same for the whole workgroup
+      case 1: acc = group_mfma<1>(a, row, base, h, zz, xs, acc); break;
+      case 2: acc = group_mfma<2>(a, row, base, h, zz, xs, acc); break;
+      case 3: acc = group_mfma<3>(a, row, base, h, zz, xs, acc); break;
+      default: acc = group_mfma<4>(a, row, base, h, zz, xs, acc); break;
+    }
+    const float s2 = (float)(0.5 * sd);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) y[v] = fmaf(s2, acc[v], y[v]);
+  }
+  if (blockIdx.x * DM_ROWS + wave * 32 + l32 < a.n) {
+    float* o = a.out + (int64_t)blockIdx.y * a.split_stride + row;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int t = 8 * (v >> 2) + 4 * h + (v & 3);   // accumulator register v of lane (l32, h): token t, output row l32
+      if (t < a.t_x) o[(int64_t)t * a.ldo] = y[v];
+    }
+  }
+}
+
 template <int T>
 slim_status launch(slim_ctx* ctx, const DqArgs& a, dim3 grid, size_t smem) {
-  SLIM_LAUNCH(ctx, "dequant_matmul", dequant_matmul<T>, grid, dim3(DQ_THREADS), smem, a);
+  SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul<T>", dequant_matmul<T>, grid, dim3(DQ_THREADS), smem, a);
   return SLIM_OK;
 }
 
@@ -161,11 +306,19 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   const int k = m / beta;
   int T = 1;
   while (T < t_x) T *= 2;
-  const size_t smem = sizeof(float) * (size_t)T * beta;
-  const int gx = slim_cdiv(n, DQ_THREADS);
-  // enough workgroups to fill the chip twice over, by splitting the groups
+  // fp16 activations that can be fetched 16 bytes at a time go to the matrix-core kernel
+  // (a layer too small to give every CU a few workgroups of that kernel is bound by launch and reduction, and
+  // for one or two tokens the plain kernel, whose workgroups cover twice the rows, is the quicker one there)
   const int cus = std::max(1, ctx->num_cus);
-  const int splits_wanted = std::max(1, std::min(k, (2 * cus + gx - 1) / gx));
+  const bool small = 2 * slim_cdiv(n, DM_ROWS) < cus;
+  const bool mfma = x_dtype == SLIM_F16 && slim_aligned16(X) && ldx % 8 == 0 &&
+                    (beta == 32 || beta == 64 || beta % 128 == 0) && !(small && t_x <= 2);
+  const size_t smem = mfma ? sizeof(uint16_t) * (size_t)DM_TOK * (beta + DM_PAD) : sizeof(float) * (size_t)T * beta;
+  const int gx = slim_cdiv(n, mfma ? DM_ROWS : DQ_THREADS);
+  // enough workgroups per CU to hide the latency of their loads behind one another, by splitting the groups;
+  // fewer for a small layer, where the reduction over the splits would cost more than the splits gain
+  const int per_cu = small ? 2 : 8;
+  const int splits_wanted = std::max(1, std::min(k, (per_cu * cus + gx - 1) / gx));
   const int gper = slim_cdiv(k, splits_wanted);
   const int splits = slim_cdiv(k, gper);
 
@@ -199,7 +352,10 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
     a.split_stride = 0;
   }
   const dim3 grid(gx, splits);
-  slim_status st;
+  slim_status st = SLIM_OK;
+  if (mfma) {
+    SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma", dequant_matmul_mfma, grid, dim3(64 * DM_WAVES), smem, a);
+  } else
   switch (T) {
     case 1: st = launch<1>(ctx, a, grid, smem); break;
     case 2: st = launch<2>(ctx, a, grid, smem); break;

@@ -414,7 +414,9 @@ def test_pack(slim, beta, n):
 # its error is bounded by a few m * 2^-24 times sum |x| |w| for that output; 1e-5 of that sum (m <= 1024 here) has
 # a safe margin.  The oracle is float64.
 @pytest.mark.parametrize("beta,n,m,t_x,dtype", [(128, 300, 512, 1, torch.float16), (32, 70, 160, 3, torch.float16),
-                                                (64, 520, 1024, 16, torch.bfloat16), (256, 64, 512, 5, torch.float16)])
+                                                (64, 520, 1024, 16, torch.bfloat16), (256, 64, 512, 5, torch.float16),
+                                                (64, 200, 512, 16, torch.float16), (128, 260, 1024, 9, torch.float16),
+                                                (512, 40, 1024, 4, torch.float16)])
 def test_dequant_matmul(slim, beta, n, m, t_x, dtype):
     rng = np.random.default_rng(beta + n + t_x)
     k = m // beta
