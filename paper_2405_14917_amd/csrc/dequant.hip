@@ -168,24 +168,22 @@ __device__ __forceinline__ void spread_codes(unsigned v, unsigned (&t)[4]) {
   }
 }
 
-// One sub-block of SUB codes (SUB / 16 MFMA steps) of one group: `w` holds the NW = SUB * B / 32 words of the lane's
+// One sub-block of SUB codes (SUB / 16 MFMA steps) of one group: `w` holds the SUB * B / 32 words of the lane's
 // output row; xs points at the lane's token row of the activation tile, at this sub-block's first column.
 template <int B, int SUB>
-__device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[SUB * B / 32], int h, half2v zz,
-                                                  const _Float16* xs, float16v acc) {
+__device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[16], int h, half2v zz, const _Float16* xs,
+                                                  float16v acc) {
   constexpr int NW = SUB * B / 32;
 #pragma unroll
   for (int st = 0; st < SUB / 16; ++st) {
     // unit 2 st + h of the stream: 8 codes = 8 B bits starting at bit 8 B (2 st + h)
-    unsigned v0, v1;                                 // the unit for h = 0 and for h = 1
     auto unit_bits = [&](int unit) -> unsigned {
       const int bit = 8 * B * unit, wi = bit / 32, sh = bit % 32;
       if (sh + 8 * B <= 32) return w[wi] >> sh;
       const uint64_t two = (uint64_t)w[wi] | ((uint64_t)w[(wi + 1 < NW) ? wi + 1 : wi] << 32);
       return (unsigned)(two >> sh);
     };
-    v0 = unit_bits(2 * st);
-    v1 = unit_bits(2 * st + 1);
+    const unsigned v0 = unit_bits(2 * st), v1 = unit_bits(2 * st + 1);   // the unit for h = 0 and for h = 1
     unsigned t[4];
     spread_codes<B>(h ? v1 : v0, t);
     half8v bfrag;
@@ -201,77 +199,90 @@ __device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[SUB * B / 
   return acc;
 }
 
-template <int B>
-__device__ __forceinline__ float16v group_mfma(const DqArgs& a, int row, int base, int h, half2v zz,
-                                               const _Float16* xs, float16v acc) {
-  const uint32_t* p = a.packed + (int64_t)base * a.ldp + row;
-  if (a.beta >= 128) {
-    for (int sb = 0; sb < a.beta / 128; ++sb) {
-      unsigned w[4 * B];
-#pragma unroll
-      for (int wi = 0; wi < 4 * B; ++wi) w[wi] = p[(int64_t)(sb * 4 * B + wi) * a.ldp];
-      acc = subblock_mfma<B, 128>(w, h, zz, xs + 128 * sb, acc);
-    }
-  } else if (a.beta == 64) {
-    unsigned w[2 * B];
-#pragma unroll
-    for (int wi = 0; wi < 2 * B; ++wi) w[wi] = p[(int64_t)wi * a.ldp];
-    acc = subblock_mfma<B, 64>(w, h, zz, xs, acc);
-  } else {
-    unsigned w[B];
-#pragma unroll
-    for (int wi = 0; wi < B; ++wi) w[wi] = p[(int64_t)wi * a.ldp];
-    acc = subblock_mfma<B, 32>(w, h, zz, xs, acc);
-  }
-  return acc;
-}
-
+// SUB = min(beta, 128): a group is worked off in beta / SUB sub-blocks.  The activations of the workgroup's whole
+// group range are put into LDS once (rows of the real tokens plus one row of zeros that the lanes of the other
+// token slots read); the words, scale and zero of the next sub-block are fetched while the current one is
+// multiplied, so that a workgroup waits for memory once, not once per group.
+template <int SUB>
 __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
-  extern __shared__ __align__(16) _Float16 xh[];   // [DM_TOK][beta + DM_PAD], columns of every 8 in the order 0 4 1 5 2 6 3 7
+  extern __shared__ __align__(16) _Float16 xh[];   // [t_x + 1][cols + DM_PAD], every 8 columns in the order 0 4 1 5 2 6 3 7
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
-  const int ldxs = a.beta + DM_PAD;
   const int row = min(blockIdx.x * DM_ROWS + wave * 32 + l32, a.n - 1);    // clamped: rows past the end are not stored
   const int g0 = blockIdx.y * a.gper, g1 = min(a.k, g0 + a.gper);
+  const int cols = (g1 - g0) * a.beta, ldxs = cols + DM_PAD;
+  const uint16_t* X = static_cast<const uint16_t*>(a.X);
+  for (int idx = tid; idx < (a.t_x + 1) * (cols / 8); idx += 64 * DM_WAVES) {
+    const int t = idx / (cols / 8), c = idx - t * (cols / 8);
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    if (t < a.t_x) raw = *reinterpret_cast<const uint4*>(X + (int64_t)t * a.ldx + (int64_t)g0 * a.beta + 8 * c);
+    // halves 0..7 of the chunk are (raw.x lo, hi), (raw.y lo, hi), ...; stored as 0 4 1 5 2 6 3 7
+    uint4 o;
+    o.x = (raw.x & 0xffffu) | (raw.z << 16);
+    o.y = (raw.x >> 16) | (raw.z & 0xffff0000u);
+    o.z = (raw.y & 0xffffu) | (raw.w << 16);
+    o.w = (raw.y >> 16) | (raw.w & 0xffff0000u);
+    *reinterpret_cast<uint4*>(xh + t * ldxs + 8 * c) = o;
+  }
+  const _Float16* xs = xh + min(l32, a.t_x) * ldxs;
+  // The scales (halved: the codes are doubled) and the zeros (as 1024 + 2 z in fp16) of the workgroup's rows and
+  // groups, fetched together: per (row, group) loads by the lane that owns the row would touch 32 cache lines per
+  // instruction, eight times the requests of the packed words themselves.
+  const int gcount = g1 - g0;
+  float* sp = reinterpret_cast<float*>(xh + (a.t_x + 1) * ldxs);            // [DM_ROWS][gcount]
+  _Float16* zp = reinterpret_cast<_Float16*>(sp + DM_ROWS * gcount);          // [DM_ROWS][gcount]
+  for (int idx = tid; idx < DM_ROWS * gcount; idx += 64 * DM_WAVES) {
+    const int r = idx / gcount, gi = idx - r * gcount;
+    const int64_t src = (int64_t)min(blockIdx.x * DM_ROWS + r, a.n - 1) * a.k + g0 + gi;
+    sp[idx] = (float)(0.5 * a.scale[src]);
+    zp[idx] = (_Float16)(float)(1024.0 + 2.0 * a.zero[src]);                  // exact: 2 z is an integer below 1024
+  }
+  const int prow = (wave * 32 + l32) * gcount;
+
+  const int nsub = a.beta / SUB, units = (g1 - g0) * nsub;
+  auto width = [&](int g) { return (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + 1; };
+  // fetch of unit u: the words of the lane's row
+  auto fetch = [&](int u, unsigned (&w)[16]) {
+    const int g = g0 + u / nsub, sb = u - (u / nsub) * nsub;
+    const int nwu = SUB * width(g) / 32;
+    const uint32_t* p = a.packed + (int64_t)(a.row_off[g] + sb * nwu) * a.ldp + row;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[i] = (i < nwu) ? p[(int64_t)i * a.ldp] : 0u;
+  };
+  unsigned wc[16], wn[16];
+  fetch(0, wc);
+  __syncthreads();                                 // the activation tile and the parameters are complete
+
   float y[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) y[v] = 0.f;
-  const uint16_t* X = static_cast<const uint16_t*>(a.X);
-  for (int g = g0; g < g1; ++g) {
-    __syncthreads();
-    for (int idx = tid; idx < DM_TOK * (a.beta / 8); idx += 64 * DM_WAVES) {
-      const int t = idx / (a.beta / 8), c = idx - t * (a.beta / 8);
-      uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-      if (t < a.t_x) raw = *reinterpret_cast<const uint4*>(X + (int64_t)t * a.ldx + (int64_t)g * a.beta + 8 * c);
-      // halves 0..7 of the chunk are (raw.x lo, hi), (raw.y lo, hi), ...; stored as 0 4 1 5 2 6 3 7
-      uint4 o;
-      o.x = (raw.x & 0xffffu) | (raw.z << 16);
-      o.y = (raw.x >> 16) | (raw.z & 0xffff0000u);
-      o.z = (raw.y & 0xffffu) | (raw.w << 16);
-      o.w = (raw.y >> 16) | (raw.w & 0xffff0000u);
-      *reinterpret_cast<uint4*>(xh + t * ldxs + 8 * c) = o;
-    }
-    __syncthreads();
-    const int b = (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + 1;
-    const int base = a.row_off[g];
-    const double sd = a.scale[(int64_t)row * a.k + g], zd = a.zero[(int64_t)row * a.k + g];
-    const _Float16 zc = (_Float16)(float)(1024.0 + 2.0 * zd);             // exact: 2 z is an integer below 1024
+  float16v acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int u = 0; u < units; ++u) {
+    const int g = g0 + u / nsub, sb = u - (u / nsub) * nsub;
+    if (u + 1 < units) fetch(u + 1, wn);
+    const _Float16 zc = zp[prow + (g - g0)];
     half2v zz;
     zz[0] = zc;
     zz[1] = zc;
-    float16v acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    const _Float16* xs = xh + l32 * ldxs;
-    switch (b) {                                   // the same for the whole workgroup
-      case 1: acc = group_mfma<1>(a, row, base, h, zz, xs, acc); break;
-      case 2: acc = group_mfma<2>(a, row, base, h, zz, xs, acc); break;
-      case 3: acc = group_mfma<3>(a, row, base, h, zz, xs, acc); break;
-      default: acc = group_mfma<4>(a, row, base, h, zz, xs, acc); break;
+    const _Float16* xu = xs + (g - g0) * a.beta + sb * SUB;
+    switch (width(g)) {                            // the same for the whole workgroup
+      case 1: acc = subblock_mfma<1, SUB>(wc, h, zz, xu, acc); break;
+      case 2: acc = subblock_mfma<2, SUB>(wc, h, zz, xu, acc); break;
+      case 3: acc = subblock_mfma<3, SUB>(wc, h, zz, xu, acc); break;
+      default: acc = subblock_mfma<4, SUB>(wc, h, zz, xu, acc); break;
     }
-    const float s2 = (float)(0.5 * sd);
+    if (sb == nsub - 1) {                          // the group is complete: its scale (times the 1/2 of the doubled codes)
+      const float s2 = sp[prow + (g - g0)];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) y[v] = fmaf(s2, acc[v], y[v]);
+      for (int v = 0; v < 16; ++v) {
+        y[v] = fmaf(s2, acc[v], y[v]);
+        acc[v] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) wc[i] = wn[i];
   }
   if (blockIdx.x * DM_ROWS + wave * 32 + l32 < a.n) {
     float* o = a.out + (int64_t)blockIdx.y * a.split_stride + row;
@@ -313,13 +324,18 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   const bool small = 2 * slim_cdiv(n, DM_ROWS) < cus;
   const bool mfma = x_dtype == SLIM_F16 && slim_aligned16(X) && ldx % 8 == 0 &&
                     (beta == 32 || beta == 64 || beta % 128 == 0) && !(small && t_x <= 2);
-  const size_t smem = mfma ? sizeof(uint16_t) * (size_t)DM_TOK * (beta + DM_PAD) : sizeof(float) * (size_t)T * beta;
+  size_t smem = sizeof(float) * (size_t)T * beta;   // (the matrix-core kernel's depends on the split, below)
   const int gx = slim_cdiv(n, mfma ? DM_ROWS : DQ_THREADS);
   // enough workgroups per CU to hide the latency of their loads behind one another, by splitting the groups;
   // fewer for a small layer, where the reduction over the splits would cost more than the splits gain
   const int per_cu = small ? 2 : 8;
   const int splits_wanted = std::max(1, std::min(k, (per_cu * cus + gx - 1) / gx));
-  const int gper = slim_cdiv(k, splits_wanted);
+  int gper = slim_cdiv(k, splits_wanted);
+  if (mfma) {
+    // the activations of a workgroup's group range have to fit into 64 KiB of LDS
+    const int fit = std::max(1, (int)((48 * 1024 / (2 * (t_x + 1)) - DM_PAD) / beta));
+    gper = std::min(gper, fit);
+  }
   const int splits = slim_cdiv(k, gper);
 
   DqArgs a;
@@ -354,7 +370,13 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   const dim3 grid(gx, splits);
   slim_status st = SLIM_OK;
   if (mfma) {
-    SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma", dequant_matmul_mfma, grid, dim3(64 * DM_WAVES), smem, a);
+    smem = sizeof(uint16_t) * (size_t)(t_x + 1) * ((size_t)gper * beta + DM_PAD) + (size_t)DM_ROWS * gper * 6;
+    if (beta >= 128)
+      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<128>", dequant_matmul_mfma<128>, grid, dim3(64 * DM_WAVES), smem, a);
+    else if (beta == 64)
+      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<64>", dequant_matmul_mfma<64>, grid, dim3(64 * DM_WAVES), smem, a);
+    else
+      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<32>", dequant_matmul_mfma<32>, grid, dim3(64 * DM_WAVES), smem, a);
   } else
   switch (T) {
     case 1: st = launch<1>(ctx, a, grid, smem); break;
