@@ -8,8 +8,8 @@
 //
 // Per group of beta columns four kernels run back to back on the stream:
 //   block_stats   shifted sums of the current block (for the block-wide 3-sigma rule), per row slab
-//   sqc_search    one workgroup per 8 rows: row min/max/mean|w|, loss weights, then every
-//                 (row, candidate) pair is one thread that walks the row's beta weights in LDS;
+//   sqc_search_fast / sqc_search_weighted   a few rows per workgroup: row min/max/mean|w|, the mask or the loss
+//                 weights, then a few lanes per (row, 4 or 5 candidates) walk the row's weights in LDS;
 //                 wavefront argmin with ties to the lower candidate index
 //   gptq_sweep4   four rows per wavefront (16 lanes each), the row's beta weights in registers, the
 //                 beta x beta block of U in LDS; beta serial steps of quantise -> error -> rank-1 update
@@ -93,7 +93,9 @@ __device__ __forceinline__ void minmax_params(double wmin, double wmax, int bits
   z = -rint(wmin / delta0);
 }
 
-__global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
+// sqc_search_weighted: the candidate search with a loss weight per element (explicit weights, or
+// omega = w^2 / [H^-1]_jj^2), which the weights and the losses of a row pass through LDS for.
+__global__ __launch_bounds__(SQC_THREADS) void sqc_search_weighted(SqcArgs a) {
   extern __shared__ __align__(16) double smem[];
   const int beta = a.beta, ncand = a.ncand;
   const int RW = a.rows_per_wg;
@@ -101,36 +103,10 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
   double* om = wrow + RW * beta;                  // [RW][beta]
   double* loss = om + RW * beta;                  // [RW][ncand]
   double* rp = loss + RW * ncand;                 // [RW][4]: delta0, z, alpha, unused
-  double* red = rp + RW * 4;                      // [256] + 2
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r0 = blockIdx.x * RW;
   const int rows = min(RW, a.n - r0);
   const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
-  const bool need_mask = (a.omega == nullptr && a.weight_mode == SLIM_WEIGHT_MASK_MEAN);
-
-  // block-wide mu and 3 sigma from the slab partials, reduced in a fixed order
-  double mu = 0.0, thr = 0.0;
-  if (need_mask && a.scope == SLIM_SCOPE_BLOCK) {
-    double s1 = 0.0, s2 = 0.0;
-    for (int p = tid; p < a.nstat; p += SQC_THREADS) {
-      s1 += a.stat_partial[2 * p];
-      s2 += a.stat_partial[2 * p + 1];
-    }
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
-    if (lane == 0) {
-      red[2 * wave] = s1;
-      red[2 * wave + 1] = s2;
-    }
-    __syncthreads();
-    const double S1 = ((red[0] + red[2]) + red[4]) + red[6];
-    const double S2 = ((red[1] + red[3]) + red[5]) + red[7];
-    const double cnt = (double)a.n * (double)beta;
-    const double m1 = S1 / cnt;
-    const double var = fmax(S2 / cnt - m1 * m1, 0.0);
-    mu = a.W[0] + m1;
-    thr = 3.0 * sqrt(var);
-  }
 
   for (int idx = tid; idx < rows * beta; idx += SQC_THREADS) {
     const int r = idx / beta, c = idx - r * beta;
@@ -141,13 +117,12 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
   // per-row statistics and loss weights: wavefront w takes rows w, w + 4
   for (int r = wave; r < rows; r += SQC_THREADS / 64) {
     const double* w = wrow + r * beta;
-    double mn = INFINITY, mx = -INFINITY, sabs = 0.0, sum = 0.0;
+    double mn = INFINITY, mx = -INFINITY, sabs = 0.0;
     for (int c = lane; c < beta; c += 64) {
       const double v = w[c];
       mn = fmin(mn, v);
       mx = fmax(mx, v);
       sabs += fabs(v);
-      sum += v;
     }
     mn = wave_min(mn);
     mx = wave_max(mx);
@@ -161,33 +136,11 @@ __global__ __launch_bounds__(SQC_THREADS) void sqc_search(SqcArgs a) {
     }
     if (a.omega) {
       for (int c = lane; c < beta; c += 64) om[r * beta + c] = a.omega[(int64_t)(r0 + r) * beta + c];
-    } else if (a.weight_mode == SLIM_WEIGHT_UNIFORM) {
-      for (int c = lane; c < beta; c += 64) om[r * beta + c] = 1.0;
-    } else if (a.weight_mode == SLIM_WEIGHT_ELEMENT) {
+    } else {
       for (int c = lane; c < beta; c += 64) {
         const double d = a.dblk[c];
         om[r * beta + c] = (w[c] * w[c]) / (d * d);
       }
-    } else {
-      double rmu = mu, rthr = thr;
-      if (a.scope == SLIM_SCOPE_ROW) {
-        sum = wave_sum(sum);
-        rmu = sum / (double)beta;
-        double ss = 0.0;
-        for (int c = lane; c < beta; c += 64) {
-          const double d = w[c] - rmu;
-          ss += d * d;
-        }
-        ss = wave_sum(ss);
-        rthr = 3.0 * sqrt(ss / (double)beta);
-      }
-      int ns = 0;
-      for (int c = lane; c < beta; c += 64) ns += (fabs(w[c] - rmu) > rthr) ? 1 : 0;
-      ns = wave_sum_int(ns);
-      const int nus = beta - ns;
-      const double ws = ns ? 1.0 / (double)ns : 0.0;
-      const double wus = nus ? 1.0 / (double)nus : 0.0;
-      for (int c = lane; c < beta; c += 64) om[r * beta + c] = (fabs(w[c] - rmu) > rthr) ? ws : wus;
     }
   }
   __syncthreads();
@@ -297,7 +250,7 @@ int sqc_rows_per_wg(int ncand) {
 }
 
 size_t sqc_smem_bytes(int beta, int ncand, int rows) {
-  return sizeof(double) * ((size_t)2 * rows * beta + (size_t)rows * ncand + rows * 4 + SQC_THREADS + 2);
+  return sizeof(double) * ((size_t)2 * rows * beta + (size_t)rows * ncand + rows * 4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -342,6 +295,347 @@ __device__ __forceinline__ double vmin_f64(double a, double b) {
 #else
   return a < b ? a : b;
 #endif
+}
+
+// ------------------------------------------------------------------------------------------
+// sqc_search_fast: the candidate search for the two loss weightings that need no weight per element, the default
+// L = L_s / |s| + L_us / |us| over the 3-sigma mask and the unweighted Eq. 5.  Both are read off two plain sums
+// of squared errors: over all weights of the row (the main loop, six fp64 instructions per weight and candidate:
+// multiply by the reciprocal step, round, clamp twice, error, accumulate) and over the few salient ones, which a
+// second short loop visits again; L = (all - salient) / |us| + salient / |s|.
+// Four neighbouring lanes (a quad) share a (row, 5 candidates) item, each taking every fourth pair of weights,
+// so a weight pair read from LDS serves ten loss chains; with 100 candidates a row is 80 threads and a workgroup
+// of 320 threads takes four rows, which gives every SIMD of a CU the same number of wavefronts.  Reductions go
+// through DPP inside a 16-lane row and lane reads across rows.
+// ------------------------------------------------------------------------------------------
+typedef double double2v __attribute__((ext_vector_type(2)));
+constexpr int SQF_CPT = 5;     // candidates per lane
+constexpr int SQF_PAD = 8;     // doubles of padding per LDS row
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_b32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  return __hiloint2double(dpp_b32<CTRL>(__double2hiint(v)), dpp_b32<CTRL>(__double2loint(v)));
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+struct OpSum { __device__ static double f(double a, double b) { return a + b; } };
+struct OpMin { __device__ static double f(double a, double b) { return fmin(a, b); } };
+struct OpMax { __device__ static double f(double a, double b) { return fmax(a, b); } };
+// every lane receives the reduction over the wavefront; the same association in every lane
+template <typename OP>
+__device__ __forceinline__ double wave_allreduce(double v) {
+  v = OP::f(v, dpp_f64<DPP_XOR1>(v));
+  v = OP::f(v, dpp_f64<DPP_XOR2>(v));
+  v = OP::f(v, dpp_f64<DPP_HALF_MIRROR>(v));
+  v = OP::f(v, dpp_f64<DPP_MIRROR>(v));
+  const double r0 = read_lane_f64(v, 0), r1 = read_lane_f64(v, 16), r2 = read_lane_f64(v, 32), r3 = read_lane_f64(v, 48);
+  return OP::f(OP::f(r0, r1), OP::f(r2, r3));
+}
+
+// reciprocal to full precision without the division sequence (two Newton steps on the hardware estimate)
+__device__ __forceinline__ double fast_rcp(double d) {
+  double r = __builtin_amdgcn_rcp(d);
+  r = fma(fma(-d, r, 1.0), r, r);
+  r = fma(fma(-d, r, 1.0), r, r);
+  return r;
+}
+
+__global__ __launch_bounds__(1024, 5) void sqc_search_fast(SqcArgs a) {
+  extern __shared__ __align__(16) double smem[];
+  const int beta = a.beta, ncand = a.ncand, RW = a.rows_per_wg;
+  const int stride = beta + SQF_PAD;
+  double* wrow = smem;                            // [RW][stride]  the rows' weights
+  double* sal = wrow + RW * stride;               // [RW][stride]  each row's salient weights, compacted
+  double* loss = sal + RW * stride;               // [RW][ncand]
+  double* rp = loss + RW * ncand;                 // [RW][8]: delta0, z, alpha, 1/|s|, 1/|us|, |s|, row sum
+  double* red = rp + RW * 8;                      // [2 * 16]
+  double* tgrid = red + 32;                       // [ncand]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+  const bool sign_mode = (a.bits == 1 && a.q1_mode == SLIM_Q1_SIGN);
+  const bool need_mask = (a.weight_mode == SLIM_WEIGHT_MASK_MEAN);
+  const bool block_scope = need_mask && a.scope == SLIM_SCOPE_BLOCK;
+  const int nsets = (a.n + RW - 1) / RW;
+
+  // A workgroup takes sets of RW rows in turn.  When a wavefront has one row to fetch and it fits two
+  // registers per lane, the rows of the next set are fetched before the search of the current one starts.
+  const bool ahead = RW <= nwaves && beta <= 128;
+  double pre[2] = {0.0, 0.0};
+  auto fetch_row = [&](int set) {
+    const int row = set * RW + wave;
+    if (set < nsets && wave < RW && row < a.n) {
+      const double* src = a.W + (int64_t)row * a.ldw;
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        if (q * 64 + lane < beta) pre[q] = src[q * 64 + lane];
+    }
+  };
+  if (ahead) fetch_row(blockIdx.x);
+
+  // the candidate grid goes to LDS once
+  for (int c = tid; c < ncand; c += blockDim.x) tgrid[c] = a.tau[c];
+  const int groups = (ncand + SQF_CPT - 1) / SQF_CPT;
+  const int tpr = 4 * groups;
+  // block-wide mean and 3 sigma from the slab partials, once per workgroup, summed in a fixed order
+  double mu = 0.0, thr = 0.0;
+  if (block_scope) {
+    double s1 = 0.0, s2 = 0.0;
+    for (int p = tid; p < a.nstat; p += blockDim.x) {
+      s1 += a.stat_partial[2 * p];
+      s2 += a.stat_partial[2 * p + 1];
+    }
+    s1 = wave_allreduce<OpSum>(s1);
+    s2 = wave_allreduce<OpSum>(s2);
+    if (lane == 0) {
+      red[2 * wave] = s1;
+      red[2 * wave + 1] = s2;
+    }
+    __syncthreads();
+    double S1 = 0.0, S2 = 0.0;
+    for (int w = 0; w < nwaves; ++w) {
+      S1 += red[2 * w];
+      S2 += red[2 * w + 1];
+    }
+    const double cnt = (double)a.n * (double)beta;
+    const double m1 = S1 / cnt;
+    const double var = fmax(S2 / cnt - m1 * m1, 0.0);
+    mu = a.W[0] + m1;
+    thr = 3.0 * sqrt(var);
+  }
+  const double qmax = (double)((1 << a.bits) - 1);
+
+  for (int set = blockIdx.x; set < nsets; set += gridDim.x) {
+    const int r0 = set * RW;
+    const int rows = min(RW, a.n - r0);
+    // a wavefront per row: the row goes to LDS; its minimum, maximum and sum of magnitudes give the parameters,
+    // its salient weights are copied to the row's list and their number decides the two loss weights
+    for (int r = wave; r < rows; r += nwaves) {
+      const double* src = a.W + (int64_t)(r0 + r) * a.ldw;
+      double* w = wrow + r * stride;
+      double mn = INFINITY, mx = -INFINITY, sabs = 0.0, sum = 0.0;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int c = q * 64 + lane;
+        if (c < beta) {
+          const double v = ahead ? pre[q] : src[c];
+          w[c] = v;
+          mn = fmin(mn, v);
+          mx = fmax(mx, v);
+          sabs += fabs(v);
+          sum += v;
+        }
+      }
+      for (int c = 128 + lane; c < beta; c += 64) {
+        const double v = src[c];
+        w[c] = v;
+        mn = fmin(mn, v);
+        mx = fmax(mx, v);
+        sabs += fabs(v);
+        sum += v;
+      }
+      mn = wave_allreduce<OpMin>(mn);
+      mx = wave_allreduce<OpMax>(mx);
+      sabs = wave_allreduce<OpSum>(sabs);
+      int ns = 0;
+      if (need_mask) {
+        double rmu = mu, rthr = thr;
+        if (!block_scope) {
+          rmu = wave_allreduce<OpSum>(sum) / (double)beta;
+          double ss = 0.0;
+          for (int c = lane; c < beta; c += 64) {
+            const double d = w[c] - rmu;
+            ss += d * d;
+          }
+          ss = wave_allreduce<OpSum>(ss);
+          rthr = 3.0 * sqrt(ss / (double)beta);
+        }
+        for (int c0 = 0; c0 < beta; c0 += 64) {
+          const int c = c0 + lane;
+          const double v = c < beta ? w[c] : 0.0;
+          const bool s = c < beta && fabs(v - rmu) > rthr;
+          const unsigned long long b = __ballot(s);
+          const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
+          if (s) sal[r * stride + ns + before] = v;
+          ns += __builtin_popcountll(b);
+        }
+      }
+      if (lane == 0) {
+        double d0 = 1.0, z = 0.0;
+        if (!sign_mode) minmax_params(mn, mx, a.bits, d0, z);
+        const int nus = beta - ns;
+        double ws = 0.0, wus = 1.0;
+        if (need_mask) {
+          ws = ns ? fast_rcp((double)ns) : 0.0;
+          wus = nus ? fast_rcp((double)nus) : 0.0;
+        }
+        rp[r * 8 + 0] = d0;
+        rp[r * 8 + 1] = z;
+        rp[r * 8 + 2] = sabs / (double)beta;
+        rp[r * 8 + 3] = ws;
+        rp[r * 8 + 4] = wus;
+        reinterpret_cast<int*>(rp + r * 8 + 5)[0] = ns;
+      }
+    }
+    if (ahead) fetch_row(set + gridDim.x);
+    __syncthreads();
+
+    // main loop: a quad of lanes per (row, SQF_CPT candidates)
+    for (int s0 = 0; s0 < rows * tpr; s0 += blockDim.x) {
+      const int s = s0 + tid;
+      const bool live = s < rows * tpr;
+      const int sc = min(s, rows * tpr - 1);
+      const int r = sc / tpr, rem = sc - r * tpr;
+      const int c0 = (rem >> 2) * SQF_CPT, p = rem & 3;
+      const double* w = wrow + r * stride;
+      const double* sl = sal + r * stride;
+      const double* par = rp + r * 8;
+      const int ns = reinterpret_cast<const int*>(par + 5)[0];
+      // L = wus * (sum over all) + (ws - wus) * (sum over the salient ones)
+      const double wus = par[4], wdiff = par[3] - par[4];
+      double L[SQF_CPT], dl[SQF_CPT], rd[SQF_CPT];
+#pragma unroll
+      for (int i = 0; i < SQF_CPT; ++i) {
+        const double tc = tgrid[min(c0 + i, ncand - 1)];
+        L[i] = 0.0;
+        // SIGN: the level tau * alpha; otherwise the step tau * delta0 and its reciprocal.  The loss is continuous
+        // across a rounding tie (both neighbouring codes are equally far), so the candidate losses may use a
+        // reciprocal; the codes themselves are decided with a true division.
+        dl[i] = tc * (sign_mode ? par[2] : par[0]);
+        rd[i] = fast_rcp(dl[i]);
+      }
+      if (sign_mode) {
+        // |w - sign(w) level| = ||w| - level|
+        for (int j = 0; j < beta / 8; ++j) {
+          const double2v v2 = *reinterpret_cast<const double2v*>(w + (4 * j + p) * 2);
+#pragma unroll
+          for (int i = 0; i < SQF_CPT; ++i) {
+            const double e0 = fabs(v2.x) - dl[i], e1 = fabs(v2.y) - dl[i];
+            L[i] = fma(e0, e0, L[i]);
+            L[i] = fma(e1, e1, L[i]);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < SQF_CPT; ++i) L[i] *= wus;
+        for (int j = p; j < ns; j += 4) {
+          const double v = sl[j];
+#pragma unroll
+          for (int i = 0; i < SQF_CPT; ++i) {
+            const double e = fabs(v) - dl[i];
+            L[i] = fma(e * wdiff, e, L[i]);
+          }
+        }
+      } else {
+        // clamp(rint(x) + z, 0, qmax) - z == clamp(rint(x), -z, qmax - z): one add and one subtract less per element
+        const double z = par[1];
+        const double lo = -z, hi = qmax - z;
+        double2v nxt = *reinterpret_cast<const double2v*>(w + p * 2);
+        for (int j = 0; j < beta / 8; ++j) {
+          const double2v v2 = nxt;
+          nxt = *reinterpret_cast<const double2v*>(w + (4 * min(j + 1, beta / 8 - 1) + p) * 2);   // one pair ahead
+          // stage by stage over the five candidates' independent chains, so that a wavefront need not wait on
+          // its own results
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const double v = h ? v2.y : v2.x;
+            double x[SQF_CPT];
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) x[i] = v * rd[i];
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) x[i] = rint(x[i]);
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) x[i] = fmax(x[i], lo);
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) x[i] = fmin(x[i], hi);
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) x[i] = fma(-dl[i], x[i], v);
+#pragma unroll
+            for (int i = 0; i < SQF_CPT; ++i) L[i] = fma(x[i], x[i], L[i]);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < SQF_CPT; ++i) L[i] *= wus;
+        for (int j = p; j < ns; j += 4) {
+          const double v = sl[j];
+#pragma unroll
+          for (int i = 0; i < SQF_CPT; ++i) {
+            const double q = fmin(fmax(rint(v * rd[i]), lo), hi);
+            const double e = fma(-dl[i], q, v);
+            L[i] = fma(e * wdiff, e, L[i]);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < SQF_CPT; ++i) {
+        double t = L[i];                                   // this lane's share: the loss is linear in the sums
+        t += dpp_f64<DPP_XOR1>(t);
+        t += dpp_f64<DPP_XOR2>(t);
+        if (live && p == 0 && c0 + i < ncand) loss[r * ncand + c0 + i] = t;
+      }
+    }
+    __syncthreads();
+
+    // first minimum per row
+    for (int r = wave; r < rows; r += nwaves) {
+      double best = INFINITY;
+      int bi = 0x7fffffff;
+      for (int c = lane; c < ncand; c += 64) {
+        const double L = loss[r * ncand + c];
+        if (L < best) {
+          best = L;
+          bi = c;
+        }
+      }
+#define SQF_ARGMIN_STEP(CTRL)                                                   \
+      {                                                                           \
+        const double ob = dpp_f64<CTRL>(best);                                    \
+        const int oi = dpp_b32<CTRL>(bi);                                         \
+        if (ob < best || (ob == best && oi < bi)) {                               \
+          best = ob;                                                              \
+          bi = oi;                                                                \
+        }                                                                         \
+      }
+      SQF_ARGMIN_STEP(DPP_XOR1)
+      SQF_ARGMIN_STEP(DPP_XOR2)
+      SQF_ARGMIN_STEP(DPP_HALF_MIRROR)
+      SQF_ARGMIN_STEP(DPP_MIRROR)
+#undef SQF_ARGMIN_STEP
+#pragma unroll
+      for (int src = 16; src < 64; src += 16) {
+        const double ob = read_lane_f64(best, src);
+        const int oi = __builtin_amdgcn_readlane(bi, src);
+        if (lane == 0 && (ob < best || (ob == best && oi < bi))) {
+          best = ob;
+          bi = oi;
+        }
+      }
+      if (lane == 0) {
+        if (bi == 0x7fffffff) bi = 0;
+        const int64_t o = (int64_t)(r0 + r) * a.out_stride;
+        const double tc = tgrid[bi];
+        if (sign_mode) {
+          a.scale[o] = 2.0 * tc * rp[r * 8 + 2];
+          a.zero[o] = 0.5;
+        } else {
+          a.scale[o] = tc * rp[r * 8 + 0];
+          a.zero[o] = rp[r * 8 + 1];
+        }
+        if (a.cand_idx) a.cand_idx[o] = bi;
+      }
+    }
+  }
+}
+
+// launch shape of sqc_search_fast: rows per workgroup and threads
+void sqf_shape(int beta, int ncand, int& rows, int& threads, size_t& smem) {
+  const int tpr = 4 * ((ncand + SQF_CPT - 1) / SQF_CPT);
+  rows = std::max(1, std::min(16, 320 / tpr));
+  const size_t per_row = sizeof(double) * (2 * (size_t)(beta + SQF_PAD) + ncand + 8);
+  rows = (int)std::max<size_t>(1, std::min<size_t>(rows, (60 * 1024) / per_row));
+  threads = std::min(1024, ((rows * tpr + 63) / 64) * 64);
+  smem = rows * per_row + sizeof(double) * (32 + ncand);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -606,15 +900,31 @@ slim_status launch_stats_and_sqc(slim_ctx* ctx, SqcArgs a, double* stat_partial)
     a.stat_partial = stat_partial;
     SLIM_LAUNCH(ctx, "sqc_block_stats", block_stats, dim3(a.nstat), dim3(256), 0, a.W, a.ldw, a.n, a.beta, stat_partial);
   }
+  if (a.omega == nullptr && (a.weight_mode == SLIM_WEIGHT_MASK_MEAN || a.weight_mode == SLIM_WEIGHT_UNIFORM)) {
+    int threads = 0;
+    size_t smem = 0;
+    sqf_shape(a.beta, a.ncand, a.rows_per_wg, threads, smem);
+    if (smem > 64 * 1024) {
+      static bool done = false;
+      slim_status st = allow_big_lds(ctx, sqc_search_fast, done);
+      if (st != SLIM_OK) return st;
+    }
+    // no more workgroups than are resident at once: each takes sets of rows in turn and fetches ahead
+    int per_cu = 0;
+    SLIM_HIP_TRY(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sqc_search_fast, threads, smem));
+    const int wgs = std::min(slim_cdiv(a.n, a.rows_per_wg), std::max(1, per_cu) * std::max(1, ctx->num_cus));
+    SLIM_LAUNCH(ctx, "sqc_search", sqc_search_fast, dim3(wgs), dim3(threads), smem, a);
+    return SLIM_OK;
+  }
   a.rows_per_wg = sqc_rows_per_wg(a.ncand);
   const size_t smem = sqc_smem_bytes(a.beta, a.ncand, a.rows_per_wg);
   if (smem > 160 * 1024) return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "sqc: beta * ncand too large for LDS");
   if (smem > 64 * 1024) {
     static bool done = false;
-    slim_status st = allow_big_lds(ctx, sqc_search, done);
+    slim_status st = allow_big_lds(ctx, sqc_search_weighted, done);
     if (st != SLIM_OK) return st;
   }
-  SLIM_LAUNCH(ctx, "sqc_search", sqc_search, dim3(slim_cdiv(a.n, a.rows_per_wg)), dim3(SQC_THREADS), smem, a);
+  SLIM_LAUNCH(ctx, "sqc_search", sqc_search_weighted, dim3(slim_cdiv(a.n, a.rows_per_wg)), dim3(SQC_THREADS), smem, a);
   return SLIM_OK;
 }
 
