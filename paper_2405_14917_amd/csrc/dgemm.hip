@@ -156,7 +156,10 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   const int tiles_n = (d.N + BN - 1) / BN;
   const int tiles_m = (d.M + BM - 1) / BM;
   if (pid >= tiles_m * tiles_n) return;
-  const int bi = pid / tiles_n, bj = pid % tiles_n;
+  // tiles with the longest K range first: with an upper triangular B those are the last columns (with an upper
+  // triangular A the first rows, which come first anyway)
+  const int bi = pid / tiles_n;
+  const int bj = (d.flags & SLIM_GEMM_B_UPPER) ? tiles_n - 1 - pid % tiles_n : pid % tiles_n;
   const int row0 = bi * BM, col0 = bj * BN;
   if ((d.flags & SLIM_GEMM_UPPER_ONLY) && row0 >= col0 + BN) return;
 
@@ -443,7 +446,10 @@ slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, co
 slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs_dev,
                                int count, int max_M, int max_N) {
   if (count == 0 || max_M == 0 || max_N == 0) return SLIM_OK;
-  if (use_small_tiles(max_M, max_N, count)) {
+  // The products of a batch have triangular operands, so the K ranges of their tiles differ by large factors: up to
+  // two rounds of 128 x 128 tiles would last as long as the longest tile, while many 64 x 64 tiles per CU even out.
+  const bool uneven = (int64_t)slim_cdiv(max_M, 128) * slim_cdiv(max_N, 128) * count <= 2 * (int64_t)ctx->num_cus;
+  if (uneven || use_small_tiles(max_M, max_N, count)) {
     const int tiles = slim_cdiv(max_M, 64) * slim_cdiv(max_N, 64);
     if (trans_b)
       SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_batched_kernel<1, 64, 64>"), (dgemm_batched_kernel<1, 64, 64>),
