@@ -43,24 +43,48 @@ __global__ __launch_bounds__(256) void damp_lambda(const float* __restrict__ G, 
   if (threadIdx.x == 0) *lam_out = percdamp * (red[0] / (double)m);
 }
 
-// A = s * G + lambda I on and above the diagonal, zero below
+// A = s * G + lambda I on and above the diagonal, zero below; U = 0.  V consecutive columns per thread.
+template <int V>
 __global__ __launch_bounds__(256) void widen_damp(const float* __restrict__ G, int64_t ldg, int m, double s,
                                                   const double* __restrict__ lam, double* __restrict__ A,
-                                                  int64_t lda) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
+                                                  int64_t lda, double* __restrict__ U, int64_t ldu) {
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * V;
   const int r = blockIdx.y;
-  if (c >= m) return;
-  double v = 0.0;
-  if (c >= r) {
-    v = s * (double)G[(int64_t)r * ldg + c];
-    if (c == r) v += *lam;
+  if (c0 >= m) return;
+  float g[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) g[v] = 0.0f;
+  if (c0 + V - 1 >= r) {                       // something of this piece lies on or above the diagonal
+    const float* src = G + (int64_t)r * ldg + c0;
+    if (V == 4) {
+      const float4 t = *reinterpret_cast<const float4*>(src);
+      g[0] = t.x, g[1] = t.y, g[2] = t.z, g[3] = t.w;
+    } else if (V == 2) {
+      const float2 t = *reinterpret_cast<const float2*>(src);
+      g[0] = t.x, g[1] = t.y;
+    } else {
+      g[0] = src[0];
+    }
   }
-  A[(int64_t)r * lda + c] = v;
-}
-
-__global__ __launch_bounds__(256) void zero_matrix(double* __restrict__ A, int64_t lda, int m) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c < m) A[(int64_t)blockIdx.y * lda + c] = 0.0;
+  double a[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    const int c = c0 + v;
+    a[v] = c >= r ? s * (double)g[v] : 0.0;
+    if (c == r) a[v] += *lam;
+  }
+  double* da = A + (int64_t)r * lda + c0;
+  double* du = U + (int64_t)r * ldu + c0;
+  if (V == 1) {
+    da[0] = a[0];
+    du[0] = 0.0;
+  } else {
+#pragma unroll
+    for (int v = 0; v < V; v += 2) {
+      *reinterpret_cast<double2*>(da + v) = make_double2(a[v], a[v + 1]);
+      *reinterpret_cast<double2*>(du + v) = make_double2(0.0, 0.0);
+    }
+  }
 }
 
 // 1 / x to full double precision for positive finite x: hardware estimate plus two Newton steps
@@ -372,9 +396,14 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
 
   const double s = 2.0 / (double)n_tokens;
   SLIM_LAUNCH(ctx, "inv_lambda", damp_lambda, dim3(1), dim3(256), 0, G, ldg, m, s, percdamp, lam, flag);
-  const dim3 mgrid(slim_cdiv(m, 256), m);
-  SLIM_LAUNCH(ctx, "inv_widen", widen_damp, mgrid, dim3(256), 0, G, ldg, m, s, lam, A, lda);
-  SLIM_LAUNCH(ctx, "inv_zero_u", zero_matrix, mgrid, dim3(256), 0, U, ldu, m);
+  // one pass writes A (widened, damped) and clears U; 4 / 2 / 1 columns per thread as alignment allows
+  const bool g16 = (reinterpret_cast<uintptr_t>(G) & 15u) == 0, g8 = (reinterpret_cast<uintptr_t>(G) & 7u) == 0;
+  if (m % 4 == 0 && ldg % 4 == 0 && ldu % 4 == 0 && g16)
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<4>, dim3(slim_cdiv(m, 1024), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
+  else if (ldg % 2 == 0 && g8)
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<2>, dim3(slim_cdiv(m, 512), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
+  else
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<1>, dim3(slim_cdiv(m, 256), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
 
   // ---- descriptors of the triangular inverse (pairwise merging of inverted diagonal ranges), staged first so
   //      that no host synchronisation falls between the factorisation and the inverse

@@ -42,27 +42,41 @@ __global__ __launch_bounds__(256) void colsumsq_partial(const T* __restrict__ W,
   for (int j = 0; j < 4; ++j) partial[(int64_t)blockIdx.y * m + c0 + j] = acc[j];
 }
 
-// one workgroup per group g: col_sal for its beta columns, then the group mean
-__global__ __launch_bounds__(256) void salience_finalize(const double* __restrict__ partial, int nparts, int n,
-                                                         int m, int beta, const double* __restrict__ dden,
-                                                         int64_t dstride, double* __restrict__ col_sal,
-                                                         double* __restrict__ group_sal) {
-  __shared__ double red[256];
+// one workgroup per group g: col_sal for its beta columns, then the group mean.  The 1024 threads split the
+// partial sums of a column among 1024 / beta slices (every slice-th part each), which are added in slice order.
+__global__ __launch_bounds__(1024) void salience_finalize(const double* __restrict__ partial, int nparts, int n,
+                                                          int m, int beta, const double* __restrict__ dden,
+                                                          int64_t dstride, double* __restrict__ col_sal,
+                                                          double* __restrict__ group_sal) {
+  __shared__ double red[1024];
   const int g = blockIdx.x;
-  double tsum = 0.0;
-  for (int j = threadIdx.x; j < beta; j += 256) {
+  const int cp = min(beta, 1024);               // columns per pass
+  const int slices = 1024 / cp;
+  const int jj = threadIdx.x % cp, sl = threadIdx.x / cp;
+  double v = 0.0;                               // sum of the column saliences this thread finishes
+  for (int j0 = 0; j0 < beta; j0 += cp) {
+    const int j = j0 + jj;
     const int c = g * beta + j;
     double s = 0.0;
-    for (int p = 0; p < nparts; ++p) s += partial[(int64_t)p * m + c];
-    const double d = dden[(int64_t)c * dstride];
-    const double v = s / (d * d);
-    col_sal[c] = v;
-    tsum += v;
+    if (sl < slices && j < beta)
+      for (int p = sl; p < nparts; p += slices) s += partial[(int64_t)p * m + c];
+    __syncthreads();
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (sl == 0 && j < beta) {
+      double t = 0.0;
+      for (int q = 0; q < slices; ++q) t += red[q * cp + jj];
+      const double d = dden[(int64_t)c * dstride];
+      const double cs = t / (d * d);
+      col_sal[c] = cs;
+      v += cs;
+    }
   }
-  red[threadIdx.x] = tsum;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+  red[threadIdx.x] = v;
+  __syncthreads();
+  for (int st = 512; st > 0; st >>= 1) {
+    if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
     __syncthreads();
   }
   if (threadIdx.x == 0) group_sal[g] = red[0] / ((double)n * (double)beta);
@@ -113,7 +127,7 @@ extern "C" slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_
   else
     SLIM_LAUNCH(ctx, "salience_colsumsq", colsumsq_partial<float>, grid, block, 0, static_cast<const float*>(W), n, m,
                 ldw, rpp, dden, dstride, partial, elem_sal);
-  SLIM_LAUNCH(ctx, "salience_finalize", salience_finalize, dim3(m / beta), dim3(256), 0, partial, nparts, n, m, beta,
+  SLIM_LAUNCH(ctx, "salience_finalize", salience_finalize, dim3(m / beta), dim3(1024), 0, partial, nparts, n, m, beta,
               dden, dstride, col_sal, group_sal);
   return SLIM_OK;
 }
