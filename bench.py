@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 import numpy as np
 import torch
 
-from paper_2405_14917_amd import binding, synth
+from paper_2405_14917_amd import binding, pipeline, synth
 
 PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e12}
 # HBM bytes per launch measured with two `rocprofv3 --pmc` runs of this command (FETCH_SIZE, WRITE_SIZE), each
@@ -45,46 +45,18 @@ def resident_inputs(cfg):
     return W, X
 
 
-class Pass:
-    """The hot path over one resident layer; all buffers are allocated once, outside the timed region.
-
-    Two library contexts on two streams: the half of the bit allocation that needs neither the Hessian nor the
-    salience (the reference outputs and the outputs of the all-N-bit weights, two n x m x t_s products) is enqueued
-    on the second stream before the inverse, whose chain of small kernels leaves most of the chip idle."""
+class Pass(pipeline.LayerPass):
+    """The hot path over one resident layer of a benchmark configuration; all buffers are allocated once, outside
+    the timed region (the order of the entry points and the two-stream overlap are the package's LayerPass)."""
 
     def __init__(self, slim, cfg, W, X):
-        self.slim, self.cfg, self.W, self.X = slim, cfg, W, X
-        m = cfg.m
-        self.G = torch.zeros((m, m), dtype=torch.float32, device="cuda")
-        self.U = torch.empty((m, m), dtype=torch.float64, device="cuda")
-        self.d = torch.empty(m, dtype=torch.float64, device="cuda")
-        self.Xs = X[:, : min(T_SBA, cfg.t)]
-        self.main = torch.cuda.current_stream()
-        self.side = torch.cuda.Stream()
-        with torch.cuda.stream(self.side):
-            self.slim_sba = binding.Slim("cuda:0")
-
-    def contexts(self):
-        return [self.slim, self.slim_sba]
+        super().__init__(slim, cfg.m, cfg.beta, cfg.N, cfg.percdamp, T_SBA)
+        self.cfg, self.W, self.X = cfg, W, X
 
     def step(self):
-        cfg, s, s2 = self.cfg, self.slim, self.slim_sba
-        self.G.zero_()
-        nt = s.hessian_accumulate(self.X, self.G, 0)
-        self.side.wait_stream(self.main)               # the Gram kernel has the chip to itself
-        s2.sba_prepare(self.W, cfg.beta, cfg.N, self.Xs)
-        s.hessian_inverse(self.G, nt, cfg.percdamp, U=self.U, hinv_diag=self.d)
-        _, grp, _ = s.salience(self.W, self.d, cfg.beta)
-        self.side.wait_stream(self.main)
-        with torch.cuda.stream(self.side):
-            bits, p_star, _ = s2.sba_allocate(self.W, grp, cfg.beta, cfg.N, self.Xs)
-        grp.record_stream(self.side)
-        bits.record_stream(self.main)
-        self.main.wait_stream(self.side)
-        out = s.gptq_quantize(self.W, self.U, bits, cfg.beta)
-        packed, gbits, row_off, m_star = s.pack(out["codes"], bits, cfg.beta, packed_rows=cfg.m * (cfg.N + 1) // 32)
-        self.stored = (packed, gbits, row_off, out["scale"], out["zero"])
-        return p_star, m_star
+        r = self.run(self.W, self.X)
+        self.stored = (r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"])
+        return r["p_star"], r["m_star"]
 
     def inference(self, tokens=1, reps=100):
         """Not part of the step: the linear layer on the stored form of the last pass (App. B.2), `tokens`
@@ -102,10 +74,6 @@ class Pass:
         torch.cuda.synchronize()
         nbytes = packed.numel() * 4 + gbits.numel() * 4 + row_off.numel() * 4 + scale.numel() * 8 + zero.numel() * 8
         return e0.elapsed_time(e1) * 1e3 / reps, nbytes
-
-    def close(self):
-        self.slim_sba.close()
-
 
 def algorithmic_work(name, cfg, launches_per_step):
     """(bound, peak key, work per launch) for the kernels that can dominate a step.  Work is
@@ -315,6 +283,17 @@ def main():
     us, nbytes = job.inference(tokens=1)
     line["inference"] = {"kernel": "dequant_matmul", "tokens": 1, "us_per_call": us, "stored_bytes": nbytes,
                          "GB_per_s": nbytes / us / 1e3, "frac_hbm": nbytes / (us * 1e-6) / PEAK["hbm"]}
+    # beside the metric too: three layers that read the same input (q/k/v of a block) with one Hessian and one
+    # inverse between them; the three layers are this layer's weights three times, the result per layer is the
+    # step's own
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    shared_reps = 2
+    for _ in range(shared_reps):
+        job.run_shared_input([W, W, W], X)
+    torch.cuda.synchronize()
+    line["shared_input"] = {"layers": 3, "ms_per_layer": (time.perf_counter() - t0) * 1e3 / (3 * shared_reps),
+                            "note": "one Gram matrix and one inverse for three layers of the step's shape"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:

@@ -463,6 +463,36 @@ def test_dequant_matmul_after_the_whole_pass(slim):
         slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, dev(X)[:, :17].t().contiguous())
 
 
+def test_layers_that_share_their_input_share_the_hessian(slim):
+    """The driver for q/k/v-like layers (one Hessian, one inverse) gives every layer what the single-layer
+    driver gives it alone, bit for bit, and the single-layer driver is the sequence of the entry points."""
+    from paper_2405_14917_amd import pipeline
+    m, beta, N, t = 512, 128, 2, 2048
+    Wa, X = small_layer(92, n=256, m=m, t=t, beta=beta)
+    Wb, _ = small_layer(93, n=384, m=m, t=t, beta=beta)
+    Wc, _ = small_layer(94, n=256, m=m, t=t, beta=beta)
+    drv = pipeline.LayerPass(slim, m, beta, N, 0.01, t_sba=256)
+    try:
+        Xd = dev(X)
+        shared = drv.run_shared_input([dev(Wa), dev(Wb), dev(Wc)], Xd)
+        for W, r in zip((Wa, Wb, Wc), shared):
+            alone = drv.run(dev(W), Xd)
+            assert r["p_star"] == alone["p_star"] and r["m_star"] == alone["m_star"]
+            for key in ("bits", "codes", "scale", "zero", "packed", "gbits", "row_off"):
+                assert torch.equal(r[key], alone[key]), key
+        # the single-layer driver against the entry points called one by one on one context
+        G = torch.zeros((m, m), dtype=torch.float32, device="cuda")
+        nt = slim.hessian_accumulate(Xd, G, 0)
+        U, d = slim.hessian_inverse(G, nt, 0.01)
+        _, grp, _ = slim.salience(dev(Wb), d, beta)
+        bits, p_star, _ = slim.sba_allocate(dev(Wb), grp, beta, N, Xd[:, :256])
+        out = slim.gptq_quantize(dev(Wb), U, bits, beta)
+        assert p_star == shared[1]["p_star"] and torch.equal(bits, shared[1]["bits"])
+        assert torch.equal(out["codes"], shared[1]["codes"]) and torch.equal(out["scale"], shared[1]["scale"])
+    finally:
+        drv.close()
+
+
 def test_pack_rejects_bad_input(slim):
     from paper_2405_14917_amd import binding
     codes = dev(np.zeros((8, 128), dtype=np.uint8))
