@@ -56,7 +56,7 @@ class Pass(pipeline.LayerPass):
     def step(self):
         r = self.run(self.W, self.X)
         self.stored = (r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"])
-        return r["p_star"], r["m_star"]
+        return r["p_star"], r["m_star"]      # 0-dim device tensors: reading them is the caller's synchronisation
 
     def inference(self, tokens=1, reps=100):
         """Not part of the step: the linear layer on the stored form of the last pass (App. B.2), `tokens`
@@ -275,7 +275,7 @@ def main():
         "config": {"workload": "%s: LLaMA-7B q_proj shaped layer W %dx%d %s, X %dx%d f16, group %d, %d-bit average, "
                                "1%% damping, 100 SQC candidates, SBA objective on %d tokens" % (
                                    cfg.name, cfg.n, cfg.m, cfg.w_dtype, cfg.m, cfg.t, cfg.beta, cfg.N, min(T_SBA, cfg.t)),
-                   "p_star": p_star, "m_star": m_star},
+                   "p_star": int(p_star), "m_star": int(m_star)},
         "roofline": roofline,
         "kernels": others,
     }

@@ -14,10 +14,13 @@
  *    slim_destroy.
  *  - Work is enqueued on the HIP stream given to slim_create.  A call returns as soon as its work
  *    is enqueued, except where it has a host output (info, p_star, obj_curve, m_star): those calls
- *    synchronise the stream before returning.
+ *    wait until that output has arrived (slim_hessian_inverse: until the factorisation is done, with
+ *    the rest of its work still in flight).  p_star, obj_curve and m_star may be NULL: the call then
+ *    does not wait, so a caller can run a whole pass without stalling the stream.  slim_gptq_quantize reads the
+ *    widths back for validation and kernel selection, behind work it has already enqueued.
  *  - Return value: SLIM_OK or a negative slim_status.  No exceptions, no aborts.  After an error
- *    slim_last_error(ctx) describes it; on SLIM_ERR_INVALID_ARG / SLIM_ERR_UNSUPPORTED nothing has
- *    been launched and no output was touched.
+ *    slim_last_error(ctx) describes it; on SLIM_ERR_INVALID_ARG / SLIM_ERR_UNSUPPORTED no output
+ *    was touched (at most work on the library's own workspace has been launched).
  *  - Device pointers must be 16-byte aligned, leading dimensions of 16-bit matrices multiples
  *    of 8 elements.
  *  - Calls on one context must not overlap in time (one stream, one workspace).
@@ -130,7 +133,7 @@ slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int 
  *   squared error of the same outputs, || x W^T - x W_p^T ||_F^2 (the loss of Eq. 3; the variant of App. D).
  *   X_s       m x t_s (F16/BF16), tokens contiguous, the calibration tokens used by the objective
  *   bits      device, k bytes: the chosen width of every group
- *   p_star    host
+ *   p_star    host, or NULL
  *   obj_curve host, floor(k/2)+1 doubles or NULL: the objective for every p
  *   N must be 2 or 3 (widths 1..4).  All arithmetic is fp64.
  */
@@ -202,7 +205,9 @@ slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype,
  *   gbits      ceil(k/16) words: bits[g]-1 as a 2-bit value, 16 groups per word, least significant first
  *   packed_rows  capacity of `packed` in rows; if m_star exceeds it the call fails with
  *              SLIM_ERR_INVALID_ARG and writes nothing beyond the capacity
- *   m_star     host
+ *   m_star     host, or NULL: the call then does not wait for the stream and can report neither a width outside
+ *              1..4 nor a capacity that is too small (it still writes nothing beyond the capacity); m_star is
+ *              row_off[k]
  *   beta * b must be a multiple of 32 for every width in use (beta a multiple of 32).
  */
 slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,

@@ -209,8 +209,9 @@ class Slim:
                                               ctypes.byref(params) if params is not None else None))
 
     def sba_allocate(self, W: torch.Tensor, group_sal: torch.Tensor, beta: int, N: int, Xs: torch.Tensor,
-                     params: Optional[SlimParams] = None, objective: int = OBJ_KL):
-        """Returns (bits uint8 device tensor (k,), p_star, obj_curve numpy (k//2+1,))."""
+                     params: Optional[SlimParams] = None, objective: int = OBJ_KL, host_outputs: bool = True):
+        """Returns (bits uint8 device tensor (k,), p_star, obj_curve numpy (k//2+1,)); with host_outputs=False the
+        call does not wait for the stream and the last two are None."""
         _need_cuda(W, group_sal, Xs)
         n, m = W.shape
         k = m // beta
@@ -221,7 +222,10 @@ class Slim:
         self._check(self.lib.slim_sba_allocate(self.ctx, _ptr(W), _DT[W.dtype], n, m, W.stride(0), _ptr(group_sal), beta,
                                                N, objective, _ptr(Xs), _DT[Xs.dtype], t_s, Xs.stride(0),
                                                ctypes.byref(params) if params is not None else None, _ptr(bits),
-                                               ctypes.byref(p_star), curve))
+                                               ctypes.byref(p_star) if host_outputs else None,
+                                               curve if host_outputs else None))
+        if not host_outputs:
+            return bits, None, None
         return bits, int(p_star.value), np.frombuffer(curve, dtype=np.float64).copy()
 
     # ---- a5 + a6
@@ -263,8 +267,11 @@ class Slim:
         return dict(codes=codes, scale=scale, zero=zero, What=what, sum_e2=se2)
 
     # ---- a9
-    def pack(self, codes: torch.Tensor, bits: torch.Tensor, beta: int, packed_rows: Optional[int] = None):
-        """Returns (packed uint32-as-int32 (m_star, n), gbits (ceil(k/16),), row_off int32 (k+1,), m_star)."""
+    def pack(self, codes: torch.Tensor, bits: torch.Tensor, beta: int, packed_rows: Optional[int] = None,
+             host_outputs: bool = True):
+        """Returns (packed uint32-as-int32 (m_star, n), gbits (ceil(k/16),), row_off int32 (k+1,), m_star); with
+        host_outputs=False the call does not wait for the stream: packed then has all rows of its capacity (zero
+        from row m_star = row_off[k] on) and m_star is None."""
         _need_cuda(codes, bits)
         n, m = codes.shape
         k = m // beta
@@ -274,7 +281,9 @@ class Slim:
         row_off = torch.zeros(k + 1, dtype=torch.int32, device=codes.device)
         m_star = ctypes.c_int(0)
         self._check(self.lib.slim_pack(self.ctx, _ptr(codes), n, m, codes.stride(0), _ptr(bits), beta, _ptr(packed), cap,
-                                       _ptr(gbits), _ptr(row_off), ctypes.byref(m_star)))
+                                       _ptr(gbits), _ptr(row_off), ctypes.byref(m_star) if host_outputs else None))
+        if not host_outputs:
+            return packed, gbits, row_off, None
         return packed[: m_star.value], gbits, row_off, int(m_star.value)
 
     # ---- n1

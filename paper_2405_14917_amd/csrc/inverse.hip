@@ -461,11 +461,17 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   if (!descs.empty()) {
     if (descs.size() * sizeof(slim_gemm_desc) > (size_t)SLIM_HPIN_BYTES)
       return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_hessian_inverse: m too large for the descriptor staging buffer");
-    // the staging buffer may still be read by an earlier asynchronous copy
-    SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    // The staging buffer may still be read by the copy of an earlier call that ended on an error; every other use
+    // of it has been waited for.  No wait for the stream itself: the launches of the factorisation below are
+    // enqueued while earlier work (the Gram matrix) still runs, so its chain of small kernels finds them ready.
+    st = slim_ensure_side(ctx);
+    if (st != SLIM_OK) return st;
+    if (ctx->staging_copy_pending) SLIM_HIP_TRY(ctx, hipEventSynchronize(ctx->ev[13]));
     memcpy(ctx->hpin, descs.data(), descs.size() * sizeof(slim_gemm_desc));
     SLIM_HIP_TRY(ctx, hipMemcpyAsync(descs_dev, ctx->hpin, descs.size() * sizeof(slim_gemm_desc),
                                      hipMemcpyHostToDevice, ctx->stream));
+    SLIM_HIP_TRY(ctx, hipEventRecord(ctx->ev[13], ctx->stream));
+    ctx->staging_copy_pending = true;
   }
 
   // ---- factorisation from the bottom-right corner upwards.  Blocks of 64 columns, groups of GRP blocks;
@@ -626,6 +632,12 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       far_issued = true;
     }
   }
+  // The pivots are all known once the last diagonal block is done: the flag travels to the host from here, and the
+  // call returns when it has arrived, with the triangular inverse still in flight on the stream.
+  int* host = reinterpret_cast<int*>(ctx->hpin);
+  hipEvent_t ev_info = ctx->ev[11];
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host, flag, sizeof(int), hipMemcpyDeviceToHost, s0));
+  SLIM_HIP_TRY(ctx, hipEventRecord(ev_info, s0));
   // the triangular inverse reads every panel of R and overwrites A
   if (nblk > 1) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_gemm[1 & 3], 0));
   if (far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_far[last_far_slot], 0));
@@ -644,9 +656,8 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   SLIM_LAUNCH(ctx, "inv_diag_colsumsq", colsumsq_upper, dim3(slim_cdiv(m, 64), parts), dim3(256), 0, U, ldu, m, partial);
   SLIM_LAUNCH(ctx, "inv_diag_finalize", colsum_finalize, dim3(slim_cdiv(m, 256)), dim3(256), 0, partial, parts, m, hinv_diag);
 
-  int* host = reinterpret_cast<int*>(ctx->hpin);
-  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
-  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  SLIM_HIP_TRY(ctx, hipEventSynchronize(ev_info));
+  ctx->staging_copy_pending = false;               // the copy of the descriptors lies before the flag's on the stream
   *info = host[0];
   if (host[0] != 0)
     return slim_fail(ctx, SLIM_ERR_NOT_PD, "slim_hessian_inverse: H + lambda I is not positive definite (pivot at column %d)", host[0]);

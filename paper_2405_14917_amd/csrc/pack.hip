@@ -93,7 +93,7 @@ extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int
                                  int beta, uint32_t* packed, int64_t packed_rows, uint32_t* gbits, int32_t* row_off,
                                  int* m_star) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;
-  SLIM_REQUIRE(ctx, codes && bits && packed && gbits && row_off && m_star, "slim_pack: null pointer");
+  SLIM_REQUIRE(ctx, codes && bits && packed && gbits && row_off, "slim_pack: null pointer");
   SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_pack: need n, m > 0 and beta | m");
   SLIM_REQUIRE(ctx, beta % 32 == 0, "slim_pack: beta must be a multiple of 32 (got %d)", beta);
   SLIM_REQUIRE(ctx, ldc >= m && ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0,
@@ -105,6 +105,7 @@ extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int
   const size_t smem = (size_t)PACK_ROWS * (beta + 4);
   SLIM_LAUNCH(ctx, "pack_codes", pack_codes, dim3(slim_cdiv(n, PACK_ROWS), k), dim3(PACK_ROWS), smem, codes, n, ldc,
               bits, beta, row_off, packed, packed_rows);
+  if (!m_star) return SLIM_OK;                     // nothing for the host: the call does not wait (and cannot report)
   int* host = reinterpret_cast<int*>(ctx->hpin);
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(&host[0], row_off + k, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(&host[1], flags, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));

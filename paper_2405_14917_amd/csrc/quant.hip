@@ -1018,15 +1018,14 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   const int k = m / beta;
   SLIM_REQUIRE(ctx, k <= SLIM_HPIN_BYTES, "slim_gptq_quantize: too many groups");
 
-  // widths to the host: they select kernel arguments, and they must be valid before anything runs
+  // widths to the host: they select kernel arguments, and they must be valid before any output is touched.  The
+  // copy is on its way while the working copy of W is made (workspace only), so the stream does not idle for it.
   uint8_t* bits_h = reinterpret_cast<uint8_t*>(ctx->hpin);
+  st = slim_ensure_side(ctx);
+  if (st != SLIM_OK) return st;
+  hipEvent_t ev_bits = ctx->ev[12];
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(bits_h, bits, k, hipMemcpyDeviceToHost, ctx->stream));
-  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-  std::vector<int> gb(k);
-  for (int g = 0; g < k; ++g) {
-    gb[g] = bits_h[g];
-    SLIM_REQUIRE(ctx, gb[g] >= 1 && gb[g] <= 4, "slim_gptq_quantize: bits[%d] = %d is outside 1..4", g, gb[g]);
-  }
+  SLIM_HIP_TRY(ctx, hipEventRecord(ev_bits, ctx->stream));
 
   const int nstat = slim_cdiv(n, STAT_ROWS);
   // Trailing updates (Alg. 1 line 12) in two levels: inside a window of WINC columns every swept block updates
@@ -1049,6 +1048,12 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   if (st != SLIM_OK) return st;
   st = slim_zero_f64(ctx, "gptq_zero", row_e2, n);
   if (st != SLIM_OK) return st;
+  SLIM_HIP_TRY(ctx, hipEventSynchronize(ev_bits));
+  std::vector<int> gb(k);
+  for (int g = 0; g < k; ++g) {
+    gb[g] = bits_h[g];
+    SLIM_REQUIRE(ctx, gb[g] >= 1 && gb[g] <= 4, "slim_gptq_quantize: bits[%d] = %d is outside 1..4", g, gb[g]);
+  }
 
   // Rows per workgroup of the sweep: as few as fill the chip, so that small layers spread over every compute
   // unit and large ones share each workgroup's copy of the U block among more rows.

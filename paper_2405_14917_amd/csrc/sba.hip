@@ -650,7 +650,7 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   slim_params prm;
   slim_default_params(&prm);
   if (params) prm = *params;
-  SLIM_REQUIRE(ctx, group_sal && bits && p_star, "slim_sba_allocate: null pointer");
+  SLIM_REQUIRE(ctx, group_sal && bits, "slim_sba_allocate: null pointer");
   slim_status st = sba_check(ctx, "slim_sba_allocate", W, w_dtype, n, m, ldw, beta, N, objective, X_s, x_dtype, t_s, ldxs, prm);
   if (st != SLIM_OK) return st;
   // a preceding slim_sba_prepare with the same arguments has left the rank-independent part in the workspace
@@ -748,12 +748,13 @@ extern "C" slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtyp
   SLIM_LAUNCH(ctx, "sba_finalize", sba_finalize, dim3(1), dim3(256), 0, block_sums, kl_blocks, obj, pmax, order, k, N,
               bits, pstar_dev);
 
+  if (!p_star && !obj_curve) return SLIM_OK;       // nothing for the host: the call does not wait
   double* host_obj = reinterpret_cast<double*>(ctx->hpin);
   int* host_p = reinterpret_cast<int*>(ctx->hpin + sizeof(double) * (size_t)(pmax + 1));
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(host_obj, obj, sizeof(double) * (pmax + 1), hipMemcpyDeviceToHost, ctx->stream));
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(host_p, pstar_dev, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
   SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-  *p_star = *host_p;
+  if (p_star) *p_star = *host_p;
   if (obj_curve) memcpy(obj_curve, host_obj, sizeof(double) * (pmax + 1));
   return SLIM_OK;
 }

@@ -55,6 +55,7 @@ struct slim_ctx {
   hipStream_t side = nullptr, side2 = nullptr;
   bool on_side = false;           // `stream` temporarily names a side stream (profiling entries say so)
   hipEvent_t ev[SLIM_NUM_EVENTS] = {};
+  bool staging_copy_pending = false;   // a host-to-device copy out of hpin that no one has waited for yet (ev[13])
   slim_sba_prepared sba_prep;
   // profiling
   bool prof = false;

@@ -47,23 +47,26 @@ class LayerPass:
         """Salience, bit allocation (on the second context when its first half is already there), sweep, packing."""
         s, s2 = self.slim, self.slim_sba
         _, grp, _ = s.salience(W, self.d, self.beta)
+        # no call here asks for a host output, so the host never waits for the stream inside a pass (the sweep reads
+        # the widths back itself, behind work it has already enqueued); p_star and m_star stay on the device
         if prepared:
             self.side.wait_stream(self.main)
             with torch.cuda.stream(self.side):
-                bits, p_star, _ = s2.sba_allocate(W, grp, self.beta, self.N, Xs)
+                bits, _, _ = s2.sba_allocate(W, grp, self.beta, self.N, Xs, host_outputs=False)
             grp.record_stream(self.side)
             bits.record_stream(self.main)
             self.main.wait_stream(self.side)
         else:
-            bits, p_star, _ = s.sba_allocate(W, grp, self.beta, self.N, Xs)
+            bits, _, _ = s.sba_allocate(W, grp, self.beta, self.N, Xs, host_outputs=False)
         out = s.gptq_quantize(W, self.U, bits, self.beta)
-        packed, gbits, row_off, m_star = s.pack(out["codes"], bits, self.beta,
-                                                packed_rows=self.m * (self.N + 1) // 32)
-        return {"bits": bits, "p_star": p_star, "codes": out["codes"], "scale": out["scale"], "zero": out["zero"],
-                "packed": packed, "gbits": gbits, "row_off": row_off, "m_star": m_star}
+        packed, gbits, row_off, _ = s.pack(out["codes"], bits, self.beta, packed_rows=self.m * (self.N + 1) // 32,
+                                           host_outputs=False)
+        return {"bits": bits, "p_star": (bits == self.N - 1).sum(), "codes": out["codes"], "scale": out["scale"],
+                "zero": out["zero"], "packed": packed, "gbits": gbits, "row_off": row_off, "m_star": row_off[-1]}
 
     def run(self, W, X):
-        """One layer: W (n x m), X (m x t, fp16 / bf16, tokens contiguous)."""
+        """One layer: W (n x m), X (m x t, fp16 / bf16, tokens contiguous).  Returns device tensors only (p_star and
+        m_star as 0-dim tensors; packed with the rows of its capacity, zero from row m_star on)."""
         Xs = self._hessian_and_first_prepare(W, X)
         return self._allocate_quantize_pack(W, Xs, True)
 
