@@ -489,6 +489,11 @@ def test_layers_that_share_their_input_share_the_hessian(slim):
         out = slim.gptq_quantize(dev(Wb), U, bits, beta)
         assert p_star == shared[1]["p_star"] and torch.equal(bits, shared[1]["bits"])
         assert torch.equal(out["codes"], shared[1]["codes"]) and torch.equal(out["scale"], shared[1]["scale"])
+        # the calls that were told to give no host output (and so did not wait) wrote what the waiting ones write
+        packed, gbits, row_off, m_star = slim.pack(out["codes"], bits, beta)
+        assert m_star == int(shared[1]["m_star"]) and torch.equal(row_off, shared[1]["row_off"])
+        assert torch.equal(packed, shared[1]["packed"][:m_star]) and torch.equal(gbits, shared[1]["gbits"])
+        assert not shared[1]["packed"][m_star:].any()
     finally:
         drv.close()
 
