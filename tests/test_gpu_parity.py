@@ -270,6 +270,32 @@ def test_sqc_calibrate(slim, beta, bits):
             assert np.allclose(s[ok], so[ok], rtol=1e-14, atol=0)
 
 
+@pytest.mark.parametrize("n,beta,ncand,bits", [(1, 128, 1, 2), (17, 32, 3, 3), (300, 128, 1024, 2), (1500, 64, 100, 1),
+                                               (6000, 128, 20, 2), (257, 512, 333, 4)])
+def test_sqc_calibrate_grid_sizes_and_row_counts(slim, n, beta, ncand, bits):
+    """Grids from one candidate to the maximum (a row then takes from 4 to 820 threads of the search kernel), row
+    counts below one workgroup and beyond one round of workgroups (persistent workgroups, rows fetched ahead), a
+    row of outliers (every weight salient under the block-wide rule) and constant rows."""
+    from paper_2405_14917_amd import binding
+    rng = np.random.default_rng(n + beta + ncand)
+    blk = rng.standard_t(4, (n, beta)) * 0.02
+    if n > 8:
+        blk[2] = rng.standard_normal(beta) * 3.0          # every weight of this row lies outside 3 sigma of the block
+        blk[5] = 0.0
+        blk[7] = -0.25
+    tau = np.linspace(0.9, 1.1, ncand, endpoint=False) if ncand > 1 else np.array([1.0])   # not symmetric about 1
+    for mode, scope in ((orc.WEIGHT_MASK_MEAN, orc.SCOPE_BLOCK), (orc.WEIGHT_MASK_MEAN, orc.SCOPE_ROW),
+                        (orc.WEIGHT_UNIFORM, orc.SCOPE_BLOCK)):
+        so, zo, co, mg = orc.sqc_calibrate(blk, bits, tau, mode, scope)
+        s, z, c = slim.sqc_calibrate(dev(blk), bits, binding.make_params(mode, scope), tau=dev(tau))
+        s, z, c = host(s), host(z), host(c)
+        ok = mg > MARGIN
+        assert ok.sum() >= 0.9 * n - 3 or ncand > 300     # constant rows tie everywhere; a fine grid has near-ties
+        assert np.array_equal(c[ok], co[ok])
+        assert np.array_equal(z, zo)
+        assert np.allclose(s[ok], so[ok], rtol=1e-14, atol=0)
+
+
 def test_sqc_explicit_weights_element_mode_and_affine_one_bit(slim):
     from paper_2405_14917_amd import binding
     rng = np.random.default_rng(99)
