@@ -27,16 +27,16 @@ using slimdev::read_lane_f64;
 constexpr int NB = 64;          // diagonal block
 
 // mean of the diagonal of H = s * G, then lambda; single workgroup, fixed order
-__global__ __launch_bounds__(256) void damp_lambda(const float* __restrict__ G, int64_t ldg, int m, double s,
-                                                   double percdamp, double* __restrict__ lam_out,
-                                                   int* __restrict__ flag) {
-  __shared__ double red[256];
+__global__ __launch_bounds__(1024) void damp_lambda(const float* __restrict__ G, int64_t ldg, int m, double s,
+                                                    double percdamp, double* __restrict__ lam_out,
+                                                    int* __restrict__ flag) {
+  __shared__ double red[1024];
   if (threadIdx.x == 0) *flag = 0;
   double acc = 0.0;
-  for (int i = threadIdx.x; i < m; i += 256) acc += s * (double)G[(int64_t)i * ldg + i];
+  for (int i = threadIdx.x; i < m; i += 1024) acc += s * (double)G[(int64_t)i * ldg + i];
   red[threadIdx.x] = acc;
   __syncthreads();
-  for (int st = 128; st > 0; st >>= 1) {
+  for (int st = 512; st > 0; st >>= 1) {
     if (threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
     __syncthreads();
   }
@@ -395,7 +395,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   int* flag = ctx->dflags + 1;
 
   const double s = 2.0 / (double)n_tokens;
-  SLIM_LAUNCH(ctx, "inv_lambda", damp_lambda, dim3(1), dim3(256), 0, G, ldg, m, s, percdamp, lam, flag);
+  SLIM_LAUNCH(ctx, "inv_lambda", damp_lambda, dim3(1), dim3(1024), 0, G, ldg, m, s, percdamp, lam, flag);
   // one pass writes A (widened, damped) and clears U; 4 / 2 / 1 columns per thread as alignment allows
   const bool g16 = (reinterpret_cast<uintptr_t>(G) & 15u) == 0, g8 = (reinterpret_cast<uintptr_t>(G) & 7u) == 0;
   if (m % 4 == 0 && ldg % 4 == 0 && ldu % 4 == 0 && g16)
