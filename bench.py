@@ -28,8 +28,8 @@ PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e
 # HBM bytes per launch measured with two `rocprofv3 --pmc` runs of this command (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for the 64 MiB copy below (FETCH_SIZE reads 32 MiB for it: factor 2.0;
 # WRITE_SIZE reads 64 MiB: factor 1.0); see profiles/dgemm_gram_C2_hbm_traffic.md.  Keyed by (config, kernel).
-TRAFFIC_BYTES = {("C2", "gram_kernel_full<false>"): 2.0 * 2.750e6 * 1024 + 1.0 * 3.277e5 * 1024,
-                 ("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.379e5 * 1024 + 1.0 * 9.011e4 * 1024}
+TRAFFIC_BYTES = {("C2", "gram_kernel_full<false>"): 2.0 * 2.646e6 * 1024 + 1.0 * 3.277e5 * 1024,
+                 ("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.380e5 * 1024 + 1.0 * 9.011e4 * 1024}
 T_SBA = 2048
 
 
@@ -72,7 +72,8 @@ class Pass(pipeline.LayerPass):
             self.slim.dequant_matmul(packed, gbits, row_off, scale, zero, self.cfg.beta, x, Y=y)
         e1.record()
         torch.cuda.synchronize()
-        nbytes = packed.numel() * 4 + gbits.numel() * 4 + row_off.numel() * 4 + scale.numel() * 8 + zero.numel() * 8
+        m_star = int(row_off[-1])                     # packed holds the rows of its capacity; the layer fills m_star
+        nbytes = m_star * packed.shape[1] * 4 + gbits.numel() * 4 + row_off.numel() * 4 + scale.numel() * 8 + zero.numel() * 8
         return e0.elapsed_time(e1) * 1e3 / reps, nbytes
 
 def algorithmic_work(name, cfg, launches_per_step):
@@ -180,6 +181,7 @@ def main():
     ap.add_argument("--config", default="C2", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=2)
+    ap.add_argument("--no-shared-input", action="store_true", help="skip the three-layer figure beside the metric")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the pass is a single-GPU job); run with --gpus 1")
@@ -286,14 +288,15 @@ def main():
     # beside the metric too: three layers that read the same input (q/k/v of a block) with one Hessian and one
     # inverse between them; the three layers are this layer's weights three times, the result per layer is the
     # step's own
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    shared_reps = 2
-    for _ in range(shared_reps):
-        job.run_shared_input([W, W, W], X)
-    torch.cuda.synchronize()
-    line["shared_input"] = {"layers": 3, "ms_per_layer": (time.perf_counter() - t0) * 1e3 / (3 * shared_reps),
-                            "note": "one Gram matrix and one inverse for three layers of the step's shape"}
+    if not args.no_shared_input:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        shared_reps = 2
+        for _ in range(shared_reps):
+            job.run_shared_input([W, W, W], X)
+        torch.cuda.synchronize()
+        line["shared_input"] = {"layers": 3, "ms_per_layer": (time.perf_counter() - t0) * 1e3 / (3 * shared_reps),
+                                "note": "one Gram matrix and one inverse for three layers of the step's shape"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:

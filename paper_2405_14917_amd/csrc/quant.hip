@@ -24,7 +24,7 @@ namespace {
 
 using namespace slimdev;
 
-constexpr int SQC_CPT = 4;        // candidates per thread in sqc_search
+constexpr int SQC_CPT = 4;        // candidates per thread in sqc_search_weighted
 constexpr int SQC_THREADS = 256;
 constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
 
