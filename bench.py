@@ -138,10 +138,10 @@ def cpu_baseline(cfg):
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count() or 1
-    n_s = min(cfg.n, 512)
-    t_gram = min(cfg.t, 2 * synth.CHUNK_TOKENS)
+    n_s = min(cfg.n, 2048)                        # about 10 s of host work on C2
+    t_gram = min(cfg.t, 4 * synth.CHUNK_TOKENS)
     W = synth.make_weights(cfg)[:n_s].astype(np.float64)
-    X0 = np.concatenate([synth.activation_chunk(cfg, c) for c in range(min(2, synth.n_chunks(cfg)))], axis=1)
+    X0 = np.concatenate([synth.activation_chunk(cfg, c) for c in range(min(4, synth.n_chunks(cfg)))], axis=1)
     tm = {}
     t0 = time.perf_counter()
     G = np.zeros((cfg.m, cfg.m))
