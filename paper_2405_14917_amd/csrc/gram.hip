@@ -356,10 +356,11 @@ __device__ __forceinline__ void load_frags_full(Frags& f, const uint16_t* ap, co
 }
 
 // One K step of the fast path in a fixed issue order: its 16 MFMAs, after every second one an operand read of
-// the next K step (into the other fragment set), after every third MFMA of the first three K steps a direct
-// load of the next slab.  The loads are spread out because the four wavefronts of a CU together must not ask
-// the vector memory path for more than it moves (64 bytes per cycle): bunched up, they stall the wavefront at
-// issue and the matrix pipe behind it; the last K step is left free so that the last load has time to land.
+// the next K step (into the other fragment set), after every other MFMA of the first two K steps a direct
+// load of the next slab.  That is the rate the vector memory path takes from four wavefronts (64 bytes per
+// cycle for the CU; one load per MFMA stalls the wavefront at issue and the matrix pipe behind it, measured),
+// and it leaves the second half of the slab for the last load to land (one load per three MFMAs, with a
+// quarter of the slab left, was 3 % slower).
 template <bool BF16, int S>
 __device__ __forceinline__ void kstep_full(float16v (&acc)[4][4], const Frags& cf, Frags& nf, const uint16_t* nap,
                                            const uint16_t* nbp, unsigned ldsn, const unsigned (&off)[CHUNKS],
@@ -378,8 +379,8 @@ __device__ __forceinline__ void kstep_full(float16v (&acc)[4][4], const Frags& c
       __builtin_amdgcn_sched_barrier(0);
     }
     const int gm = 16 * S + m;             // index of this MFMA in the iteration
-    if (gm % 3 == 1 && gm / 3 < 2 * CHUNKS) {
-      const int d = gm / 3, c = d >> 1;
+    if (gm % 2 == 1 && gm / 2 < 2 * CHUNKS) {
+      const int d = gm / 2, c = d >> 1;
       if (d & 1)
         direct_load(ldsn + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
       else
@@ -440,6 +441,28 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   __syncthreads();
   int cur = 0;
   const int64_t nslab = (kend - kbeg) / BK;
+  if (bi == bj && wm == 1 && wn == 0) {
+    // The lower left quarter of a tile on the diagonal is the transpose of its upper right one and is never read
+    // back: this wavefront only fetches its share of the slabs and keeps the barriers.  Nothing gets faster for
+    // its workgroup, but a sixteenth of the chip's matrix-core work (and power, which is what limits the clock
+    // here) is not spent.
+    for (int64_t it = 0; it < nslab; ++it) {
+      const int64_t adv = (it + 1 < nslab) ? BK * 2 : 0;
+      baseA += adv;
+      baseB += adv;
+      const unsigned ldsn = lds0 + (unsigned)(cur ^ 1) * STAGE_BYTES;
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        direct_load(ldsn + c * CHUNK_BYTES, off[c], baseA);
+        direct_load(ldsn + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
+        __builtin_amdgcn_s_sleep(1);               // spread over the first half of the slab like the other wavefronts' loads
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      cur ^= 1;
+    }
+    return;
+  }
   for (int64_t it = 0; it < nslab; ++it) {
     // the fetch behind the last slab re-reads the last slab (stays in bounds); its data is never multiplied
     const int64_t adv = (it + 1 < nslab) ? BK * 2 : 0;
