@@ -159,3 +159,30 @@ def test_sweep_sampled_rows_and_identities(slim, layer):
     assert m_star == mo == CFG.m * CFG.N // 32
     assert np.array_equal(host(row_off), ro) and np.array_equal(host(gbits).view(np.uint32), go)
     assert np.array_equal(host(packed).view(np.uint32), po)
+
+
+def test_pass_as_timed_equals_the_entry_points_one_by_one(slim, layer):
+    """The driver bench.py times (two contexts on two streams, the first half of the bit allocation beside the
+    inverse in the persistent half-chip form, no host outputs, the inverse returning with its triangular inverse in
+    flight) gives bit for bit what the entry points give when called one after the other on one context."""
+    from paper_2405_14917_amd import pipeline
+    Wd, Xd = layer["Wd"], layer["Xd"]
+    drv = pipeline.LayerPass(slim, CFG.m, CFG.beta, CFG.N, CFG.percdamp, t_sba=2048)
+    try:
+        r1 = drv.run(Wd, Xd)
+        r2 = drv.run(Wd, Xd)                                   # and it is reproducible
+        G = torch.zeros((CFG.m, CFG.m), dtype=torch.float32, device="cuda")
+        nt = slim.hessian_accumulate(Xd, G, 0)
+        U, d = slim.hessian_inverse(G, nt, CFG.percdamp)
+        _, grp, _ = slim.salience(Wd, d, CFG.beta)
+        bits, p_star, _ = slim.sba_allocate(Wd, grp, CFG.beta, CFG.N, Xd[:, :2048])
+        out = slim.gptq_quantize(Wd, U, bits, CFG.beta)
+        packed, gbits, row_off, m_star = slim.pack(out["codes"], bits, CFG.beta)
+        assert torch.equal(U, drv.U) and torch.equal(d, drv.d)
+        for r in (r1, r2):
+            assert int(r["p_star"]) == p_star and int(r["m_star"]) == m_star
+            assert torch.equal(r["bits"], bits) and torch.equal(r["codes"], out["codes"])
+            assert torch.equal(r["scale"], out["scale"]) and torch.equal(r["zero"], out["zero"])
+            assert torch.equal(r["packed"][:m_star], packed) and torch.equal(r["row_off"], row_off)
+    finally:
+        drv.close()
