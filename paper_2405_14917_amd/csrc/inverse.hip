@@ -43,7 +43,10 @@ __global__ __launch_bounds__(1024) void damp_lambda(const float* __restrict__ G,
   if (threadIdx.x == 0) *lam_out = percdamp * (red[0] / (double)m);
 }
 
-// A = s * G + lambda I on and above the diagonal, zero below; U = 0.  V consecutive columns per thread.
+// A = s * G + lambda I on and above the diagonal; U = 0 below it.  V consecutive columns per thread.
+// What lies below the diagonal of A is never read as a value that matters (the updates that sweep over it only
+// add to it), and every element of U on or above the diagonal is written later (the inverted diagonal blocks,
+// then the merged off-diagonal ones), so pieces entirely on one side are written to one matrix only.
 template <int V>
 __global__ __launch_bounds__(256) void widen_damp(const float* __restrict__ G, int64_t ldg, int m, double s,
                                                   const double* __restrict__ lam, double* __restrict__ A,
@@ -75,14 +78,16 @@ __global__ __launch_bounds__(256) void widen_damp(const float* __restrict__ G, i
   }
   double* da = A + (int64_t)r * lda + c0;
   double* du = U + (int64_t)r * ldu + c0;
+  const bool upper = c0 + V - 1 >= r;          // has an element on or above the diagonal
+  const bool lower = c0 < r;                   // has an element below it
   if (V == 1) {
-    da[0] = a[0];
-    du[0] = 0.0;
+    if (upper) da[0] = a[0];
+    if (lower) du[0] = 0.0;
   } else {
 #pragma unroll
     for (int v = 0; v < V; v += 2) {
-      *reinterpret_cast<double2*>(da + v) = make_double2(a[v], a[v + 1]);
-      *reinterpret_cast<double2*>(du + v) = make_double2(0.0, 0.0);
+      if (upper) *reinterpret_cast<double2*>(da + v) = make_double2(a[v], a[v + 1]);
+      if (lower) *reinterpret_cast<double2*>(du + v) = make_double2(0.0, 0.0);
     }
   }
 }

@@ -244,6 +244,24 @@ def test_sba_ties_keep_lower_group_first(slim):
         assert p_star == p_o and np.array_equal(host(bits), bits_o)
 
 
+def test_inverse_writes_every_element_of_its_outputs(slim):
+    """U and hinv_diag come back complete whatever the buffers held before (NaN here), for sizes with one block,
+    a ragged last block, and block counts that are not powers of two."""
+    for m in (40, 64, 200, 320, 704):
+        rng = np.random.default_rng(m)
+        X = rng.standard_normal((m, 3 * m))
+        G = np.zeros((m, m))
+        orc.gram_accumulate(G, X)
+        Uo, do, _ = orc.hessian_inverse(G, 3 * m, 0.01)
+        U = torch.full((m, m), float("nan"), dtype=torch.float64, device="cuda")
+        d = torch.full((m,), float("nan"), dtype=torch.float64, device="cuda")
+        slim.hessian_inverse(dev(G.astype(np.float32)), 3 * m, 0.01, U=U, hinv_diag=d)
+        U, d = host(U), host(d)
+        assert np.isfinite(U).all() and np.isfinite(d).all()
+        assert np.array_equal(np.tril(U, -1), np.zeros((m, m)))
+        assert np.allclose(U, Uo, rtol=0, atol=2e-5 * np.abs(Uo).max()) and np.allclose(d, do, rtol=1e-4)
+
+
 # ------------------------------------------------------------------------------------------ a5 + a6
 @pytest.mark.parametrize("beta", [32, 64, 128, 256, 512])
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
