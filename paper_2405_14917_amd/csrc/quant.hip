@@ -312,30 +312,6 @@ typedef double double2v __attribute__((ext_vector_type(2)));
 constexpr int SQF_CPT = 5;     // candidates per lane
 constexpr int SQF_PAD = 8;     // doubles of padding per LDS row
 
-template <int CTRL>
-__device__ __forceinline__ int dpp_b32(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
-}
-template <int CTRL>
-__device__ __forceinline__ double dpp_f64(double v) {
-  return __hiloint2double(dpp_b32<CTRL>(__double2hiint(v)), dpp_b32<CTRL>(__double2loint(v)));
-}
-constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
-
-struct OpSum { __device__ static double f(double a, double b) { return a + b; } };
-struct OpMin { __device__ static double f(double a, double b) { return fmin(a, b); } };
-struct OpMax { __device__ static double f(double a, double b) { return fmax(a, b); } };
-// every lane receives the reduction over the wavefront; the same association in every lane
-template <typename OP>
-__device__ __forceinline__ double wave_allreduce(double v) {
-  v = OP::f(v, dpp_f64<DPP_XOR1>(v));
-  v = OP::f(v, dpp_f64<DPP_XOR2>(v));
-  v = OP::f(v, dpp_f64<DPP_HALF_MIRROR>(v));
-  v = OP::f(v, dpp_f64<DPP_MIRROR>(v));
-  const double r0 = read_lane_f64(v, 0), r1 = read_lane_f64(v, 16), r2 = read_lane_f64(v, 32), r3 = read_lane_f64(v, 48);
-  return OP::f(OP::f(r0, r1), OP::f(r2, r3));
-}
-
 // reciprocal to full precision without the division sequence (two Newton steps on the hardware estimate)
 __device__ __forceinline__ double fast_rcp(double d) {
   double r = __builtin_amdgcn_rcp(d);

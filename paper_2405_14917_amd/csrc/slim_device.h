@@ -61,32 +61,46 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
   return __hiloint2double(hi, lo);
 }
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v += shfl_xor_f64(v, s);
-  return v;
-}
-__device__ __forceinline__ double wave_min(double v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v = fmin(v, shfl_xor_f64(v, s));
-  return v;
-}
-__device__ __forceinline__ double wave_max(double v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v = fmax(v, shfl_xor_f64(v, s));
-  return v;
-}
-__device__ __forceinline__ int wave_sum_int(int v) {
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, WAVE);
-  return v;
-}
-
 // value of `v` held by lane `src` (src must be wavefront-uniform)
 __device__ __forceinline__ double read_lane_f64(double v, int src) {
   const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
   const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
   return __hiloint2double(hi, lo);
+}
+
+// Data-parallel-primitive moves inside a 16-lane row: vector instructions, where a shuffle goes through the LDS
+// hardware (a kernel that reduces once per 1 KiB it reads is bound by that instead of by memory).
+template <int CTRL>
+__device__ __forceinline__ int dpp_b32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  return __hiloint2double(dpp_b32<CTRL>(__double2hiint(v)), dpp_b32<CTRL>(__double2loint(v)));
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+struct OpSum { __device__ static double f(double a, double b) { return a + b; } };
+struct OpMin { __device__ static double f(double a, double b) { return fmin(a, b); } };
+struct OpMax { __device__ static double f(double a, double b) { return fmax(a, b); } };
+// lanes 1, 2 apart, then the mirror images inside 8 and 16 lanes, then the four rows by lane reads: the same
+// association in every lane
+template <typename OP>
+__device__ __forceinline__ double wave_allreduce(double v) {
+  v = OP::f(v, dpp_f64<DPP_XOR1>(v));
+  v = OP::f(v, dpp_f64<DPP_XOR2>(v));
+  v = OP::f(v, dpp_f64<DPP_HALF_MIRROR>(v));
+  v = OP::f(v, dpp_f64<DPP_MIRROR>(v));
+  const double r0 = read_lane_f64(v, 0), r1 = read_lane_f64(v, 16), r2 = read_lane_f64(v, 32), r3 = read_lane_f64(v, 48);
+  return OP::f(OP::f(r0, r1), OP::f(r2, r3));
+}
+__device__ __forceinline__ double wave_sum(double v) { return wave_allreduce<OpSum>(v); }
+__device__ __forceinline__ double wave_min(double v) { return wave_allreduce<OpMin>(v); }
+__device__ __forceinline__ double wave_max(double v) { return wave_allreduce<OpMax>(v); }
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, WAVE);
+  return v;
 }
 
 }  // namespace slimdev
