@@ -67,3 +67,24 @@ def test_null_context_is_rejected_without_a_gpu(binding):
     assert lib.slim_last_error(None) == b"null context"
     nt = ctypes.c_int64(0)
     assert lib.slim_hessian_accumulate(None, None, 0, 8, 8, 8, None, 8, ctypes.byref(nt)) == binding.ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(binding, monkeypatch, tmp_path):
+    """There is no CPU fallback: without the built library the binding raises instead of computing anything."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libslim.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()
+    with pytest.raises(FileNotFoundError):
+        binding.default_tau()
+
+
+def test_the_product_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing in the package refers to it."""
+    pkg = os.path.join(ROOT, "paper_2405_14917_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
+                assert "slim_oracle" not in text, f
