@@ -523,6 +523,10 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       c->on_side = false;
     }
   };
+  struct AttachGuard {  // no event stays offered to a later call's launch when this one returns early
+    slim_ctx* c;
+    ~AttachGuard() { c->attach_event = nullptr; }
+  } attach_guard{ctx};
   bool far_issued = false;
   int last_far_slot = 0;
   for (int J = nblk - 1; J >= 0; --J) {
@@ -540,9 +544,13 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
     ca.ldv = ldu;
     ca.flag = flag;
     ca.col_base = j0;
+    // The event that the GEMMs of this block wait for rides on the kernel's own completion signal (a separate record
+    // is one more packet for the command processor between two diagonal steps, whose chain is what the
+    // factorisation takes).
+    if (J > 0) ctx->attach_event = ev_step[J & 3];
     SLIM_LAUNCH(ctx, "inv_chol_diag", chol_step, dim3(1), dim3(1024), CHOL_LDS, ca);
     if (J == 0) break;
-    SLIM_HIP_TRY(ctx, hipEventRecord(ev_step[J & 3], s0));
+    SLIM_HIP_TRY(ctx, slim_attach_flush(ctx));
 
     // ---- s1: GEMMs of block J
     const int G = J / GRP;                          // group of block J
@@ -568,9 +576,13 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       d.flags = 0;
       d.alpha = 1.0;
       d.beta = 0.0;
+      // the stage's event goes with its last launch
+      const bool has_window = jn > 0;
+      const bool has_group = J == G * GRP + 1 && g0 > 0;
+      if (!has_window && !has_group) ctx->attach_event = ev_gemm[J & 3];
       st = slim_dgemm(ctx, "inv_panel_dgemm", 1, d);
       if (st != SLIM_OK) return st;
-      if (jn > 0) {
+      if (has_window) {
         // the window of the first block of a group lies in the group to the left, which far() of the group
         // before this one also writes
         if (wstart < g0 && far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_far[last_far_slot], 0));
@@ -585,10 +597,11 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
         d.K = nbk;
         d.alpha = -1.0;
         d.beta = 1.0;
+        if (!has_group) ctx->attach_event = ev_gemm[J & 3];
         st = slim_dgemm(ctx, "inv_window_dgemm", 1, d);
         if (st != SLIM_OK) return st;
       }
-      if (J == G * GRP + 1 && g0 > 0) {
+      if (has_group) {
         // every panel of the group except the first block's is complete: bring the group to the left up to date
         const int gp = g0 - GRP * NB;               // first column of the group to the left
         if (far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_far[last_far_slot], 0));
@@ -603,10 +616,11 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
         d.K = g1 - j0;
         d.alpha = -1.0;
         d.beta = 1.0;
+        ctx->attach_event = ev_gemm[J & 3];
         st = slim_dgemm(ctx, "inv_group_next_dgemm", 1, d);
         if (st != SLIM_OK) return st;
       }
-      SLIM_HIP_TRY(ctx, hipEventRecord(ev_gemm[J & 3], s1));
+      SLIM_HIP_TRY(ctx, slim_attach_flush(ctx));
     }
     // ---- s2: everything two or more groups to the left, once all panels of the group exist
     if (J == G * GRP && g0 - GRP * NB > 0) {
@@ -630,10 +644,11 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       d.flags = SLIM_GEMM_UPPER_ONLY | (gp <= 4096 ? SLIM_GEMM_ONE_PER_CU : 0);
       d.alpha = -1.0;
       d.beta = 1.0;
+      last_far_slot ^= 1;
+      ctx->attach_event = ev_far[last_far_slot];
       st = slim_dgemm(ctx, "inv_syrk_dgemm", 1, d);
       if (st != SLIM_OK) return st;
-      last_far_slot ^= 1;
-      SLIM_HIP_TRY(ctx, hipEventRecord(ev_far[last_far_slot], s2));
+      SLIM_HIP_TRY(ctx, slim_attach_flush(ctx));
       far_issued = true;
     }
   }

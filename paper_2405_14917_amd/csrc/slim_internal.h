@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstdarg>
@@ -55,6 +56,10 @@ struct slim_ctx {
   hipStream_t side = nullptr, side2 = nullptr;
   bool on_side = false;           // `stream` temporarily names a side stream (profiling entries say so)
   hipEvent_t ev[SLIM_NUM_EVENTS] = {};
+  // When set (and profiling is off), the next SLIM_LAUNCH signals this event through the kernel's own completion
+  // signal instead of a separate record behind it (one packet less between dependent small kernels); the launch
+  // clears it.  slim_attach_flush() records it the ordinary way if no launch took it.
+  hipEvent_t attach_event = nullptr;
   bool staging_copy_pending = false;   // a host-to-device copy out of hpin that no one has waited for yet (ev[13])
   slim_sba_prepared sba_prep;
   // profiling
@@ -99,7 +104,13 @@ void slim_prof_end(slim_ctx* ctx);
 #define SLIM_LAUNCH(ctx, name, kernel, grid, block, shmem, ...)                              \
   do {                                                                                       \
     if ((ctx)->prof) slim_prof_begin((ctx), (name));                                         \
-    hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (ctx)->stream, __VA_ARGS__);        \
+    if ((ctx)->attach_event && !(ctx)->prof) {                                               \
+      hipExtLaunchKernelGGL(kernel, (grid), (block), (shmem), (ctx)->stream, nullptr,        \
+                            (ctx)->attach_event, 0, __VA_ARGS__);                            \
+      (ctx)->attach_event = nullptr;                                                         \
+    } else {                                                                                 \
+      hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (ctx)->stream, __VA_ARGS__);      \
+    }                                                                                        \
     if ((ctx)->prof) slim_prof_end((ctx));                                                   \
     hipError_t e__ = hipGetLastError();                                                      \
     if (e__ != hipSuccess)                                                                   \
@@ -111,6 +122,14 @@ void slim_prof_end(slim_ctx* ctx);
   do {                                                                                       \
     if (!(cond)) return slim_fail((ctx), SLIM_ERR_INVALID_ARG, __VA_ARGS__);                 \
   } while (0)
+
+// Records an event that was offered to a launch which did not happen (or happened under profiling).
+inline hipError_t slim_attach_flush(slim_ctx* ctx) {
+  if (!ctx->attach_event) return hipSuccess;
+  hipEvent_t e = ctx->attach_event;
+  ctx->attach_event = nullptr;
+  return hipEventRecord(e, ctx->stream);
+}
 
 inline bool slim_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int slim_cdiv(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
