@@ -473,7 +473,15 @@ def reconstruction_error(W: np.ndarray, What: np.ndarray, G: np.ndarray) -> floa
 # ----------------------------------------------------------------------------------------
 # Storage (App. B.2)
 # ----------------------------------------------------------------------------------------
-def pack(codes: np.ndarray, bits: np.ndarray, beta: int):
+def bit_base_for(N: int) -> int:
+    """The width that the 2-bit group value 0 stands for (App. B.2 gives the value 2 bits).  A layer of target
+    width N holds the widths N - 1, N, N + 1 only (the constraint of Eq. 5), so three of the four values are
+    ever used: value = width - 1 covers the targets 2 and 3 (widths 1..4); above them (the 4-bit setting of
+    App. G) the values count from N - 2, which maps N - 1, N, N + 1 to 1, 2, 3 for every target."""
+    return max(1, int(N) - 2)
+
+
+def pack(codes: np.ndarray, bits: np.ndarray, beta: int, bit_base: int = 1):
     """Returns (packed uint32 (m_star, n), gbits uint32 (ceil(k/16),), row_off int32 (k+1,), m_star).
 
     W^T is split into groups along its rows; for each (group g, output row i) the beta codes,
@@ -481,8 +489,9 @@ def pack(codes: np.ndarray, bits: np.ndarray, beta: int):
     [r*b, (r+1)*b)) cut into 32-bit words that are stacked along the row axis of packed,
     starting at row_off[g]; groups follow one another without padding and no word mixes two
     widths (beta * b is a multiple of 32).  row_off is the running sum of beta*b_g/32.
-    gbits stores b_g - 1 as a 2-bit value, 16 groups per word, least significant first."""
+    gbits stores b_g - bit_base as a 2-bit value, 16 groups per word, least significant first."""
     codes = np.asarray(codes)
+    assert all(0 <= int(b) - bit_base <= 3 for b in bits)
     n, m = codes.shape
     k = m // beta
     words = [(beta * int(b)) // 32 for b in bits]
@@ -501,11 +510,11 @@ def pack(codes: np.ndarray, bits: np.ndarray, beta: int):
                 packed[row_off[g] + wi, i] = (stream >> (32 * wi)) & 0xFFFFFFFF
     gbits = np.zeros((k + 15) // 16, dtype=np.uint32)
     for g in range(k):
-        gbits[g // 16] |= np.uint32((int(bits[g]) - 1) << (2 * (g % 16)))
+        gbits[g // 16] |= np.uint32((int(bits[g]) - bit_base) << (2 * (g % 16)))
     return packed, gbits, row_off, m_star
 
 
-def pack_fast(codes: np.ndarray, bits: np.ndarray, beta: int):
+def pack_fast(codes: np.ndarray, bits: np.ndarray, beta: int, bit_base: int = 1):
     """Same result as pack, built from an explicit bit matrix instead of Python integers, for
     layers too large for the loop form; tested equal to it."""
     codes = np.asarray(codes, dtype=np.uint8)
@@ -526,14 +535,14 @@ def pack_fast(codes: np.ndarray, bits: np.ndarray, beta: int):
         packed[row_off[g]:row_off[g + 1], :] = w.T.astype(np.uint32)
     gbits = np.zeros((k + 15) // 16, dtype=np.uint32)
     for g in range(k):
-        gbits[g // 16] |= np.uint32((int(bits[g]) - 1) << (2 * (g % 16)))
+        gbits[g // 16] |= np.uint32((int(bits[g]) - bit_base) << (2 * (g % 16)))
     return packed, gbits, row_off, m_star
 
 
-def unpack(packed: np.ndarray, gbits: np.ndarray, beta: int, k: int) -> tuple:
+def unpack(packed: np.ndarray, gbits: np.ndarray, beta: int, k: int, bit_base: int = 1) -> tuple:
     """Inverse of pack: returns (codes (n, m) uint8, bits (k,) uint8)."""
     n = packed.shape[1]
-    bits = np.array([((int(gbits[g // 16]) >> (2 * (g % 16))) & 3) + 1 for g in range(k)], dtype=np.uint8)
+    bits = np.array([((int(gbits[g // 16]) >> (2 * (g % 16))) & 3) + bit_base for g in range(k)], dtype=np.uint8)
     codes = np.zeros((n, k * beta), dtype=np.uint8)
     off = 0
     for g in range(k):
@@ -550,7 +559,7 @@ def unpack(packed: np.ndarray, gbits: np.ndarray, beta: int, k: int) -> tuple:
 
 
 def dequant_matmul(packed: np.ndarray, gbits: np.ndarray, row_off: np.ndarray, scale: np.ndarray,
-                   zero: np.ndarray, beta: int, X: np.ndarray) -> np.ndarray:
+                   zero: np.ndarray, beta: int, X: np.ndarray, bit_base: int = 1) -> np.ndarray:
     """The linear layer on the stored form (App. B.2, inference): the weights are dequantised group by group from
     the packed integers, the group-width array and the start rows, W^_ij = scale[i, g] * (q_ij - zero[i, g]) with
     g = j // beta (Eq. 1), and multiplied with the activations: Y = X W^^T for X of shape (t, m).  Plain float64.
@@ -562,7 +571,7 @@ def dequant_matmul(packed: np.ndarray, gbits: np.ndarray, row_off: np.ndarray, s
     X = np.asarray(X, dtype=np.float64)
     Y = np.zeros((X.shape[0], n))
     for g in range(k):
-        b = ((int(gbits[g // 16]) >> (2 * (g % 16))) & 3) + 1
+        b = ((int(gbits[g // 16]) >> (2 * (g % 16))) & 3) + bit_base
         nw = int(row_off[g + 1]) - int(row_off[g])
         assert nw * 32 == beta * b
         words = packed[int(row_off[g]):int(row_off[g + 1]), :].astype(np.uint64)        # (nw, n)
@@ -609,5 +618,5 @@ def slim_layer(W: np.ndarray, X_chunks, beta: int, N: int, percdamp: float = 0.0
                bits=bits, p_star=p_star, obj_curve=obj, sba_margin=sba_margin,
                recon=reconstruction_error(W64, out["What"], G))
     if do_pack:
-        out["packed"], out["gbits"], out["row_off"], out["m_star"] = pack(out["codes"], bits, beta)
+        out["packed"], out["gbits"], out["row_off"], out["m_star"] = pack(out["codes"], bits, beta, bit_base_for(N))
     return out

@@ -317,6 +317,70 @@ def test_pack_roundtrip_sizes_and_fast_form():
     assert gb.tolist() == [0, 3]
 
 
+def test_pack_five_bit_groups_and_the_width_base_by_hand():
+    """The 4-bit target (App. G) holds widths 3, 4, 5: the 2-bit group value (App. B.2) then counts from 2."""
+    assert [orc.bit_base_for(N) for N in (2, 3, 4, 5)] == [1, 1, 2, 3]
+    # 32 five-bit codes = 160 bits = 5 words; element 6 occupies stream bits 30..34 and straddles words 0 and 1,
+    # element 12 bits 60..64 (words 1 and 2), element 31 bits 155..159 (top of word 4)
+    c5 = np.zeros((1, 32), dtype=np.uint8)
+    c5[0, 0] = 0b11111
+    c5[0, 6] = 0b10110
+    c5[0, 12] = 0b10001
+    c5[0, 31] = 0b11010
+    packed, gbits, row_off, m_star = orc.pack(c5, np.array([5]), 32, bit_base=2)
+    assert m_star == 5 and row_off.tolist() == [0, 5]
+    assert packed[:, 0].tolist() == [0b11111 | (0b10 << 30), 0b101 | (0b0001 << 28), 0b1, 0, 0b11010 << 27]
+    assert gbits.tolist() == [3]                                                  # width 5 stored as 5 - 2
+    c2, b2 = orc.unpack(packed, gbits, 32, 1, bit_base=2)
+    assert np.array_equal(c2, c5) and b2.tolist() == [5]
+    # widths 3, 4, 5 side by side: values 1, 2, 3; row offsets 3, 4, 5 words per 32 elements
+    rng = np.random.default_rng(5)
+    bits = np.array([3, 5, 4, 5, 3], dtype=np.uint8)
+    codes = np.concatenate([rng.integers(0, 2 ** b, (4, 32)) for b in bits], axis=1).astype(np.uint8)
+    packed, gbits, row_off, m_star = orc.pack(codes, bits, 32, bit_base=2)
+    assert row_off.tolist() == [0, 3, 8, 12, 17, 20] and m_star == 20 == 5 * 32 * 4 // 32
+    assert gbits.tolist() == [1 | (3 << 2) | (2 << 4) | (3 << 6) | (1 << 8)]
+    pf = orc.pack_fast(codes, bits, 32, bit_base=2)
+    assert np.array_equal(pf[0], packed) and np.array_equal(pf[1], gbits) and np.array_equal(pf[2], row_off)
+    c2, b2 = orc.unpack(packed, gbits, 32, 5, bit_base=2)
+    assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
+    # the same words read with the wrong base give other widths: the base is part of the stored form
+    assert orc.unpack(packed[:3], gbits, 32, 1, bit_base=1)[1].tolist() == [2]
+    # dequantisation on the stored form against the dense product
+    scale = rng.uniform(0.01, 0.1, (4, 5))
+    zero = np.concatenate([rng.integers(0, 2 ** b, (4, 1)) for b in bits], axis=1).astype(np.float64)
+    What = np.repeat(scale, 32, axis=1) * (codes.astype(np.float64) - np.repeat(zero, 32, axis=1))
+    X = rng.standard_normal((3, 160))
+    Y = orc.dequant_matmul(packed, gbits, row_off, scale, zero, 32, X, bit_base=2)
+    assert np.allclose(Y, X @ What.T, rtol=1e-12, atol=1e-12)
+
+
+def test_pipeline_four_bit_target():
+    """Alg. 1 at N = 4: widths 3, 4, 5 in equal numbers at both ends of the ranking, average width 4, and the
+    stored form reproduces the quantiser's codes and weights."""
+    rng = np.random.default_rng(44)
+    n, beta, k = 12, 32, 6
+    m = k * beta
+    W = rng.standard_normal((n, m)) * 0.05
+    X = rng.standard_normal((m, 3 * m)) * rng.lognormal(0, 1, m)[:, None]
+    out = orc.slim_layer(W, [X], beta, 4, t_sba=64)
+    bits = out["bits"]
+    assert set(bits.tolist()) <= {3, 4, 5}
+    assert (bits == 3).sum() == (bits == 5).sum() == out["p_star"] and bits.astype(int).sum() == 4 * k
+    assert out["m_star"] == m * 4 // 32
+    assert int(out["codes"].max()) <= 31
+    for g in range(k):
+        assert int(out["codes"][:, g * beta:(g + 1) * beta].max()) <= 2 ** int(bits[g]) - 1
+    c2, b2 = orc.unpack(out["packed"], out["gbits"], beta, k, bit_base=orc.bit_base_for(4))
+    assert np.array_equal(c2, out["codes"]) and np.array_equal(b2, bits)
+    Xin = rng.standard_normal((2, m))
+    Y = orc.dequant_matmul(out["packed"], out["gbits"], out["row_off"], out["scale"], out["zero"], beta, Xin,
+                           bit_base=orc.bit_base_for(4))
+    assert np.allclose(Y, Xin @ out["What"].T, rtol=1e-12, atol=1e-12)
+    # a wider target can only lower the reconstruction error of the same layer
+    assert out["recon"] < orc.slim_layer(W, [X], beta, 3, t_sba=64)["recon"]
+
+
 # ----------------------------------------------------------------- inference on the stored form ------
 def test_dequant_matmul_worked_example_by_hand():
     # one output row, one group of 32 two-bit codes 0,1,2,3 repeating (words 0xE4E4E4E4, see above),
