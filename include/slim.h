@@ -135,7 +135,8 @@ slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int 
  *   bits      device, k bytes: the chosen width of every group
  *   p_star    host, or NULL
  *   obj_curve host, floor(k/2)+1 doubles or NULL: the objective for every p
- *   N must be 2 or 3 (widths 1..4).  All arithmetic is fp64.
+ *   N in 2..7 (widths N - 1 .. N + 1 within 1..8; the paper's settings are N = 2, 3 and, in App. G, 4).  All
+ *   arithmetic is fp64.
  */
 slim_status slim_sba_allocate(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
                               const double* group_sal, int beta, int N, int objective, const void* X_s,
@@ -167,7 +168,7 @@ slim_status slim_sba_prepare(slim_ctx* ctx, const void* W, slim_dtype w_dtype, i
  *   hinv_diag_blk  beta values of [H^-1]_jj for the block's columns, needed by SLIM_WEIGHT_ELEMENT only
  *   tau       ncand candidates (device), or NULL for the default grid (then ncand is ignored)
  *   scale, zero  n doubles each;  cand_idx  n ints or NULL
- *   beta in {32, 64, 128, 256, 512}; bits in 1..4.
+ *   beta in {32, 64, 128, 256, 512}; bits in 1..8.
  */
 slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, int n, int beta, int bits,
                                const double* omega, const double* hinv_diag_blk, const slim_params* params,
@@ -180,7 +181,7 @@ slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, i
  *   group get w_j -= e U_cj; after the group all later columns get W[:, later] -= E_b U[b, later].
  *   W         n x m, F16/BF16/F32, read only; the working copy (fp64) lives in the workspace
  *   U         from slim_hessian_inverse (fp64, upper triangular, zero below the diagonal)
- *   bits      device, k bytes, every value in 1..4
+ *   bits      device, k bytes, every value in 1..8 (codes are bytes)
  *   beta        32, 64, 128, 256 or 512
  *   gptq_block  columns swept between two trailing updates: beta, or 128 for wider groups (groups wider than
  *               128 columns are always swept in 128-column blocks; the result does not depend on it)
@@ -202,17 +203,21 @@ slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype,
  *   packed     m_star x n 32-bit words (ld = n): for group g and output row i the beta codes form a
  *              little-endian bit stream (element r at bits [r b, (r+1) b)) whose words occupy rows
  *              row_off[g] .. of column i.  No padding, no word mixes two widths.
- *   gbits      ceil(k/16) words: bits[g]-1 as a 2-bit value, 16 groups per word, least significant first
+ *   gbits      ceil(k/16) words: bits[g] - bit_base as a 2-bit value, 16 groups per word, least significant first
+ *   bit_base   the width that the value 0 stands for.  A layer of target width N holds the widths N - 1, N, N + 1
+ *              only (Eq. 5), so three of the four values are ever used: 1 for the targets 2 and 3 (widths 1..4);
+ *              N - 2 above them (2 for the 4-bit setting of App. G, widths 3..5).  It belongs to the stored form:
+ *              a reader needs the same value.
  *   packed_rows  capacity of `packed` in rows; if m_star exceeds it the call fails with
  *              SLIM_ERR_INVALID_ARG and writes nothing beyond the capacity
  *   m_star     host, or NULL: the call then does not wait for the stream and can report neither a width outside
- *              1..4 nor a capacity that is too small (it still writes nothing beyond the capacity); m_star is
+ *              bit_base .. bit_base + 3 nor a capacity that is too small (it still writes nothing beyond the capacity); m_star is
  *              row_off[k]
- *   beta * b must be a multiple of 32 for every width in use (beta a multiple of 32).
+ *   beta * b must be a multiple of 32 for every width in use (beta a multiple of 32); widths up to 8.
  */
 slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,
-                      int beta, uint32_t* packed, int64_t packed_rows, uint32_t* gbits, int32_t* row_off,
-                      int* m_star);
+                      int beta, int bit_base, uint32_t* packed, int64_t packed_rows, uint32_t* gbits,
+                      int32_t* row_off, int* m_star);
 
 /* ---------------------------------------------------------------------------------------------
  * n1  Linear layer on the stored form (App. B.2, inference; built from the list of next steps).
@@ -224,6 +229,7 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
  *   Y        t_x x n fp32 (ldy >= n), overwritten
  *   beta     a multiple of 32 that divides m
+ *   bit_base as given to slim_pack; 1 or 2 (widths up to 5), anything else is SLIM_ERR_UNSUPPORTED
  * Arithmetic: codes and activations are exact; per (row, group) sum (q - z) x in fp32 (for fp16 activations on
  * the matrix cores, with 2 (q - z) formed exactly in fp16), times the scale rounded to fp32; the sums of group
  * ranges are added in a fixed order (deterministic, no atomics).
@@ -231,8 +237,8 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  */
 slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
                                 const int32_t* row_off, const double* scale, const double* zero, int n, int m,
-                                int beta, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx, float* Y,
-                                int64_t ldy);
+                                int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx,
+                                float* Y, int64_t ldy);
 
 /* ---------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the context's stream (measurement aid, host only).

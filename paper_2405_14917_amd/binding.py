@@ -38,6 +38,12 @@ class SlimParams(ctypes.Structure):
                 ("q1_mode", ctypes.c_int), ("sal_mode", ctypes.c_int)]
 
 
+def bit_base_for(N: int) -> int:
+    """The width that the 2-bit group value 0 of the stored form stands for, for a layer of target width N (App. B.2):
+    1 for the targets 2 and 3, N - 2 above them, so that N - 1, N, N + 1 always fit the four values."""
+    return max(1, int(N) - 2)
+
+
 class SlimError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__("libslim status %d: %s" % (status, message))
@@ -83,9 +89,9 @@ def load() -> ctypes.CDLL:
                                        c_int, c_int, P(SlimParams), c_void_p, c_void_p, c_int, c_void_p, c_void_p,
                                        c_void_p, c_void_p, c_int, c_void_p]
     lib.slim_dequant_matmul.argtypes = [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
-                                        c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
-    lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_void_p, c_i64, c_void_p,
-                              c_void_p, P(c_int)]
+                                        c_int, c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
+    lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_int, c_void_p, c_i64,
+                              c_void_p, c_void_p, P(c_int)]
     lib.slim_profile_enable.argtypes = [c_void_p, c_int]
     lib.slim_profile_collect.argtypes = [c_void_p]
     lib.slim_profile_collect.restype = c_int
@@ -268,19 +274,20 @@ class Slim:
 
     # ---- a9
     def pack(self, codes: torch.Tensor, bits: torch.Tensor, beta: int, packed_rows: Optional[int] = None,
-             host_outputs: bool = True):
+             host_outputs: bool = True, bit_base: int = 1):
         """Returns (packed uint32-as-int32 (m_star, n), gbits (ceil(k/16),), row_off int32 (k+1,), m_star); with
         host_outputs=False the call does not wait for the stream: packed then has all rows of its capacity (zero
-        from row m_star = row_off[k] on) and m_star is None."""
+        from row m_star = row_off[k] on) and m_star is None.  bit_base is the width that the 2-bit group value 0
+        stands for (bit_base_for(N) of the layer's target width)."""
         _need_cuda(codes, bits)
         n, m = codes.shape
         k = m // beta
-        cap = m * 4 // 32 if packed_rows is None else packed_rows     # widest allowed code is 4 bits
+        cap = m * (bit_base + 3) // 32 if packed_rows is None else packed_rows     # the widest width the base allows
         packed = torch.zeros((max(cap, 1), n), dtype=torch.int32, device=codes.device)
         gbits = torch.zeros((k + 15) // 16, dtype=torch.int32, device=codes.device)
         row_off = torch.zeros(k + 1, dtype=torch.int32, device=codes.device)
         m_star = ctypes.c_int(0)
-        self._check(self.lib.slim_pack(self.ctx, _ptr(codes), n, m, codes.stride(0), _ptr(bits), beta, _ptr(packed), cap,
+        self._check(self.lib.slim_pack(self.ctx, _ptr(codes), n, m, codes.stride(0), _ptr(bits), beta, bit_base, _ptr(packed), cap,
                                        _ptr(gbits), _ptr(row_off), ctypes.byref(m_star) if host_outputs else None))
         if not host_outputs:
             return packed, gbits, row_off, None
@@ -288,7 +295,8 @@ class Slim:
 
     # ---- n1
     def dequant_matmul(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,
-                       zero: torch.Tensor, beta: int, X: torch.Tensor, Y: Optional[torch.Tensor] = None):
+                       zero: torch.Tensor, beta: int, X: torch.Tensor, Y: Optional[torch.Tensor] = None,
+                       bit_base: int = 1):
         """Y (t_x, n) float32 = X (t_x, m) float16 / bfloat16 times the dequantised weights, from the stored form."""
         _need_cuda(packed, gbits, row_off, scale, zero, X)
         n = packed.shape[1]
@@ -296,7 +304,7 @@ class Slim:
         assert scale.dtype == torch.float64 and zero.dtype == torch.float64 and scale.stride(0) == m // beta
         Y = torch.empty((t_x, n), dtype=torch.float32, device=X.device) if Y is None else Y
         self._check(self.lib.slim_dequant_matmul(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
-                                                 _ptr(scale), _ptr(zero), n, m, beta, _ptr(X), _DT[X.dtype], t_x,
+                                                 _ptr(scale), _ptr(zero), n, m, beta, bit_base, _ptr(X), _DT[X.dtype], t_x,
                                                  X.stride(0), _ptr(Y), Y.stride(0)))
         return Y
 

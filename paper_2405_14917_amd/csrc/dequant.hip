@@ -33,6 +33,7 @@ struct DqArgs {
   const double* scale;   // n x k
   const double* zero;    // n x k
   int n, m, beta, k;
+  int bit_base;          // the width that the 2-bit group value 0 stands for
   const void* X;         // t_x x m, 16-bit
   int x_bf16;
   int t_x;
@@ -65,6 +66,16 @@ __device__ __forceinline__ void chunk_dot(const uint32_t (&w)[B], float z, const
     for (int e = 0; e < 21; ++e) use(e, (unsigned)(lo >> (3 * e)) & 7u);
 #pragma unroll
     for (int e = 21; e < 32; ++e) use(e, (unsigned)(hi >> (3 * (e - 21))) & 7u);
+  } else if (32 % B != 0) {
+    // any other width that does not divide 32 (5: 160 bits in 5 words): an element that straddles takes its upper
+    // bits from the next word; every index and shift is a compile-time constant after unrolling
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+      const int wi = (e * B) / 32, sh = (e * B) % 32;
+      unsigned v = w[wi] >> sh;
+      if (sh + B > 32) v |= w[(wi + 1) % B] << (32 - sh);
+      use(e, v & ((1u << B) - 1u));
+    }
   } else {
     constexpr int PER = 32 / B;            // elements per word: no element straddles two words
 #pragma unroll
@@ -103,7 +114,7 @@ __global__ __launch_bounds__(DQ_THREADS) void dequant_matmul(DqArgs a) {
     }
     __syncthreads();
     if (i < a.n) {
-      const int b = (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + 1;
+      const int b = (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + a.bit_base;
       const int base = a.row_off[g];
       const float s = (float)a.scale[(int64_t)i * a.k + g], z = (float)a.zero[(int64_t)i * a.k + g];
       float acc[T];
@@ -113,7 +124,8 @@ __global__ __launch_bounds__(DQ_THREADS) void dequant_matmul(DqArgs a) {
         case 1: group_dot<1, T>(a, i, base, z, xs, acc); break;
         case 2: group_dot<2, T>(a, i, base, z, xs, acc); break;
         case 3: group_dot<3, T>(a, i, base, z, xs, acc); break;
-        default: group_dot<4, T>(a, i, base, z, xs, acc); break;
+        case 4: group_dot<4, T>(a, i, base, z, xs, acc); break;
+        default: group_dot<5, T>(a, i, base, z, xs, acc); break;
       }
 #pragma unroll
       for (int t = 0; t < T; ++t) y[t] = fmaf(s, acc[t], y[t]);
@@ -168,14 +180,37 @@ __device__ __forceinline__ void spread_codes(unsigned v, unsigned (&t)[4]) {
   }
 }
 
+// the same for codes wider than 4 bits: the 8 codes take 8 B > 32 bits
+template <int B>
+__device__ __forceinline__ void spread_codes_wide(uint64_t v, unsigned (&t)[4]) {
+  constexpr unsigned M = (1u << B) - 1u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    t[j] = (((unsigned)(v >> (B * j)) & M) << 1) | (((unsigned)(v >> (B * (j + 4))) & M) << 17) | 0x64006400u;
+}
+
 // One sub-block of SUB codes (SUB / 16 MFMA steps) of one group: `w` holds the SUB * B / 32 words of the lane's
 // output row; xs points at the lane's token row of the activation tile, at this sub-block's first column.
-template <int B, int SUB>
-__device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[16], int h, half2v zz, const _Float16* xs,
+template <int B, int SUB, int MAXW>
+__device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[MAXW], int h, half2v zz, const _Float16* xs,
                                                   float16v acc) {
   constexpr int NW = SUB * B / 32;
+  static_assert(NW <= MAXW, "the sub-block's words do not fit the register array");
 #pragma unroll
   for (int st = 0; st < SUB / 16; ++st) {
+    unsigned t[4];
+    if constexpr (B > 4) {
+      // 8 codes = 8 B bits (at most 64) starting at bit 8 B (2 st + h): always within two consecutive words for
+      // B = 5 (the start is a multiple of 8, so at most 24 + 40 bits)
+      static_assert(B == 5, "wider codes would span three words");
+      auto unit_wide = [&](int unit) -> uint64_t {
+        const int bit = 8 * B * unit, wi = bit / 32, sh = bit % 32;
+        const uint64_t two = (uint64_t)w[wi] | ((uint64_t)w[(wi + 1 < NW) ? wi + 1 : wi] << 32);
+        return two >> sh;
+      };
+      const uint64_t v0 = unit_wide(2 * st), v1 = unit_wide(2 * st + 1);
+      spread_codes_wide<B>(h ? v1 : v0, t);
+    } else {
     // unit 2 st + h of the stream: 8 codes = 8 B bits starting at bit 8 B (2 st + h)
     auto unit_bits = [&](int unit) -> unsigned {
       const int bit = 8 * B * unit, wi = bit / 32, sh = bit % 32;
@@ -184,8 +219,8 @@ __device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[16], int h
       return (unsigned)(two >> sh);
     };
     const unsigned v0 = unit_bits(2 * st), v1 = unit_bits(2 * st + 1);   // the unit for h = 0 and for h = 1
-    unsigned t[4];
     spread_codes<B>(h ? v1 : v0, t);
+    }
     half8v bfrag;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -203,7 +238,8 @@ __device__ __forceinline__ float16v subblock_mfma(const unsigned (&w)[16], int h
 // group range are put into LDS once (rows of the real tokens plus one row of zeros that the lanes of the other
 // token slots read); the words, scale and zero of the next sub-block are fetched while the current one is
 // multiplied, so that a workgroup waits for memory once, not once per group.
-template <int SUB>
+// MAXW: words of a sub-block at the widest width in the layer (16 for widths up to 4, 20 with five-bit groups).
+template <int SUB, int MAXW>
 __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
   extern __shared__ __align__(16) _Float16 xh[];   // [t_x + 1][cols + DM_PAD], every 8 columns in the order 0 4 1 5 2 6 3 7
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -240,16 +276,16 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
   const int prow = (wave * 32 + l32) * gcount;
 
   const int nsub = a.beta / SUB, units = (g1 - g0) * nsub;
-  auto width = [&](int g) { return (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + 1; };
+  auto width = [&](int g) { return (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + a.bit_base; };
   // fetch of unit u: the words of the lane's row
-  auto fetch = [&](int u, unsigned (&w)[16]) {
+  auto fetch = [&](int u, unsigned (&w)[MAXW]) {
     const int g = g0 + u / nsub, sb = u - (u / nsub) * nsub;
     const int nwu = SUB * width(g) / 32;
     const uint32_t* p = a.packed + (int64_t)(a.row_off[g] + sb * nwu) * a.ldp + row;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) w[i] = (i < nwu) ? p[(int64_t)i * a.ldp] : 0u;
+    for (int i = 0; i < MAXW; ++i) w[i] = (i < nwu) ? p[(int64_t)i * a.ldp] : 0u;
   };
-  unsigned wc[16], wn[16];
+  unsigned wc[MAXW], wn[MAXW];
   fetch(0, wc);
   __syncthreads();                                 // the activation tile and the parameters are complete
 
@@ -268,10 +304,13 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
     zz[1] = zc;
     const _Float16* xu = xs + (g - g0) * a.beta + sb * SUB;
     switch (width(g)) {                            // the same for the whole workgroup
-      case 1: acc = subblock_mfma<1, SUB>(wc, h, zz, xu, acc); break;
-      case 2: acc = subblock_mfma<2, SUB>(wc, h, zz, xu, acc); break;
-      case 3: acc = subblock_mfma<3, SUB>(wc, h, zz, xu, acc); break;
-      default: acc = subblock_mfma<4, SUB>(wc, h, zz, xu, acc); break;
+      case 1: acc = subblock_mfma<1, SUB, MAXW>(wc, h, zz, xu, acc); break;
+      case 2: acc = subblock_mfma<2, SUB, MAXW>(wc, h, zz, xu, acc); break;
+      case 3: acc = subblock_mfma<3, SUB, MAXW>(wc, h, zz, xu, acc); break;
+      case 4: acc = subblock_mfma<4, SUB, MAXW>(wc, h, zz, xu, acc); break;
+      default:
+        if constexpr (MAXW >= 20) acc = subblock_mfma<5, SUB, MAXW>(wc, h, zz, xu, acc);
+        break;
     }
     if (sb == nsub - 1) {                          // the group is complete: its scale (times the 1/2 of the doubled codes)
       const float s2 = sp[prow + (g - g0)];
@@ -282,7 +321,7 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) wc[i] = wn[i];
+    for (int i = 0; i < MAXW; ++i) wc[i] = wn[i];
   }
   if (blockIdx.x * DM_ROWS + wave * 32 + l32 < a.n) {
     float* o = a.out + (int64_t)blockIdx.y * a.split_stride + row;
@@ -304,8 +343,8 @@ slim_status launch(slim_ctx* ctx, const DqArgs& a, dim3 grid, size_t smem) {
 
 extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
                                            const int32_t* row_off, const double* scale, const double* zero, int n,
-                                           int m, int beta, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx,
-                                           float* Y, int64_t ldy) {
+                                           int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
+                                           int64_t ldx, float* Y, int64_t ldy) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;
   SLIM_REQUIRE(ctx, packed && gbits && row_off && scale && zero && X && Y, "slim_dequant_matmul: null pointer");
   SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_dequant_matmul: need n, m > 0 and beta | m");
@@ -314,6 +353,9 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   SLIM_REQUIRE(ctx, ldp >= n && ldx >= m && ldy >= n, "slim_dequant_matmul: leading dimension too small");
   if (x_dtype != SLIM_F16 && x_dtype != SLIM_BF16)
     return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_dequant_matmul: X must be F16 or BF16");
+  if (bit_base != 1 && bit_base != 2)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_dequant_matmul: bit_base must be 1 or 2 (widths up to 5), got %d",
+                     bit_base);
   const int k = m / beta;
   int T = 1;
   while (T < t_x) T *= 2;
@@ -349,6 +391,7 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   a.m = m;
   a.beta = beta;
   a.k = k;
+  a.bit_base = bit_base;
   a.X = X;
   a.x_bf16 = (x_dtype == SLIM_BF16);
   a.t_x = t_x;
@@ -371,12 +414,18 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   slim_status st = SLIM_OK;
   if (mfma) {
     smem = sizeof(uint16_t) * (size_t)(t_x + 1) * ((size_t)gper * beta + DM_PAD) + (size_t)DM_ROWS * gper * 6;
-    if (beta >= 128)
-      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<128>", dequant_matmul_mfma<128>, grid, dim3(64 * DM_WAVES), smem, a);
-    else if (beta == 64)
-      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<64>", dequant_matmul_mfma<64>, grid, dim3(64 * DM_WAVES), smem, a);
-    else
-      SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<32>", dequant_matmul_mfma<32>, grid, dim3(64 * DM_WAVES), smem, a);
+#define SLIM_DQ_MFMA(SUB, MAXW)                                                                              \
+  SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<" #SUB ", " #MAXW ">", (dequant_matmul_mfma<SUB, MAXW>), grid, \
+              dim3(64 * DM_WAVES), smem, a)
+    const bool wide = bit_base + 3 > 4;            // the layer may hold five-bit groups
+    if (beta >= 128) {
+      if (wide) SLIM_DQ_MFMA(128, 20); else SLIM_DQ_MFMA(128, 16);
+    } else if (beta == 64) {
+      if (wide) SLIM_DQ_MFMA(64, 20); else SLIM_DQ_MFMA(64, 16);
+    } else {
+      if (wide) SLIM_DQ_MFMA(32, 20); else SLIM_DQ_MFMA(32, 16);
+    }
+#undef SLIM_DQ_MFMA
   } else
   switch (T) {
     case 1: st = launch<1>(ctx, a, grid, smem); break;

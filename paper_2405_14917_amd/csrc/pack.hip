@@ -12,7 +12,7 @@ namespace {
 constexpr int PACK_ROWS = 64;
 
 // single workgroup: validates widths, exclusive scan of beta * b_g / 32, width array
-__global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bits, int k, int beta,
+__global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bits, int k, int beta, int bit_base,
                                                  int32_t* __restrict__ row_off, uint32_t* __restrict__ gbits,
                                                  int* __restrict__ flags) {
   __shared__ int32_t part[256];
@@ -23,7 +23,7 @@ __global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bit
   int bad = 0;
   for (int g = g0; g < g1; ++g) {
     const int b = bits[g];
-    if (b < 1 || b > 4 || (beta * b) % 32 != 0) bad = 1;
+    if (b < bit_base || b > bit_base + 3 || b > 8 || (beta * b) % 32 != 0) bad = 1;
     s += beta * b / 32;
   }
   part[tid] = s;
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bit
   const int nw = (k + 15) / 16;
   for (int w = tid; w < nw; w += 256) {
     uint32_t v = 0;
-    for (int j = 0; j < 16 && w * 16 + j < k; ++j) v |= (uint32_t)((bits[w * 16 + j] - 1) & 3) << (2 * j);
+    for (int j = 0; j < 16 && w * 16 + j < k; ++j) v |= (uint32_t)((bits[w * 16 + j] - bit_base) & 3) << (2 * j);
     gbits[w] = v;
   }
 }
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(PACK_ROWS) void pack_codes(const uint8_t* __restric
   const int rows = min(PACK_ROWS, n - i0);
   const int stride = beta + 4;
   const int b = bits[g];
-  if (b < 1 || b > 4) return;
+  if (b < 1 || b > 8) return;
   // beta is a multiple of 32: read 4 codes per thread and step
   const int quads = beta / 4;
   for (int idx = threadIdx.x; idx < rows * quads; idx += PACK_ROWS) {
@@ -90,8 +90,8 @@ __global__ __launch_bounds__(PACK_ROWS) void pack_codes(const uint8_t* __restric
 }  // namespace
 
 extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,
-                                 int beta, uint32_t* packed, int64_t packed_rows, uint32_t* gbits, int32_t* row_off,
-                                 int* m_star) {
+                                 int beta, int bit_base, uint32_t* packed, int64_t packed_rows, uint32_t* gbits,
+                                 int32_t* row_off, int* m_star) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;
   SLIM_REQUIRE(ctx, codes && bits && packed && gbits && row_off, "slim_pack: null pointer");
   SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_pack: need n, m > 0 and beta | m");
@@ -99,9 +99,10 @@ extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int
   SLIM_REQUIRE(ctx, ldc >= m && ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0,
                "slim_pack: codes must be 4-byte aligned with ldc a multiple of 4");
   SLIM_REQUIRE(ctx, packed_rows >= 0, "slim_pack: negative capacity");
+  SLIM_REQUIRE(ctx, bit_base >= 1 && bit_base <= 5, "slim_pack: bit_base must be in 1..5 (got %d)", bit_base);
   const int k = m / beta;
   int* flags = ctx->dflags;   // flags[0] is cleared by pack_scan itself
-  SLIM_LAUNCH(ctx, "pack_scan", pack_scan, dim3(1), dim3(256), 0, bits, k, beta, row_off, gbits, flags);
+  SLIM_LAUNCH(ctx, "pack_scan", pack_scan, dim3(1), dim3(256), 0, bits, k, beta, bit_base, row_off, gbits, flags);
   const size_t smem = (size_t)PACK_ROWS * (beta + 4);
   SLIM_LAUNCH(ctx, "pack_codes", pack_codes, dim3(slim_cdiv(n, PACK_ROWS), k), dim3(PACK_ROWS), smem, codes, n, ldc,
               bits, beta, row_off, packed, packed_rows);
@@ -112,7 +113,8 @@ extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int
   SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   *m_star = host[0];
   if (host[1] != 0)
-    return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "slim_pack: a width is outside 1..4 or beta * width is not a multiple of 32");
+    return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "slim_pack: a width is outside bit_base .. bit_base + 3 (%d .. %d, at most 8) or beta * width is not a multiple of 32",
+                     bit_base, bit_base + 3);
   if (host[0] > packed_rows)
     return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "slim_pack: packed needs %d rows, capacity is %lld", host[0],
                      (long long)packed_rows);

@@ -926,7 +926,7 @@ extern "C" slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int
   if (st != SLIM_OK) return st;
   SLIM_REQUIRE(ctx, Wblk && scale && zero, "slim_sqc_calibrate: null pointer");
   SLIM_REQUIRE(ctx, n > 0 && ldw >= beta, "slim_sqc_calibrate: need n > 0 and ldw >= beta");
-  SLIM_REQUIRE(ctx, bits >= 1 && bits <= 4, "slim_sqc_calibrate: bits must be in 1..4 (got %d)", bits);
+  SLIM_REQUIRE(ctx, bits >= 1 && bits <= 8, "slim_sqc_calibrate: bits must be in 1..8 (got %d)", bits);
   if (!beta_supported(beta))
     return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_sqc_calibrate: beta must be 32, 64, 128, 256 or 512 (got %d)", beta);
   if (!tau) {
@@ -1028,7 +1028,7 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   std::vector<int> gb(k);
   for (int g = 0; g < k; ++g) {
     gb[g] = bits_h[g];
-    SLIM_REQUIRE(ctx, gb[g] >= 1 && gb[g] <= 4, "slim_gptq_quantize: bits[%d] = %d is outside 1..4", g, gb[g]);
+    SLIM_REQUIRE(ctx, gb[g] >= 1 && gb[g] <= 8, "slim_gptq_quantize: bits[%d] = %d is outside 1..8", g, gb[g]);
   }
 
   // Rows per workgroup of the sweep: as few as fill the chip, so that small layers spread over every compute

@@ -524,7 +524,7 @@ slim_status sba_check(slim_ctx* ctx, const char* fn, const void* W, slim_dtype w
                       const slim_params& prm) {
   SLIM_REQUIRE(ctx, W && X_s, "%s: null pointer", fn);
   SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "%s: need n, m > 0 and beta | m", fn);
-  SLIM_REQUIRE(ctx, N == 2 || N == 3, "%s: N must be 2 or 3 (got %d)", fn, N);
+  SLIM_REQUIRE(ctx, N >= 2 && N <= 7, "%s: N must be in 2..7 (got %d)", fn, N);
   SLIM_REQUIRE(ctx, beta % 4 == 0 && ldw >= m && ldw % 4 == 0, "%s: beta and ldw must be multiples of 4", fn);
   SLIM_REQUIRE(ctx, t_s > 0 && t_s % 4 == 0 && ldxs >= t_s && ldxs % 4 == 0,
                "%s: t_s and ldxs must be positive multiples of 4", fn);

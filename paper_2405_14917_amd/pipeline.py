@@ -18,6 +18,7 @@ class LayerPass:
 
     def __init__(self, slim, m, beta, N, percdamp=0.01, t_sba=2048, device="cuda:0"):
         self.slim, self.m, self.beta, self.N, self.percdamp, self.t_sba = slim, m, beta, N, percdamp, t_sba
+        self.bit_base = binding.bit_base_for(N)     # of the stored form: what its 2-bit group value 0 stands for
         self.G = torch.zeros((m, m), dtype=torch.float32, device=device)
         self.U = torch.empty((m, m), dtype=torch.float64, device=device)
         self.d = torch.empty(m, dtype=torch.float64, device=device)
@@ -60,8 +61,9 @@ class LayerPass:
             bits, _, _ = s.sba_allocate(W, grp, self.beta, self.N, Xs, host_outputs=False)
         out = s.gptq_quantize(W, self.U, bits, self.beta)
         packed, gbits, row_off, _ = s.pack(out["codes"], bits, self.beta, packed_rows=self.m * (self.N + 1) // 32,
-                                           host_outputs=False)
-        return {"bits": bits, "p_star": (bits == self.N - 1).sum(), "codes": out["codes"], "scale": out["scale"],
+                                           host_outputs=False, bit_base=self.bit_base)
+        return {"bits": bits, "bit_base": self.bit_base, "p_star": (bits == self.N - 1).sum(), "codes": out["codes"],
+                "scale": out["scale"],
                 "zero": out["zero"], "packed": packed, "gbits": gbits, "row_off": row_off, "m_star": row_off[-1]}
 
     def run(self, W, X):

@@ -154,7 +154,8 @@ def test_salience(slim, dtype):
 # n = 72 and t_s = 132 take the search with a GEMM launch and a reduction per candidate; the shapes with whole
 # 128 x 128 output tiles take the search in one kernel
 @pytest.mark.parametrize("N,beta,m,ts,n", [(2, 64, 256, 128, 72), (3, 32, 288, 64, 72), (2, 128, 640, 132, 72),
-                                           (2, 64, 512, 256, 384), (3, 32, 256, 128, 128), (2, 128, 1024, 128, 256)])
+                                           (2, 64, 512, 256, 384), (3, 32, 256, 128, 128), (2, 128, 1024, 128, 256),
+                                           (4, 32, 288, 64, 72), (4, 64, 512, 256, 384)])   # widths 3, 4, 5 (App. G)
 def test_sba_allocate(slim, N, beta, m, ts, n):
     W, X = small_layer(10 + N + beta, n=n, m=m, t=max(ts, 4 * m) // 4 * 4, beta=beta)
     G = np.zeros((m, m))
@@ -264,7 +265,7 @@ def test_inverse_writes_every_element_of_its_outputs(slim):
 
 # ------------------------------------------------------------------------------------------ a5 + a6
 @pytest.mark.parametrize("beta", [32, 64, 128, 256, 512])
-@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 8])
 def test_sqc_calibrate(slim, beta, bits):
     from paper_2405_14917_amd import binding
     rng = np.random.default_rng(beta * 10 + bits)
@@ -395,6 +396,14 @@ def test_gptq_quantize_many_rows(slim, beta, n, m):
     _gptq_case(slim, W, X, bits, beta)
 
 
+def test_gptq_quantize_widths_of_the_four_bit_target_and_beyond(slim):
+    """Widths 3, 4, 5 (the 4-bit setting of App. G) and the widest codes a byte holds."""
+    W, X = small_layer(77, n=130, m=640, t=2560, beta=128)
+    _gptq_case(slim, W, X, np.array([5, 3, 4, 5, 3], dtype=np.uint8), 128)
+    W, X = small_layer(78, n=60, m=256, t=1024, beta=64)
+    _gptq_case(slim, W, X, np.array([6, 8, 5, 7], dtype=np.uint8), 64)
+
+
 def test_gptq_modes_and_fp32_weights(slim):
     from paper_2405_14917_amd import binding
     W, X = small_layer(77, n=64, m=256, t=1024, beta=64, w_dtype=np.float32)
@@ -453,6 +462,32 @@ def test_pack(slim, beta, n):
     assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
 
 
+@pytest.mark.parametrize("beta,n,base", [(128, 200, 2), (32, 70, 2), (64, 130, 5), (32, 64, 3)])
+def test_pack_with_a_width_base(slim, beta, n, base):
+    """Five-bit groups and wider: the 2-bit group value counts from bit_base (2 for the 4-bit target)."""
+    from paper_2405_14917_amd import binding
+    assert [binding.bit_base_for(N) for N in (2, 3, 4, 5)] == [orc.bit_base_for(N) for N in (2, 3, 4, 5)] == [1, 1, 2, 3]
+    rng = np.random.default_rng(beta + n + base)
+    k = 21
+    bits = rng.integers(base, base + 4, size=k).astype(np.uint8)
+    bits[:4] = np.arange(base, base + 4)
+    codes = np.concatenate([rng.integers(0, 2 ** int(b), (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    po, go, ro, mo = orc.pack_fast(codes, bits, beta, bit_base=base)
+    packed, gbits, row_off, m_star = slim.pack(dev(codes), dev(bits), beta, bit_base=base)
+    assert m_star == mo and np.array_equal(host(row_off), ro)
+    assert np.array_equal(host(gbits).view(np.uint32), go)
+    assert np.array_equal(host(packed).view(np.uint32), po)
+    c2, b2 = orc.unpack(host(packed).view(np.uint32), host(gbits).view(np.uint32), beta, k, bit_base=base)
+    assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
+    # a width below the base, or more than three above it, has no 2-bit value
+    for bad in (base - 1, base + 4):
+        bits_bad = bits.copy()
+        bits_bad[5] = bad
+        with pytest.raises(binding.SlimError) as ei:
+            slim.pack(dev(codes), dev(bits_bad), beta, bit_base=base)
+        assert ei.value.status == binding.ERR_INVALID_ARG
+
+
 # ------------------------------------------------------------------------------------------ n1
 # Tolerance: the kernel forms sum (q - z) x per (row, group) and the sum over the groups in fp32 (exact inputs), so
 # its error is bounded by a few m * 2^-24 times sum |x| |w| for that output; 1e-5 of that sum (m <= 1024 here) has
@@ -487,6 +522,70 @@ def test_dequant_matmul(slim, beta, n, m, t_x, dtype):
     Yw = torch.full((t_x, n + 3), -1.0, dtype=torch.float32, device="cuda")
     slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, Xw[:, :m], Y=Yw[:, :n])
     assert np.array_equal(host(Yw[:, :n]), Y) and np.all(host(Yw[:, n:]) == -1.0)
+
+
+@pytest.mark.parametrize("beta,n,m,t_x,dtype", [(128, 300, 1024, 1, torch.float16), (32, 70, 256, 3, torch.float16),
+                                                (64, 520, 1024, 16, torch.bfloat16), (256, 64, 1024, 5, torch.float16),
+                                                (64, 200, 512, 16, torch.float16), (128, 100, 512, 2, torch.float16)])
+def test_dequant_matmul_with_five_bit_groups(slim, beta, n, m, t_x, dtype):
+    """The stored form of the 4-bit target (widths 3, 4, 5; the group value counts from 2), both kernel forms."""
+    from paper_2405_14917_amd import binding
+    rng = np.random.default_rng(beta + n + t_x + 5)
+    k = m // beta
+    bits = rng.integers(2, 6, size=k).astype(np.uint8)
+    bits[: min(k, 4)] = np.array([5, 3, 4, 2])[: min(k, 4)]
+    bits[-1] = 5
+    codes = np.concatenate([rng.integers(0, 2 ** int(b), (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    codes[:, -1] = 31                                                     # the last element of a five-bit stream
+    codes[:, 0] = 31
+    scale = np.abs(rng.standard_normal((n, k))) * 0.01 + 1e-3
+    zero = np.stack([rng.integers(0, 2 ** int(b), n).astype(np.float64) for b in bits], axis=1)
+    packed_o, gbits_o, row_off_o, m_star = orc.pack_fast(codes, bits, beta, bit_base=2)
+    X = torch.from_numpy(rng.standard_normal((t_x, m))).to(dtype)
+    Y_o = orc.dequant_matmul(packed_o, gbits_o, row_off_o, scale, zero, beta, X.double().numpy(), bit_base=2)
+    packed, gbits, row_off, ms = slim.pack(dev(codes), dev(bits), beta, bit_base=2)
+    assert ms == m_star and np.array_equal(host(packed).view(np.uint32), packed_o)
+    Y = host(slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, X.cuda(), bit_base=2))
+    What = np.repeat(scale, beta, axis=1) * (codes - np.repeat(zero, beta, axis=1))
+    bound = np.abs(X.double().numpy()) @ np.abs(What).T
+    assert Y.shape == (t_x, n) and np.all(np.abs(Y - Y_o) <= 1e-5 * bound + 1e-30)
+    with pytest.raises(binding.SlimError) as ei:
+        slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, X.cuda(), bit_base=3)
+    assert ei.value.status == binding.ERR_UNSUPPORTED
+
+
+def test_whole_pass_four_bit_target(slim):
+    """Alg. 1 at N = 4 (App. G) through the driver of the timed pass, against the oracle's pass, and the linear layer
+    on its stored form."""
+    from paper_2405_14917_amd import pipeline
+    m, beta, N, t, n = 512, 64, 4, 2048, 192
+    W, X = small_layer(95, n=n, m=m, t=t, beta=beta)
+    ref = orc.slim_layer(W, [X], beta, N, t_sba=256)
+    drv = pipeline.LayerPass(slim, m, beta, N, 0.01, t_sba=256)
+    try:
+        r = drv.run(dev(W), dev(X))
+        torch.cuda.synchronize()
+        bits = host(r["bits"])
+        assert r["bit_base"] == 2 and set(bits.tolist()) <= {3, 4, 5} and bits.astype(int).sum() == N * (m // beta)
+        if ref["sba_margin"] > MARGIN:
+            assert int(r["p_star"]) == ref["p_star"] and np.array_equal(bits, ref["bits"])
+            assert np.array_equal(host(r["gbits"]).view(np.uint32), ref["gbits"])
+            assert np.array_equal(host(r["row_off"]), ref["row_off"])
+        assert int(r["m_star"]) == m * N // 32 == ref["m_star"]
+        codes, scale, zero = host(r["codes"]), host(r["scale"]), host(r["zero"])
+        What = np.repeat(scale, beta, axis=1) * (codes - np.repeat(zero, beta, axis=1))
+        rec = orc.reconstruction_error(W, What, ref["G"])
+        print("N = 4: codes equal %.4f, recon gpu %.6e oracle %.6e" % ((codes == ref["codes"]).mean(), rec, ref["recon"]))
+        assert abs(rec - ref["recon"]) <= 0.01 * ref["recon"]
+        c2, b2 = orc.unpack(host(r["packed"][: int(r["m_star"])]).view(np.uint32), host(r["gbits"]).view(np.uint32), beta,
+                            m // beta, bit_base=2)
+        assert np.array_equal(c2, codes) and np.array_equal(b2, bits)
+        Xin = dev(X)[:, 7:10].t().contiguous()
+        Y = host(slim.dequant_matmul(r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"], beta, Xin, bit_base=2))
+        Xn = host(Xin).astype(np.float64)
+        assert np.all(np.abs(Y - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
+    finally:
+        drv.close()
 
 
 def test_dequant_matmul_after_the_whole_pass(slim):
@@ -567,9 +666,10 @@ def test_invalid_arguments_are_rejected(slim):
     with pytest.raises(binding.SlimError) as ei:
         slim.gptq_quantize(W, U, dev(np.array([2, 2, 2, 2], dtype=np.uint8)), 48)
     assert ei.value.status == binding.ERR_INVALID_ARG or ei.value.status == binding.ERR_UNSUPPORTED
-    with pytest.raises(binding.SlimError) as ei:
-        slim.sba_allocate(W, dev(np.ones(2)), 64, 5, dev(np.zeros((128, 64), dtype=np.float16)))
-    assert ei.value.status == binding.ERR_INVALID_ARG
+    for N in (1, 8):                                   # widths N - 1 .. N + 1 must lie in 1..8
+        with pytest.raises(binding.SlimError) as ei:
+            slim.sba_allocate(W, dev(np.ones(2)), 64, N, dev(np.zeros((128, 64), dtype=np.float16)))
+        assert ei.value.status == binding.ERR_INVALID_ARG
     with pytest.raises(binding.SlimError) as ei:
         slim.hessian_accumulate(dev(np.zeros((12, 64), dtype=np.float16)), torch.zeros((12, 12), device="cuda"))
     assert ei.value.status == binding.ERR_INVALID_ARG
