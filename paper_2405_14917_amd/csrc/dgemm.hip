@@ -400,11 +400,10 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
   return SLIM_OK;
 }
 
-// Half of the chip: next to a factorisation, whose own bulk updates want whole CUs too, this has measured best.
-int slim_dgemm_reserved_cus(const slim_ctx* ctx) { return std::max(1, ctx->num_cus / 2); }
-
-slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count) {
+slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count,
+                                int cus) {
   if (count < 1 || count > 2) return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "dgemm: one or two products per reserved launch");
+  if (cus < 1 || cus > ctx->num_cus) return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "dgemm: reserved launch on %d CUs", cus);
   bool wide = true;
   int tiles = 0;
   for (int i = 0; i < count; ++i) {
@@ -427,7 +426,7 @@ slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, co
   slim_status st = trans_b ? allow_lds(ctx, dgemm_reserved_wide_kernel<1>, wide1) : allow_lds(ctx, dgemm_reserved_wide_kernel<0>, wide0);
   if (st != SLIM_OK) return st;
   // as many rounds as the CUs that may be used need, and then no more workgroups than fill those rounds
-  const int usable = slim_dgemm_reserved_cus(ctx);
+  const int usable = cus;
   const int rounds = slim_cdiv(tiles, usable);
   const int wgs = slim_cdiv(tiles, rounds);
   WidePair w;

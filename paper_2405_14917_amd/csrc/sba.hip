@@ -571,10 +571,14 @@ slim_status sba_rank_independent(slim_ctx* ctx, const SbaWorkspace& w, const voi
   // as long as the inverse does; the rest follows in the ordinary form, which wants the whole chip.  The inverse
   // is modelled as its chain of m / 64 diagonal steps of 45 us plus m^3 / 3 flops of triangular inversion at
   // 50 TFLOP/s, the persistent form at 85 % of the matrix cores of its CUs.
+  // Their share of the chip, next to a factorisation whose own bulk updates want whole CUs too: 5/8 when the layer
+  // has no more outputs than inputs (the products are then about as long as the inverse, and a larger share ends
+  // them with it), half of it otherwise (most of the products follows after the inverse anyway, and the inverse
+  // gains more from the CUs); both measured, on 4096 x 4096 .. 28672 x 8192 layers.
   int rows_beside = 0;
+  const int cus = std::max(1, n <= m ? ctx->num_cus * 5 / 8 : ctx->num_cus / 2);
   if (beside_chain && n % 256 == 0 && t_s % 128 == 0 && m % 16 == 0) {
     const double t_inv = (m / 64) * 45e-6 + (double)m * m * m / 3.0 / 50e12;
-    const int cus = slim_dgemm_reserved_cus(ctx);
     const double rate = 0.85 * 78.6e12 * cus / std::max(1, ctx->num_cus);
     const int64_t tiles_per_block = 2 * (t_s / 128);            // of 256 rows, both products
     int64_t tiles_fit = (int64_t)(rate * t_inv / (2.0 * 256 * 128 * m));
@@ -584,7 +588,7 @@ slim_status sba_rank_independent(slim_ctx* ctx, const SbaWorkspace& w, const voi
   if (rows_beside > 0) {
     slim_gemm_desc part[2] = {pair[0], pair[1]};
     part[0].M = part[1].M = rows_beside;
-    st = slim_dgemm_reserved(ctx, "sba_output_dgemm", 0, part, 2);
+    st = slim_dgemm_reserved(ctx, "sba_output_dgemm", 0, part, 2, cus);
     if (st != SLIM_OK) return st;
   }
   if (rows_beside < n) {

@@ -159,10 +159,10 @@ struct slim_gemm_desc {
 slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc& d);
 // One or two products (host descriptors) beside a latency-critical chain on other streams: persistent workgroups
 // on all but a few CUs, as with SLIM_GEMM_ONE_PER_CU, in one launch.
-slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count);
-// CUs such a launch occupies when every product is edge-free (M % 256 == 0, N % 128 == 0, K % 16 == 0, no flags):
-// it then works on 256 x 128 tiles, one workgroup per CU.
-int slim_dgemm_reserved_cus(const slim_ctx* ctx);
+// `cus`: the CUs the launch may occupy when every product is edge-free (M % 256 == 0, N % 128 == 0, K % 16 == 0,
+// no flags): it then works on 256 x 128 tiles, one workgroup per CU.
+slim_status slim_dgemm_reserved(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs, int count,
+                                int cus);
 // Batched form: `descs` is a device array of `count` descriptors; max_M / max_N bound the grid.
 slim_status slim_dgemm_batched(slim_ctx* ctx, const char* name, int trans_b, const slim_gemm_desc* descs_dev,
                                int count, int max_M, int max_N);
