@@ -10,9 +10,10 @@
 //  * K advances in slabs of 64 tokens (128 bytes per row = one cache line) through two LDS stages;
 //    the next slab is fetched into registers while the current one is multiplied; rows are padded to
 //    72 halves so that the 16-byte operand reads of consecutive rows fall into different banks.
-//  * Split-K: workgroup id = tile * S + s.  Workgroups are dealt round-robin to the 8 XCDs, so with S a
-//    multiple of 8 every XCD works on one token range and the slab of X that all of its tiles share
-//    stays in that XCD's L2.
+//  * Split-K: every tile is cut into S token ranges.  Workgroup ids run over the tiles fastest, so the chip works
+//    on one or two token ranges at a time (HBM is read about once; the XCDs share through the memory-side cache),
+//    and the workgroups dealt to one XCD (id mod 8) form a compact set of tiles that shares row blocks of X in
+//    that XCD's L2 (decode_work).
 //  * Every workgroup writes its partial 256 x 256 tile to a slot of a scratch buffer; a second kernel adds the
 //    slots of a tile to G in a fixed order (deterministic, no floating-point atomics) and mirrors the upper
 //    triangle.
@@ -43,16 +44,21 @@ struct GramArgs {
   int64_t t;           // tokens in this chunk
   int64_t kchunk;      // tokens per split (multiple of BK)
   int S;               // number of splits
-  int n_main;          // workgroups that take a whole split of their tile: ids 0 .. n_main-1 = tile * S + split
+  int n_main;          // workgroups that take a whole split of their tile: ids 0 .. n_main-1 (order: decode_work)
   int tiles_main;      // tiles handled that way; the tiles behind them are split `f` ways more
   int f;               // sub-splits per split of a tail tile
   int64_t subchunk;    // tokens per sub-split (multiple of BK)
   float* P;            // partial tiles: [slot][TM][TM]
 };
 
-// Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  Workgroup ids
-// keep `split` as the fastest index everywhere, so that with S a multiple of 8 the XCD (id mod 8) of a
-// workgroup is determined by its token range.  The slots of one tile are contiguous.
+// Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  The slots of one
+// tile are contiguous.  Workgroup ids run over the tiles fastest and the token ranges slowest: the workgroups that
+// are on the chip at the same time then cover every tile for one or two token ranges, so the chip as a whole reads
+// a narrow band of X at a time (what one XCD has fetched the others find in the memory-side cache, and HBM is read
+// about once), and XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact
+// set that shares its row blocks in that XCD's L2.  With the token range fastest instead (every XCD on a range of
+// its own) each round of workgroups fetched nearly all of X again: 5.4 x the size of X from memory per launch at
+// m = 4096, and the kernel, which is limited by power, ran 4 % (m = 4096) to 10 % (m = 11008) slower.
 struct WorkItem {
   int tile;
   int64_t kbeg, kend;
@@ -61,11 +67,14 @@ struct WorkItem {
 __device__ __forceinline__ WorkItem decode_work(const GramArgs& a, int id) {
   WorkItem w;
   if (id < a.n_main) {
-    w.tile = id / a.S;
-    const int split = id - w.tile * a.S;
+    const int split = id / a.tiles_main;
+    const int j = id - split * a.tiles_main;
+    // j = c + 8 q: class c owns tiles_main / 8 consecutive tiles (one more for the first tiles_main % 8 classes)
+    const int c = j % 8, per = a.tiles_main / 8, rest = a.tiles_main % 8;
+    w.tile = c * per + min(c, rest) + j / 8;
     w.kbeg = (int64_t)split * a.kchunk;
     w.kend = min(a.t, w.kbeg + a.kchunk);
-    w.slot = id;
+    w.slot = (int64_t)w.tile * a.S + split;
   } else {
     const int j = id - a.n_main;
     const int split = j % a.S, q = j / a.S;
@@ -89,9 +98,9 @@ __device__ __forceinline__ void decode_triangle(int t, int& bi, int& bj) {
 }
 
 // Tile index -> tile (bi <= bj) of the upper triangle of an nt x nt grid.  Tiles are numbered supertile by
-// supertile (SUPER x SUPER tiles, the supertiles column by column over the triangle): the ~32 workgroups that
-// run at the same time on one XCD then cover a compact square of tiles that needs 2 x SUPER row blocks of X
-// per slab instead of one plus one per tile, and most of their operand loads hit in that XCD's L2.
+// supertile (SUPER x SUPER tiles, the supertiles column by column over the triangle): a run of consecutive tile
+// indices, which is what one XCD works on at a time, then covers a compact patch of tiles that needs few row
+// blocks of X per slab, and most of its operand loads hit in that XCD's L2.
 constexpr int SUPER = 6;
 __device__ __forceinline__ void decode_tile(int t, int nt, int& bi, int& bj) {
   const int ns = (nt + SUPER - 1) / SUPER;
