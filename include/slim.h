@@ -229,7 +229,10 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
  *   Y        t_x x n fp32 (ldy >= n), overwritten
  *   beta     a multiple of 32 that divides m
- *   bit_base as given to slim_pack; 1 or 2 (widths up to 5), anything else is SLIM_ERR_UNSUPPORTED
+ *   bit_base as given to slim_pack; 1 or 2 (widths up to 5), anything else is SLIM_ERR_UNSUPPORTED.  A group whose
+ *            width (from gbits and bit_base) disagrees with its rows, (row_off[g+1] - row_off[g]) * 32 != beta * width,
+ *            is skipped (it adds nothing to Y): no read ever leaves the rows 0 .. row_off[k] - 1 that the stored form
+ *            declares, also when it is read with the wrong bit_base
  * Arithmetic: codes and activations are exact; per (row, group) sum (q - z) x in fp32 (for fp16 activations on
  * the matrix cores, with 2 (q - z) formed exactly in fp16), times the scale rounded to fp32; the sums of group
  * ranges are added in a fixed order (deterministic, no atomics).

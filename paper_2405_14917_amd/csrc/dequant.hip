@@ -116,6 +116,9 @@ __global__ __launch_bounds__(DQ_THREADS) void dequant_matmul(DqArgs a) {
     if (i < a.n) {
       const int b = (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + a.bit_base;
       const int base = a.row_off[g];
+      // a group whose start rows disagree with its width (a stored form read with the wrong bit_base, or a damaged
+      // one) is skipped: its words are never touched, so no read leaves the rows the stored form itself declares
+      if ((a.row_off[g + 1] - base) * 32 != a.beta * b) continue;
       const float s = (float)a.scale[(int64_t)i * a.k + g], z = (float)a.zero[(int64_t)i * a.k + g];
       float acc[T];
 #pragma unroll
@@ -278,9 +281,14 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
   const int nsub = a.beta / SUB, units = (g1 - g0) * nsub;
   auto width = [&](int g) { return (int)((a.gbits[g >> 4] >> (2 * (g & 15))) & 3u) + a.bit_base; };
   // fetch of unit u: the words of the lane's row
+  // 0 for a group whose start rows disagree with its width: such a group is skipped and none of its words is read
+  auto checked_width = [&](int g) {
+    const int b = width(g);
+    return ((a.row_off[g + 1] - a.row_off[g]) * 32 == a.beta * b) ? b : 0;
+  };
   auto fetch = [&](int u, unsigned (&w)[MAXW]) {
     const int g = g0 + u / nsub, sb = u - (u / nsub) * nsub;
-    const int nwu = SUB * width(g) / 32;
+    const int nwu = SUB * checked_width(g) / 32;
     const uint32_t* p = a.packed + (int64_t)(a.row_off[g] + sb * nwu) * a.ldp + row;
 #pragma unroll
     for (int i = 0; i < MAXW; ++i) w[i] = (i < nwu) ? p[(int64_t)i * a.ldp] : 0u;
@@ -303,7 +311,8 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
     zz[0] = zc;
     zz[1] = zc;
     const _Float16* xu = xs + (g - g0) * a.beta + sb * SUB;
-    switch (width(g)) {                            // the same for the whole workgroup
+    switch (checked_width(g)) {                    // the same for the whole workgroup
+      case 0: break;
       case 1: acc = subblock_mfma<1, SUB, MAXW>(wc, h, zz, xu, acc); break;
       case 2: acc = subblock_mfma<2, SUB, MAXW>(wc, h, zz, xu, acc); break;
       case 3: acc = subblock_mfma<3, SUB, MAXW>(wc, h, zz, xu, acc); break;

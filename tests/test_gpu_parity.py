@@ -554,6 +554,29 @@ def test_dequant_matmul_with_five_bit_groups(slim, beta, n, m, t_x, dtype):
     assert ei.value.status == binding.ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("dtype,t_x", [(torch.float16, 4), (torch.bfloat16, 2)])
+def test_dequant_matmul_skips_groups_whose_width_disagrees_with_their_rows(slim, dtype, t_x):
+    """A stored form read with the wrong width base: every group then claims more words than it has, none of them
+    is read, and the result is zero instead of a read past the stored rows."""
+    rng = np.random.default_rng(17)
+    beta, n, k = 64, 300, 8
+    m = k * beta
+    bits = np.array([1, 2, 3, 2, 1, 3, 2, 3], dtype=np.uint8)
+    codes = np.concatenate([rng.integers(0, 2 ** int(b), (n, beta)) for b in bits], axis=1).astype(np.uint8)
+    scale = np.abs(rng.standard_normal((n, k))) * 0.01 + 1e-3
+    zero = np.stack([rng.integers(0, 2 ** int(b), n).astype(np.float64) for b in bits], axis=1)
+    packed, gbits, row_off, _ = slim.pack(dev(codes), dev(bits), beta)
+    X = torch.from_numpy(rng.standard_normal((t_x, m))).to(dtype).cuda()
+    Y = host(slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, X, bit_base=2))
+    assert Y.shape == (t_x, n) and not Y.any()
+    # one consistent group among them is still multiplied: the stored widths of groups 0 .. 6 raised by hand
+    Yo = orc.dequant_matmul(host(packed).view(np.uint32), host(gbits).view(np.uint32), host(row_off), scale, zero, beta,
+                            X.double().cpu().numpy())
+    Yg = host(slim.dequant_matmul(packed, gbits, row_off, dev(scale), dev(zero), beta, X))
+    What = np.repeat(scale, beta, axis=1) * (codes - np.repeat(zero, beta, axis=1))
+    assert np.all(np.abs(Yg - Yo) <= 1e-5 * (np.abs(X.double().cpu().numpy()) @ np.abs(What).T) + 1e-30)
+
+
 def test_whole_pass_four_bit_target(slim):
     """Alg. 1 at N = 4 (App. G) through the driver of the timed pass, against the oracle's pass, and the linear layer
     on its stored form."""
