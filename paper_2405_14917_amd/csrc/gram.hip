@@ -18,8 +18,9 @@
 //    slots of a tile to G in a fixed order (deterministic, no floating-point atomics) and mirrors the upper
 //    triangle.
 //  * Balance: workgroups run one per CU in rounds of as many as the chip has CUs.  When the last round would be
-//    at most half full, the tiles in it are split further along K so that it is full of shorter workgroups
-//    (a 4096-wide Gram matrix has 136 tiles: 4.25 rounds of work instead of 5 rounds of time).
+//    at most half full, the tiles in it are split further along K so that it is full of shorter workgroups; S is
+//    the power of two for which a model of the rounds and of the reduction is shortest (a 4096-wide Gram matrix
+//    has 136 tiles: S = 2, one round of 128 tiles x 2 ranges and a round of 8 tiles cut 32 ways).
 #include <algorithm>
 
 #include "slim_internal.h"
@@ -607,11 +608,56 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   const int nt = slim_cdiv(m, TM);
   const int tiles = nt * (nt + 1) / 2;
   const int64_t iters = (t_c + BK - 1) / BK;
-  int S = 8;
-  while ((int64_t)tiles * S < 1024 && (int64_t)S * 2 * 4 <= iters) S *= 2;
-  if (S > iters) S = (int)iters;
-  const int64_t kchunk = ((iters + S - 1) / S) * BK;
-  S = (int)((t_c + kchunk - 1) / kchunk);
+  // Token ranges per tile: the number S (a power of two) for which a model of the launch is shortest.  A workgroup
+  // takes 1/S of a tile's time; n = tiles * S workgroups run in rounds of one per CU; the tiles of a last round that
+  // is at most half full are split f ways more, so that it is full of workgroups 1/f as long (m = 4096: 136 tiles,
+  // S = 2 gives one round plus 8 tiles cut 32 ways; m = 5120: 210 tiles, S = 4 gives 3 1/3 rounds where S = 1 or 2
+  // leave a fifth of the chip idle); every slot costs its 256 KB twice (written here, read by the reduction).
+  // Few ranges are better beyond the smaller reduction: each workgroup's fill and drain is paid once per range.
+  const int ncu = ctx->num_cus > 0 ? ctx->num_cus : 256;
+  struct Plan {
+    int S, tail_tiles, f;
+    int64_t kchunk, subchunk;
+    double cost;
+  };
+  auto plan_for = [&](int S_try) {
+    Plan p;
+    int S = (int)std::min<int64_t>(S_try, iters);
+    p.kchunk = ((iters + S - 1) / S) * BK;
+    S = (int)((t_c + p.kchunk - 1) / p.kchunk);
+    p.S = S;
+    const int64_t n_items = (int64_t)tiles * S;
+    const int64_t nsl = p.kchunk / BK;
+    p.tail_tiles = 0;
+    p.f = 1;
+    const int r = (int)(n_items % ncu);
+    if (n_items > ncu && r >= S && 2 * r <= ncu) {
+      p.tail_tiles = r / S;
+      p.f = (int)std::min<int64_t>(ncu / (p.tail_tiles * S), nsl);
+      if (p.f < 2) {
+        p.tail_tiles = 0;
+        p.f = 1;
+      }
+    }
+    p.subchunk = p.kchunk;
+    if (p.tail_tiles > 0) {
+      p.subchunk = ((nsl + p.f - 1) / p.f) * BK;
+      p.f = (int)((p.kchunk + p.subchunk - 1) / p.subchunk);   // every sub-split non-empty
+    }
+    const int64_t n_main = (int64_t)(tiles - p.tail_tiles) * S;
+    const double rounds = (double)((n_main + ncu - 1) / ncu) + (p.tail_tiles > 0 ? 1.0 / p.f : 0.0);
+    const int64_t slots = n_main + (int64_t)p.tail_tiles * S * p.f;
+    const double t_wg = 2.0 * TM * TM * (double)p.kchunk / 4.6e12;            // seconds per workgroup at 4.6 TFLOP/s per CU
+    p.cost = rounds * t_wg + (double)slots * TM * TM * sizeof(float) / 4.2e12;  // + the reduction's read of the slots
+    return p;
+  };
+  Plan best = plan_for(1);
+  for (int S_try = 2; S_try <= 1024 && (int64_t)S_try * 4 <= iters; S_try *= 2) {
+    const Plan p = plan_for(S_try);
+    if (p.cost < best.cost * 0.995) best = p;
+  }
+  const int S = best.S, tail_tiles = best.tail_tiles, f = best.f;
+  const int64_t kchunk = best.kchunk, subchunk = best.subchunk;
 
   GramArgs a;
   a.X = static_cast<const uint16_t*>(X);
@@ -620,25 +666,6 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.t = t_c;
   a.kchunk = kchunk;
   a.S = S;
-  // the tiles of a last round that is at most half full are split f ways more
-  const int ncu = ctx->num_cus > 0 ? ctx->num_cus : 256;
-  const int64_t n_items = (int64_t)tiles * S;
-  const int64_t nsl = kchunk / BK;
-  int tail_tiles = 0, f = 1;
-  const int r = (int)(n_items % ncu);
-  if (n_items > ncu && r >= S && 2 * r <= ncu) {
-    tail_tiles = r / S;
-    f = (int)std::min<int64_t>(ncu / (tail_tiles * S), nsl);
-    if (f < 2) {
-      tail_tiles = 0;
-      f = 1;
-    }
-  }
-  int64_t subchunk = kchunk;
-  if (tail_tiles > 0) {
-    subchunk = ((nsl + f - 1) / f) * BK;
-    f = (int)((kchunk + subchunk - 1) / subchunk);   // every sub-split non-empty
-  }
   a.tiles_main = tiles - tail_tiles;
   a.n_main = a.tiles_main * S;
   a.f = f;
