@@ -28,8 +28,8 @@ PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e
 # HBM bytes per launch measured with two `rocprofv3 --pmc` runs of this command (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for the 64 MiB copy below (FETCH_SIZE reads 32 MiB for it: factor 2.0;
 # WRITE_SIZE reads 64 MiB: factor 1.0); see profiles/dgemm_gram_C2_hbm_traffic.md.  Keyed by (config, kernel).
-TRAFFIC_BYTES = {("C2", "gram_kernel_full<false>"): 2.0 * 3.813e6 * 1024 + 1.0 * 3.149e5 * 1024,
-                 ("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.384e5 * 1024 + 1.0 * 9.011e4 * 1024}
+TRAFFIC_BYTES = {("C2", "gram_kernel_full<false>"): 2.0 * 4.108e6 * 1024 + 1.0 * 1.233e5 * 1024,
+                 ("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.379e5 * 1024 + 1.0 * 9.011e4 * 1024}
 T_SBA = 2048
 
 
