@@ -11,9 +11,9 @@
 //    the next slab is fetched into registers while the current one is multiplied; rows are padded to
 //    72 halves so that the 16-byte operand reads of consecutive rows fall into different banks.
 //  * Split-K: every tile is cut into S token ranges.  Workgroup ids run over the tiles fastest, so the chip works
-//    on one or two token ranges at a time (HBM is read about once; the XCDs share through the memory-side cache),
-//    and the workgroups dealt to one XCD (id mod 8) form a compact set of tiles that shares row blocks of X in
-//    that XCD's L2 (decode_work).
+//    on one or two token ranges at a time and all XCDs stream through the same narrow band of X together, and the
+//    workgroups dealt to one XCD (id mod 8) form a compact set of tiles that shares row blocks of X in that
+//    XCD's L2 (decode_work).
 //  * Every workgroup writes its partial 256 x 256 tile to a slot of a scratch buffer; a second kernel adds the
 //    slots of a tile to G in a fixed order (deterministic, no floating-point atomics) and mirrors the upper
 //    triangle.
@@ -55,11 +55,11 @@ struct GramArgs {
 // Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  The slots of one
 // tile are contiguous.  Workgroup ids run over the tiles fastest and the token ranges slowest: the workgroups that
 // are on the chip at the same time then cover every tile for one or two token ranges, so the chip as a whole reads
-// a narrow band of X at a time (what one XCD has fetched the others find in the memory-side cache, and HBM is read
-// about once), and XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact
-// set that shares its row blocks in that XCD's L2.  With the token range fastest instead (every XCD on a range of
-// its own) each round of workgroups fetched nearly all of X again: 5.4 x the size of X from memory per launch at
-// m = 4096, and the kernel, which is limited by power, ran 4 % (m = 4096) to 10 % (m = 11008) slower.
+// a narrow band of X at a time (the eight XCDs ask the memory side for the same lines at about the same time), and
+// XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact set that shares
+// its row blocks in that XCD's L2.  With the token range fastest instead (every XCD on a range of its own, the
+// requests of a moment spread over all of X) the kernel, which is limited by power, ran 4 % (m = 4096) to 10 %
+// (m = 11008) slower, although its L2s requested less.
 struct WorkItem {
   int tile;
   int64_t kbeg, kend;
