@@ -30,6 +30,9 @@ pin can decide are marked "parity unpinned" here:
   (BLOCK / ROW), the salience denominator (diag of H^-1 vs diag of its Cholesky
   factor) and the token subset used by the SBA objective.  Each is a mode switch
   with the same default on both sides; the formula of each mode is pinned.
+  Likewise the bit order inside the packed words and the meaning of the 2-bit group
+  value (width minus bit_base, bit_base_for(N)): App. B.2 gives the structure only;
+  the layout written here is pinned by hand-worked words and round trips.
 """
 from __future__ import annotations
 
