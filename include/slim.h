@@ -205,7 +205,7 @@ slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype,
  *              row_off[g] .. of column i.  No padding, no word mixes two widths.
  *   gbits      ceil(k/16) words: bits[g] - bit_base as a 2-bit value, 16 groups per word, least significant first
  *   bit_base   the width that the value 0 stands for.  A layer of target width N holds the widths N - 1, N, N + 1
- *              only (Eq. 5), so three of the four values are ever used: 1 for the targets 2 and 3 (widths 1..4);
+ *              only (constraint of Eq. 4), so three of the four values are ever used: 1 for the targets 2 and 3 (widths 1..4);
  *              N - 2 above them (2 for the 4-bit setting of App. G, widths 3..5).  It belongs to the stored form:
  *              a reader needs the same value.
  *   packed_rows  capacity of `packed` in rows; if m_star exceeds it the call fails with

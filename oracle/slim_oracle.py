@@ -478,7 +478,7 @@ def reconstruction_error(W: np.ndarray, What: np.ndarray, G: np.ndarray) -> floa
 # ----------------------------------------------------------------------------------------
 def bit_base_for(N: int) -> int:
     """The width that the 2-bit group value 0 stands for (App. B.2 gives the value 2 bits).  A layer of target
-    width N holds the widths N - 1, N, N + 1 only (the constraint of Eq. 5), so three of the four values are
+    width N holds the widths N - 1, N, N + 1 only (the constraint of Eq. 4), so three of the four values are
     ever used: value = width - 1 covers the targets 2 and 3 (widths 1..4); above them (the 4-bit setting of
     App. G) the values count from N - 2, which maps N - 1, N, N + 1 to 1, 2, 3 for every target."""
     return max(1, int(N) - 2)

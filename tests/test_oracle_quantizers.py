@@ -174,6 +174,38 @@ def test_sqc_weight_modes_reduce_to_uniform():
     assert np.array_equal(ce, c1)
 
 
+def test_sqc_element_weights_by_hand():
+    """ELEMENT loss weights are the element salience of Def. 1, omega_j = w_j^2 / d_j^2 with d = diag(H^-1):
+    numbers worked by hand with a non-constant w and a non-unit d, so that a wrong exponent on either fails."""
+    w = np.array([0.5, -1.0, 2.0, 0.25])
+    d = np.array([0.5, 2.0, 1.0, 0.25])
+    # w^2 = [0.25, 1, 4, 0.0625];  d^2 = [0.25, 4, 1, 0.0625]
+    assert orc.sqc_weights(w, None, orc.WEIGHT_ELEMENT, d).tolist() == [1.0, 0.25, 4.0, 1.0]
+    blk = np.stack([w, 2.0 * w])
+    assert orc._omega_rows(blk, orc.WEIGHT_ELEMENT, orc.SCOPE_BLOCK, d).tolist() == [[1.0, 0.25, 4.0, 1.0],
+                                                                                    [4.0, 1.0, 16.0, 4.0]]
+    # the loss of the tau = 1 candidate at 2 bits: range [-1, 2], delta0 = 1, z = 1;
+    # round(w) = [0 (tie to even), -1, 2, 0] -> q = [1, 0, 3, 1] -> w_hat = [0, -1, 2, 0]; errors [0.5, 0, 0, 0.25]
+    # L = 1.0 * 0.25 + 1.0 * 0.0625 = 0.3125   (w^2/d would give 0.140625, |w|/d^2 0.75, uniform 0.3125 + 0 ...)
+    tau = orc.tau_grid()
+    om = orc.sqc_weights(w, None, orc.WEIGHT_ELEMENT, d)
+    _, z, _, losses = orc.sqc_search(w, 2, tau, om)
+    assert z == 1.0 and losses[50] == 0.3125
+    # a second vector where the weights change the winner: the heavy element decides the step
+    w2 = np.array([0.0, 0.3, 0.6, 0.95, 3.0, 1.5, 2.1, 2.7])
+    d2 = np.array([1.0, 1.0, 1.0, 0.05, 1.0, 1.0, 1.0, 1.0])
+    om2 = orc.sqc_weights(w2, None, orc.WEIGHT_ELEMENT, d2)
+    assert om2[3] == pytest.approx(0.95 ** 2 / 0.05 ** 2, rel=1e-15)
+    s_e, _, c_e, L_e = orc.sqc_search(w2, 2, tau, om2)
+    s_u, _, c_u, L_u = orc.sqc_search(w2, 2, tau, np.ones(8))
+    # element 3 carries 361 of the weight: its error (0.95 - q * delta)^2 must be near its minimum at the winner
+    e3 = np.array([(0.95 - t * np.clip(np.rint(0.95 / t), 0, 3)) ** 2 for t in tau])
+    assert e3[c_e] <= e3.min() + 1e-4 and c_e != c_u
+    # and through the block interface, with d handed over per column
+    se, ze, ce, _ = orc.sqc_calibrate(np.stack([w2, w2]), 2, tau, orc.WEIGHT_ELEMENT, d=d2)
+    assert ce.tolist() == [c_e, c_e] and se[0] == s_e
+
+
 def test_sqc_mask_mean_by_hand():
     # one masked element with a large error dominates under MASK_MEAN, not under UNIFORM
     w = np.array([0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 3.0])

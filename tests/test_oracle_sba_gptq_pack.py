@@ -260,8 +260,20 @@ def test_pipeline_c1_properties():
     assert np.argmax(out["group_sal"]) in set((ch // cfg.beta).tolist())
     codes2, bits2 = orc.unpack(out["packed"], out["gbits"], cfg.beta, cfg.k)
     assert np.array_equal(codes2, out["codes"]) and np.array_equal(bits2, bits)
-    # every group's SQC result is at least as good as its tau = 1 candidate (L* <= L(min-max))
+    # every group's SQC result is at least as good as its tau = 1 candidate (L* <= L(min-max)).  The weights a
+    # group is calibrated on are the original ones minus the compensation of all earlier columns (W - W_hat = E U)
     assert np.all(out["cand_idx"] >= 0) and np.all(out["cand_idx"] < 100)
+    tau = orc.tau_grid()
+    W64 = W.astype(np.float64)
+    for g in range(cfg.k):
+        b0 = g * cfg.beta
+        cur = W64[:, b0:b0 + cfg.beta] - out["E"][:, :b0] @ out["U"][:b0, b0:b0 + cfg.beta]
+        mask = orc.block_mask(cur)
+        for i in range(0, cfg.n, 17):
+            om = orc.sqc_weights(cur[i], mask[i], orc.WEIGHT_MASK_MEAN)
+            _, _, c, losses = orc.sqc_search(cur[i], int(bits[g]), tau, om)
+            assert c == out["cand_idx"][i, g]
+            assert losses[c] <= losses[50]
 
 
 # ----------------------------------------------------------------------------- storage ---
