@@ -1,10 +1,14 @@
 """Benchmark of the whole per-layer quantisation pass (all seven entry points, a1 .. a9) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C3] [--no-cpu-baseline] [--also C2,C4,C5]
 
 A step is one complete pass over one synthetic layer: Hessian accumulation over all calibration
 tokens, damped inverse + Cholesky factor, salience, SBA, SQC + GPTQ sweep, packing.  Inputs (W, X)
 are resident in HBM before the timed region.  Prints ONE JSON line.
+
+The default workload is the target of the build: the LLaMA-7B down_proj shaped layer (4096 x 11008, 128 x 2048
+calibration tokens, 2 bits on average).  The other full-size configurations are timed briefly afterwards and
+reported beside the metric under `other_configs` (a few steps each, no per-kernel figures).
 """
 from __future__ import annotations
 
@@ -25,12 +29,18 @@ import torch
 from paper_2405_14917_amd import binding, pipeline, synth
 
 PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e12}
-# HBM bytes per launch measured with two `rocprofv3 --pmc` runs of this command (FETCH_SIZE, WRITE_SIZE), each
-# scaled by what the same counter reads for the 64 MiB copy below (FETCH_SIZE reads 32 MiB for it: factor 2.0;
-# WRITE_SIZE reads 64 MiB: factor 1.0); see profiles/dgemm_gram_C2_hbm_traffic.md.  Keyed by (config, kernel).
-TRAFFIC_BYTES = {("C2", "gram_kernel_full<false>"): 2.0 * 4.108e6 * 1024 + 1.0 * 1.233e5 * 1024,
-                 ("C2", "dgemm_kernel<0, 128, 128>"): 2.0 * 1.379e5 * 1024 + 1.0 * 9.011e4 * 1024}
+# HBM bytes per launch of the dominant kernel function, from two `rocprofv3 --pmc` runs of this command (FETCH_SIZE,
+# then WRITE_SIZE, in KiB per dispatch), each scaled by what the same counter reads for the 64 MiB copy that this
+# program issues for that purpose; the files under profiles/ that are named here give the commands and the readings.
+# Keyed by (config, kernel function); a configuration without such a run reports null.
+TRAFFIC_BYTES = {
+    # profiles/gram_C2_hbm_traffic.md
+    ("C2", "gram_kernel_full<false>"): 2.0 * 4.108e6 * 1024 + 1.0 * 1.233e5 * 1024,
+}
+SHAPE_NAMES = {"C1": "tiny layer", "C2": "LLaMA-7B q_proj shaped layer", "C3": "LLaMA-7B down_proj shaped layer",
+               "C4": "LLaMA-13B up_proj shaped layer", "C5": "LLaMA-70B-shaped MLP layer"}
 T_SBA = 2048
+INV_GRP = 4          # diagonal blocks of 64 columns per group of the factorisation (csrc/inverse.hip)
 
 
 def resident_inputs(cfg):
@@ -77,79 +87,106 @@ class Pass(pipeline.LayerPass):
         return e0.elapsed_time(e1) * 1e3 / reps, nbytes
 
 def algorithmic_work(name, cfg, launches_per_step):
-    """(bound, peak key, work per launch) for the kernels that can dominate a step.  Work is
-    ALGORITHMIC: distinct results only (e.g. the Gram matrix is credited with its triangle)."""
+    """(bound, peak key, work per launch) for every step of the path.  Work is ALGORITHMIC: distinct results
+    only (the Gram matrix is credited with its triangle), bytes that have to move at least once.  `bound` is the
+    roof that binds the step: "mfma" (flops), "alu" (flops of plain vector arithmetic), "hbm" (bytes), or
+    "latency" for the serial chain of diagonal blocks, which is rated as microseconds per link x links."""
     n, m, t, beta = cfg.n, cfg.m, cfg.t, cfg.beta
     k = m // beta
     ts = min(T_SBA, t)
+    L = max(launches_per_step, 1)
     if name.startswith("gram_mfma"):
-        return "mfma", "mfma_f16", float(m) * (m + 1) * t / launches_per_step
+        return "mfma", "mfma_f16", float(m) * (m + 1) * t / L
     if name == "sba_output_dgemm":
-        # two products per step (reference outputs, outputs of the all-N-bit weights), in one launch or two
-        return "mfma", "mfma_f64", 2.0 * (2.0 * n * m * ts) / max(launches_per_step, 1)
+        # two products per step (reference outputs, outputs of the all-N-bit weights), in one launch or several
+        return "mfma", "mfma_f64", 2.0 * (2.0 * n * m * ts) / L
     if name == "sba_update_dgemm":
         return "mfma", "mfma_f64", 4.0 * n * beta * ts
     if name == "sba_search":
         # the k/2 rank-2beta updates of the search, in one kernel
-        return "mfma", "mfma_f64", (k // 2) * 4.0 * n * beta * ts / max(launches_per_step, 1)
+        return "mfma", "mfma_f64", (k // 2) * 4.0 * n * beta * ts / L
     if name == "gptq_trailing_dgemm":
         # rank-512 update of the columns behind each window of 512 columns
         tot = sum(2.0 * n * (min(m, w0 + 512) - w0) * (m - min(m, w0 + 512)) for w0 in range(0, m, 512))
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
+        return "mfma", "mfma_f64", tot / L
     if name == "gptq_window_dgemm":
         sb = min(beta, 128)
         tot = sum(2.0 * n * sb * (min(m, (b0 // 512) * 512 + 512) - b0 - sb) for b0 in range(0, m, sb))
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
-    if name == "inv_window_dgemm":
-        # rank-64 update of the columns between the start of the group of block J-1 and block J, rows above J-1
-        tot = sum(2.0 * (j0 - 64) * (j0 - ((j0 // 64 - 1) // 4) * 256) * min(64, m - j0) for j0 in range(128, m, 64))
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
-    if name == "inv_group_next_dgemm":
-        tot = sum(2.0 * g0 * 256 * (min(m, g0 + 256) - g0 - 64) for g0 in range(256, m, 256) if min(m, g0 + 256) - g0 > 64)
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
-    if name == "inv_syrk_dgemm":
-        tot = sum(float(g0 - 256) * (g0 - 255) * (min(m, g0 + 256) - g0) for g0 in range(512, m, 256))
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
-    if name == "inv_trtri_dgemm":
-        return "mfma", "mfma_f64", float(m) ** 3 / 3.0 / max(launches_per_step, 1)
-    if name == "inv_panel_dgemm":
-        tot = sum(2.0 * j0 * 64 * 64 / 2 for j0 in range(64, m, 64))
-        return "mfma", "mfma_f64", tot / max(launches_per_step, 1)
+        return "mfma", "mfma_f64", tot / L
+    if name.startswith("inv_") and name.endswith("_dgemm"):
+        # The factorisation and the triangular inverse together are (2/3) m^3 flops; the launch sites share them
+        # as follows (each formula counts what that site's products compute, triangles once).
+        if name == "inv_trtri_dgemm":
+            tot = float(m) ** 3 / 3.0
+        elif name == "inv_panel_dgemm":
+            tot = sum(2.0 * j0 * 64 * 64 / 2 for j0 in range(64, m, 64))
+        elif name == "inv_window_dgemm":
+            tot = sum(2.0 * (j0 - 64) * (j0 - ((j0 // 64 - 1) // INV_GRP) * INV_GRP * 64) * min(64, m - j0)
+                      for j0 in range(128, m, 64))
+        elif name == "inv_group_next_dgemm":
+            w = INV_GRP * 64
+            tot = sum(2.0 * g0 * w * (min(m, g0 + w) - g0 - 64) for g0 in range(w, m, w) if min(m, g0 + w) - g0 > 64)
+        elif name == "inv_syrk_dgemm":
+            w = INV_GRP * 64
+            tot = sum(float(g0 - w) * (g0 - w + 1) * (min(m, g0 + w) - g0) for g0 in range(2 * w, m, w))
+        else:
+            tot = 0.0
+        return "mfma", "mfma_f64", tot / L
+    if name == "inv_chol_diag":
+        return "latency", None, 0.0                                   # m / 64 dependent diagonal blocks
     if name == "sqc_search":
         return "alu", "alu_f64", 9.0 * cfg.ncand * n * beta          # ~9 fp64 operations per weight and candidate
     if name == "gptq_sweep":
         return "alu", "alu_f64", float(n) * beta * beta              # rank-1 updates inside the group
-    if name == "sba_kl_step":
-        return "hbm", "hbm", 2.0 * 8 * n * ts      # one pass over P and the candidate's outputs
-    if name == "salience_colsumsq":
-        return "hbm", "hbm", 2.0 * n * m
-    if name == "pack_codes":
-        return "hbm", "hbm", n * m * (1.0 + cfg.N / 8.0)
-    if name == "gram_reduce":
-        return "hbm", "hbm", 4.0 * m * m
+    hbm = {
+        "sba_kl_step": 2.0 * 8 * n * ts,                 # one pass over P and the candidate's outputs
+        "salience_colsumsq": 2.0 * n * m,                # W once (16-bit)
+        "pack_codes": n * m * (1.0 + cfg.N / 8.0),       # codes in, words out
+        "gram_reduce": 4.0 * m * m,                      # G once
+        "inv_widen": 10.0 * m * m,                       # upper half of G in (4 B), upper A and lower U out (8 B each)
+        "inv_diag_colsumsq": 4.0 * m * m,                # upper triangle of U (8 B) once
+        "gptq_widen": 10.0 * n * m / L,                  # W (16-bit) in, fp64 working copy out
+        "sba_widen_w": 10.0 * n * m,
+        "sba_widen_x": 10.0 * m * ts,
+        "sba_fakequant": 16.0 * n * m,                   # fp64 weights in, fake-quantised fp64 weights out
+        "sba_gather_x": 16.0 * (k // 2) * 2 * beta * ts,
+        "sba_kl_ref": 4.0 * 8 * n * ts / L,              # the reference outputs: read twice, written once, read once
+        "sqc_block_stats": 8.0 * n * beta,
+    }
+    if name in hbm:
+        return "hbm", "hbm", hbm[name]
     return "hbm", "hbm", 0.0
 
 
 def cpu_baseline(cfg):
-    """The oracle as it stands, timed on this host on a bounded sample of the same layer and scaled to
-    the full layer by each stage's own size dependence."""
+    """The oracle as it stands, timed on this host on a bounded sample of the same layer (about 20 s of host work)
+    and scaled to the full layer by each stage's own size dependence."""
     from oracle import slim_oracle as orc
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count() or 1
-    n_s = min(cfg.n, 2048)                        # about 10 s of host work on C2
-    t_gram = min(cfg.t, 4 * synth.CHUNK_TOKENS)
+    # sample sizes: rows of W, tokens for the Gram matrix, leading block of G for the inverse (cubic scaling)
+    n_s = min(cfg.n, 2048 if cfg.m <= 4096 else (512 if cfg.m <= 8192 else 256))
+    t_gram = min(cfg.t, (4 if cfg.m <= 4096 else 1) * synth.CHUNK_TOKENS)
+    m_inv = min(cfg.m, 4096)
     W = synth.make_weights(cfg)[:n_s].astype(np.float64)
-    X0 = np.concatenate([synth.activation_chunk(cfg, c) for c in range(min(4, synth.n_chunks(cfg)))], axis=1)
+    X0 = np.concatenate([synth.activation_chunk(cfg, c) for c in range(t_gram // synth.CHUNK_TOKENS or 1)], axis=1)
     tm = {}
     t0 = time.perf_counter()
     G = np.zeros((cfg.m, cfg.m))
     orc.gram_accumulate(G, X0[:, :t_gram])
     tm["gram"] = (time.perf_counter() - t0) * (cfg.t / t_gram)
     t0 = time.perf_counter()
-    U, d, _ = orc.hessian_inverse(G, t_gram, cfg.percdamp)
-    tm["inverse"] = time.perf_counter() - t0
+    orc.hessian_inverse(G[:m_inv, :m_inv], t_gram, cfg.percdamp)
+    tm["inverse"] = (time.perf_counter() - t0) * (cfg.m / m_inv) ** 3
+    # second-order information for the later stages: exact for the sampled leading block, a damped diagonal beyond
+    # it (the later stages' cost does not depend on the values)
+    if m_inv < cfg.m:
+        Hd = 2.0 / t_gram * np.diag(G) + cfg.percdamp * 2.0 / t_gram * np.mean(np.diag(G))
+        U, d = np.diag(Hd ** -0.5), 1.0 / Hd
+    else:
+        U, d, _ = orc.hessian_inverse(G, t_gram, cfg.percdamp)
     rows = cfg.n / n_s
     t0 = time.perf_counter()
     _, grp, _ = orc.salience(W, d, cfg.beta)
@@ -166,11 +203,29 @@ def cpu_baseline(cfg):
     total = sum(tm.values())
     return {
         "value": cfg.n * cfg.m / total, "unit": "weights/s", "cores": cores, "kind": "oracle",
-        "sample": "Gram on %d of %d tokens (x%.0f), inverse at full size, salience/SBA/SQC+GPTQ/pack on %d of %d "
-                  "rows (x%.0f); scaled seconds per stage: %s" % (
-                      t_gram, cfg.t, cfg.t / t_gram, n_s, cfg.n, rows,
+        "sample": "Gram on %d of %d tokens (x%.0f), inverse of the leading %d x %d block (x%.1f, cubic), "
+                  "salience/SBA/SQC+GPTQ/pack on %d of %d rows (x%.0f); scaled seconds per stage: %s" % (
+                      t_gram, cfg.t, cfg.t / t_gram, m_inv, m_inv, (cfg.m / m_inv) ** 3, n_s, cfg.n, rows,
                       ", ".join("%s %.1f" % kv for kv in tm.items())),
     }
+
+
+def workload_text(cfg):
+    return ("%s: %s W %dx%d %s, X %dx%d f16 (%d calibration tokens), group %d, %d-bit average, 1%% damping, "
+            "%d SQC candidates, SBA objective on %d tokens" % (
+                cfg.name, SHAPE_NAMES.get(cfg.name, "layer"), cfg.n, cfg.m, cfg.w_dtype, cfg.m, cfg.t, cfg.t, cfg.beta,
+                cfg.N, cfg.ncand, min(T_SBA, cfg.t)))
+
+
+def timed_steps(job, steps, warmup):
+    for _ in range(warmup):
+        job.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        p_star, m_star = job.step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps, int(p_star), int(m_star)
 
 
 def main():
@@ -178,10 +233,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="C2", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--config", default="C3", choices=sorted(synth.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--no-shared-input", action="store_true", help="skip the three-layer figure beside the metric")
+    ap.add_argument("--also", default="C2,C4,C5",
+                    help="other configurations to time briefly beside the metric (comma separated, '' for none)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the pass is a single-GPU job); run with --gpus 1")
@@ -198,14 +255,7 @@ def main():
     calib_dst.copy_(calib_src)
     del calib_dst
 
-    for _ in range(args.warmup):
-        job.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        p_star, m_star = job.step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step, p_star, m_star = timed_steps(job, args.steps, args.warmup)
 
     # per-kernel durations with HIP events on the library's stream, in extra steps of the same job
     for c in job.contexts():
@@ -220,9 +270,10 @@ def main():
             prof[full] = (a[0] + ms, a[1] + cnt)
         c.profile_enable(False)
     # A profiling entry is named "<step>" or "<step>@<kernel function>" (launch sites that choose among several
-    # kernel functions say which one ran).  `kernels` is keyed by step; the roofline is given for the kernel
-    # FUNCTION with the largest share of the GPU time, under the name rocprofv3 lists it by, so that its average
-    # duration can be compared with the rocprofv3 summary of the same command (profiles/).
+    # kernel functions say which one ran), with "#side" appended for launches on the library's side streams.
+    # `kernels` is keyed by step.  The roofline is given for the kernel FUNCTION with the largest share of the GPU
+    # time among ALL functions (side streams and the persistent reserved forms included), under the name rocprofv3
+    # lists it by, so that its average duration can be compared with the rocprofv3 summary of the same command.
     kernels, functions = {}, {}
     for full, (ms, cnt) in prof.items():
         full, _, side = full.partition("#")
@@ -244,29 +295,39 @@ def main():
             # a step that ran on several kernel functions is credited to them in proportion to their time
             f["work"] += k["work_per_step"] * args.profile_steps * (ms / k["ms"] if k["ms"] > 0 else 0.0)
     roofline = None
-    # Launches on the library's side streams ("#side") and the persistent "reserved" GEMM forms run beside another
-    # stream's chain of kernels by design: their durations overlap that work instead of adding to the step, so
-    # they do not compete for the place of the dominant function (they are listed in `kernels` like the rest).
-    rated = {fn: f for fn, f in functions.items()
-             if f["work"] > 0 and not fn.startswith("dgemm_reserved") and not fn.endswith("#side")}
-    if rated:
-        dom = max(rated, key=lambda fn: rated[fn]["ms"])
-        f = rated[dom]
-        achieved = f["work"] / (f["ms"] * 1e-3)
-        unit = {"mfma": "TFLOP/s", "alu": "TFLOP/s", "hbm": "GB/s"}[f["bound"]]
-        div = 1e9 if f["bound"] == "hbm" else 1e12
-        roofline = {"kernel": dom, "bound": f["bound"], "achieved": achieved / div, "peak": PEAK[f["peak_key"]] / div,
-                    "unit": unit, "frac": achieved / PEAK[f["peak_key"]], "traffic": TRAFFIC_BYTES.get((cfg.name, dom)),
-                    "avg_us": 1e3 * f["ms"] / f["cnt"], "launches_per_step": f["cnt"] / args.profile_steps,
-                    "ms_per_step": f["ms"] / args.profile_steps}
-    # the other rooflines the metric names, for the record (per step of the path)
-    others = {}
-    for name, k in kernels.items():
-        if k["work_per_step"] > 0:
-            others[name] = {"ms_per_step": round(k["ms_per_step"], 4), "bound": k["bound"],
-                            "frac": round(k["work_per_step"] / (k["ms_per_step"] * 1e-3) / PEAK[k["peak_key"]], 4)}
+    if functions:
+        dom = max(functions, key=lambda fn: functions[fn]["ms"])
+        f = functions[dom]
+        if f["bound"] == "latency":
+            roofline = {"kernel": dom, "bound": "latency", "achieved": None, "peak": None, "unit": "us per link",
+                        "frac": None, "traffic": None, "avg_us": 1e3 * f["ms"] / f["cnt"],
+                        "launches_per_step": f["cnt"] / args.profile_steps, "ms_per_step": f["ms"] / args.profile_steps}
         else:
-            others[name] = {"ms_per_step": round(k["ms_per_step"], 4)}
+            achieved = f["work"] / (f["ms"] * 1e-3)
+            unit = {"mfma": "TFLOP/s", "alu": "TFLOP/s", "hbm": "GB/s"}[f["bound"]]
+            div = 1e9 if f["bound"] == "hbm" else 1e12
+            roofline = {"kernel": dom.partition("#")[0], "bound": f["bound"], "achieved": achieved / div,
+                        "peak": PEAK[f["peak_key"]] / div, "unit": unit, "frac": achieved / PEAK[f["peak_key"]],
+                        "traffic": TRAFFIC_BYTES.get((cfg.name, dom.partition("#")[0])),
+                        "avg_us": 1e3 * f["ms"] / f["cnt"], "launches_per_step": f["cnt"] / args.profile_steps,
+                        "ms_per_step": f["ms"] / args.profile_steps}
+    # every step of the path for the record: time, the roof that binds it, the fraction of that roof, and the time
+    # the step would take at the roof (its floor).  The chain of diagonal blocks is rated by its latency.
+    others, floor_ms = {}, 0.0
+    for name, k in kernels.items():
+        entry = {"ms_per_step": round(k["ms_per_step"], 4), "launches_per_step": k["launches_per_step"],
+                 "bound": k["bound"]}
+        if k["bound"] == "latency":
+            entry["latency"] = {"us_per_link": round(k["avg_us"], 2), "links": k["launches_per_step"]}
+        elif k["work_per_step"] > 0:
+            floor = k["work_per_step"] / PEAK[k["peak_key"]] * 1e3
+            floor_ms += floor
+            entry["floor_ms"] = round(floor, 4)
+            entry["frac"] = round(floor / k["ms_per_step"], 4)
+        others[name] = entry
+    whole_pass = {"sum_of_floors_ms": floor_ms, "frac": floor_ms / ms_per_step,
+                  "note": "sum over the steps of (algorithmic work / peak of the roof that binds the step) against "
+                          "the measured ms_per_step; the alu entries count an FMA as two operations"}
 
     line = {
         "metric": "weights_quantized_per_s", "value": cfg.n * cfg.m / (ms_per_step * 1e-3), "unit": "weights/s",
@@ -274,11 +335,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 x f16 -> f32 (Gram MFMA), f64 (inverse, salience, SBA, SQC, GPTQ sweep), u8/u32 (pack)",
         "data": "synthetic",
-        "config": {"workload": "%s: LLaMA-7B q_proj shaped layer W %dx%d %s, X %dx%d f16, group %d, %d-bit average, "
-                               "1%% damping, 100 SQC candidates, SBA objective on %d tokens" % (
-                                   cfg.name, cfg.n, cfg.m, cfg.w_dtype, cfg.m, cfg.t, cfg.beta, cfg.N, min(T_SBA, cfg.t)),
-                   "p_star": int(p_star), "m_star": int(m_star)},
+        "config": {"workload": workload_text(cfg), "p_star": p_star, "m_star": m_star},
         "roofline": roofline,
+        "whole_pass": whole_pass,
         "kernels": others,
     }
     # beside the metric: the inference kernel of the stored form (next step of the path, not part of `value`)
@@ -297,11 +356,28 @@ def main():
         torch.cuda.synchronize()
         line["shared_input"] = {"layers": 3, "ms_per_layer": (time.perf_counter() - t0) * 1e3 / (3 * shared_reps),
                                 "note": "one Gram matrix and one inverse for three layers of the step's shape"}
+    job.close()
+    del job, W, X, calib_src
+    torch.cuda.empty_cache()
+    # the other full-size configurations, a few steps each
+    other_cfgs = {}
+    for name in [c for c in args.also.split(",") if c and c != cfg.name]:
+        if name not in synth.CONFIGS:
+            sys.exit("bench.py: unknown configuration %r in --also" % name)
+        oc = synth.CONFIGS[name]
+        Wo, Xo = resident_inputs(oc)
+        ojob = Pass(slim, oc, Wo, Xo)
+        ms, ps, mst = timed_steps(ojob, 3, 1)
+        other_cfgs[name] = {"workload": workload_text(oc), "ms_per_step": ms, "value": oc.n * oc.m / (ms * 1e-3),
+                            "unit": "weights/s", "steps": 3, "warmup": 1, "p_star": ps, "m_star": mst}
+        ojob.close()
+        del ojob, Wo, Xo
+        torch.cuda.empty_cache()
+    line["other_configs"] = other_cfgs
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:
         line["cpu_baseline"] = None
-    job.close()
     slim.close()
     print(json.dumps(line))
 
