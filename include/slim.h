@@ -244,6 +244,25 @@ slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t l
                                 float* Y, int64_t ldy);
 
 /* ---------------------------------------------------------------------------------------------
+ * slim_dequant_matmul for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and launch shapes, bit for bit the same Y;
+ * the partial sums of the group ranges go to a fixed buffer of SLIM_DEQUANT_NOALLOC_MAX_FLOATS floats (16 MiB) that
+ * every GPU the library runs on holds from the time its code is loaded there until the process ends, instead of the
+ * context's workspace.  The call allocates and frees nothing (no hipMalloc, no hipFree, no events; per-kernel timing
+ * is off for its length).
+ *   A layer needs (group ranges) x t_x x n floats, where the number of group ranges is chosen to fill the chip
+ *   (about 8 x CUs / ceil(n / 128), at most k, one when that product is 1: then the buffer is not used).  If that
+ *   exceeds the buffer the call returns SLIM_ERR_UNSUPPORTED and touches nothing; the error text gives the figures.
+ *   All contexts on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two streams) race.
+ *   Nothing in it has to be zero before a call; every value read is written by the same call first.
+ */
+#define SLIM_DEQUANT_NOALLOC_MAX_FLOATS ((size_t)4 << 20)
+slim_status slim_dequant_matmul_noalloc(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
+                                        const int32_t* row_off, const double* scale, const double* zero, int n,
+                                        int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
+                                        int64_t ldx, float* Y, int64_t ldy);
+
+/* ---------------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the context's stream (measurement aid, host only).
  * While enabled, every kernel launch of the library is bracketed by an event pair.
  * An entry is named after the step of the path ("sba_output_dgemm"), followed by "@" and the kernel function

@@ -29,6 +29,7 @@ EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
     "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
+    "slim_dequant_matmul_noalloc",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -90,6 +91,7 @@ def load() -> ctypes.CDLL:
                                        c_void_p, c_void_p, c_int, c_void_p]
     lib.slim_dequant_matmul.argtypes = [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
                                         c_int, c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
+    lib.slim_dequant_matmul_noalloc.argtypes = lib.slim_dequant_matmul.argtypes
     lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_int, c_void_p, c_i64,
                               c_void_p, c_void_p, P(c_int)]
     lib.slim_profile_enable.argtypes = [c_void_p, c_int]
@@ -296,14 +298,16 @@ class Slim:
     # ---- n1
     def dequant_matmul(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,
                        zero: torch.Tensor, beta: int, X: torch.Tensor, Y: Optional[torch.Tensor] = None,
-                       bit_base: int = 1):
-        """Y (t_x, n) float32 = X (t_x, m) float16 / bfloat16 times the dequantised weights, from the stored form."""
+                       bit_base: int = 1, noalloc: bool = False):
+        """Y (t_x, n) float32 = X (t_x, m) float16 / bfloat16 times the dequantised weights, from the stored form.
+        noalloc=True calls slim_dequant_matmul_noalloc (Y must then be passed in, so that nothing is allocated)."""
         _need_cuda(packed, gbits, row_off, scale, zero, X)
         n = packed.shape[1]
         t_x, m = X.shape
         assert scale.dtype == torch.float64 and zero.dtype == torch.float64 and scale.stride(0) == m // beta
         Y = torch.empty((t_x, n), dtype=torch.float32, device=X.device) if Y is None else Y
-        self._check(self.lib.slim_dequant_matmul(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
+        fn = self.lib.slim_dequant_matmul_noalloc if noalloc else self.lib.slim_dequant_matmul
+        self._check(fn(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
                                                  _ptr(scale), _ptr(zero), n, m, beta, bit_base, _ptr(X), _DT[X.dtype], t_x,
                                                  X.stride(0), _ptr(Y), Y.stride(0)))
         return Y

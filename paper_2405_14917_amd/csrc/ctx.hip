@@ -134,6 +134,10 @@ slim_status slim_create(slim_ctx** out, void* hip_stream) {
   if (e != hipSuccess) return bail(e, "hipMemcpyAsync(tau)");
   e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return bail(e, "hipStreamSynchronize");
+  if (slim_dq_scratch_resolve(ctx) != SLIM_OK) {
+    fprintf(stderr, "slim_create: %s\n", ctx->err);
+    return bail(hipErrorUnknown, "looking up the fixed buffer");
+  }
   *out = ctx;
   return SLIM_OK;
 }

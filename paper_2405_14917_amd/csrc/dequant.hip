@@ -15,6 +15,8 @@
 // atomics.
 #include <algorithm>
 
+#include <mutex>
+
 #include "slim_device.h"
 #include "slim_internal.h"
 
@@ -348,23 +350,31 @@ slim_status launch(slim_ctx* ctx, const DqArgs& a, dim3 grid, size_t smem) {
   return SLIM_OK;
 }
 
-}  // namespace
+// Partial sums of the group ranges for callers that must not allocate: one array per GPU, held from the moment the
+// library's code is loaded on that GPU until the process ends.  Host code never uses the array's name as an
+// address; the device address is asked for once per device (slim_dq_scratch_resolve) and kept.
+constexpr size_t DQ_SCRATCH_FLOATS = SLIM_DEQUANT_NOALLOC_MAX_FLOATS;      // 16 MiB
+static __device__ __align__(256) float scratch[DQ_SCRATCH_FLOATS];
 
-extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
-                                           const int32_t* row_off, const double* scale, const double* zero, int n,
-                                           int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
-                                           int64_t ldx, float* Y, int64_t ldy) {
-  if (!ctx) return SLIM_ERR_INVALID_ARG;
-  SLIM_REQUIRE(ctx, packed && gbits && row_off && scale && zero && X && Y, "slim_dequant_matmul: null pointer");
-  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_dequant_matmul: need n, m > 0 and beta | m");
-  SLIM_REQUIRE(ctx, beta % 32 == 0, "slim_dequant_matmul: beta must be a multiple of 32 (got %d)", beta);
-  SLIM_REQUIRE(ctx, t_x >= 1 && t_x <= DQ_MAX_T, "slim_dequant_matmul: t_x must be in 1..%d (got %d)", DQ_MAX_T, t_x);
-  SLIM_REQUIRE(ctx, ldp >= n && ldx >= m && ldy >= n, "slim_dequant_matmul: leading dimension too small");
+constexpr int DQ_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[DQ_MAX_DEVICES] = {};
+
+// The whole call.  `fixed` = nullptr: partial sums go to the context's workspace (grown if needed); otherwise to
+// `fixed`, which holds `fixed_floats` floats, and nothing is allocated.
+slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* packed, int64_t ldp,
+                               const uint32_t* gbits, const int32_t* row_off, const double* scale, const double* zero,
+                               int n, int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
+                               int64_t ldx, float* Y, int64_t ldy, float* fixed, size_t fixed_floats) {
+  SLIM_REQUIRE(ctx, packed && gbits && row_off && scale && zero && X && Y, "%s: null pointer", fn);
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "%s: need n, m > 0 and beta | m", fn);
+  SLIM_REQUIRE(ctx, beta % 32 == 0, "%s: beta must be a multiple of 32 (got %d)", fn, beta);
+  SLIM_REQUIRE(ctx, t_x >= 1 && t_x <= DQ_MAX_T, "%s: t_x must be in 1..%d (got %d)", fn, DQ_MAX_T, t_x);
+  SLIM_REQUIRE(ctx, ldp >= n && ldx >= m && ldy >= n, "%s: leading dimension too small", fn);
   if (x_dtype != SLIM_F16 && x_dtype != SLIM_BF16)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_dequant_matmul: X must be F16 or BF16");
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "%s: X must be F16 or BF16", fn);
   if (bit_base != 1 && bit_base != 2)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_dequant_matmul: bit_base must be 1 or 2 (widths up to 5), got %d",
-                     bit_base);
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "%s: bit_base must be 1 or 2 (widths up to 5), got %d", fn, bit_base);
   const int k = m / beta;
   int T = 1;
   while (T < t_x) T *= 2;
@@ -408,9 +418,19 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
   a.gper = gper;
   float* part = nullptr;
   if (splits > 1) {
-    slim_status st = slim_ws_reserve(ctx, slim_ws_round(sizeof(float) * (size_t)splits * t_x * n));
-    if (st != SLIM_OK) return st;
-    part = static_cast<float*>(slim_ws_alloc(ctx, sizeof(float) * (size_t)splits * t_x * n));
+    const size_t part_floats = (size_t)splits * t_x * n;
+    if (fixed) {
+      if (part_floats > fixed_floats)
+        return slim_fail(ctx, SLIM_ERR_UNSUPPORTED,
+                         "%s: this layer needs %zu floats of partial sums (%d group ranges x %d tokens x %d rows), the "
+                         "fixed buffer holds %zu: fewer tokens per call, or slim_dequant_matmul", fn, part_floats,
+                         splits, t_x, n, fixed_floats);
+      part = fixed;
+    } else {
+      slim_status st = slim_ws_reserve(ctx, slim_ws_round(sizeof(float) * part_floats));
+      if (st != SLIM_OK) return st;
+      part = static_cast<float*>(slim_ws_alloc(ctx, sizeof(float) * part_floats));
+    }
     a.out = part;
     a.ldo = n;
     a.split_stride = (int64_t)t_x * n;
@@ -448,4 +468,52 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
     SLIM_LAUNCH(ctx, "dequant_reduce", dequant_reduce, dim3(slim_cdiv((int64_t)t_x * n, 256)), dim3(256), 0, part, splits,
                 a.split_stride, t_x, n, Y, ldy);
   return SLIM_OK;
+}
+
+}  // namespace
+
+// Device address of this GPU's copy of the fixed buffer: asked for once per device, with that device current
+// (slim_create calls this on the context's device), and kept for the life of the process.
+slim_status slim_dq_scratch_resolve(slim_ctx* ctx) {
+  if (ctx->device < 0 || ctx->device >= DQ_MAX_DEVICES)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "device ordinal %d is beyond the %d this library keeps buffers for",
+                     ctx->device, DQ_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[ctx->device]) {
+    int cur = -1;
+    SLIM_HIP_TRY(ctx, hipGetDevice(&cur));
+    if (cur != ctx->device) return slim_fail(ctx, SLIM_ERR_INVALID_ARG, "the context's device is not the current one");
+    float* ptr = nullptr;
+    SLIM_HIP_TRY(ctx, hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+    if (!ptr) return slim_fail(ctx, SLIM_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[ctx->device] = ptr;
+  }
+  ctx->dq_scratch = g_scratch_ptr[ctx->device];
+  return SLIM_OK;
+}
+
+extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
+                                           const int32_t* row_off, const double* scale, const double* zero, int n,
+                                           int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
+                                           int64_t ldx, float* Y, int64_t ldy) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  return dequant_matmul_run(ctx, "slim_dequant_matmul", packed, ldp, gbits, row_off, scale, zero, n, m, beta, bit_base,
+                            X, x_dtype, t_x, ldx, Y, ldy, nullptr, 0);
+}
+
+extern "C" slim_status slim_dequant_matmul_noalloc(slim_ctx* ctx, const uint32_t* packed, int64_t ldp,
+                                                 const uint32_t* gbits, const int32_t* row_off, const double* scale,
+                                                 const double* zero, int n, int m, int beta, int bit_base,
+                                                 const void* X, slim_dtype x_dtype, int t_x, int64_t ldx, float* Y,
+                                                 int64_t ldy) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  if (!ctx->dq_scratch) return slim_fail(ctx, SLIM_ERR_HIP, "slim_dequant_matmul_noalloc: the fixed buffer was not resolved");
+  // per-kernel event timing creates events on demand, which allocates: it is off for the length of this call
+  const bool prof = ctx->prof;
+  ctx->prof = false;
+  const slim_status st = dequant_matmul_run(ctx, "slim_dequant_matmul_noalloc", packed, ldp, gbits, row_off, scale, zero,
+                                            n, m, beta, bit_base, X, x_dtype, t_x, ldx, Y, ldy, ctx->dq_scratch,
+                                            DQ_SCRATCH_FLOATS);
+  ctx->prof = prof;
+  return st;
 }

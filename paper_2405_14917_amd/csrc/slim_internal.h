@@ -62,6 +62,7 @@ struct slim_ctx {
   hipEvent_t attach_event = nullptr;
   bool staging_copy_pending = false;   // a host-to-device copy out of hpin that no one has waited for yet (ev[13])
   slim_sba_prepared sba_prep;
+  float* dq_scratch = nullptr;    // this device's copy of the fixed partial-sum buffer of slim_dequant_matmul_noalloc
   // profiling
   bool prof = false;
   std::vector<slim_prof_pending> pending;
@@ -79,6 +80,9 @@ slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...);
 slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes);
 void* slim_ws_alloc(slim_ctx* ctx, size_t bytes);
 inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255); }
+
+// Looks up (once per device) the device address of the fixed buffer of slim_dequant_matmul_noalloc (dequant.hip).
+slim_status slim_dq_scratch_resolve(slim_ctx* ctx);
 
 // Creates the side streams and their events on first use.
 slim_status slim_ensure_side(slim_ctx* ctx);
