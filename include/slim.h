@@ -20,7 +20,9 @@
  *    widths back for validation and kernel selection, behind work it has already enqueued.
  *  - Return value: SLIM_OK or a negative slim_status.  No exceptions, no aborts.  After an error
  *    slim_last_error(ctx) describes it; on SLIM_ERR_INVALID_ARG / SLIM_ERR_UNSUPPORTED no output
- *    was touched (at most work on the library's own workspace has been launched).
+ *    was touched (at most work on the library's own workspace has been launched).  The one exception are the two
+ *    checks of slim_pack that depend on device data (a width outside the range, a capacity that is too small): they
+ *    are made on the device while the call runs, and packed / gbits / row_off then hold no valid result.
  *  - Device pointers must be 16-byte aligned, leading dimensions of 16-bit matrices multiples
  *    of 8 elements.
  *  - Calls on one context must not overlap in time (one stream, one workspace).
@@ -224,8 +226,10 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
  *   Y[t][i] = sum_j X[t][j] * scale[i][g] * (q_ij - zero[i][g]),   g = j / beta   (Eq. 1),
  *   the codes q_ij decoded from packed / gbits / row_off exactly as slim_pack writes them.
  *   packed   m_star x n words (ld = ldp >= n);  gbits ceil(k/16) words;  row_off k+1 ints   (device)
- *   scale, zero   n x k doubles (ld = k), as written by slim_gptq_quantize (device); every zero must be a
- *            multiple of 1/2 in [0, 255] (Eq. 1 gives integers, the sign form of width 1 uses 1/2)
+ *   scale, zero   n x k doubles (ld = k), as written by slim_gptq_quantize (device); a zero that is a
+ *            multiple of 1/2 within +-511 takes the fastest path (Eq. 1 gives integers, the sign form of width 1 uses
+ *            1/2); any other finite zero (Eq. 1 does not bound -round(w_min / delta0): a group of one sign with a narrow
+ *            range has a large one) is accepted and costs that (row, group) a correction term
  *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
  *   Y        t_x x n fp32 (ldy >= n), overwritten
  *   beta     a multiple of 32 that divides m

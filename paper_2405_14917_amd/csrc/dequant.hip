@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void dequant_reduce(const float* __restrict__ 
 // row (its scale and zero are lane constants) and the 16 tokens of its accumulator registers.  The second
 // operand is 2 (q - z), formed exactly in fp16 from the packed codes without any conversion instruction: a code
 // q shifted left by one and OR-ed into the mantissa of 1024.0 is the fp16 number 1024 + 2 q, and subtracting
-// 1024 + 2 z (2 z is an integer: zeros are integers, or 1/2 for the sign form of width 1) leaves 2 (q - z);
+// 1024 + 2 z (2 z is an integer: zeros are integers, or 1/2 for the sign form of width 1; other zeros: see below) leaves 2 (q - z);
 // the factor 1/2 goes into the scale.  Two codes are handled per instruction (packed fp16): the eight codes a
 // lane needs for one MFMA are first spread so that code j sits in the low and code j + 4 in the high half of a
 // register, and the activations are stored in LDS in that order (0 4 1 5 2 6 3 7) to match.  Products are exact
@@ -270,13 +270,20 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
   // groups, fetched together: per (row, group) loads by the lane that owns the row would touch 32 cache lines per
   // instruction, eight times the requests of the packed words themselves.
   const int gcount = g1 - g0;
+  // A zero outside that form (Eq. 1 puts no bound on -round(w_min / delta0): a group of one sign with a narrow
+  // range has a large one) is split: z0, the nearest value that has the form, goes through the matrix cores, and
+  // the rest enters as  - 2 (z - z0) sum_j x_j  when the group is complete (zr != 0, rare).
   float* sp = reinterpret_cast<float*>(xh + (a.t_x + 1) * ldxs);            // [DM_ROWS][gcount]
-  _Float16* zp = reinterpret_cast<_Float16*>(sp + DM_ROWS * gcount);          // [DM_ROWS][gcount]
+  float* zr = sp + DM_ROWS * gcount;                                          // [DM_ROWS][gcount]
+  _Float16* zp = reinterpret_cast<_Float16*>(zr + DM_ROWS * gcount);          // [DM_ROWS][gcount]
   for (int idx = tid; idx < DM_ROWS * gcount; idx += 64 * DM_WAVES) {
     const int r = idx / gcount, gi = idx - r * gcount;
     const int64_t src = (int64_t)min(blockIdx.x * DM_ROWS + r, a.n - 1) * a.k + g0 + gi;
     sp[idx] = (float)(0.5 * a.scale[src]);
-    zp[idx] = (_Float16)(float)(1024.0 + 2.0 * a.zero[src]);                  // exact: 2 z is an integer below 1024
+    const double z2 = 2.0 * a.zero[src];
+    const double z02 = fmin(fmax(rint(z2), -1022.0), 1022.0);
+    zp[idx] = (_Float16)(float)(1024.0 + z02);                                // exact: an integer in 2 .. 2046
+    zr[idx] = (float)(z2 - z02);
   }
   const int prow = (wave * 32 + l32) * gcount;
 
@@ -324,6 +331,19 @@ __global__ __launch_bounds__(64 * DM_WAVES) void dequant_matmul_mfma(DqArgs a) {
         break;
     }
     if (sb == nsub - 1) {                          // the group is complete: its scale (times the 1/2 of the doubled codes)
+      const float rest = zr[prow + (g - g0)];
+      if (__builtin_amdgcn_ballot_w64(rest != 0.f) != 0 && checked_width(g) != 0) {
+        // some row of this wavefront has a zero that the fp16 form does not hold: the part it does not hold times
+        // the sum of the group's activations, per token (the order of the tile's columns does not matter for a sum)
+#pragma unroll 1
+        for (int v = 0; v < 16; ++v) {
+          const int t = 8 * (v >> 2) + 4 * h + (v & 3);
+          const _Float16* xt = xh + min(t, a.t_x) * ldxs + (g - g0) * a.beta;
+          float sx = 0.f;
+          for (int j = 0; j < a.beta; ++j) sx += (float)xt[j];
+          acc[v] = fmaf(-rest, sx, acc[v]);
+        }
+      }
       const float s2 = sp[prow + (g - g0)];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -393,8 +413,9 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
   const int splits_wanted = std::max(1, std::min(k, (per_cu * cus + gx - 1) / gx));
   int gper = slim_cdiv(k, splits_wanted);
   if (mfma) {
-    // the activations of a workgroup's group range have to fit into 64 KiB of LDS
-    const int fit = std::max(1, (int)((48 * 1024 / (2 * (t_x + 1)) - DM_PAD) / beta));
+    // the activations of a workgroup's group range (t_x + 1 rows of 16-bit values) and its rows' parameters
+    // (10 bytes per row and group) have to fit into 64 KiB of LDS
+    const int fit = std::max(1, (int)((64 * 1024 - 2 * (t_x + 1) * DM_PAD) / (2 * (t_x + 1) * beta + 10 * DM_ROWS)));
     gper = std::min(gper, fit);
   }
   const int splits = slim_cdiv(k, gper);
@@ -442,7 +463,7 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
   const dim3 grid(gx, splits);
   slim_status st = SLIM_OK;
   if (mfma) {
-    smem = sizeof(uint16_t) * (size_t)(t_x + 1) * ((size_t)gper * beta + DM_PAD) + (size_t)DM_ROWS * gper * 6;
+    smem = sizeof(uint16_t) * (size_t)(t_x + 1) * ((size_t)gper * beta + DM_PAD) + (size_t)DM_ROWS * gper * 10;
 #define SLIM_DQ_MFMA(SUB, MAXW)                                                                              \
   SLIM_LAUNCH(ctx, "dequant_matmul@dequant_matmul_mfma<" #SUB ", " #MAXW ">", (dequant_matmul_mfma<SUB, MAXW>), grid, \
               dim3(64 * DM_WAVES), smem, a)

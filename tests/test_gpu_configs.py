@@ -7,11 +7,14 @@ import numpy as np
 import pytest
 import torch
 
+from e2e_checks import check_end_to_end
 from oracle import slim_oracle as orc
 from paper_2405_14917_amd import synth
 
 pytestmark = pytest.mark.gpu
 MARGIN = 1e-6
+# end to end: floors of (equal codes, rows identical code for code) and bound of the Frobenius distance; see e2e_checks
+E2E_FLOORS = (0.998, 0.95, 5e-2)
 
 CASES = {
     "C3-N2": (synth.scaled(synth.CONFIGS["C3"], n=192, m=1408, t=6144), 2),
@@ -54,12 +57,28 @@ def test_reduced_config(slim, name):
     assert np.max(np.abs(Gg - ref["G"]) / scale) < 2e-6 * np.sqrt(cfg.t / 512)
 
     U, d = slim.hessian_inverse(G, nt, cfg.percdamp)
-    assert np.linalg.norm(host(U) - ref["U"]) / np.linalg.norm(ref["U"]) < 1e-3    # fp32 Gram in, fp64 after
+    u_err = np.linalg.norm(host(U) - ref["U"]) / np.linalg.norm(ref["U"])
+    print("%s: ||U - U_o||_F / ||U_o||_F = %.3e (fp32 Gram in, fp64 after)" % (name, u_err))
+    assert u_err < 1e-4
     _, grp, _ = slim.salience(Wd, d, cfg.beta)
     assert np.allclose(host(grp), ref["group_sal"], rtol=1e-3)
     bits, p_star, obj = slim.sba_allocate(Wd, grp, cfg.beta, N, Xd[:, :t_sba])
-    order_ok = np.array_equal(np.argsort(host(grp), kind="stable"), np.argsort(ref["group_sal"], kind="stable"))
-    if order_ok:
+    # Stage parity of the allocation on the HIP path's own salience (always taken): the oracle's search fed with it
+    bits_o, p_o, obj_o, margin_o = orc.sba_allocate(W.astype(np.float64), host(grp), cfg.beta, N,
+                                                    X[:, :t_sba].astype(np.float64))
+    assert np.allclose(obj, obj_o, rtol=1e-8)
+    if margin_o > MARGIN:
+        assert p_star == p_o and np.array_equal(host(bits), bits_o)
+    else:
+        print("%s: the two best SBA candidates lie within the margin (%.2e): widths not compared" % (name, margin_o))
+    # End to end the ranking can differ only between groups whose saliences agree to the accuracy of the Gram matrix
+    order_g, order_o = np.argsort(host(grp), kind="stable"), np.argsort(ref["group_sal"], kind="stable")
+    moved = order_g != order_o
+    if moved.any():
+        so = ref["group_sal"]
+        assert np.allclose(so[order_g[moved]], so[order_o[moved]], rtol=1e-3), "ranking differs beyond fp32 Gram accuracy"
+        print("%s: %d positions of the salience ranking differ from the oracle's (near-equal groups)" % (name, moved.sum()))
+    else:
         assert np.allclose(obj, ref["obj_curve"], rtol=1e-8)
         if ref["sba_margin"] > MARGIN:
             assert p_star == ref["p_star"] and np.array_equal(host(bits), ref["bits"])
@@ -71,11 +90,11 @@ def test_reduced_config(slim, name):
     assert m_star == cfg.m * N // 32
     c2, b2 = orc.unpack(host(packed).view(np.uint32), host(gbits).view(np.uint32), cfg.beta, cfg.k)
     assert np.array_equal(c2, host(out["codes"])) and np.array_equal(b2, host(bits))
-    if np.array_equal(host(bits), ref["bits"]):
-        rec = orc.reconstruction_error(W, host(out["What"]), ref["G"])
-        print("%s: p*=%d codes equal %.4f recon gpu %.5e oracle %.5e" %
-              (name, p_star, (host(out["codes"]) == ref["codes"]).mean(), rec, ref["recon"]))
-        assert abs(rec - ref["recon"]) <= 0.01 * ref["recon"]
+    assert np.array_equal(host(bits), ref["bits"]), "%s: end-to-end widths differ from the oracle's" % name
+    rec = orc.reconstruction_error(W, host(out["What"]), ref["G"])
+    print("%s: p*=%d recon gpu %.5e oracle %.5e" % (name, p_star, rec, ref["recon"]))
+    assert abs(rec - ref["recon"]) <= 0.01 * ref["recon"]
+    check_end_to_end(name, host(out["codes"]), host(out["What"]), ref, *E2E_FLOORS)
 
     # the sweep on the ORACLE's second-order information and bits: code for code
     chk = slim.gptq_quantize(Wd, torch.from_numpy(np.ascontiguousarray(ref["U"])).cuda(),
