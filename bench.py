@@ -59,9 +59,15 @@ class Pass(pipeline.LayerPass):
     """The hot path over one resident layer of a benchmark configuration; all buffers are allocated once, outside
     the timed region (the order of the entry points and the two-stream overlap are the package's LayerPass)."""
 
-    def __init__(self, slim, cfg, W, X):
-        super().__init__(slim, cfg.m, cfg.beta, cfg.N, cfg.percdamp, T_SBA)
+    def __init__(self, cfg, W, X):
+        # both contexts work in caller memory sized by slim_workspace_query: no entry point allocates
+        slim = binding.Slim("cuda:0", binding.workspace_query(cfg.n, cfg.m, cfg.beta, cfg.t, min(T_SBA, cfg.t), 1))
+        super().__init__(slim, cfg.m, cfg.beta, cfg.N, cfg.percdamp, T_SBA, n=cfg.n)
         self.cfg, self.W, self.X = cfg, W, X
+
+    def close(self):
+        super().close()
+        self.slim.close()
 
     def step(self):
         r = self.run(self.W, self.X)
@@ -244,9 +250,8 @@ def main():
         sys.exit("bench.py: this build runs on ONE GPU (the pass is a single-GPU job); run with --gpus 1")
 
     cfg = synth.CONFIGS[args.config]
-    slim = binding.Slim("cuda:0")
     W, X = resident_inputs(cfg)
-    job = Pass(slim, cfg, W, X)
+    job = Pass(cfg, W, X)
 
     # a plain device-to-device copy of known size (64 MiB read, 64 MiB written): the yardstick that HBM
     # traffic counters of a rocprofv3 --pmc run of this command are scaled by
@@ -366,7 +371,7 @@ def main():
             sys.exit("bench.py: unknown configuration %r in --also" % name)
         oc = synth.CONFIGS[name]
         Wo, Xo = resident_inputs(oc)
-        ojob = Pass(slim, oc, Wo, Xo)
+        ojob = Pass(oc, Wo, Xo)
         ms, ps, mst = timed_steps(ojob, 3, 1)
         other_cfgs[name] = {"workload": workload_text(oc), "ms_per_step": ms, "value": oc.n * oc.m / (ms * 1e-3),
                             "unit": "weights/s", "steps": 3, "warmup": 1, "p_star": ps, "m_star": mst}
@@ -378,7 +383,6 @@ def main():
         line["cpu_baseline"] = cpu_baseline(cfg)
     else:
         line["cpu_baseline"] = None
-    slim.close()
     print(json.dumps(line))
 
 

@@ -10,8 +10,8 @@
  * Conventions for every entry point
  *  - Pointers are DEVICE pointers unless the comment says "host".  All matrices are row-major with
  *    an explicit leading dimension counted in elements.  The caller owns every buffer passed in;
- *    the library keeps an internal, grow-only device workspace tied to the context and frees it in
- *    slim_destroy.
+ *    the library's device workspace is either the caller's too (given to slim_create, sized with
+ *    slim_workspace_query: then no entry point allocates) or an internal grow-only one that slim_destroy frees.
  *  - Work is enqueued on the HIP stream given to slim_create.  A call returns as soon as its work
  *    is enqueued, except where it has a host output (info, p_star, obj_curve, m_star): those calls
  *    wait until that output has arrived (slim_hessian_inverse: until the factorisation is done, with
@@ -44,7 +44,7 @@ typedef enum {
   SLIM_OK = 0,
   SLIM_ERR_INVALID_ARG = -1, /* bad size, null / misaligned pointer, inconsistent arguments   */
   SLIM_ERR_NOT_PD = -2,      /* H + lambda I is not positive definite                           */
-  SLIM_ERR_ALLOC = -3,       /* the internal workspace could not be grown                       */
+  SLIM_ERR_ALLOC = -3,       /* the workspace could not be grown, or the caller's is too small   */
   SLIM_ERR_HIP = -4,         /* a HIP runtime call failed                                       */
   SLIM_ERR_UNSUPPORTED = -5  /* valid in the paper's terms but not built (dtype, mode, size)    */
 } slim_status;
@@ -81,9 +81,30 @@ void slim_default_params(slim_params* p);
  * and returns the number of candidates (100).  tau_host may be NULL to query the count. */
 int slim_default_tau(double* tau_host, int cap);
 
+/* Shape of a layer, for slim_workspace_query: n output rows, m input channels, group size beta, t_c tokens per
+ * call of slim_hessian_accumulate, t_s tokens of the SBA objective, t_x tokens per call of slim_dequant_matmul.
+ * A field that is 0 leaves out the entry points that need it. */
+typedef struct slim_shape {
+  int n, m, beta;
+  int64_t t_c, t_s;
+  int t_x;
+} slim_shape;
+
+/* Host only.  Bytes of device workspace that the entry points need for a layer of exactly this shape: the largest
+ * requirement of any single entry point (calls on one context run one after the other and reuse the workspace).
+ * num_cus: compute units of the device (the split of the Gram matrix and of the linear layer depend on it); 0 = 256.
+ * For several shapes take the largest answer: the requirement is not monotone in the sizes (a small Gram matrix
+ * is split into more token ranges). */
+size_t slim_workspace_query(const slim_shape* shape, int num_cus);
+
 /* Creates a context bound to `hip_stream` (a hipStream_t, may be NULL for the default stream) on
- * the current device.  Allocates small fixed device buffers (default tau grid, flags). */
-slim_status slim_create(slim_ctx** out, void* hip_stream);
+ * the current device.  Allocates small fixed device buffers (default tau grid, flags).
+ *   workspace, workspace_bytes   device memory of the caller (256-byte aligned) that the entry points use as their
+ *       workspace until slim_destroy: with it NO entry point calls hipMalloc or hipFree, and a call whose shape needs
+ *       more than workspace_bytes returns SLIM_ERR_ALLOC without touching anything (slim_workspace_query gives the
+ *       size).  workspace = NULL: the context keeps a workspace of its own that grows on demand (hipMalloc / hipFree and
+ *       a stream synchronisation inside the first call of every larger shape) and is freed by slim_destroy. */
+slim_status slim_create(slim_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes);
 slim_status slim_destroy(slim_ctx* ctx);
 const char* slim_last_error(const slim_ctx* ctx);
 /* Bytes of device workspace currently held by the context (host only). */

@@ -27,7 +27,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32, torch.float
 # every symbol include/slim.h declares
 EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
-    "slim_workspace_bytes", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
+    "slim_workspace_bytes", "slim_workspace_query", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
     "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
     "slim_dequant_matmul_noalloc",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
@@ -37,6 +37,16 @@ EXPORTS = [
 class SlimParams(ctypes.Structure):
     _fields_ = [("sqc_weight_mode", ctypes.c_int), ("mask_scope", ctypes.c_int),
                 ("q1_mode", ctypes.c_int), ("sal_mode", ctypes.c_int)]
+
+
+class SlimShape(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int), ("m", ctypes.c_int), ("beta", ctypes.c_int), ("t_c", ctypes.c_int64),
+                ("t_s", ctypes.c_int64), ("t_x", ctypes.c_int)]
+
+
+def workspace_query(n: int, m: int, beta: int, t_c: int = 0, t_s: int = 0, t_x: int = 0, num_cus: int = 0) -> int:
+    """Bytes of workspace the entry points need for a layer of this shape (host only, no GPU needed)."""
+    return int(load().slim_workspace_query(ctypes.byref(SlimShape(n, m, beta, t_c, t_s, t_x)), num_cus))
 
 
 def bit_base_for(N: int) -> int:
@@ -69,7 +79,9 @@ def load() -> ctypes.CDLL:
     lib.slim_default_params.restype = None
     lib.slim_default_tau.argtypes = [P(c_double), c_int]
     lib.slim_default_tau.restype = c_int
-    lib.slim_create.argtypes = [P(c_void_p), c_void_p]
+    lib.slim_create.argtypes = [P(c_void_p), c_void_p, c_void_p, ctypes.c_size_t]
+    lib.slim_workspace_query.argtypes = [P(SlimShape), c_int]
+    lib.slim_workspace_query.restype = ctypes.c_size_t
     lib.slim_destroy.argtypes = [c_void_p]
     lib.slim_last_error.argtypes = [c_void_p]
     lib.slim_last_error.restype = ctypes.c_char_p
@@ -102,7 +114,7 @@ def load() -> ctypes.CDLL:
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("slim_default_params", "slim_default_tau", "slim_last_error", "slim_workspace_bytes",
-                        "slim_profile_collect"):
+                        "slim_workspace_query", "slim_profile_collect"):
             fn.restype = c_int
     _lib = lib
     return lib
@@ -137,13 +149,21 @@ def _need_cuda(*tensors):
 class Slim:
     """A library context bound to the current torch stream of `device`."""
 
-    def __init__(self, device: str = "cuda:0"):
+    def __init__(self, device: str = "cuda:0", workspace_bytes: int = 0):
+        """workspace_bytes > 0: the context works in a buffer of that size allocated here, once (see
+        workspace_query), and no entry point allocates device memory; 0: the library grows its own on demand."""
         self.lib = load()
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.stream = torch.cuda.current_stream(self.device)
+        self.workspace = (torch.empty(workspace_bytes + 256, dtype=torch.uint8, device=self.device)
+                          if workspace_bytes > 0 else None)
+        ws_ptr = None
+        if self.workspace is not None:
+            ws_ptr = ctypes.c_void_p((self.workspace.data_ptr() + 255) // 256 * 256)
         handle = ctypes.c_void_p()
-        st = self.lib.slim_create(ctypes.byref(handle), ctypes.c_void_p(self.stream.cuda_stream))
+        st = self.lib.slim_create(ctypes.byref(handle), ctypes.c_void_p(self.stream.cuda_stream), ws_ptr,
+                                  workspace_bytes)
         if st != SLIM_OK:
             raise SlimError(st, "slim_create failed")
         self.ctx = handle

@@ -18,6 +18,9 @@ slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes) {
   ctx->ws_off = 0;
   ctx->sba_prep.valid = false;    // whoever reserves is about to overwrite what a prepare call left
   if (bytes <= ctx->ws_bytes) return SLIM_OK;
+  if (ctx->ws_external)
+    return slim_fail(ctx, SLIM_ERR_ALLOC, "the workspace given to slim_create holds %zu bytes, this call needs %zu "
+                     "(slim_workspace_query gives the size for a shape)", ctx->ws_bytes, bytes);
   // the old buffer may still be in use by work enqueued earlier
   SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   if (ctx->ws) {
@@ -103,12 +106,18 @@ int slim_default_tau(double* tau_host, int cap) {
   return 2 * n;
 }
 
-slim_status slim_create(slim_ctx** out, void* hip_stream) {
+slim_status slim_create(slim_ctx** out, void* hip_stream, void* workspace, size_t workspace_bytes) {
   if (!out) return SLIM_ERR_INVALID_ARG;
   *out = nullptr;
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SLIM_ERR_INVALID_ARG;
   slim_ctx* ctx = new (std::nothrow) slim_ctx();
   if (!ctx) return SLIM_ERR_ALLOC;
   ctx->stream = static_cast<hipStream_t>(hip_stream);
+  if (workspace) {
+    ctx->ws = static_cast<char*>(workspace);
+    ctx->ws_bytes = workspace_bytes;
+    ctx->ws_external = true;
+  }
   auto bail = [&](hipError_t e, const char* what) {
     fprintf(stderr, "slim_create: %s failed: %s\n", what, hipGetErrorString(e));
     if (ctx->tau_default) (void)hipFree(ctx->tau_default);
@@ -160,7 +169,7 @@ slim_status slim_destroy(slim_ctx* ctx) {
       (void)hipStreamDestroy(ctx->side2);
     }
   }
-  if (ctx->ws) (void)hipFree(ctx->ws);
+  if (ctx->ws && !ctx->ws_external) (void)hipFree(ctx->ws);
   if (ctx->tau_default) (void)hipFree(ctx->tau_default);
   if (ctx->dflags) (void)hipFree(ctx->dflags);
   if (ctx->hpin) (void)hipHostFree(ctx->hpin);
@@ -171,6 +180,22 @@ slim_status slim_destroy(slim_ctx* ctx) {
 const char* slim_last_error(const slim_ctx* ctx) { return ctx ? ctx->err : "null context"; }
 
 size_t slim_workspace_bytes(const slim_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+size_t slim_workspace_query(const slim_shape* s, int num_cus) {
+  if (!s || s->m <= 0) return 0;
+  const int ncu = num_cus > 0 ? num_cus : 256;
+  size_t need = 0;
+  if (s->t_c > 0) need = std::max(need, slim_ws_need_gram(s->m, s->t_c, ncu));
+  need = std::max(need, slim_ws_need_inverse(s->m));
+  if (s->n > 0) {
+    need = std::max(need, slim_ws_need_salience(s->n, s->m));
+    need = std::max(need, slim_ws_need_sqc(s->n));
+    need = std::max(need, slim_ws_need_gptq(s->n, s->m));
+    if (s->beta > 0 && s->t_s > 0) need = std::max(need, slim_ws_need_sba(s->n, s->m, s->beta, s->t_s));
+    if (s->beta > 0 && s->t_x > 0) need = std::max(need, slim_ws_need_dequant(s->n, s->m, s->beta, s->t_x, ncu));
+  }
+  return need;
+}
 
 slim_status slim_profile_enable(slim_ctx* ctx, int on) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;

@@ -380,6 +380,25 @@ constexpr int DQ_MAX_DEVICES = 64;
 std::mutex g_scratch_mu;
 float* g_scratch_ptr[DQ_MAX_DEVICES] = {};
 
+// Group ranges the layer is split into (and groups per range), for the matrix-core kernel or the plain one:
+// enough workgroups per CU to hide the latency of their loads behind one another; fewer for a small layer, where
+// the reduction over the ranges would cost more than the ranges gain.
+int dq_splits(int n, int m, int beta, int t_x, int cus, bool mfma, int& gper) {
+  const int k = m / beta;
+  const bool small = 2 * slim_cdiv(n, DM_ROWS) < cus;
+  const int gx = slim_cdiv(n, mfma ? DM_ROWS : DQ_THREADS);
+  const int per_cu = small ? 2 : 8;
+  const int splits_wanted = std::max(1, std::min(k, (per_cu * cus + gx - 1) / gx));
+  gper = slim_cdiv(k, splits_wanted);
+  if (mfma) {
+    // the activations of a workgroup's group range (t_x + 1 rows of 16-bit values) and its rows' parameters
+    // (10 bytes per row and group) have to fit into 64 KiB of LDS
+    const int fit = std::max(1, (int)((64 * 1024 - 2 * (t_x + 1) * DM_PAD) / (2 * (t_x + 1) * beta + 10 * DM_ROWS)));
+    gper = std::min(gper, fit);
+  }
+  return slim_cdiv(k, gper);
+}
+
 // The whole call.  `fixed` = nullptr: partial sums go to the context's workspace (grown if needed); otherwise to
 // `fixed`, which holds `fixed_floats` floats, and nothing is allocated.
 slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* packed, int64_t ldp,
@@ -407,18 +426,8 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
                     (beta == 32 || beta == 64 || beta % 128 == 0) && !(small && t_x <= 2);
   size_t smem = sizeof(float) * (size_t)T * beta;   // (the matrix-core kernel's depends on the split, below)
   const int gx = slim_cdiv(n, mfma ? DM_ROWS : DQ_THREADS);
-  // enough workgroups per CU to hide the latency of their loads behind one another, by splitting the groups;
-  // fewer for a small layer, where the reduction over the splits would cost more than the splits gain
-  const int per_cu = small ? 2 : 8;
-  const int splits_wanted = std::max(1, std::min(k, (per_cu * cus + gx - 1) / gx));
-  int gper = slim_cdiv(k, splits_wanted);
-  if (mfma) {
-    // the activations of a workgroup's group range (t_x + 1 rows of 16-bit values) and its rows' parameters
-    // (10 bytes per row and group) have to fit into 64 KiB of LDS
-    const int fit = std::max(1, (int)((64 * 1024 - 2 * (t_x + 1) * DM_PAD) / (2 * (t_x + 1) * beta + 10 * DM_ROWS)));
-    gper = std::min(gper, fit);
-  }
-  const int splits = slim_cdiv(k, gper);
+  int gper = 0;
+  const int splits = dq_splits(n, m, beta, t_x, cus, mfma, gper);
 
   DqArgs a;
   a.packed = packed;
@@ -448,7 +457,7 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
                          splits, t_x, n, fixed_floats);
       part = fixed;
     } else {
-      slim_status st = slim_ws_reserve(ctx, slim_ws_round(sizeof(float) * part_floats));
+      slim_status st = slim_ws_reserve(ctx, slim_ws_need_dequant(n, m, beta, t_x, cus));
       if (st != SLIM_OK) return st;
       part = static_cast<float*>(slim_ws_alloc(ctx, sizeof(float) * part_floats));
     }
@@ -492,6 +501,16 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
 }
 
 }  // namespace
+
+size_t slim_ws_need_dequant(int n, int m, int beta, int t_x, int ncu) {
+  size_t need = 0;
+  for (int mfma = 0; mfma < 2; ++mfma) {       // whichever kernel the activations' type and alignment select
+    int gper = 0;
+    const int splits = dq_splits(n, m, beta, t_x, std::max(1, ncu), mfma != 0, gper);
+    if (splits > 1) need = std::max(need, slim_ws_round(sizeof(float) * (size_t)splits * t_x * n));
+  }
+  return need;
+}
 
 // Device address of this GPU's copy of the fixed buffer: asked for once per device, with that device current
 // (slim_create calls this on the context's device), and kept for the life of the process.

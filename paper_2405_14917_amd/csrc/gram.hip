@@ -591,37 +591,25 @@ __global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict
   }
 }
 
-}  // namespace
+// Token ranges per tile: the number S (a power of two) for which a model of the launch is shortest.  A workgroup
+// takes 1/S of a tile's time; n = tiles * S workgroups run in rounds of one per CU; the tiles of a last round that
+// is at most half full are split f ways more, so that it is full of workgroups 1/f as long (m = 4096: 136 tiles,
+// S = 2 gives one round plus 8 tiles cut 32 ways; m = 5120: 210 tiles, S = 4 gives 3 1/3 rounds where S = 1 or 2
+// leave a fifth of the chip idle); every slot costs its 256 KB twice (written here, read by the reduction).
+// Few ranges are better beyond the smaller reduction: each workgroup's fill and drain is paid once per range.
+struct GramPlan {
+  int S, tail_tiles, f;
+  int64_t kchunk, subchunk;
+  int64_t nwg;           // workgroups = slots of partial tiles
+  double cost;
+};
 
-extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, slim_dtype x_dtype, int m, int64_t t_c,
-                                               int64_t ldx, float* G, int64_t ldg, int64_t* n_tokens) {
-  if (!ctx) return SLIM_ERR_INVALID_ARG;
-  SLIM_REQUIRE(ctx, X && G && n_tokens, "slim_hessian_accumulate: null pointer");
-  SLIM_REQUIRE(ctx, m > 0 && t_c > 0, "slim_hessian_accumulate: need m > 0 and t_c > 0");
-  SLIM_REQUIRE(ctx, m % 8 == 0, "slim_hessian_accumulate: m must be a multiple of 8 (got %d)", m);
-  SLIM_REQUIRE(ctx, ldx >= t_c && ldx % 8 == 0, "slim_hessian_accumulate: ldx must be >= t_c and a multiple of 8");
-  SLIM_REQUIRE(ctx, ldg >= m, "slim_hessian_accumulate: ldg < m");
-  SLIM_REQUIRE(ctx, slim_aligned16(X) && slim_aligned16(G), "slim_hessian_accumulate: misaligned pointer");
-  if (x_dtype != SLIM_F16 && x_dtype != SLIM_BF16)
-    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_hessian_accumulate: X must be F16 or BF16");
-
+GramPlan gram_plan(int m, int64_t t_c, int ncu) {
   const int nt = slim_cdiv(m, TM);
   const int tiles = nt * (nt + 1) / 2;
   const int64_t iters = (t_c + BK - 1) / BK;
-  // Token ranges per tile: the number S (a power of two) for which a model of the launch is shortest.  A workgroup
-  // takes 1/S of a tile's time; n = tiles * S workgroups run in rounds of one per CU; the tiles of a last round that
-  // is at most half full are split f ways more, so that it is full of workgroups 1/f as long (m = 4096: 136 tiles,
-  // S = 2 gives one round plus 8 tiles cut 32 ways; m = 5120: 210 tiles, S = 4 gives 3 1/3 rounds where S = 1 or 2
-  // leave a fifth of the chip idle); every slot costs its 256 KB twice (written here, read by the reduction).
-  // Few ranges are better beyond the smaller reduction: each workgroup's fill and drain is paid once per range.
-  const int ncu = ctx->num_cus > 0 ? ctx->num_cus : 256;
-  struct Plan {
-    int S, tail_tiles, f;
-    int64_t kchunk, subchunk;
-    double cost;
-  };
   auto plan_for = [&](int S_try) {
-    Plan p;
+    GramPlan p;
     int S = (int)std::min<int64_t>(S_try, iters);
     p.kchunk = ((iters + S - 1) / S) * BK;
     S = (int)((t_c + p.kchunk - 1) / p.kchunk);
@@ -646,16 +634,40 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
     }
     const int64_t n_main = (int64_t)(tiles - p.tail_tiles) * S;
     const double rounds = (double)((n_main + ncu - 1) / ncu) + (p.tail_tiles > 0 ? 1.0 / p.f : 0.0);
-    const int64_t slots = n_main + (int64_t)p.tail_tiles * S * p.f;
+    p.nwg = n_main + (int64_t)p.tail_tiles * S * p.f;
     const double t_wg = 2.0 * TM * TM * (double)p.kchunk / 4.6e12;            // seconds per workgroup at 4.6 TFLOP/s per CU
-    p.cost = rounds * t_wg + (double)slots * TM * TM * sizeof(float) / 4.2e12;  // + the reduction's read of the slots
+    p.cost = rounds * t_wg + (double)p.nwg * TM * TM * sizeof(float) / 4.2e12;  // + the reduction's read of the slots
     return p;
   };
-  Plan best = plan_for(1);
+  GramPlan best = plan_for(1);
   for (int S_try = 2; S_try <= 1024 && (int64_t)S_try * 4 <= iters; S_try *= 2) {
-    const Plan p = plan_for(S_try);
+    const GramPlan p = plan_for(S_try);
     if (p.cost < best.cost * 0.995) best = p;
   }
+  return best;
+}
+
+}  // namespace
+
+size_t slim_ws_need_gram(int m, int64_t t_c, int ncu) {
+  return slim_ws_round(sizeof(float) * (size_t)gram_plan(m, t_c, ncu).nwg * TM * TM);
+}
+
+extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, slim_dtype x_dtype, int m, int64_t t_c,
+                                               int64_t ldx, float* G, int64_t ldg, int64_t* n_tokens) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, X && G && n_tokens, "slim_hessian_accumulate: null pointer");
+  SLIM_REQUIRE(ctx, m > 0 && t_c > 0, "slim_hessian_accumulate: need m > 0 and t_c > 0");
+  SLIM_REQUIRE(ctx, m % 8 == 0, "slim_hessian_accumulate: m must be a multiple of 8 (got %d)", m);
+  SLIM_REQUIRE(ctx, ldx >= t_c && ldx % 8 == 0, "slim_hessian_accumulate: ldx must be >= t_c and a multiple of 8");
+  SLIM_REQUIRE(ctx, ldg >= m, "slim_hessian_accumulate: ldg < m");
+  SLIM_REQUIRE(ctx, slim_aligned16(X) && slim_aligned16(G), "slim_hessian_accumulate: misaligned pointer");
+  if (x_dtype != SLIM_F16 && x_dtype != SLIM_BF16)
+    return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_hessian_accumulate: X must be F16 or BF16");
+
+  const int nt = slim_cdiv(m, TM);
+  const int tiles = nt * (nt + 1) / 2;
+  const GramPlan best = gram_plan(m, t_c, ctx->num_cus > 0 ? ctx->num_cus : 256);
   const int S = best.S, tail_tiles = best.tail_tiles, f = best.f;
   const int64_t kchunk = best.kchunk, subchunk = best.subchunk;
 
@@ -673,7 +685,7 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   const int64_t nwg = (int64_t)a.n_main + (int64_t)tail_tiles * S * f;
 
   const size_t pbytes = sizeof(float) * (size_t)nwg * TM * TM;
-  slim_status st = slim_ws_reserve(ctx, slim_ws_round(pbytes));
+  slim_status st = slim_ws_reserve(ctx, slim_ws_need_gram(m, t_c, ctx->num_cus > 0 ? ctx->num_cus : 256));
   if (st != SLIM_OK) return st;
   a.P = static_cast<float*>(slim_ws_alloc(ctx, pbytes));
 

@@ -366,6 +366,12 @@ __global__ __launch_bounds__(256) void colsum_finalize(const double* __restrict_
 
 }  // namespace
 
+size_t slim_ws_need_inverse(int m) {
+  const int nblk = slim_cdiv(m, NB), parts = slim_cdiv(m, 256);
+  return 2 * slim_ws_round(sizeof(double) * (size_t)m * m) + slim_ws_round(sizeof(double) * (size_t)parts * m) +
+         slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * nblk + 8)) + 256;
+}
+
 extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64_t ldg, int m, int64_t n_tokens,
                                             double percdamp, double* U, int64_t ldu, double* hinv_diag, int* info) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;
@@ -390,7 +396,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   const size_t bytes_A = slim_ws_round(sizeof(double) * (size_t)m * m);
   const size_t bytes_part = slim_ws_round(sizeof(double) * (size_t)parts * m);
   const size_t bytes_desc = slim_ws_round(sizeof(slim_gemm_desc) * (size_t)(2 * nblk + 8));
-  slim_status st = slim_ws_reserve(ctx, 2 * bytes_A + bytes_part + bytes_desc + 256);
+  slim_status st = slim_ws_reserve(ctx, slim_ws_need_inverse(m));
   if (st != SLIM_OK) return st;
   double* A = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));
   double* R = static_cast<double*>(slim_ws_alloc(ctx, bytes_A));

@@ -27,6 +27,7 @@ using namespace slimdev;
 constexpr int SQC_CPT = 4;        // candidates per thread in sqc_search_weighted
 constexpr int SQC_THREADS = 256;
 constexpr int STAT_ROWS = 8;      // rows per workgroup in block_stats
+constexpr int GPTQ_WINC = 512;    // columns per window of the sweep's two-level trailing updates
 
 // ------------------------------------------------------------------------------------------
 // Shifted first and second moments of an n x beta block, one partial pair per slab of STAT_ROWS rows.
@@ -916,6 +917,13 @@ slim_status check_params(slim_ctx* ctx, const slim_params* p, slim_params& out) 
 
 }  // namespace
 
+size_t slim_ws_need_sqc(int n) { return slim_ws_round(sizeof(double) * 2 * slim_cdiv(n, STAT_ROWS)); }
+
+size_t slim_ws_need_gptq(int n, int m) {
+  return slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * GPTQ_WINC) +
+         slim_ws_round(sizeof(double) * 2 * slim_cdiv(n, STAT_ROWS)) + slim_ws_round(sizeof(double) * n);
+}
+
 extern "C" slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int64_t ldw, int n, int beta, int bits,
                                           const double* omega, const double* hinv_diag_blk,
                                           const slim_params* params, const double* tau, int ncand, double* scale,
@@ -937,7 +945,7 @@ extern "C" slim_status slim_sqc_calibrate(slim_ctx* ctx, const double* Wblk, int
   SLIM_REQUIRE(ctx, !(omega == nullptr && prm.sqc_weight_mode == SLIM_WEIGHT_ELEMENT && hinv_diag_blk == nullptr),
                "slim_sqc_calibrate: ELEMENT weights need hinv_diag_blk");
   const int nstat = slim_cdiv(n, STAT_ROWS);
-  st = slim_ws_reserve(ctx, slim_ws_round(sizeof(double) * 2 * nstat));
+  st = slim_ws_reserve(ctx, slim_ws_need_sqc(n));
   if (st != SLIM_OK) return st;
   double* stat_partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * 2 * nstat));
   SqcArgs a;
@@ -1010,10 +1018,8 @@ extern "C" slim_status slim_gptq_quantize(slim_ctx* ctx, const void* W, slim_dty
   // 16 bytes of W per 32 flops and is bound by memory; this way most of the work has four times that intensity.
   // WINC is a multiple of every supported group size, so a group never straddles a window and the calibration at
   // a group's first column sees columns that have received every earlier block's update.
-  const int WINC = 512;
-  const size_t need = slim_ws_round(sizeof(double) * (size_t)n * m) + slim_ws_round(sizeof(double) * (size_t)n * WINC) +
-                      slim_ws_round(sizeof(double) * 2 * nstat) + slim_ws_round(sizeof(double) * n);
-  st = slim_ws_reserve(ctx, need);
+  constexpr int WINC = GPTQ_WINC;
+  st = slim_ws_reserve(ctx, slim_ws_need_gptq(n, m));
   if (st != SLIM_OK) return st;
   double* Wc = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * m));
   double* E = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)n * WINC));

@@ -84,6 +84,21 @@ __global__ __launch_bounds__(1024) void salience_finalize(const double* __restri
 
 }  // namespace
 
+// row slabs of the partial column sums: about 1024 workgroups in flight
+static void salience_parts(int n, int m, int& nparts, int& rpp) {
+  const int gx = slim_cdiv(m, 1024);
+  nparts = (1024 + gx - 1) / gx;
+  if (nparts > n) nparts = n;
+  rpp = slim_cdiv(n, nparts);
+  nparts = slim_cdiv(n, rpp);
+}
+
+size_t slim_ws_need_salience(int n, int m) {
+  int nparts = 0, rpp = 0;
+  salience_parts(n, m, nparts, rpp);
+  return slim_ws_round(sizeof(double) * (size_t)nparts * m);
+}
+
 extern "C" slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
                                      const double* U, int64_t ldu, const double* hinv_diag, int sal_mode,
                                      int beta, double* col_sal, double* group_sal, double* elem_sal) {
@@ -109,11 +124,9 @@ extern "C" slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_
     return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_salience: W must be F16, BF16 or F32");
 
   const int gx = slim_cdiv(m, 1024);
-  int nparts = (1024 + gx - 1) / gx;          // about 1024 workgroups in flight
-  if (nparts > n) nparts = n;
-  const int rpp = slim_cdiv(n, nparts);
-  nparts = slim_cdiv(n, rpp);
-  slim_status st = slim_ws_reserve(ctx, slim_ws_round(sizeof(double) * (size_t)nparts * m));
+  int nparts = 0, rpp = 0;
+  salience_parts(n, m, nparts, rpp);
+  slim_status st = slim_ws_reserve(ctx, slim_ws_need_salience(n, m));
   if (st != SLIM_OK) return st;
   double* partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)nparts * m));
 

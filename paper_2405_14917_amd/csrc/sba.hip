@@ -482,6 +482,24 @@ struct SbaWorkspace {
   int *order, *rank_of, *pstar_dev;
 };
 
+}  // namespace
+
+size_t slim_ws_need_sba(int n, int m, int beta, int64_t t_s) {
+  const int k = m / beta, pmax = k / 2;
+  const bool fused = n % SEARCH_TILE == 0 && t_s % SEARCH_TILE == 0 && (2 * beta) % 16 == 0;
+  const int parts = slim_cdiv(n, fused ? SEARCH_TILE : 256), kl_blocks = slim_cdiv(t_s, 256);
+  const size_t bW = slim_ws_round(sizeof(double) * (size_t)n * m);
+  const size_t bX = slim_ws_round(sizeof(double) * (size_t)m * t_s);
+  const size_t bY = slim_ws_round(sizeof(double) * (size_t)n * t_s);
+  const size_t bPart = slim_ws_round(sizeof(double) * (size_t)parts * t_s * KL_PART);
+  const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(pmax + 2) * (size_t)(kl_blocks + 1));
+  const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * k + 2));
+  const size_t bTok = slim_ws_round(sizeof(double) * 3 * (size_t)t_s);
+  return 3 * bW + 2 * bX + 2 * bY + (size_t)(pmax + 1) * bPart + bObj + bOrd + bTok + 256;
+}
+
+namespace {
+
 slim_status sba_workspace(slim_ctx* ctx, int n, int m, int beta, int64_t t_s, SbaWorkspace& w) {
   w.k = m / beta;
   w.pmax = w.k / 2;
@@ -497,8 +515,7 @@ slim_status sba_workspace(slim_ctx* ctx, int n, int m, int beta, int64_t t_s, Sb
   const size_t bObj = slim_ws_round(sizeof(double) * (size_t)(w.pmax + 2) * (size_t)(w.kl_blocks + 1));
   const size_t bOrd = slim_ws_round(sizeof(int) * (size_t)(2 * w.k + 2));
   const size_t bTok = slim_ws_round(sizeof(double) * 3 * (size_t)t_s);
-  slim_status st =
-      slim_ws_reserve(ctx, 3 * bW + 2 * bX + 2 * bY + (size_t)(w.pmax + 1) * bPart + bObj + bOrd + bTok + 256);
+  slim_status st = slim_ws_reserve(ctx, slim_ws_need_sba(n, m, beta, t_s));
   if (st != SLIM_OK) return st;
   w.W64 = static_cast<double*>(slim_ws_alloc(ctx, bW));
   w.WN = static_cast<double*>(slim_ws_alloc(ctx, bW));

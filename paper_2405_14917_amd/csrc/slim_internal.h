@@ -47,6 +47,7 @@ struct slim_ctx {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   size_t ws_off = 0;
+  bool ws_external = false;       // the workspace is the caller's (given to slim_create): never grown, never freed
   // small fixed buffers
   double* tau_default = nullptr;  // device, SLIM_DEFAULT_NCAND doubles
   int ncand_default = 0;
@@ -80,6 +81,16 @@ slim_status slim_fail(slim_ctx* ctx, slim_status code, const char* fmt, ...);
 slim_status slim_ws_reserve(slim_ctx* ctx, size_t bytes);
 void* slim_ws_alloc(slim_ctx* ctx, size_t bytes);
 inline size_t slim_ws_round(size_t bytes) { return (bytes + 255) & ~size_t(255); }
+
+// Bytes of workspace each entry point reserves for a layer of the given shape (host only; the entry points use the
+// same functions, so slim_workspace_query, their maximum, is exact).  ncu = compute units of the device.
+size_t slim_ws_need_gram(int m, int64_t t_c, int ncu);
+size_t slim_ws_need_inverse(int m);
+size_t slim_ws_need_salience(int n, int m);
+size_t slim_ws_need_sba(int n, int m, int beta, int64_t t_s);
+size_t slim_ws_need_sqc(int n);
+size_t slim_ws_need_gptq(int n, int m);
+size_t slim_ws_need_dequant(int n, int m, int beta, int t_x, int ncu);
 
 // Looks up (once per device) the device address of the fixed buffer of slim_dequant_matmul_noalloc (dequant.hip).
 slim_status slim_dq_scratch_resolve(slim_ctx* ctx);

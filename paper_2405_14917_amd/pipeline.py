@@ -16,7 +16,10 @@ class LayerPass:
     salience (the reference outputs and the outputs of the all-N-bit weights, two n x m x t_s products) is enqueued
     on the second stream before the inverse, whose chain of small kernels leaves most of the chip idle."""
 
-    def __init__(self, slim, m, beta, N, percdamp=0.01, t_sba=2048, device="cuda:0"):
+    def __init__(self, slim, m, beta, N, percdamp=0.01, t_sba=2048, device="cuda:0", n=None):
+        """n (output rows of the largest layer that will be passed): if given, the second context gets a workspace of
+        the size slim_workspace_query states for the bit allocation of such a layer, allocated here once, so that no
+        call on it allocates; without it the context grows its own."""
         self.slim, self.m, self.beta, self.N, self.percdamp, self.t_sba = slim, m, beta, N, percdamp, t_sba
         self.bit_base = binding.bit_base_for(N)     # of the stored form: what its 2-bit group value 0 stands for
         self.G = torch.zeros((m, m), dtype=torch.float32, device=device)
@@ -25,7 +28,7 @@ class LayerPass:
         self.main = torch.cuda.current_stream()
         self.side = torch.cuda.Stream()
         with torch.cuda.stream(self.side):
-            self.slim_sba = binding.Slim(device)
+            self.slim_sba = binding.Slim(device, 0 if n is None else binding.workspace_query(n, m, beta, 0, t_sba))
 
     def contexts(self):
         return [self.slim, self.slim_sba]
@@ -48,8 +51,9 @@ class LayerPass:
         """Salience, bit allocation (on the second context when its first half is already there), sweep, packing."""
         s, s2 = self.slim, self.slim_sba
         _, grp, _ = s.salience(W, self.d, self.beta)
-        # no call here asks for a host output, so the host never waits for the stream inside a pass (the sweep reads
-        # the widths back itself, behind work it has already enqueued); p_star and m_star stay on the device
+        # no call here asks for a host output (p_star and m_star stay on the device).  The one wait of the host
+        # inside a pass is the sweep's: it reads the k widths back, for validation and to choose its kernels, behind
+        # the widening of W that it has already enqueued
         if prepared:
             self.side.wait_stream(self.main)
             with torch.cuda.stream(self.side):

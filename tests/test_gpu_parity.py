@@ -717,6 +717,50 @@ def test_layers_that_share_their_input_share_the_hessian(slim):
         drv.close()
 
 
+def test_caller_workspace_of_the_queried_size(slim):
+    """Contexts that work in caller memory of exactly the size slim_workspace_query states run the whole pass and
+    give what the self-growing contexts give, bit for bit; no call changes the workspace; one byte less than a call
+    needs and it is refused (SLIM_ERR_ALLOC) before anything is touched."""
+    from paper_2405_14917_amd import binding, pipeline
+    n, m, beta, N, t, ts = 320, 768, 128, 2, 4096, 256
+    W, X = small_layer(96, n=n, m=m, t=t, beta=beta)
+    need = binding.workspace_query(n, m, beta, t, ts, 4)
+    fixed = binding.Slim("cuda:0", need)
+    try:
+        assert fixed.workspace_bytes() == need
+        drv_f = pipeline.LayerPass(fixed, m, beta, N, 0.01, t_sba=ts, n=n)
+        drv_g = pipeline.LayerPass(slim, m, beta, N, 0.01, t_sba=ts)
+        try:
+            a, b = drv_f.run(dev(W), dev(X)), drv_g.run(dev(W), dev(X))
+            torch.cuda.synchronize()
+            for key in ("bits", "codes", "scale", "zero", "packed", "gbits", "row_off"):
+                assert torch.equal(a[key], b[key]), key
+            assert torch.equal(drv_f.U, drv_g.U)
+            assert fixed.workspace_bytes() == need
+            assert drv_f.slim_sba.workspace_bytes() == binding.workspace_query(n, m, beta, 0, ts)
+            Xin = dev(X)[:, :4].t().contiguous()
+            Ya = fixed.dequant_matmul(a["packed"], a["gbits"], a["row_off"], a["scale"], a["zero"], beta, Xin)
+            Yb = slim.dequant_matmul(b["packed"], b["gbits"], b["row_off"], b["scale"], b["zero"], beta, Xin)
+            assert torch.equal(Ya, Yb)
+        finally:
+            drv_f.close()
+            drv_g.close()
+    finally:
+        fixed.close()
+    # too small for the inverse of this m: refused, outputs untouched
+    tiny = binding.Slim("cuda:0", binding.workspace_query(0, m, 0) - 256)
+    try:
+        G = torch.eye(m, dtype=torch.float32, device="cuda")
+        U = torch.full((m, m), 7.0, dtype=torch.float64, device="cuda")
+        with pytest.raises(binding.SlimError) as e:
+            tiny.hessian_inverse(G, 16, 0.01, U=U)
+        assert e.value.status == binding.ERR_ALLOC and "slim_workspace_query" in str(e.value)
+        torch.cuda.synchronize()
+        assert bool((U == 7.0).all())
+    finally:
+        tiny.close()
+
+
 def test_pack_rejects_bad_input(slim):
     from paper_2405_14917_amd import binding
     codes = dev(np.zeros((8, 128), dtype=np.uint8))

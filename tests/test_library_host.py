@@ -88,3 +88,21 @@ def test_the_product_never_imports_the_oracle():
                 text = open(os.path.join(dirpath, f), errors="ignore").read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
                 assert "slim_oracle" not in text, f
+
+
+def test_workspace_query_is_host_only_and_follows_the_entry_points(binding):
+    """slim_workspace_query needs no GPU; for the benchmark shapes the inverse (two m x m fp64 matrices), the bit
+    allocation (three n x m and two n x t_s fp64 matrices) or the partial tiles of the Gram matrix dominate."""
+    q = binding.workspace_query
+    assert q(0, 0, 0) == 0
+    m = 4096
+    assert q(0, m, 0) >= 2 * 8 * m * m                        # the inverse alone
+    assert q(0, m, 0, t_c=131072, num_cus=256) >= q(0, m, 0)   # plus the Gram matrix's partial tiles
+    n, beta, ts = 4096, 128, 2048
+    sba = 3 * 8 * n * m + 2 * 8 * m * ts + 2 * 8 * n * ts
+    assert q(n, m, beta, t_s=ts) >= sba
+    assert q(n, m, beta) >= 8 * n * m + 8 * n * 512           # the sweep: working copy of W and a window of errors
+    full = q(n, m, beta, 131072, ts, 16, 256)
+    assert full == max(q(0, m, 0, t_c=131072, num_cus=256), q(n, m, beta, t_s=ts), q(n, m, beta, t_x=16, num_cus=256))
+    # a small Gram matrix is split into more token ranges: the requirement is not monotone in m
+    assert q(0, 256, 0, t_c=1 << 20, num_cus=256) > 0
