@@ -51,43 +51,54 @@ template <int V>
 __global__ __launch_bounds__(256) void widen_damp(const float* __restrict__ G, int64_t ldg, int m, double s,
                                                   const double* __restrict__ lam, double* __restrict__ A,
                                                   int64_t lda, double* __restrict__ U, int64_t ldu) {
+  constexpr int ROWS = 8;                      // rows per thread: the loads of all of them are issued first
   const int c0 = (blockIdx.x * 256 + threadIdx.x) * V;
-  const int r = blockIdx.y;
+  const int r0 = blockIdx.y * ROWS;
   if (c0 >= m) return;
-  float g[V];
+  float g[ROWS][V];
 #pragma unroll
-  for (int v = 0; v < V; ++v) g[v] = 0.0f;
-  if (c0 + V - 1 >= r) {                       // something of this piece lies on or above the diagonal
-    const float* src = G + (int64_t)r * ldg + c0;
-    if (V == 4) {
-      const float4 t = *reinterpret_cast<const float4*>(src);
-      g[0] = t.x, g[1] = t.y, g[2] = t.z, g[3] = t.w;
-    } else if (V == 2) {
-      const float2 t = *reinterpret_cast<const float2*>(src);
-      g[0] = t.x, g[1] = t.y;
-    } else {
-      g[0] = src[0];
+  for (int q = 0; q < ROWS; ++q) {
+    const int r = r0 + q;
+#pragma unroll
+    for (int v = 0; v < V; ++v) g[q][v] = 0.0f;
+    if (r < m && c0 + V - 1 >= r) {            // something of this piece lies on or above the diagonal
+      const float* src = G + (int64_t)r * ldg + c0;
+      if (V == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        g[q][0] = t.x, g[q][1] = t.y, g[q][2] = t.z, g[q][3] = t.w;
+      } else if (V == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(src);
+        g[q][0] = t.x, g[q][1] = t.y;
+      } else {
+        g[q][0] = src[0];
+      }
     }
   }
-  double a[V];
+  const double lambda = *lam;
 #pragma unroll
-  for (int v = 0; v < V; ++v) {
-    const int c = c0 + v;
-    a[v] = c >= r ? s * (double)g[v] : 0.0;
-    if (c == r) a[v] += *lam;
-  }
-  double* da = A + (int64_t)r * lda + c0;
-  double* du = U + (int64_t)r * ldu + c0;
-  const bool upper = c0 + V - 1 >= r;          // has an element on or above the diagonal
-  const bool lower = c0 < r;                   // has an element below it
-  if (V == 1) {
-    if (upper) da[0] = a[0];
-    if (lower) du[0] = 0.0;
-  } else {
+  for (int q = 0; q < ROWS; ++q) {
+    const int r = r0 + q;
+    if (r >= m) break;
+    double a[V];
 #pragma unroll
-    for (int v = 0; v < V; v += 2) {
-      if (upper) *reinterpret_cast<double2*>(da + v) = make_double2(a[v], a[v + 1]);
-      if (lower) *reinterpret_cast<double2*>(du + v) = make_double2(0.0, 0.0);
+    for (int v = 0; v < V; ++v) {
+      const int c = c0 + v;
+      a[v] = c >= r ? s * (double)g[q][v] : 0.0;
+      if (c == r) a[v] += lambda;
+    }
+    double* da = A + (int64_t)r * lda + c0;
+    double* du = U + (int64_t)r * ldu + c0;
+    const bool upper = c0 + V - 1 >= r;        // has an element on or above the diagonal
+    const bool lower = c0 < r;                 // has an element below it
+    if (V == 1) {
+      if (upper) da[0] = a[0];
+      if (lower) du[0] = 0.0;
+    } else {
+#pragma unroll
+      for (int v = 0; v < V; v += 2) {
+        if (upper) *reinterpret_cast<double2*>(da + v) = make_double2(a[v], a[v + 1]);
+        if (lower) *reinterpret_cast<double2*>(du + v) = make_double2(0.0, 0.0);
+      }
     }
   }
 }
@@ -410,11 +421,11 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   // one pass writes A (widened, damped) and clears U; 4 / 2 / 1 columns per thread as alignment allows
   const bool g16 = (reinterpret_cast<uintptr_t>(G) & 15u) == 0, g8 = (reinterpret_cast<uintptr_t>(G) & 7u) == 0;
   if (m % 4 == 0 && ldg % 4 == 0 && ldu % 4 == 0 && g16)
-    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<4>, dim3(slim_cdiv(m, 1024), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<4>, dim3(slim_cdiv(m, 1024), slim_cdiv(m, 8)), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
   else if (ldg % 2 == 0 && g8)
-    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<2>, dim3(slim_cdiv(m, 512), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<2>, dim3(slim_cdiv(m, 512), slim_cdiv(m, 8)), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
   else
-    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<1>, dim3(slim_cdiv(m, 256), m), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
+    SLIM_LAUNCH(ctx, "inv_widen", widen_damp<1>, dim3(slim_cdiv(m, 256), slim_cdiv(m, 8)), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
 
   // ---- descriptors of the triangular inverse (pairwise merging of inverted diagonal ranges), staged first so
   //      that no host synchronisation falls between the factorisation and the inverse

@@ -2,14 +2,14 @@
 // group its start row in the packed matrix), the 2-bit-per-group width array, and the bit-packing of the
 // codes.  Integer work only; bound by HBM traffic (1 byte read per weight, N/8 bytes written).
 //
-// pack_codes: one workgroup per (group, slab of 64 output rows).  The slab's 64 x beta codes are read
-// with coalesced row accesses into LDS; then thread i of the slab assembles the words of output row i
-// one by one, so that the 64 threads write 64 consecutive words of one row of the packed matrix.
+// pack_codes: one workgroup per (group, slab of 256 output rows).  The slab's 256 x beta codes are read
+// with coalesced row accesses into LDS (four codes per word); then thread i of the slab assembles the words of
+// output row i one by one, so that the 256 threads write 256 consecutive words of one row of the packed matrix.
 #include "slim_internal.h"
 
 namespace {
 
-constexpr int PACK_ROWS = 64;
+constexpr int PACK_ROWS = 256;
 
 // single workgroup: validates widths, exclusive scan of beta * b_g / 32, width array
 __global__ __launch_bounds__(256) void pack_scan(const uint8_t* __restrict__ bits, int k, int beta, int bit_base,
@@ -51,39 +51,69 @@ __global__ __launch_bounds__(PACK_ROWS) void pack_codes(const uint8_t* __restric
                                                         const uint8_t* __restrict__ bits, int beta,
                                                         const int32_t* __restrict__ row_off,
                                                         uint32_t* __restrict__ packed, int64_t packed_rows) {
-  extern __shared__ uint8_t tile[];   // [PACK_ROWS][beta + 4]
+  extern __shared__ uint32_t tile[];   // [PACK_ROWS][beta / 4 + 1] words of four codes each
   const int g = blockIdx.y;
   const int i0 = blockIdx.x * PACK_ROWS;
   const int rows = min(PACK_ROWS, n - i0);
-  const int stride = beta + 4;
+  const int quads = beta / 4;          // beta is a multiple of 32
+  const int stride = quads + 1;        // odd: the rows' words fall into different banks
   const int b = bits[g];
   if (b < 1 || b > 8) return;
-  // beta is a multiple of 32: read 4 codes per thread and step
-  const int quads = beta / 4;
-  for (int idx = threadIdx.x; idx < rows * quads; idx += PACK_ROWS) {
-    const int r = idx / quads, q = idx - r * quads;
-    const uint32_t v = *reinterpret_cast<const uint32_t*>(codes + (int64_t)(i0 + r) * ldc + (int64_t)g * beta + 4 * q);
-    *reinterpret_cast<uint32_t*>(tile + r * stride + 4 * q) = v;
+  // the slab's codes, sixteen per thread and step where the alignment allows (rows read in whole, coalesced),
+  // eight loads in flight per thread
+  const uint8_t* src = codes + (int64_t)i0 * ldc + (int64_t)g * beta;
+  if ((ldc & 15) == 0 && (reinterpret_cast<uintptr_t>(codes) & 15u) == 0) {
+    const int chunks = beta / 16, total = rows * chunks;
+    for (int base = 0; base < total; base += 8 * PACK_ROWS) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int idx = min(base + u * PACK_ROWS + (int)threadIdx.x, total - 1);
+        const int r = idx / chunks, ch = idx - r * chunks;
+        v[u] = *reinterpret_cast<const uint4*>(src + (int64_t)r * ldc + 16 * ch);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int idx = base + u * PACK_ROWS + (int)threadIdx.x;
+        if (idx < total) {
+          const int r = idx / chunks, ch = idx - r * chunks;
+          uint32_t* t = tile + r * stride + 4 * ch;
+          t[0] = v[u].x, t[1] = v[u].y, t[2] = v[u].z, t[3] = v[u].w;
+        }
+      }
+    }
+  } else {
+    for (int idx = threadIdx.x; idx < rows * quads; idx += PACK_ROWS) {
+      const int r = idx / quads, q = idx - r * quads;
+      tile[r * stride + q] = *reinterpret_cast<const uint32_t*>(src + (int64_t)r * ldc + 4 * q);
+    }
   }
   __syncthreads();
   const int i = threadIdx.x;
   if (i >= rows) return;
-  const uint8_t* c = tile + i * stride;
-  const int nw = beta * b / 32;
+  // Thread i builds the bit stream of output row i0 + i: codes enter a 64-bit window from above, a word leaves it
+  // from below whenever 32 bits are complete (element r at bits [r b, (r + 1) b) of the stream, little endian).
+  const uint32_t* c = tile + i * stride;
   const uint32_t mask = (1u << b) - 1u;
-  const int64_t base = row_off[g];
-  for (int w = 0; w < nw; ++w) {
-    // the word covers stream bits [32 w, 32 w + 32): elements floor(32 w / b) .. ceil((32 w + 32) / b) - 1
-    const int e0 = (32 * w) / b;
-    const int e1 = min(beta, (32 * w + 32 + b - 1) / b);
-    uint32_t word = 0;
-    for (int e = e0; e < e1; ++e) {
-      const uint32_t v = c[e] & mask;
-      const int sh = e * b - 32 * w;
-      word |= (sh >= 0) ? (v << sh) : (v >> (-sh));
+  uint64_t win = 0;
+  int have = 0;
+  int64_t r = row_off[g];
+  uint32_t* out = packed + i0 + i;
+  // four codes at a time: the four bytes of a word are squeezed to 4 b adjacent bits in two steps (bytes to
+  // pairs, pairs to the quad), which costs the same for every width
+  const uint32_t byte_mask = mask * 0x01010101u;
+  for (int q = 0; q < quads; ++q) {
+    const uint32_t v = c[q] & byte_mask;
+    const uint32_t pair = (v & 0x00ff00ffu) | (((v >> 8) & 0x00ff00ffu) << b);      // codes (0,1) and (2,3), 2 b bits each
+    const uint32_t x = (pair & 0xffffu) | ((pair >> 16) << (2 * b));                 // all four, 4 b bits
+    win |= (uint64_t)x << have;
+    have += 4 * b;
+    if (have >= 32) {
+      if (r < packed_rows) out[r * n] = (uint32_t)win;
+      ++r;
+      win >>= 32;
+      have -= 32;
     }
-    const int64_t r = base + w;
-    if (r < packed_rows) packed[r * n + i0 + i] = word;
   }
 }
 
@@ -103,7 +133,16 @@ extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int
   const int k = m / beta;
   int* flags = ctx->dflags;   // flags[0] is cleared by pack_scan itself
   SLIM_LAUNCH(ctx, "pack_scan", pack_scan, dim3(1), dim3(256), 0, bits, k, beta, bit_base, row_off, gbits, flags);
-  const size_t smem = (size_t)PACK_ROWS * (beta + 4);
+  const size_t smem = sizeof(uint32_t) * (size_t)PACK_ROWS * (beta / 4 + 1);
+  if (smem > 160 * 1024) return slim_fail(ctx, SLIM_ERR_UNSUPPORTED, "slim_pack: beta = %d is too large (at most 636)", beta);
+  if (smem > 64 * 1024) {
+    static bool done = false;
+    if (!done) {
+      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(pack_codes),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      done = true;
+    }
+  }
   SLIM_LAUNCH(ctx, "pack_codes", pack_codes, dim3(slim_cdiv(n, PACK_ROWS), k), dim3(PACK_ROWS), smem, codes, n, ldc,
               bits, beta, row_off, packed, packed_rows);
   if (!m_star) return SLIM_OK;                     // nothing for the host: the call does not wait (and cannot report)

@@ -9,8 +9,10 @@ namespace {
 
 using slimdev::load4;
 
-// grid (ceil(m / 1024), nparts); thread -> 4 consecutive columns; part p owns rows [p*rpp, (p+1)*rpp)
-template <typename T>
+// grid (ceil(m / 1024), nparts); thread -> 4 consecutive columns; part p owns rows [p*rpp, (p+1)*rpp).
+// Rows are taken eight at a time with all eight loads issued before the first is used: the kernel is a stream
+// over W, and a thread that waits for every row's load in turn leaves most of the memory system idle.
+template <typename T, bool ELEM>
 __global__ __launch_bounds__(256) void colsumsq_partial(const T* __restrict__ W, int n, int m, int64_t ldw,
                                                         int rows_per_part, const double* __restrict__ dden,
                                                         int64_t dstride, double* __restrict__ partial,
@@ -21,21 +23,36 @@ __global__ __launch_bounds__(256) void colsumsq_partial(const T* __restrict__ W,
   const int r1 = min(n, r0 + rows_per_part);
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
   double inv[4] = {0.0, 0.0, 0.0, 0.0};
-  if (elem_sal) {
+  if (ELEM) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const double d = dden[(int64_t)(c0 + j) * dstride];
       inv[j] = d * d;
     }
   }
-  for (int r = r0; r < r1; ++r) {
+  constexpr int UR = 8;
+  int r = r0;
+  for (; r + UR <= r1; r += UR) {
+    double w[UR][4];
+#pragma unroll
+    for (int u = 0; u < UR; ++u) load4<T>(W + (int64_t)(r + u) * ldw + c0, w[u]);
+#pragma unroll
+    for (int u = 0; u < UR; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double sq = w[u][j] * w[u][j];
+        acc[j] += sq;                                   // rows in order: the sum does not depend on the unrolling
+        if (ELEM) elem_sal[(int64_t)(r + u) * m + c0 + j] = sq / inv[j];
+      }
+  }
+  for (; r < r1; ++r) {
     double w[4];
     load4<T>(W + (int64_t)r * ldw + c0, w);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const double sq = w[j] * w[j];
       acc[j] += sq;
-      if (elem_sal) elem_sal[(int64_t)r * m + c0 + j] = sq / inv[j];
+      if (ELEM) elem_sal[(int64_t)r * m + c0 + j] = sq / inv[j];
     }
   }
 #pragma unroll
@@ -84,10 +101,10 @@ __global__ __launch_bounds__(1024) void salience_finalize(const double* __restri
 
 }  // namespace
 
-// row slabs of the partial column sums: about 1024 workgroups in flight
+// row slabs of the partial column sums: about 2048 workgroups (eight per compute unit)
 static void salience_parts(int n, int m, int& nparts, int& rpp) {
   const int gx = slim_cdiv(m, 1024);
-  nparts = (1024 + gx - 1) / gx;
+  nparts = (2048 + gx - 1) / gx;
   if (nparts > n) nparts = n;
   rpp = slim_cdiv(n, nparts);
   nparts = slim_cdiv(n, rpp);
@@ -131,15 +148,17 @@ extern "C" slim_status slim_salience(slim_ctx* ctx, const void* W, slim_dtype w_
   double* partial = static_cast<double*>(slim_ws_alloc(ctx, sizeof(double) * (size_t)nparts * m));
 
   const dim3 grid(gx, nparts), block(256);
-  if (w_dtype == SLIM_F16)
-    SLIM_LAUNCH(ctx, "salience_colsumsq", colsumsq_partial<__half>, grid, block, 0, static_cast<const __half*>(W), n, m,
-                ldw, rpp, dden, dstride, partial, elem_sal);
-  else if (w_dtype == SLIM_BF16)
-    SLIM_LAUNCH(ctx, "salience_colsumsq", colsumsq_partial<__hip_bfloat16>, grid, block, 0,
-                static_cast<const __hip_bfloat16*>(W), n, m, ldw, rpp, dden, dstride, partial, elem_sal);
-  else
-    SLIM_LAUNCH(ctx, "salience_colsumsq", colsumsq_partial<float>, grid, block, 0, static_cast<const float*>(W), n, m,
-                ldw, rpp, dden, dstride, partial, elem_sal);
+#define SLIM_COLSUMSQ(T, E)                                                                                      \
+  SLIM_LAUNCH(ctx, "salience_colsumsq", (colsumsq_partial<T, E>), grid, block, 0, static_cast<const T*>(W), n, m, ldw, \
+              rpp, dden, dstride, partial, elem_sal)
+  if (w_dtype == SLIM_F16) {
+    if (elem_sal) SLIM_COLSUMSQ(__half, true); else SLIM_COLSUMSQ(__half, false);
+  } else if (w_dtype == SLIM_BF16) {
+    if (elem_sal) SLIM_COLSUMSQ(__hip_bfloat16, true); else SLIM_COLSUMSQ(__hip_bfloat16, false);
+  } else {
+    if (elem_sal) SLIM_COLSUMSQ(float, true); else SLIM_COLSUMSQ(float, false);
+  }
+#undef SLIM_COLSUMSQ
   SLIM_LAUNCH(ctx, "salience_finalize", salience_finalize, dim3(m / beta), dim3(1024), 0, partial, nparts, n, m, beta,
               dden, dstride, col_sal, group_sal);
   return SLIM_OK;
