@@ -243,6 +243,23 @@ slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t
                       int32_t* row_off, int* m_star);
 
 /* ---------------------------------------------------------------------------------------------
+ * a9  Zero points as packed integers (App. B.2: packed with one precision along the channel direction).
+ *   zero      n x k doubles (ld = ldz), as slim_gptq_quantize writes them (device)
+ *   zbits     width of a stored zero point, 2..16.  The stored value is 2 z (Eq. 1 gives integer zeros, the sign form of
+ *             width 1 has z = 1/2); a layer of target width N has zeros up to 2^(N+1) - 1, so N + 2 bits hold them
+ *   zpacked   k x ceil(n zbits / 32) words (ld = ldzp): for every group the n values form a little-endian bit stream
+ *             along the output channels, element i at bits [i zbits, (i + 1) zbits)
+ *   n_bad     host, or NULL (the call then does not wait): the number of zero points that are not a multiple of 1/2
+ *             or do not fit (Eq. 1 does not bound the zero of a group whose weights all have one sign); they are stored
+ *             as 0 or the largest value, whichever is nearer, and the layer should keep its zeros in floating point
+ * slim_unpack_zeros is the inverse (z = stored value / 2, exact).
+ */
+slim_status slim_pack_zeros(slim_ctx* ctx, const double* zero, int n, int k, int64_t ldz, int zbits, uint32_t* zpacked,
+                            int64_t ldzp, int* n_bad);
+slim_status slim_unpack_zeros(slim_ctx* ctx, const uint32_t* zpacked, int64_t ldzp, int n, int k, int zbits,
+                              double* zero, int64_t ldz);
+
+/* ---------------------------------------------------------------------------------------------
  * n1  Linear layer on the stored form (App. B.2, inference; built from the list of next steps).
  *   Y[t][i] = sum_j X[t][j] * scale[i][g] * (q_ij - zero[i][g]),   g = j / beta   (Eq. 1),
  *   the codes q_ij decoded from packed / gbits / row_off exactly as slim_pack writes them.

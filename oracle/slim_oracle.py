@@ -18,6 +18,8 @@ beta along the input dimension; k = m / beta groups; target average width N):
   sqc_calibrate       Eq. 5, Alg. 2 (SQC)         tau grid search per (row, group)
   gptq_quantize       Alg. 1 lines 5-13           column-serial quantisation with compensation
   pack / unpack       App. B.2                    per-group bit-packing, group-bit array, offsets
+  pack_zeros / unpack_zeros  App. B.2             zero points packed with one width along the channel direction
+  sequential_layers   Sec. 3.4 (GPTQ backbone)    layers quantised one after another on their quantised predecessors' outputs
   dequant_matmul      App. B.2 (inference)        y = x dequant(W_int)^T straight from the packed tensors
 
 Readings taken where the paper is silent or inconsistent are stated at the
@@ -32,7 +34,9 @@ pin can decide are marked "parity unpinned" here:
   with the same default on both sides; the formula of each mode is pinned.
   Likewise the bit order inside the packed words and the meaning of the 2-bit group
   value (width minus bit_base, bit_base_for(N)): App. B.2 gives the structure only;
-  the layout written here is pinned by hand-worked words and round trips.
+  the layout written here is pinned by hand-worked words and round trips.  The same holds
+  for the packed zero points (what is stored: 2 z; the width; the direction): App. B.2
+  says "uniform precision along the channel direction" and no more.
 """
 from __future__ import annotations
 
@@ -589,6 +593,82 @@ def dequant_matmul(packed: np.ndarray, gbits: np.ndarray, row_off: np.ndarray, s
         Wg = scale[:, g][:, None] * (q - zero[:, g][:, None])                            # (n, beta)
         Y += X[:, g * beta:(g + 1) * beta] @ Wg.T
     return Y
+
+
+def zero_bits_for(N: int) -> int:
+    """Width of a packed zero point for a layer of target width N: the stored value is 2 z (Eq. 1 gives integer
+    zeros in 0 .. 2^b - 1 for a group that straddles zero, the sign form of width 1 has z = 1/2), and the widest
+    group has N + 1 bits, so 2 z <= 2^(N+2) - 2 fits N + 2 bits."""
+    return int(N) + 2
+
+
+def pack_zeros(zero: np.ndarray, zbits: int):
+    """Zero points as packed integers (App. B.2: packed with a uniform precision along the channel direction).
+
+    zero is (n, k): output channels x groups.  For every group g the n values u_i = 2 z_ig (integers) form a
+    little-endian bit stream along the output channels, element i at bits [i zbits, (i + 1) zbits), cut into
+    32-bit words: zp[g, w].  Returns (zp uint32 (k, ceil(n zbits / 32)), n_bad): a value that is not a multiple of
+    1/2 or does not fit zbits bits (Eq. 1 does not bound the zero of a group whose weights all have one sign) is
+    counted in n_bad and stored as 0 or the largest value, whichever is nearer."""
+    zero = np.asarray(zero, dtype=np.float64)
+    n, k = zero.shape
+    top = (1 << zbits) - 1
+    nw = (n * zbits + 31) // 32
+    zp = np.zeros((k, nw), dtype=np.uint32)
+    n_bad = 0
+    for g in range(k):
+        stream = 0
+        for i in range(n):
+            u2 = 2.0 * zero[i, g]
+            u = int(np.rint(u2))
+            if u != u2 or u < 0 or u > top:
+                n_bad += 1
+                u = min(max(u, 0), top)
+            stream |= u << (i * zbits)
+        for w in range(nw):
+            zp[g, w] = (stream >> (32 * w)) & 0xFFFFFFFF
+    return zp, n_bad
+
+
+def unpack_zeros(zp: np.ndarray, n: int, zbits: int) -> np.ndarray:
+    """Inverse of pack_zeros: (n, k) float64 zero points z = u / 2."""
+    k = zp.shape[0]
+    zero = np.zeros((n, k))
+    for g in range(k):
+        stream = 0
+        for w in range(zp.shape[1]):
+            stream |= int(zp[g, w]) << (32 * w)
+        for i in range(n):
+            zero[i, g] = ((stream >> (i * zbits)) & ((1 << zbits) - 1)) / 2.0
+    return zero
+
+
+# ----------------------------------------------------------------------------------------
+# Layers one after another (Sec. 3.4: SBA and SQC inside GPTQ, whose layers are calibrated on
+# the outputs of their already quantised predecessors)
+# ----------------------------------------------------------------------------------------
+def next_layer_input(out: dict, beta: int, N: int, X: np.ndarray) -> np.ndarray:
+    """Calibration activations of the next layer: the quantised layer applied to X (m x t, channels x tokens) FROM
+    ITS STORED FORM (packed codes, group widths, start rows, scales, zeros), rounded to fp16 like every activation
+    tensor of the path: returns (n x t) float16."""
+    Y = dequant_matmul(out["packed"], out["gbits"], out["row_off"], out["scale"], out["zero"], beta,
+                       np.asarray(X, dtype=np.float64).T, bit_base_for(N))
+    return np.clip(Y, -65504.0, 65504.0).astype(np.float16).T.copy()
+
+
+def sequential_layers(Ws, X0: np.ndarray, beta: int, N: int, percdamp: float = 0.01, t_sba: int = 2048, **kw):
+    """A chain of linear layers y = W_l x, quantised in order.  Layer 0 is calibrated on X0 (m_0 x t); layer l + 1 on
+    the outputs of the QUANTISED layer l for the same tokens (next_layer_input), so that each layer compensates for
+    the error its predecessors have already made.  Returns the list of per-layer results of slim_layer, each with
+    its calibration input under "X"."""
+    X = np.asarray(X0)
+    outs = []
+    for W in Ws:
+        out = slim_layer(W, [X], beta, N, percdamp, t_sba=t_sba, **kw)
+        out["X"] = X
+        outs.append(out)
+        X = next_layer_input(out, beta, N, X)
+    return outs
 
 
 # ----------------------------------------------------------------------------------------

@@ -29,7 +29,7 @@ EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_workspace_query", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
     "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
-    "slim_dequant_matmul_noalloc",
+    "slim_dequant_matmul_noalloc", "slim_pack_zeros", "slim_unpack_zeros",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -47,6 +47,11 @@ class SlimShape(ctypes.Structure):
 def workspace_query(n: int, m: int, beta: int, t_c: int = 0, t_s: int = 0, t_x: int = 0, num_cus: int = 0) -> int:
     """Bytes of workspace the entry points need for a layer of this shape (host only, no GPU needed)."""
     return int(load().slim_workspace_query(ctypes.byref(SlimShape(n, m, beta, t_c, t_s, t_x)), num_cus))
+
+
+def zero_bits_for(N: int) -> int:
+    """Width of a packed zero point (the stored value is 2 z) for a layer of target width N (App. B.2)."""
+    return int(N) + 2
 
 
 def bit_base_for(N: int) -> int:
@@ -106,6 +111,8 @@ def load() -> ctypes.CDLL:
     lib.slim_dequant_matmul_noalloc.argtypes = lib.slim_dequant_matmul.argtypes
     lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_int, c_void_p, c_i64,
                               c_void_p, c_void_p, P(c_int)]
+    lib.slim_pack_zeros.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_int, c_void_p, c_i64, P(c_int)]
+    lib.slim_unpack_zeros.argtypes = [c_void_p, c_void_p, c_i64, c_int, c_int, c_int, c_void_p, c_i64]
     lib.slim_profile_enable.argtypes = [c_void_p, c_int]
     lib.slim_profile_collect.argtypes = [c_void_p]
     lib.slim_profile_collect.restype = c_int
@@ -314,6 +321,24 @@ class Slim:
         if not host_outputs:
             return packed, gbits, row_off, None
         return packed[: m_star.value], gbits, row_off, int(m_star.value)
+
+    def pack_zeros(self, zero: torch.Tensor, zbits: int, host_outputs: bool = True):
+        """zero float64 (n, k) -> (zpacked uint32-as-int32 (k, ceil(n zbits / 32)), number of zeros that did not fit
+        or None with host_outputs=False)."""
+        _need_cuda(zero)
+        n, k = zero.shape
+        zp = torch.empty((k, (n * zbits + 31) // 32), dtype=torch.int32, device=zero.device)
+        bad = ctypes.c_int(0)
+        self._check(self.lib.slim_pack_zeros(self.ctx, _ptr(zero), n, k, zero.stride(0), zbits, _ptr(zp), zp.stride(0),
+                                             ctypes.byref(bad) if host_outputs else None))
+        return zp, (int(bad.value) if host_outputs else None)
+
+    def unpack_zeros(self, zp: torch.Tensor, n: int, zbits: int):
+        _need_cuda(zp)
+        k = zp.shape[0]
+        zero = torch.empty((n, k), dtype=torch.float64, device=zp.device)
+        self._check(self.lib.slim_unpack_zeros(self.ctx, _ptr(zp), zp.stride(0), n, k, zbits, _ptr(zero), zero.stride(0)))
+        return zero
 
     # ---- n1
     def dequant_matmul(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,

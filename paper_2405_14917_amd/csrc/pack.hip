@@ -117,7 +117,79 @@ __global__ __launch_bounds__(PACK_ROWS) void pack_codes(const uint8_t* __restric
   }
 }
 
+// Zero points packed with one width along the output channels (App. B.2): word w of group g covers bits
+// [32 w, 32 w + 32) of the group's stream, element i (value 2 z_ig) at bits [i zbits, (i + 1) zbits).
+// Thread -> (group, word), groups fastest so that the zeros of one output channel are read side by side.
+__global__ __launch_bounds__(256) void pack_zeros_kernel(const double* __restrict__ zero, int n, int k, int64_t ldz,
+                                                         int zbits, uint32_t* __restrict__ zp, int64_t ldzp, int nw,
+                                                         int* __restrict__ n_bad) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)nw * k) return;
+  const int g = (int)(idx % k), w = (int)(idx / k);
+  const int top = (1 << zbits) - 1;
+  const int e0 = (32 * w) / zbits;
+  const int e1 = min(n, (32 * w + 32 + zbits - 1) / zbits);
+  uint32_t word = 0;
+  int bad = 0;
+  for (int i = e0; i < e1; ++i) {
+    const double u2 = 2.0 * zero[(int64_t)i * ldz + g];
+    const double ur = rint(u2);
+    int u = (ur < 0.0) ? 0 : ((ur > (double)top) ? top : (int)ur);
+    // an element that straddles two words is judged by the word that holds its first bit
+    if ((ur != u2 || ur < 0.0 || ur > (double)top) && i * zbits >= 32 * w) ++bad;
+    const int sh = i * zbits - 32 * w;
+    word |= (sh >= 0) ? ((uint32_t)u << sh) : ((uint32_t)u >> (-sh));
+  }
+  zp[(int64_t)g * ldzp + w] = word;
+  if (bad) atomicAdd(n_bad, bad);
+}
+
+__global__ __launch_bounds__(256) void unpack_zeros_kernel(const uint32_t* __restrict__ zp, int64_t ldzp, int n, int k,
+                                                           int zbits, double* __restrict__ zero, int64_t ldz) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)n * k) return;
+  const int g = (int)(idx % k), i = (int)(idx / k);
+  const int bit = i * zbits, w = bit / 32, sh = bit % 32;
+  uint64_t two = zp[(int64_t)g * ldzp + w];
+  if (sh + zbits > 32) two |= (uint64_t)zp[(int64_t)g * ldzp + w + 1] << 32;
+  zero[(int64_t)i * ldz + g] = 0.5 * (double)((two >> sh) & ((1u << zbits) - 1u));
+}
+
+__global__ void clear_flag(int* f) { *f = 0; }
+
 }  // namespace
+
+extern "C" slim_status slim_pack_zeros(slim_ctx* ctx, const double* zero, int n, int k, int64_t ldz, int zbits,
+                                       uint32_t* zpacked, int64_t ldzp, int* n_bad) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, zero && zpacked, "slim_pack_zeros: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && k > 0 && ldz >= k, "slim_pack_zeros: need n, k > 0 and ldz >= k");
+  SLIM_REQUIRE(ctx, zbits >= 2 && zbits <= 16, "slim_pack_zeros: zbits must be in 2..16 (got %d)", zbits);
+  const int nw = slim_cdiv((int64_t)n * zbits, 32);
+  SLIM_REQUIRE(ctx, ldzp >= nw, "slim_pack_zeros: ldzp must be at least ceil(n zbits / 32) = %d", nw);
+  int* flag = ctx->dflags + 2;
+  SLIM_LAUNCH(ctx, "pack_zeros_clear", clear_flag, dim3(1), dim3(1), 0, flag);
+  SLIM_LAUNCH(ctx, "pack_zeros", pack_zeros_kernel, dim3(slim_cdiv((int64_t)nw * k, 256)), dim3(256), 0, zero, n, k, ldz,
+              zbits, zpacked, ldzp, nw, flag);
+  if (!n_bad) return SLIM_OK;                      // nothing for the host: the call does not wait
+  int* host = reinterpret_cast<int*>(ctx->hpin);
+  SLIM_HIP_TRY(ctx, hipMemcpyAsync(host, flag, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+  SLIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  *n_bad = host[0];
+  return SLIM_OK;
+}
+
+extern "C" slim_status slim_unpack_zeros(slim_ctx* ctx, const uint32_t* zpacked, int64_t ldzp, int n, int k, int zbits,
+                                         double* zero, int64_t ldz) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, zero && zpacked, "slim_unpack_zeros: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && k > 0 && ldz >= k, "slim_unpack_zeros: need n, k > 0 and ldz >= k");
+  SLIM_REQUIRE(ctx, zbits >= 2 && zbits <= 16, "slim_unpack_zeros: zbits must be in 2..16 (got %d)", zbits);
+  SLIM_REQUIRE(ctx, ldzp >= slim_cdiv((int64_t)n * zbits, 32), "slim_unpack_zeros: ldzp too small");
+  SLIM_LAUNCH(ctx, "unpack_zeros", unpack_zeros_kernel, dim3(slim_cdiv((int64_t)n * k, 256)), dim3(256), 0, zpacked, ldzp,
+              n, k, zbits, zero, ldz);
+  return SLIM_OK;
+}
 
 extern "C" slim_status slim_pack(slim_ctx* ctx, const uint8_t* codes, int n, int m, int64_t ldc, const uint8_t* bits,
                                  int beta, int bit_base, uint32_t* packed, int64_t packed_rows, uint32_t* gbits,

@@ -81,3 +81,39 @@ class LayerPass:
         of every layer is the one `run` gives for it alone."""
         Xs = self._hessian_and_first_prepare(Ws[0], X)
         return [self._allocate_quantize_pack(W, Xs, i == 0) for i, W in enumerate(Ws)]
+
+
+def next_layer_input(slim, r, beta, X, n):
+    """Calibration activations of the next layer of a chain (Sec. 3.4: every layer inside the GPTQ backbone sees what
+    its quantised predecessors emit): the layer of result `r`, applied FROM ITS STORED FORM to the columns of X
+    (m x t, fp16, tokens contiguous) by the library's linear-layer kernel, 16 tokens per call, rounded to fp16 and
+    laid out channels x tokens again.  Only layout changes and the rounding happen here."""
+    t = X.shape[1]
+    Xn = torch.empty((n, t), dtype=torch.float16, device=X.device)
+    Y = torch.empty((16, n), dtype=torch.float32, device=X.device)
+    for t0 in range(0, t, 16):
+        xin = X[:, t0:t0 + 16].t().contiguous()
+        y = slim.dequant_matmul(r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"], beta, xin,
+                                Y=Y[: xin.shape[0]], bit_base=r["bit_base"])
+        Xn[:, t0:t0 + xin.shape[0]] = y.clamp(-65504.0, 65504.0).to(torch.float16).t()
+    return Xn
+
+
+def run_sequential(slim, Ws, X0, beta, N, percdamp=0.01, t_sba=2048):
+    """A chain of linear layers quantised in order, each calibrated on the output of its already quantised
+    predecessors for the same tokens (the GPTQ backbone that Sec. 3.4 puts SBA and SQC into).  Ws[l] is n_l x m_l
+    with m_{l+1} = n_l; X0 is m_0 x t.  Returns the per-layer results of LayerPass.run, each with its calibration
+    input under "X" and its packed zero points under "zpacked" (App. B.2)."""
+    X, outs = X0, []
+    for W in Ws:
+        n, m = W.shape
+        drv = LayerPass(slim, m, beta, N, percdamp, t_sba, device=str(W.device))
+        try:
+            r = drv.run(W, X)
+        finally:
+            drv.close()
+        r["X"] = X
+        r["zpacked"], _ = slim.pack_zeros(r["zero"], binding.zero_bits_for(N), host_outputs=False)
+        outs.append(r)
+        X = next_layer_input(slim, r, beta, X, n)
+    return outs

@@ -436,3 +436,67 @@ def test_dequant_matmul_is_the_dense_product_with_the_dequantised_weights():
     e[0, 3 * beta + 7] = 1.0
     col = orc.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], beta, e)[0]
     assert np.allclose(col, out["What"][:, 3 * beta + 7], rtol=1e-13, atol=0)
+
+
+# ----------------------------------------------------------------- packed zero points, layers in sequence ---
+def test_pack_zeros_worked_by_hand():
+    # App. B.2: zeros packed with one width along the channel direction; stored value 2 z
+    z = np.array([[0.0, 1.5], [3.0, 0.5], [7.0, 2.0]])                 # 3 output channels x 2 groups
+    zp, bad = orc.pack_zeros(z, 4)
+    # group 0: 2z = 0, 6, 14 -> 0 | 6 << 4 | 14 << 8 = 3680;  group 1: 3, 1, 4 -> 3 | 1 << 4 | 4 << 8 = 1043
+    assert bad == 0 and zp.dtype == np.uint32 and zp.tolist() == [[3680], [1043]]
+    assert np.array_equal(orc.unpack_zeros(zp, 3, 4), z)
+    # 5-bit values straddle the word boundary: 8 channels x 5 bits = 40 bits = 2 words
+    z5 = np.array([[15.5], [0.0], [1.0], [2.5], [15.0], [7.0], [7.5], [8.0]])     # 2z = 31 0 2 5 30 14 15 16
+    zp5, bad5 = orc.pack_zeros(z5, 5)
+    stream = sum(u << (5 * i) for i, u in enumerate([31, 0, 2, 5, 30, 14, 15, 16]))
+    assert bad5 == 0 and zp5.shape == (1, 2)
+    assert int(zp5[0, 0]) == stream & 0xFFFFFFFF and int(zp5[0, 1]) == stream >> 32
+    assert np.array_equal(orc.unpack_zeros(zp5, 8, 5), z5)
+    # what does not fit is counted and clamped: a negative zero (all-positive group), one beyond the width, a
+    # value that is not a multiple of 1/2
+    zb, nb = orc.pack_zeros(np.array([[-3.0], [9.0], [0.25], [1.0]]), 4)
+    assert nb == 3 and orc.unpack_zeros(zb, 4, 4)[:, 0].tolist() == [0.0, 7.5, 0.0, 1.0]
+    assert orc.zero_bits_for(2) == 4 and orc.zero_bits_for(3) == 5
+
+
+def test_pack_zeros_round_trip_on_a_quantised_layer():
+    W, X, _, _, _ = _small_layer(31, n=40, m=128, t=160, beta=32)
+    out = orc.slim_layer(W, [X], 32, 2, t_sba=64)
+    zb = orc.zero_bits_for(2)
+    zp, bad = orc.pack_zeros(out["zero"], zb)
+    assert bad == 0 and zp.shape == (4, (40 * zb + 31) // 32)
+    assert np.array_equal(orc.unpack_zeros(zp, 40, zb), out["zero"])
+
+
+def test_sequential_layers_use_their_quantised_predecessors():
+    """Sec. 3.4: inside the GPTQ backbone every layer is calibrated on what its quantised predecessors emit."""
+    rng = np.random.default_rng(32)
+    m, n0, n1, t, beta, N = 128, 96, 32, 256, 32, 2
+    W0 = (rng.standard_normal((n0, m)) * 0.05).astype(np.float16)
+    W1 = (rng.standard_normal((n1, n0)) * 0.05).astype(np.float16)
+    X0 = rng.standard_normal((m, t)).astype(np.float16)
+    outs = orc.sequential_layers([W0, W1], X0, beta, N, t_sba=64)
+    a, b = outs
+    assert np.array_equal(a["X"], X0) and b["X"].shape == (n0, t) and b["X"].dtype == np.float16
+    # the second layer's input is the first layer's QUANTISED weights applied to X0 (dense product with What) ...
+    dense = (a["What"] @ X0.astype(np.float64))
+    assert np.array_equal(b["X"], dense.astype(np.float16))
+    # ... not the original weights' output (quantisation at 2 bits is lossy)
+    assert not np.array_equal(b["X"], (W0.astype(np.float64) @ X0.astype(np.float64)).astype(np.float16))
+    # and the second layer is Alg. 1 on that input
+    alone = orc.slim_layer(W1, [b["X"]], beta, N, t_sba=64)
+    for key in ("bits", "codes", "scale", "zero", "packed"):
+        assert np.array_equal(b[key], alone[key]), key
+    # a first layer that quantisation represents exactly hands on the unquantised output: then the chain equals
+    # the second layer calibrated on W0 X0
+    levels = np.array([-1.0, 0.0, 1.0, 2.0]) / 64.0                    # delta0 = 1/64, z = 1: an exact 2-bit grid in fp16
+    W0e = levels[rng.integers(0, 4, (n0, m))]
+    W0e[:, ::32] = levels[0]
+    W0e[:, 1::32] = levels[3]                                          # every (row, group) spans the whole grid
+    W0e = W0e.astype(np.float16)
+    oe = orc.sequential_layers([W0e, W1], X0, beta, N, t_sba=64)
+    assert np.all(oe[0]["bits"] == 2)           # uniform precision has objective zero and is the first minimum
+    assert np.allclose(oe[0]["What"], W0e.astype(np.float64), rtol=0, atol=1e-9)
+    ref1 = orc.slim_layer(W1, [(W0e.astype(np.float64) @ X0.astype(np.float64)).astype(np.float16)], beta, N, t_sba=64)
+    assert np.mean(oe[1]["codes"] == ref1["codes"]) > 0.99
