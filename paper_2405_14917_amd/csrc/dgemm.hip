@@ -156,10 +156,14 @@ __device__ __forceinline__ void gemm_body(const slim_gemm_desc& d, int pid, doub
   const int tiles_n = (d.N + BN - 1) / BN;
   const int tiles_m = (d.M + BM - 1) / BM;
   if (pid >= tiles_m * tiles_n) return;
-  // tiles with the longest K range first: with an upper triangular B those are the last columns (with an upper
-  // triangular A the first rows, which come first anyway)
-  const int bi = pid / tiles_n;
-  const int bj = (d.flags & SLIM_GEMM_B_UPPER) ? tiles_n - 1 - pid % tiles_n : pid % tiles_n;
+  // Tiles with the longest K range first.  With an upper triangular A those are the first rows, which come first
+  // anyway.  With an upper triangular B they are the last columns: the tiles are then numbered column by column from
+  // the last column, so that the tiles on the chip at one time have the same K range and end together (numbered row
+  // by row, every row mixes K ranges from one slab to all of them, and a 4096^3 product of the triangular inverse
+  // took 1.98 ms instead of 1.17).
+  const bool colmajor = (d.flags & SLIM_GEMM_B_UPPER) != 0;
+  const int bi = colmajor ? pid % tiles_m : pid / tiles_n;
+  const int bj = colmajor ? tiles_n - 1 - pid / tiles_m : pid % tiles_n;
   const int row0 = bi * BM, col0 = bj * BN;
   if ((d.flags & SLIM_GEMM_UPPER_ONLY) && row0 >= col0 + BN) return;
 

@@ -50,16 +50,27 @@ struct GramArgs {
   int f;               // sub-splits per split of a tail tile
   int64_t subchunk;    // tokens per sub-split (multiple of BK)
   float* P;            // partial tiles: [slot][TM][TM]
+  int interleave;      // 1: consecutive workgroup ids (= consecutive XCDs) take consecutive tiles
+  int super;           // edge of a supertile, in tiles
 };
 
 // Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  The slots of one
 // tile are contiguous.  Workgroup ids run over the tiles fastest and the token ranges slowest: the workgroups that
 // are on the chip at the same time then cover every tile for one or two token ranges, so the chip as a whole reads
-// a narrow band of X at a time (the eight XCDs ask the memory side for the same lines at about the same time), and
-// XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact set that shares
-// its row blocks in that XCD's L2.  With the token range fastest instead (every XCD on a range of its own, the
-// requests of a moment spread over all of X) the kernel, which is limited by power, ran 4 % (m = 4096) to 10 %
-// (m = 11008) slower, although its L2s requested less.
+// a narrow band of X at a time.  With the token range fastest instead (every XCD on a range of its own, the
+// requests of a moment spread over all of X) the kernel ran 4 % (m = 4096) to 10 % (m = 11008) slower, although its
+// L2s requested less.  Workgroup id mod 8 is the XCD.  Two dealings of the tiles to the XCDs:
+//   runs        XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact set
+//               that shares its row blocks in that XCD's L2;
+//   interleaved consecutive ids take consecutive tiles, so the 256 tiles of a round form ONE compact block of the
+//               triangle (a 16 x 16 supertile: 32 row blocks for 256 tiles) and every row block is wanted by all
+//               XCDs at about the same time: the first request for a line goes to memory, the other XCDs' find it
+//               in the memory-side cache.  Measured with counters and probes on this kernel: what costs time is not
+//               the number of L2 misses (a variant in which the 32 workgroups of an XCD read the same two row blocks,
+//               97 % hits, is 2 % faster than the real kernel) but how long a miss takes (the same variant with ALL
+//               XCDs on the same two row blocks, same hit rate, is 9 % faster): the workgroups that share a line wait
+//               for its first fetch together, one slab of prefetch distance does not cover a trip to HBM, and a
+//               fetch that another XCD has just made is served faster.
 struct WorkItem {
   int tile;
   int64_t kbeg, kend;
@@ -72,7 +83,7 @@ __device__ __forceinline__ WorkItem decode_work(const GramArgs& a, int id) {
     const int j = id - split * a.tiles_main;
     // j = c + 8 q: class c owns tiles_main / 8 consecutive tiles (one more for the first tiles_main % 8 classes)
     const int c = j % 8, per = a.tiles_main / 8, rest = a.tiles_main % 8;
-    w.tile = c * per + min(c, rest) + j / 8;
+    w.tile = a.interleave ? j : c * per + min(c, rest) + j / 8;
     w.kbeg = (int64_t)split * a.kchunk;
     w.kend = min(a.t, w.kbeg + a.kchunk);
     w.slot = (int64_t)w.tile * a.S + split;
@@ -102,8 +113,7 @@ __device__ __forceinline__ void decode_triangle(int t, int& bi, int& bj) {
 // supertile (SUPER x SUPER tiles, the supertiles column by column over the triangle): a run of consecutive tile
 // indices, which is what one XCD works on at a time, then covers a compact patch of tiles that needs few row
 // blocks of X per slab, and most of its operand loads hit in that XCD's L2.
-constexpr int SUPER = 6;
-__device__ __forceinline__ void decode_tile(int t, int nt, int& bi, int& bj) {
+__device__ __forceinline__ void decode_tile(int t, int nt, int& bi, int& bj, int SUPER) {
   const int ns = (nt + SUPER - 1) / SUPER;
   for (int J = 0; J < ns; ++J) {
     const int w = min(SUPER, nt - J * SUPER);          // columns of tiles in supertile column J
@@ -251,7 +261,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj);
+  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj, a.super);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
   const int64_t klast8 = ((a.t - 1) / 8) * 8;   // start of the last (possibly partial) 8-token chunk
@@ -407,7 +417,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const WorkItem wk = decode_work(a, blockIdx.x);
   int bi, bj;
-  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj);
+  decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj, a.super);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
   constexpr int STAGE = 2 * TM * FROW;    // halves per stage: A slab, then B slab
@@ -513,7 +523,7 @@ __global__ __launch_bounds__(256) void gram_reduce(GramArgs a, float* __restrict
   const int tile = blockIdx.x;
   const int si = blockIdx.y / (TM / RB), sj = blockIdx.y % (TM / RB);
   int bi, bj;
-  decode_tile(tile, (a.m + TM - 1) / TM, bi, bj);
+  decode_tile(tile, (a.m + TM - 1) / TM, bi, bj, a.super);
   if (bi == bj && si > sj) return;                 // below the diagonal: written as the mirror of the block above it
   const int row0 = bi * TM + si * RB, col0 = bj * TM + sj * RB;
   if (row0 >= a.m || col0 >= a.m) return;
@@ -682,6 +692,12 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.n_main = a.tiles_main * S;
   a.f = f;
   a.subchunk = subchunk;
+  // Which tiles are on the chip together, and on which XCD (decode_work): from 192 tiles on (m >= 5120), supertiles
+  // of 16 x 16 with consecutive tiles dealt round the XCDs; below that, supertiles of 6 x 6 with a run of
+  // consecutive tiles per XCD.  Measured at 262144 tokens: 2 % (m = 11008 and 5120) to 3.6 % (m = 8192) faster than
+  // the runs per XCD; at m = 4096 (128 tiles in the first round) 1 % slower.
+  a.interleave = a.tiles_main >= 192 ? 1 : 0;
+  a.super = a.interleave ? 16 : 6;
   const int64_t nwg = (int64_t)a.n_main + (int64_t)tail_tiles * S * f;
 
   const size_t pbytes = sizeof(float) * (size_t)nwg * TM * TM;
