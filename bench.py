@@ -34,8 +34,9 @@ PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e
 # program issues for that purpose; the files under profiles/ that are named here give the commands and the readings.
 # Keyed by (config, kernel function); a configuration without such a run reports null.
 TRAFFIC_BYTES = {
-    # profiles/gram_C2_hbm_traffic.md
-    ("C2", "gram_kernel_full<false>"): 2.0 * 4.108e6 * 1024 + 1.0 * 1.233e5 * 1024,
+    # profiles/gram_C3_hbm_traffic.md: FETCH_SIZE 6.761e7 KiB x 2.0 (the yardstick's 65536 KiB read as 32778),
+    # WRITE_SIZE 5.83e5 KiB x 1.0 (its 65536 KiB written read as 65536)
+    ("C3", "gram_kernel_full<false>"): 2.0 * 6.761e7 * 1024 + 1.0 * 5.83e5 * 1024,
 }
 SHAPE_NAMES = {"C1": "tiny layer", "C2": "LLaMA-7B q_proj shaped layer", "C3": "LLaMA-7B down_proj shaped layer",
                "C4": "LLaMA-13B up_proj shaped layer", "C5": "LLaMA-70B-shaped MLP layer"}
@@ -253,12 +254,13 @@ def main():
     W, X = resident_inputs(cfg)
     job = Pass(cfg, W, X)
 
-    # a plain device-to-device copy of known size (64 MiB read, 64 MiB written): the yardstick that HBM
-    # traffic counters of a rocprofv3 --pmc run of this command are scaled by
-    calib_src = X[:, : (64 << 20) // (2 * cfg.m)] if cfg.t * cfg.m * 2 >= (64 << 20) else X
+    # A plain streaming kernel of known size (64 MiB read, 64 MiB written: the negation of 32 Mi fp16 values, the only
+    # launch of torch's neg kernel in this program): the yardstick that the HBM traffic counters of a
+    # rocprofv3 --pmc run of this command are scaled by.
+    calib_src = torch.ones(32 << 20, dtype=torch.float16, device="cuda")
     calib_dst = torch.empty_like(calib_src)
-    calib_dst.copy_(calib_src)
-    del calib_dst
+    torch.neg(calib_src, out=calib_dst)
+    del calib_src, calib_dst
 
     ms_per_step, p_star, m_star = timed_steps(job, args.steps, args.warmup)
 
@@ -362,7 +364,7 @@ def main():
         line["shared_input"] = {"layers": 3, "ms_per_layer": (time.perf_counter() - t0) * 1e3 / (3 * shared_reps),
                                 "note": "one Gram matrix and one inverse for three layers of the step's shape"}
     job.close()
-    del job, W, X, calib_src
+    del job, W, X
     torch.cuda.empty_cache()
     # the other full-size configurations, a few steps each
     other_cfgs = {}
