@@ -348,7 +348,6 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel(GramArgs a) {
 // of row r holds the tokens of chunk p ^ ((r >> 1) & 7).  Sixteen lanes that read the same chunk of sixteen
 // consecutive rows then hit sixteen different groups of four banks.
 constexpr int FROW = BK;                                               // halves per LDS row
-constexpr size_t kSmemFull = size_t(2) * 2 * TM * FROW * sizeof(uint16_t);   // two stages of A and B slabs
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
@@ -375,17 +374,20 @@ __device__ __forceinline__ void load_frags_full(Frags& f, const uint16_t* ap, co
   for (int j = 0; j < 4; ++j) f.b[j] = *reinterpret_cast<const uint4*>(bp + j * 32 * FROW);
 }
 
-// One K step of the fast path in a fixed issue order: its 16 MFMAs, after every second one an operand read of
-// the next K step (into the other fragment set), after every other MFMA of the first two K steps a direct
-// load of the next slab.  That is the rate the vector memory path takes from four wavefronts (64 bytes per
-// cycle for the CU; one load per MFMA stalls the wavefront at issue and the matrix pipe behind it, measured),
-// and it leaves the second half of the slab for the last load to land (one load per three MFMAs, with a
-// quarter of the slab left, was 3 % slower).
+// ---- the operand slabs in a ring of five units ----------------------------------------------------------
+// 160 KiB of LDS hold two and a half slabs.  Instead of two stages of (A slab, B slab), five units of one operand
+// slab (256 rows x 128 bytes = 32 KiB) are used in turn: slab s has its A rows in unit 2s mod 5 and its B rows in
+// unit 2s + 1 mod 5.  While slab s is multiplied, the two units that slab s - 1 has just freed take B of slab s + 1
+// and A of slab s + 2, so half of the loads are on their way a whole slab longer than with two stages, and the
+// other half can go out in the first quarter of the slab without the second half crowding the address path.
+constexpr unsigned UNIT_BYTES = TM * FROW * 2;                         // 32 KiB
+constexpr size_t kSmemRing = size_t(5) * UNIT_BYTES;
+
 template <bool BF16, int S>
-__device__ __forceinline__ void kstep_full(float16v (&acc)[4][4], const Frags& cf, Frags& nf, const uint16_t* nap,
-                                           const uint16_t* nbp, unsigned ldsn, const unsigned (&off)[CHUNKS],
-                                           const char* baseA, const char* baseB) {
-  constexpr unsigned OPB_BYTES = TM * FROW * 2, CHUNK_BYTES = 32 * FROW * 2;
+__device__ __forceinline__ void kstep_ring(float16v (&acc)[4][4], const Frags& cf, Frags& nf, const uint16_t* nap,
+                                           const uint16_t* nbp, unsigned ldsB, unsigned ldsA,
+                                           const unsigned (&off)[CHUNKS], const char* srcB, const char* srcA) {
+  constexpr unsigned CHUNK_BYTES = 32 * FROW * 2;
 #pragma unroll
   for (int m = 0; m < 16; ++m) {
     acc[m >> 2][m & 3] = mfma<BF16>(cf.a[m >> 2], cf.b[m & 3], acc[m >> 2][m & 3]);
@@ -399,19 +401,23 @@ __device__ __forceinline__ void kstep_full(float16v (&acc)[4][4], const Frags& c
       __builtin_amdgcn_sched_barrier(0);
     }
     const int gm = 16 * S + m;             // index of this MFMA in the iteration
-    if (gm % 2 == 1 && gm / 2 < 2 * CHUNKS) {
-      const int d = gm / 2, c = d >> 1;
-      if (d & 1)
-        direct_load(ldsn + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
+    // One direct load per four MFMAs over the whole slab: B of the next slab in the first half, A of the slab after
+    // it in the second.  Measured against loads crowded into the first half or quarter of the slab (one per MFMA or
+    // per two, as two stages force them to be): the even rate is 1 to 3 % faster, and the ring as a whole 3.5 % (m =
+    // 11008) to 7 % (m = 4096) faster than two stages.
+    if ((gm & 3) == 1) {
+      const int c = gm >> 2;
+      if (c < CHUNKS)
+        direct_load(ldsB + c * CHUNK_BYTES, off[c], srcB);
       else
-        direct_load(ldsn + c * CHUNK_BYTES, off[c], baseA);
+        direct_load(ldsA + (c - CHUNKS) * CHUNK_BYTES, off[c - CHUNKS], srcA);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
+__global__ __launch_bounds__(NTHREADS) void gram_kernel_ring(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -420,7 +426,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
   decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj, a.super);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
   const int64_t kbeg = wk.kbeg, kend = wk.kend;
-  constexpr int STAGE = 2 * TM * FROW;    // halves per stage: A slab, then B slab
+  constexpr int UNIT = TM * FROW;         // halves per unit
   float16v acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -428,80 +434,87 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_full(GramArgs a) {
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  // global side: this lane fetches, for c = 0 .. 7, row r0 + 32 c, chunk ch ^ swizzle(row)
   const int r0 = tid >> 3, ch = tid & 7;
-  const int gch = ch ^ ((r0 >> 1) & 7);       // ((r0 + 32 c) >> 1) & 7 == (r0 >> 1) & 7
+  const int gch = ch ^ ((r0 >> 1) & 7);
   unsigned off[CHUNKS];
 #pragma unroll
   for (int c = 0; c < CHUNKS; ++c) off[c] = (unsigned)((int64_t)(r0 + 32 * c) * a.ldx * 2 + gch * 16);
-  const char* baseA = reinterpret_cast<const char*>(a.X + (int64_t)rowA0 * a.ldx + kbeg);
-  const char* baseB = reinterpret_cast<const char*>(a.X + (int64_t)rowB0 * a.ldx + kbeg);
-  // LDS side: load c of this wavefront fills rows 32 c + 8 wave .. + 8 of a slab (1 KiB)
+  const char* const baseA = reinterpret_cast<const char*>(a.X + (int64_t)rowA0 * a.ldx + kbeg);
+  const char* const baseB = reinterpret_cast<const char*>(a.X + (int64_t)rowB0 * a.ldx + kbeg);
   const int wrow = 8 * wave * FROW;
-  // operand reads: lane (l32, lh) reads row l32 (+ 32 i) of its wavefront's half, chunk 2 s + lh of K step s
   const int l32 = lane & 31, lh = lane >> 5;
   const int xm = (l32 >> 1) & 7;
-  const int rdA = (wm * 128 + l32) * FROW, rdB = TM * FROW + (wn * 128 + l32) * FROW;
+  const int rdA = (wm * 128 + l32) * FROW, rdB = (wn * 128 + l32) * FROW;     // inside a unit
   int pos[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) pos[s] = ((2 * s + lh) ^ xm) * 8;
-
-  // LDS byte address of this wavefront's first destination row in stage 0
   const unsigned lds0 = (unsigned)__builtin_amdgcn_readfirstlane(
       (int)((unsigned)(uintptr_t)((__attribute__((address_space(3))) uint16_t*)smem) + (unsigned)wrow * 2));
-  constexpr unsigned STAGE_BYTES = STAGE * 2, OPB_BYTES = TM * FROW * 2, CHUNK_BYTES = 32 * FROW * 2;
+  constexpr unsigned CHUNK_BYTES = 32 * FROW * 2;
+  const int64_t nslab = (kend - kbeg) / BK;
+  const int64_t last = (nslab - 1) * (BK * 2);     // byte offset of the last slab: loads behind it re-read it
 
-  // prologue: slab 0 into stage 0
+  // prologue: A and B of slab 0 into units 0 and 1, A of slab 1 into unit 2
+  {
+    const char* a1 = baseA + min((int64_t)(BK * 2), last);
 #pragma unroll
-  for (int c = 0; c < CHUNKS; ++c) {
-    direct_load(lds0 + c * CHUNK_BYTES, off[c], baseA);
-    direct_load(lds0 + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
+    for (int c = 0; c < CHUNKS; ++c) {
+      direct_load(lds0 + c * CHUNK_BYTES, off[c], baseA);
+      direct_load(lds0 + UNIT_BYTES + c * CHUNK_BYTES, off[c], baseB);
+      direct_load(lds0 + 2 * UNIT_BYTES + c * CHUNK_BYTES, off[c], a1);
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  int cur = 0;
-  const int64_t nslab = (kend - kbeg) / BK;
-  if (bi == bj && wm == 1 && wn == 0) {
-    // The lower left quarter of a tile on the diagonal is the transpose of its upper right one and is never read
-    // back: this wavefront only fetches its share of the slabs and keeps the barriers.  Nothing gets faster for
-    // its workgroup, but a sixteenth of the chip's matrix-core work (and power, which is what limits the clock
-    // here) is not spent.
+  int ua = 0;                                      // unit of A of the current slab; B is the next one
+  const bool idle = (bi == bj && wm == 1 && wn == 0);   // this wavefront's quarter of a diagonal tile is never read back
+  if (idle) {
+    // only fetches its share of the slabs and keeps the barriers
     for (int64_t it = 0; it < nslab; ++it) {
-      const int64_t adv = (it + 1 < nslab) ? BK * 2 : 0;
-      baseA += adv;
-      baseB += adv;
-      const unsigned ldsn = lds0 + (unsigned)(cur ^ 1) * STAGE_BYTES;
+      const int unB = (ua + 3 >= 5) ? ua + 3 - 5 : ua + 3;
+      const int unA = (ua + 4 >= 5) ? ua + 4 - 5 : ua + 4;
+      const char* srcB = baseB + min((it + 1) * (int64_t)(BK * 2), last);
+      const char* srcA = baseA + min((it + 2) * (int64_t)(BK * 2), last);
+      const unsigned ldsB = lds0 + (unsigned)unB * UNIT_BYTES, ldsA = lds0 + (unsigned)unA * UNIT_BYTES;
 #pragma unroll
       for (int c = 0; c < CHUNKS; ++c) {
-        direct_load(ldsn + c * CHUNK_BYTES, off[c], baseA);
-        direct_load(ldsn + OPB_BYTES + c * CHUNK_BYTES, off[c], baseB);
-        __builtin_amdgcn_s_sleep(1);               // spread over the first half of the slab like the other wavefronts' loads
+        direct_load(ldsB + c * CHUNK_BYTES, off[c], srcB);
+        __builtin_amdgcn_s_sleep(1);
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        direct_load(ldsA + c * CHUNK_BYTES, off[c], srcA);
+        __builtin_amdgcn_s_sleep(2);
+      }
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
       __syncthreads();
-      cur ^= 1;
+      ua = (ua + 2 >= 5) ? ua + 2 - 5 : ua + 2;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     return;
   }
   for (int64_t it = 0; it < nslab; ++it) {
-    // the fetch behind the last slab re-reads the last slab (stays in bounds); its data is never multiplied
-    const int64_t adv = (it + 1 < nslab) ? BK * 2 : 0;
-    baseA += adv;
-    baseB += adv;
-    const uint16_t* as = smem + cur * STAGE + rdA;
-    const uint16_t* bs = smem + cur * STAGE + rdB;
-    const unsigned ldsn = lds0 + (unsigned)(cur ^ 1) * STAGE_BYTES;
+    const int ub = (ua + 1 >= 5) ? ua + 1 - 5 : ua + 1;
+    const int unB = (ua + 3 >= 5) ? ua + 3 - 5 : ua + 3;     // takes B of slab it + 1
+    const int unA = (ua + 4 >= 5) ? ua + 4 - 5 : ua + 4;     // takes A of slab it + 2
+    const char* srcB = baseB + min((it + 1) * (int64_t)(BK * 2), last);
+    const char* srcA = baseA + min((it + 2) * (int64_t)(BK * 2), last);
+    const unsigned ldsB = lds0 + (unsigned)unB * UNIT_BYTES, ldsA = lds0 + (unsigned)unA * UNIT_BYTES;
+    const uint16_t* as = smem + ua * UNIT + rdA;
+    const uint16_t* bs = smem + ub * UNIT + rdB;
     Frags f0, f1;
     load_frags_full(f0, as + pos[0], bs + pos[0]);
     __builtin_amdgcn_sched_barrier(0);
-    kstep_full<BF16, 0>(acc, f0, f1, as + pos[1], bs + pos[1], ldsn, off, baseA, baseB);
-    kstep_full<BF16, 1>(acc, f1, f0, as + pos[2], bs + pos[2], ldsn, off, baseA, baseB);
-    kstep_full<BF16, 2>(acc, f0, f1, as + pos[3], bs + pos[3], ldsn, off, baseA, baseB);
-    kstep_full<BF16, 3>(acc, f1, f0, as, bs, ldsn, off, baseA, baseB);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the slab for the next iteration has landed in LDS
+    kstep_ring<BF16, 0>(acc, f0, f1, as + pos[1], bs + pos[1], ldsB, ldsA, off, srcB, srcA);
+    kstep_ring<BF16, 1>(acc, f1, f0, as + pos[2], bs + pos[2], ldsB, ldsA, off, srcB, srcA);
+    kstep_ring<BF16, 2>(acc, f0, f1, as + pos[3], bs + pos[3], ldsB, ldsA, off, srcB, srcA);
+    kstep_ring<BF16, 3>(acc, f1, f0, as, bs, ldsB, ldsA, off, srcB, srcA);
+    // loads complete in order: all but the last eight (A of slab it + 2) have landed, i.e. A and B of slab it + 1
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     __syncthreads();
-    cur ^= 1;
+    ua = (ua + 2 >= 5) ? ua + 2 - 5 : ua + 2;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   float* P = a.P + wk.slot * (TM * TM);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -713,25 +726,25 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
                              reinterpret_cast<const void*>(gram_kernel<false, true>),
                              reinterpret_cast<const void*>(gram_kernel<true, false>),
                              reinterpret_cast<const void*>(gram_kernel<true, true>),
-                             reinterpret_cast<const void*>(gram_kernel_full<false>),
-                             reinterpret_cast<const void*>(gram_kernel_full<true>)};
+                             reinterpret_cast<const void*>(gram_kernel_ring<false>),
+                             reinterpret_cast<const void*>(gram_kernel_ring<true>)};
   static bool attr_done = false;
   if (!attr_done) {
     for (const void* fn : variants)
-      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes));
+      SLIM_HIP_TRY(ctx, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)std::max(kSmemBytes, kSmemRing)));
     attr_done = true;
   }
   const dim3 grid((unsigned)nwg), block(NTHREADS);
   if (x_dtype == SLIM_BF16) {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel_full<true>", (gram_kernel_full<true>), grid, block, kSmemFull, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel_ring<true>", (gram_kernel_ring<true>), grid, block, kSmemRing, a);
     else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, true>", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, false>", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
   } else {
     if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel_full<false>", (gram_kernel_full<false>), grid, block, kSmemFull, a);
+      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel_ring<false>", (gram_kernel_ring<false>), grid, block, kSmemRing, a);
     else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, true>", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
     else
