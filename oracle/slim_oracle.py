@@ -20,6 +20,7 @@ beta along the input dimension; k = m / beta groups; target average width N):
   pack / unpack       App. B.2                    per-group bit-packing, group-bit array, offsets
   pack_zeros / unpack_zeros  App. B.2             zero points packed with one width along the channel direction
   sequential_layers   Sec. 3.4 (GPTQ backbone)    layers quantised one after another on their quantised predecessors' outputs
+  lwc_*               Sec. 3.4, Sec. 4, App. B    SliM-LLM+: SBA widths + learnable weight clipping trained with AdamW
   dequant_matmul      App. B.2 (inference)        y = x dequant(W_int)^T straight from the packed tensors
 
 Readings taken where the paper is silent or inconsistent are stated at the
@@ -37,6 +38,14 @@ pin can decide are marked "parity unpinned" here:
   the layout written here is pinned by hand-worked words and round trips.  The same holds
   for the packed zero points (what is stored: 2 z; the width; the direction): App. B.2
   says "uniform precision along the channel direction" and no more.
+  parity unpinned: everything about SliM-LLM+ beyond "SBA widths, no SQC, the learnable weight
+  clipping of OmniQuant, AdamW" (App. B, Sec. 4): the parametrisation of the clipping (sigmoid
+  of a free parameter times the group's extreme value, start value 4), the straight-through
+  derivative of the rounding, the loss (mean squared layer-output error over the calibration
+  tokens, full batch), the optimiser's constants and the two-level affine form of 1-bit groups are
+  taken from the published description of that method and are arguments where they are numbers;
+  what is pinned is that the derivatives are those of the stated forward pass (autograd) and
+  that full clipping strength reproduces Eq. 1.
 """
 from __future__ import annotations
 
@@ -669,6 +678,99 @@ def sequential_layers(Ws, X0: np.ndarray, beta: int, N: int, percdamp: float = 0
         outs.append(out)
         X = next_layer_input(out, beta, N, X)
     return outs
+
+
+# ----------------------------------------------------------------------------------------
+# SliM-LLM+ (Sec. 3.4; Sec. 4; App. B): SBA's widths, no SQC and no compensation, a quantiser with
+# learnable weight clipping per (row, group) trained by AdamW on the layer-output error
+# ----------------------------------------------------------------------------------------
+def lwc_forward(W: np.ndarray, gamma: np.ndarray, beta_p: np.ndarray, bits: np.ndarray, beta: int):
+    """Fake quantisation with learnable clipping.  For every (row i, group g), with M and m_ the largest and the
+    smallest weight of the (row, group):  hi = sigmoid(gamma_ig) M,  lo = sigmoid(beta_ig) m_,
+    delta = (hi - lo) / (2^b - 1),  z = -round(lo / delta),  q = clamp(round(w / delta) + z, 0, 2^b - 1),
+    w_hat = delta (q - z)   (Eq. 1 on the clipped range; every width, 1 bit included, in this affine form).
+    A (row, group) with hi <= lo (all weights zero) gets delta = 1, z = 0.
+    Returns a dict: What (n, m), codes (n, m) uint8, scale, zero (n, k), and what the derivatives need."""
+    W = np.asarray(W, dtype=np.float64)
+    n, m = W.shape
+    k = m // beta
+    Wg = W.reshape(n, k, beta)
+    Q = (2.0 ** np.asarray(bits, dtype=np.float64) - 1.0)[None, :]                 # (1, k)
+    M, m_ = Wg.max(axis=2), Wg.min(axis=2)
+    s_hi, s_lo = 1.0 / (1.0 + np.exp(-gamma)), 1.0 / (1.0 + np.exp(-beta_p))
+    hi, lo = s_hi * M, s_lo * m_
+    live = hi > lo
+    delta = np.where(live, (hi - lo) / Q, 1.0)
+    z = np.where(live, -np.rint(lo / delta), 0.0)
+    u = np.rint(Wg / delta[:, :, None]) + z[:, :, None]
+    q = np.clip(u, 0.0, Q[:, :, None])
+    What = delta[:, :, None] * (q - z[:, :, None])
+    inside = (u >= 0.0) & (u <= Q[:, :, None])
+    return dict(What=What.reshape(n, m), codes=q.reshape(n, m).astype(np.uint8), scale=delta, zero=z, q=q, inside=inside,
+                M=M, m_=m_, s_hi=s_hi, s_lo=s_lo, lo=lo, Q=Q, live=live, Wg=Wg,
+                round_margin=np.where(inside, 0.5 - np.abs(Wg / delta[:, :, None] - np.rint(Wg / delta[:, :, None])),
+                                      np.inf).reshape(n, m))
+
+
+def lwc_loss_and_grads(W, G, n_tokens, gamma, beta_p, bits, beta):
+    """Loss L = || (W - W_hat) X ||_F^2 / (n T) = tr(dW G dW^T) / (n T) (Eq. 3 with G = X X^T; the mean squared error
+    of the layer's outputs) and its derivatives with respect to gamma and beta_p, the rounding taken as the identity
+    in the backward pass (straight-through) and the clamp passing derivatives where it does not clip:
+        g = dL/dW_hat = 2 (W_hat - W) G / (n T)
+        dW_hat_j/d delta = (q_j - z) - w_j / delta   (not clipped),   (q_j - z) - lo / delta   (clipped)
+        dW_hat_j/d lo at fixed delta = 0 (not clipped), 1 (clipped)            [through z = -round(lo / delta)]
+        delta = (hi - lo) / Q,  hi = sigmoid(gamma) M,  lo = sigmoid(beta_p) m_."""
+    f = lwc_forward(W, gamma, beta_p, bits, beta)
+    W = np.asarray(W, dtype=np.float64)
+    n, m = W.shape
+    k = m // beta
+    D = f["What"] - W
+    DG = D @ np.asarray(G, dtype=np.float64)
+    norm = float(n) * float(n_tokens)
+    loss = float(np.sum(D * DG)) / norm
+    g = (2.0 / norm) * DG.reshape(n, k, beta)
+    delta, z, lo = f["scale"][:, :, None], f["zero"][:, :, None], f["lo"][:, :, None]
+    dwd = np.where(f["inside"], (f["q"] - z) - f["Wg"] / delta, (f["q"] - z) - lo / delta)
+    s1 = np.sum(g * dwd, axis=2)                          # dL/d delta
+    s2 = np.sum(np.where(f["inside"], 0.0, g), axis=2)    # dL/d lo at fixed delta
+    d_hi = np.where(f["live"], s1 / f["Q"], 0.0)
+    d_lo = np.where(f["live"], -s1 / f["Q"] + s2, 0.0)
+    g_gamma = d_hi * f["M"] * f["s_hi"] * (1.0 - f["s_hi"])
+    g_beta = d_lo * f["m_"] * f["s_lo"] * (1.0 - f["s_lo"])
+    return loss, g_gamma, g_beta, f
+
+
+def adamw_step(p, grad, m1, v, step, lr, b1, b2, eps, weight_decay=0.0):
+    """One AdamW update (decoupled weight decay) in place; step counts from 1."""
+    p *= 1.0 - lr * weight_decay
+    m1 *= b1
+    m1 += (1.0 - b1) * grad
+    v *= b2
+    v += (1.0 - b2) * grad * grad
+    mhat = m1 / (1.0 - b1 ** step)
+    vhat = v / (1.0 - b2 ** step)
+    p -= lr * mhat / (np.sqrt(vhat) + eps)
+
+
+def lwc_quantize(W, G, n_tokens, bits, beta, steps=20, lr=1e-2, b1=0.9, b2=0.999, eps=1e-8, init=4.0):
+    """SliM-LLM+ for one layer: the widths `bits` (from SBA) stay fixed; the clipping strengths gamma, beta_p of every
+    (row, group) start at `init` and take `steps` full-batch AdamW steps on lwc_loss_and_grads; the layer is then
+    quantised with the final strengths.  Returns the forward dict of the final strengths plus loss_curve
+    (steps + 1 values: before every step and after the last), gamma, beta_p."""
+    W = np.asarray(W, dtype=np.float64)
+    n, m = W.shape
+    k = m // beta
+    gamma = np.full((n, k), float(init))
+    beta_p = np.full((n, k), float(init))
+    mg, vg, mb, vb = (np.zeros((n, k)) for _ in range(4))
+    curve = np.empty(steps + 1)
+    for it in range(1, steps + 1):
+        curve[it - 1], gg, gb, _ = lwc_loss_and_grads(W, G, n_tokens, gamma, beta_p, bits, beta)
+        adamw_step(gamma, gg, mg, vg, it, lr, b1, b2, eps)
+        adamw_step(beta_p, gb, mb, vb, it, lr, b1, b2, eps)
+    curve[steps], _, _, f = lwc_loss_and_grads(W, G, n_tokens, gamma, beta_p, bits, beta)
+    f.update(loss_curve=curve, gamma=gamma, beta_p=beta_p)
+    return f
 
 
 # ----------------------------------------------------------------------------------------
