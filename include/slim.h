@@ -88,6 +88,7 @@ typedef struct slim_shape {
   int n, m, beta;
   int64_t t_c, t_s;
   int t_x;
+  int lwc_steps;       /* steps of slim_lwc_quantize (0: that entry point is not used) */
 } slim_shape;
 
 /* Host only.  Bytes of device workspace that the entry points need for a layer of exactly this shape: the largest
@@ -284,6 +285,30 @@ slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t l
                                 const int32_t* row_off, const double* scale, const double* zero, int n, int m,
                                 int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx,
                                 float* Y, int64_t ldy);
+
+/* ---------------------------------------------------------------------------------------------
+ * n4  SliM-LLM+ on one layer (Sec. 3.4; Sec. 4; App. B; built from the list of next steps): the widths of SBA stay
+ * fixed, SQC and the error compensation are left out, and every (row, group) gets a quantiser with learnable weight
+ * clipping, trained with AdamW.  The paper names the borrowed method and the optimiser and no more; what is built:
+ *   hi = sigmoid(gamma) max_j w_j,  lo = sigmoid(beta_p) min_j w_j,  delta = (hi - lo) / (2^b - 1),
+ *   z = -round(lo / delta),  q_j = clamp(round(w_j / delta) + z, 0, 2^b - 1),  w_hat_j = delta (q_j - z)
+ *   (Eq. 1 on the clipped range; every width, 1 bit included, in this affine form; a (row, group) of zeros gets delta = 1);
+ *   loss L = tr((W - W_hat) G (W - W_hat)^T) / (n n_tokens), the mean squared error of the layer's outputs over the
+ *   calibration tokens (Eq. 3), full batch; derivatives with the rounding taken as the identity (straight-through);
+ *   gamma, beta_p start at `init` (4 in the borrowed method) and take `steps` AdamW steps (no weight decay) with
+ *   step size lr and moment constants beta1, beta2, eps; the layer is then quantised with the final strengths.
+ *   W      n x m, F16 / BF16 / F32, read only          G   m x m fp32 raw Gram matrix (both triangles), n_tokens its tokens
+ *   bits   device, k bytes in 1..8 (from slim_sba_allocate); the call waits for them to validate them
+ *   codes  n x m bytes (ld = m);  scale, zero  n x k doubles (ld = k): delta and z (integers) of every (row, group)
+ *   What   optional n x m (ld = m) in what_dtype (F32 or F64), or NULL
+ *   loss_curve   host, steps + 1 doubles or NULL: the loss before every step and after the last; NULL: the call does
+ *          not wait for its own work
+ * All arithmetic is fp64; a step costs one n x m x m product on the fp64 matrix cores and two passes over W.
+ */
+slim_status slim_lwc_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype, int n, int m, int64_t ldw,
+                              const float* G, int64_t ldg, int64_t n_tokens, const uint8_t* bits, int beta, int steps,
+                              double lr, double beta1, double beta2, double eps, double init, uint8_t* codes,
+                              double* scale, double* zero, void* What, slim_dtype what_dtype, double* loss_curve);
 
 /* ---------------------------------------------------------------------------------------------
  * slim_dequant_matmul for callers that cannot allocate device memory: code under HIP graph capture, tight serving

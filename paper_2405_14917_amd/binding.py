@@ -29,7 +29,7 @@ EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_workspace_query", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
     "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
-    "slim_dequant_matmul_noalloc", "slim_pack_zeros", "slim_unpack_zeros",
+    "slim_dequant_matmul_noalloc", "slim_pack_zeros", "slim_unpack_zeros", "slim_lwc_quantize",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -41,12 +41,13 @@ class SlimParams(ctypes.Structure):
 
 class SlimShape(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int), ("m", ctypes.c_int), ("beta", ctypes.c_int), ("t_c", ctypes.c_int64),
-                ("t_s", ctypes.c_int64), ("t_x", ctypes.c_int)]
+                ("t_s", ctypes.c_int64), ("t_x", ctypes.c_int), ("lwc_steps", ctypes.c_int)]
 
 
-def workspace_query(n: int, m: int, beta: int, t_c: int = 0, t_s: int = 0, t_x: int = 0, num_cus: int = 0) -> int:
+def workspace_query(n: int, m: int, beta: int, t_c: int = 0, t_s: int = 0, t_x: int = 0, num_cus: int = 0,
+                    lwc_steps: int = 0) -> int:
     """Bytes of workspace the entry points need for a layer of this shape (host only, no GPU needed)."""
-    return int(load().slim_workspace_query(ctypes.byref(SlimShape(n, m, beta, t_c, t_s, t_x)), num_cus))
+    return int(load().slim_workspace_query(ctypes.byref(SlimShape(n, m, beta, t_c, t_s, t_x, lwc_steps)), num_cus))
 
 
 def zero_bits_for(N: int) -> int:
@@ -113,6 +114,9 @@ def load() -> ctypes.CDLL:
                               c_void_p, c_void_p, P(c_int)]
     lib.slim_pack_zeros.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_int, c_void_p, c_i64, P(c_int)]
     lib.slim_unpack_zeros.argtypes = [c_void_p, c_void_p, c_i64, c_int, c_int, c_int, c_void_p, c_i64]
+    lib.slim_lwc_quantize.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_i64, c_void_p, c_i64, c_i64, c_void_p,
+                                      c_int, c_int, c_double, c_double, c_double, c_double, c_double, c_void_p, c_void_p,
+                                      c_void_p, c_void_p, c_int, P(c_double)]
     lib.slim_profile_enable.argtypes = [c_void_p, c_int]
     lib.slim_profile_collect.argtypes = [c_void_p]
     lib.slim_profile_collect.restype = c_int
@@ -339,6 +343,27 @@ class Slim:
         zero = torch.empty((n, k), dtype=torch.float64, device=zp.device)
         self._check(self.lib.slim_unpack_zeros(self.ctx, _ptr(zp), zp.stride(0), n, k, zbits, _ptr(zero), zero.stride(0)))
         return zero
+
+    # ---- n4
+    def lwc_quantize(self, W: torch.Tensor, G: torch.Tensor, n_tokens: int, bits: torch.Tensor, beta: int, steps: int = 20,
+                     lr: float = 1e-2, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, init: float = 4.0,
+                     want_what: Optional[torch.dtype] = None, host_outputs: bool = True):
+        """SliM-LLM+ on one layer.  Returns dict(codes uint8 (n, m), scale, zero float64 (n, k), What or None,
+        loss_curve numpy (steps + 1,) or None with host_outputs=False)."""
+        _need_cuda(W, G, bits)
+        n, m = W.shape
+        k = m // beta
+        codes = torch.empty((n, m), dtype=torch.uint8, device=W.device)
+        scale = torch.empty((n, k), dtype=torch.float64, device=W.device)
+        zero = torch.empty((n, k), dtype=torch.float64, device=W.device)
+        what = torch.empty((n, m), dtype=want_what, device=W.device) if want_what is not None else None
+        curve = (ctypes.c_double * (steps + 1))()
+        self._check(self.lib.slim_lwc_quantize(self.ctx, _ptr(W), _DT[W.dtype], n, m, W.stride(0), _ptr(G), G.stride(0),
+                                               n_tokens, _ptr(bits), beta, steps, lr, beta1, beta2, eps, init, _ptr(codes),
+                                               _ptr(scale), _ptr(zero), _ptr(what),
+                                               F32 if what is None else _DT[what.dtype], curve if host_outputs else None))
+        return dict(codes=codes, scale=scale, zero=zero, What=what,
+                    loss_curve=np.frombuffer(curve, dtype=np.float64).copy() if host_outputs else None)
 
     # ---- n1
     def dequant_matmul(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,

@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libslim.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["ctx.hip", "util.hip", "dgemm.hip", "gram.hip", "inverse.hip", "salience.hip", "sba.hip", "quant.hip",
-           "pack.hip", "dequant.hip"]
+           "pack.hip", "dequant.hip", "lwc.hip"]
 
 # packed-fp32 code generation is switched off for all device code (a device-compiler option; the host
 # pass does not know the feature and says so, which is harmless)

@@ -91,6 +91,7 @@ size_t slim_ws_need_sba(int n, int m, int beta, int64_t t_s);
 size_t slim_ws_need_sqc(int n);
 size_t slim_ws_need_gptq(int n, int m);
 size_t slim_ws_need_dequant(int n, int m, int beta, int t_x, int ncu);
+size_t slim_ws_need_lwc(int n, int m, int beta, int steps);
 
 // Looks up (once per device) the device address of the fixed buffer of slim_dequant_matmul_noalloc (dequant.hip).
 slim_status slim_dq_scratch_resolve(slim_ctx* ctx);

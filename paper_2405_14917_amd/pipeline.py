@@ -117,3 +117,23 @@ def run_sequential(slim, Ws, X0, beta, N, percdamp=0.01, t_sba=2048):
         outs.append(r)
         X = next_layer_input(slim, r, beta, X, n)
     return outs
+
+
+def run_plus(slim, W, X, beta, N, steps=20, lr=1e-2, percdamp=0.01, t_sba=2048):
+    """SliM-LLM+ on one layer (Sec. 3.4: the bit allocation of SBA plugged into a quantiser with learnable weight
+    clipping, trained with AdamW; no SQC, no error compensation): Hessian, inverse, salience and SBA as in the
+    plain pass, then slim_lwc_quantize with those widths, then packing of codes and zero points."""
+    n, m = W.shape
+    G = torch.zeros((m, m), dtype=torch.float32, device=W.device)
+    nt = slim.hessian_accumulate(X, G, 0)
+    U, d = slim.hessian_inverse(G, nt, percdamp)
+    _, grp, _ = slim.salience(W, d, beta)
+    bits, _, _ = slim.sba_allocate(W, grp, beta, N, X[:, : min(t_sba, X.shape[1])], host_outputs=False)
+    out = slim.lwc_quantize(W, G, nt, bits, beta, steps=steps, lr=lr, host_outputs=False)
+    bit_base = binding.bit_base_for(N)
+    packed, gbits, row_off, _ = slim.pack(out["codes"], bits, beta, packed_rows=m * (N + 1) // 32, host_outputs=False,
+                                          bit_base=bit_base)
+    zp, _ = slim.pack_zeros(out["zero"], binding.zero_bits_for(N), host_outputs=False)
+    out.update(bits=bits, G=G, n_tokens=nt, bit_base=bit_base, packed=packed, gbits=gbits, row_off=row_off, zpacked=zp,
+               m_star=row_off[-1])
+    return out
