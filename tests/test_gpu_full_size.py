@@ -237,6 +237,28 @@ def test_default_scope_sweep_code_for_code(slim, layer):
     assert fro < 1e-3
 
 
+def test_learnable_clipping_full_size(slim, layer):
+    """SliM-LLM+ (learnable weight clipping, three AdamW steps) on the whole layer against the oracle, fed with the
+    oracle-side Gram matrix and a fixed allocation."""
+    cfg = layer["cfg"]
+    if cfg.name != "C2":
+        pytest.skip("three oracle steps on the larger shapes take minutes; C2 exercises the same kernels at full width")
+    bits = _alloc_bits(cfg)
+    steps = 3
+    t0 = time.perf_counter()
+    ref = orc.lwc_quantize(layer["W"], layer["G32"].astype(np.float64), layer["t0"], bits, cfg.beta, steps=steps)
+    say("C2 learnable clipping: the oracle took %.1f s" % (time.perf_counter() - t0))
+    out = slim.lwc_quantize(layer["Wd"], dev(layer["G32"]), layer["t0"], dev(bits), cfg.beta, steps=steps,
+                            want_what=torch.float64)
+    assert np.allclose(out["loss_curve"], ref["loss_curve"], rtol=1e-9)
+    ok = ref["round_margin"].min(axis=1) > MARGIN
+    say("C2 learnable clipping: %d of %d rows outside the margin, loss %s" % (ok.sum(), ok.size, out["loss_curve"]))
+    assert ok.mean() > 0.75
+    assert np.array_equal(host(out["codes"])[ok], ref["codes"][ok])
+    assert np.allclose(host(out["scale"]), ref["scale"], rtol=1e-9)
+    assert np.linalg.norm(host(out["What"])[ok] - ref["What"][ok]) / np.linalg.norm(ref["What"][ok]) < 1e-8
+
+
 def test_pass_as_timed_equals_the_entry_points_one_by_one(slim, layer):
     """The driver bench.py times (two contexts on two streams, the first half of the bit allocation beside the
     inverse in the persistent part-of-the-chip form, no host outputs, the inverse returning with its triangular
