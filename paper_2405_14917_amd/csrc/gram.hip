@@ -7,13 +7,15 @@
 //  * Workgroup tile 256 x 256, 256 threads = 4 wavefronts in 2 x 2, each owning 128 x 128 as 4 x 4 MFMA
 //    tiles of 32 x 32 (256 fp32 accumulators per lane).  Per K step of 16 a wavefront reads 8 operand
 //    fragments from LDS for 16 MFMAs, which keeps LDS at about half of its bandwidth.
-//  * K advances in slabs of 64 tokens (128 bytes per row = one cache line) through two LDS stages;
-//    the next slab is fetched into registers while the current one is multiplied; rows are padded to
-//    72 halves so that the 16-byte operand reads of consecutive rows fall into different banks.
+//  * K advances in slabs of 64 tokens (128 bytes per row = one cache line).  General kernel (partial tiles,
+//    ragged token counts): two LDS stages, the next slab fetched into registers while the current one is
+//    multiplied, rows padded to 72 halves so that the 16-byte operand reads of consecutive rows fall into
+//    different banks.  Fast path (whole tiles, whole slabs; every benchmark shape): slabs go from memory to LDS
+//    directly, swizzled, into a ring of five 32 KiB units that keeps two and a half slabs on the chip
+//    (gram_kernel_ring).
 //  * Split-K: every tile is cut into S token ranges.  Workgroup ids run over the tiles fastest, so the chip works
-//    on one or two token ranges at a time and all XCDs stream through the same narrow band of X together, and the
-//    workgroups dealt to one XCD (id mod 8) form a compact set of tiles that shares row blocks of X in that
-//    XCD's L2 (decode_work).
+//    on one or two token ranges at a time and all XCDs stream through the same narrow band of X together; which
+//    tiles are on the chip together, and on which XCD, is decode_work's business.
 //  * Every workgroup writes its partial 256 x 256 tile to a slot of a scratch buffer; a second kernel adds the
 //    slots of a tile to G in a fixed order (deterministic, no floating-point atomics) and mirrors the upper
 //    triangle.
