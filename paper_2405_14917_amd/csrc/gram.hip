@@ -707,12 +707,14 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.n_main = a.tiles_main * S;
   a.f = f;
   a.subchunk = subchunk;
-  // Which tiles are on the chip together, and on which XCD (decode_work): from 192 tiles on (m >= 5120), supertiles
-  // of 16 x 16 with consecutive tiles dealt round the XCDs; below that, supertiles of 6 x 6 with a run of
-  // consecutive tiles per XCD.  Measured at 262144 tokens: 2 % (m = 11008 and 5120) to 3.6 % (m = 8192) faster than
-  // the runs per XCD; at m = 4096 (128 tiles in the first round) 1 % slower.
-  a.interleave = a.tiles_main >= 192 ? 1 : 0;
-  a.super = a.interleave ? 16 : 6;
+  // Which tiles are on the chip together, and on which XCD (decode_work).  Measured with the ring kernel at 262144
+  // tokens, three alternating runs each (one run scatters by 3 %): m = 11008 (946 tiles) 26.7 ms with supertiles of
+  // 16 x 16 dealt round the XCDs against 27.3 ms with a run of consecutive tiles per XCD; m = 8192 (528 tiles) 14.8
+  // against 13.9 ms (runs, supertiles of 8 x 8); m = 5120 (210 tiles) 5.71 against 5.53 ms.  With the two-stage
+  // kernel that preceded the ring the interleaved order won from 192 tiles on: the ring hides more of the time of a
+  // first fetch, which is what the interleaved order shortens, and the L2 hit rate of the runs counts again.
+  a.interleave = a.tiles_main >= 700 ? 1 : 0;
+  a.super = a.interleave ? 16 : (a.tiles_main >= 192 ? 8 : 6);
   const int64_t nwg = (int64_t)a.n_main + (int64_t)tail_tiles * S * f;
 
   const size_t pbytes = sizeof(float) * (size_t)nwg * TM * TM;
