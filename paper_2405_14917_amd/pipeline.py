@@ -16,25 +16,32 @@ class LayerPass:
     salience (the reference outputs and the outputs of the all-N-bit weights, two n x m x t_s products) is enqueued
     on the second stream before the inverse, whose chain of small kernels leaves most of the chip idle."""
 
-    def __init__(self, slim, m, beta, N, percdamp=0.01, t_sba=2048, device="cuda:0", n=None):
+    def __init__(self, slim, m, beta, N, percdamp=0.01, t_sba=2048, device="cuda:0", n=None, second=None):
         """n (output rows of the largest layer that will be passed): if given, the second context gets a workspace of
         the size slim_workspace_query states for the bit allocation of such a layer, allocated here once, so that no
-        call on it allocates; without it the context grows its own."""
+        call on it allocates; without it the context grows its own.  second = (stream, context): a second stream and
+        a context bound to it that the caller keeps (drivers for several shapes share one pair: every new stream may
+        land on another hardware queue, and two chains that are meant to overlap can then share one)."""
         self.slim, self.m, self.beta, self.N, self.percdamp, self.t_sba = slim, m, beta, N, percdamp, t_sba
         self.bit_base = binding.bit_base_for(N)     # of the stored form: what its 2-bit group value 0 stands for
         self.G = torch.zeros((m, m), dtype=torch.float32, device=device)
         self.U = torch.empty((m, m), dtype=torch.float64, device=device)
         self.d = torch.empty(m, dtype=torch.float64, device=device)
         self.main = torch.cuda.current_stream()
-        self.side = torch.cuda.Stream()
-        with torch.cuda.stream(self.side):
-            self.slim_sba = binding.Slim(device, 0 if n is None else binding.workspace_query(n, m, beta, 0, t_sba))
+        self.own_second = second is None
+        if second is None:
+            self.side = torch.cuda.Stream()
+            with torch.cuda.stream(self.side):
+                self.slim_sba = binding.Slim(device, 0 if n is None else binding.workspace_query(n, m, beta, 0, t_sba))
+        else:
+            self.side, self.slim_sba = second
 
     def contexts(self):
         return [self.slim, self.slim_sba]
 
     def close(self):
-        self.slim_sba.close()
+        if self.own_second:
+            self.slim_sba.close()
 
     def _hessian_and_first_prepare(self, W, X):
         """G = X X^T, then the damped inverse with the rank-independent half of W's bit allocation beside it."""
