@@ -269,7 +269,8 @@ slim_status slim_unpack_zeros(slim_ctx* ctx, const uint32_t* zpacked, int64_t ld
  *            multiple of 1/2 within +-511 takes the fastest path (Eq. 1 gives integers, the sign form of width 1 uses
  *            1/2); any other finite zero (Eq. 1 does not bound -round(w_min / delta0): a group of one sign with a narrow
  *            range has a large one) is accepted and costs that (row, group) a correction term
- *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  1 <= t_x <= 16 tokens
+ *   X        t_x x m, F16 or BF16, channels contiguous (ldx >= m);  t_x >= 1 tokens, taken 16 at a time (the kernels are
+ *            built for the few tokens of a decoding step; more tokens are a sequence of such steps on the stream)
  *   Y        t_x x n fp32 (ldy >= n), overwritten
  *   beta     a multiple of 32 that divides m
  *   bit_base as given to slim_pack; 1 or 2 (widths up to 5), anything else is SLIM_ERR_UNSUPPORTED.  A group whose
@@ -317,7 +318,7 @@ slim_status slim_lwc_quantize(slim_ctx* ctx, const void* W, slim_dtype w_dtype, 
  * every GPU the library runs on holds from the time its code is loaded there until the process ends, instead of the
  * context's workspace.  The call allocates and frees nothing (no hipMalloc, no hipFree, no events; per-kernel timing
  * is off for its length).
- *   A layer needs (group ranges) x t_x x n floats, where the number of group ranges is chosen to fill the chip
+ *   A layer needs (group ranges) x min(t_x, 16) x n floats, where the number of group ranges is chosen to fill the chip
  *   (about 8 x CUs / ceil(n / 128), at most k, one when that product is 1: then the buffer is not used).  If that
  *   exceeds the buffer the call returns SLIM_ERR_UNSUPPORTED and touches nothing; the error text gives the figures.
  *   All contexts on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two streams) race.

@@ -500,9 +500,30 @@ slim_status dequant_matmul_run(slim_ctx* ctx, const char* fn, const uint32_t* pa
   return SLIM_OK;
 }
 
+// Any number of tokens: DQ_MAX_T at a time, one after the other on the context's stream (the kernels are built for
+// the few tokens of a decoding step; a batch is a sequence of such steps).  Nothing is launched if the first slice,
+// which is the largest, is refused.
+slim_status dequant_matmul_tokens(slim_ctx* ctx, const char* fn, const uint32_t* packed, int64_t ldp,
+                                  const uint32_t* gbits, const int32_t* row_off, const double* scale,
+                                  const double* zero, int n, int m, int beta, int bit_base, const void* X,
+                                  slim_dtype x_dtype, int64_t t_x, int64_t ldx, float* Y, int64_t ldy, float* fixed,
+                                  size_t fixed_floats) {
+  SLIM_REQUIRE(ctx, t_x >= 1, "%s: t_x must be at least 1 (got %lld)", fn, (long long)t_x);
+  for (int64_t t0 = 0; t0 < t_x; t0 += DQ_MAX_T) {
+    const int tc = (int)std::min<int64_t>(DQ_MAX_T, t_x - t0);
+    const void* xs = X ? static_cast<const void*>(static_cast<const uint16_t*>(X) + t0 * ldx) : nullptr;
+    float* ys = Y ? Y + t0 * ldy : nullptr;
+    const slim_status st = dequant_matmul_run(ctx, fn, packed, ldp, gbits, row_off, scale, zero, n, m, beta, bit_base,
+                                              xs, x_dtype, tc, ldx, ys, ldy, fixed, fixed_floats);
+    if (st != SLIM_OK) return st;
+  }
+  return SLIM_OK;
+}
+
 }  // namespace
 
 size_t slim_ws_need_dequant(int n, int m, int beta, int t_x, int ncu) {
+  t_x = std::min(t_x, DQ_MAX_T);
   size_t need = 0;
   for (int mfma = 0; mfma < 2; ++mfma) {       // whichever kernel the activations' type and alignment select
     int gper = 0;
@@ -537,8 +558,8 @@ extern "C" slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed
                                            int m, int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x,
                                            int64_t ldx, float* Y, int64_t ldy) {
   if (!ctx) return SLIM_ERR_INVALID_ARG;
-  return dequant_matmul_run(ctx, "slim_dequant_matmul", packed, ldp, gbits, row_off, scale, zero, n, m, beta, bit_base,
-                            X, x_dtype, t_x, ldx, Y, ldy, nullptr, 0);
+  return dequant_matmul_tokens(ctx, "slim_dequant_matmul", packed, ldp, gbits, row_off, scale, zero, n, m, beta,
+                               bit_base, X, x_dtype, t_x, ldx, Y, ldy, nullptr, 0);
 }
 
 extern "C" slim_status slim_dequant_matmul_noalloc(slim_ctx* ctx, const uint32_t* packed, int64_t ldp,
@@ -551,9 +572,9 @@ extern "C" slim_status slim_dequant_matmul_noalloc(slim_ctx* ctx, const uint32_t
   // per-kernel event timing creates events on demand, which allocates: it is off for the length of this call
   const bool prof = ctx->prof;
   ctx->prof = false;
-  const slim_status st = dequant_matmul_run(ctx, "slim_dequant_matmul_noalloc", packed, ldp, gbits, row_off, scale, zero,
-                                            n, m, beta, bit_base, X, x_dtype, t_x, ldx, Y, ldy, ctx->dq_scratch,
-                                            DQ_SCRATCH_FLOATS);
+  const slim_status st = dequant_matmul_tokens(ctx, "slim_dequant_matmul_noalloc", packed, ldp, gbits, row_off, scale,
+                                               zero, n, m, beta, bit_base, X, x_dtype, t_x, ldx, Y, ldy,
+                                               ctx->dq_scratch, DQ_SCRATCH_FLOATS);
   ctx->prof = prof;
   return st;
 }

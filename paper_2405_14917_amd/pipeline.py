@@ -93,15 +93,15 @@ class LayerPass:
 def next_layer_input(slim, r, beta, X, n):
     """Calibration activations of the next layer of a chain (Sec. 3.4: every layer inside the GPTQ backbone sees what
     its quantised predecessors emit): the layer of result `r`, applied FROM ITS STORED FORM to the columns of X
-    (m x t, fp16, tokens contiguous) by the library's linear-layer kernel, 16 tokens per call, rounded to fp16 and
+    (m x t, fp16, tokens contiguous) by the library's linear-layer kernel (which takes its tokens 16 at a time), rounded to fp16 and
     laid out channels x tokens again.  Only layout changes and the rounding happen here."""
     t = X.shape[1]
     Xn = torch.empty((n, t), dtype=torch.float16, device=X.device)
-    Y = torch.empty((16, n), dtype=torch.float32, device=X.device)
-    for t0 in range(0, t, 16):
-        xin = X[:, t0:t0 + 16].t().contiguous()
+    step = 4096                                      # tokens per call: bounds the size of the transposed copies
+    for t0 in range(0, t, step):
+        xin = X[:, t0:t0 + step].t().contiguous()
         y = slim.dequant_matmul(r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"], beta, xin,
-                                Y=Y[: xin.shape[0]], bit_base=r["bit_base"])
+                                bit_base=r["bit_base"])
         Xn[:, t0:t0 + xin.shape[0]] = y.clamp(-65504.0, 65504.0).to(torch.float16).t()
     return Xn
 

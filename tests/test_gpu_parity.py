@@ -666,8 +666,14 @@ def test_dequant_matmul_after_the_whole_pass(slim):
     Y = host(slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, Xin))
     Xn, What = host(Xin).astype(np.float64), host(out["What"])
     assert np.all(np.abs(Y - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
-    with pytest.raises(Exception):
-        slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, dev(X)[:, :17].t().contiguous())
+    # more than 16 tokens are taken 16 at a time: the same numbers as the slices give one by one
+    Xmany = dev(X)[:, :41].t().contiguous()
+    Ymany = slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, Xmany)
+    for t0 in (0, 16, 32):
+        Ypart = slim.dequant_matmul(packed, gbits, row_off, out["scale"], out["zero"], 128, Xmany[t0:t0 + 16].contiguous())
+        assert torch.equal(Ymany[t0:t0 + 16], Ypart)
+    Xn = host(Xmany).astype(np.float64)
+    assert np.all(np.abs(host(Ymany) - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
 
 
 def test_layers_that_share_their_input_share_the_hessian(slim):
