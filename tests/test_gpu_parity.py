@@ -59,8 +59,11 @@ def small_layer(seed, n=96, m=256, t=640, beta=64, correlated=True, w_dtype=np.f
 
 # ------------------------------------------------------------------------------------------ a1
 # the last two cases have 36 tiles x 8 splits = 288 workgroups: the 32 of the last round are split further along K
+# (768, 1280, 2), (1024, 64 * 37, 1) and (2048, 4096, 1) take the fast path (whole tiles and slabs: the ring of five LDS
+# units) with off-diagonal and diagonal tiles, one to several slabs per token range and an odd number of slabs
 @pytest.mark.parametrize("m,t,chunks", [(256, 512, 1), (264, 500, 2), (520, 1100, 3), (8, 8, 1), (256, 64 * 40, 1),
-                                        (1800, 2000, 1), (2048, 2044, 1)])
+                                        (1800, 2000, 1), (2048, 2044, 1), (768, 1280, 2), (1024, 64 * 37, 1),
+                                        (2048, 4096, 1), (512, 64, 1)])
 def test_hessian_accumulate(slim, m, t, chunks):
     rng = np.random.default_rng(m + t)
     X = (rng.standard_normal((m, t)) * rng.lognormal(0, 1, m)[:, None]).astype(np.float16)
@@ -88,7 +91,7 @@ def test_hessian_accumulate(slim, m, t, chunks):
 
 def test_hessian_accumulate_bf16_and_determinism(slim):
     rng = np.random.default_rng(7)
-    m, t = 256, 768
+    m, t = 512, 768                  # three tiles, fast path
     X = torch.from_numpy(rng.standard_normal((m, t)).astype(np.float32)).to(torch.bfloat16).cuda()
     G1 = torch.zeros((m, m), dtype=torch.float32, device="cuda")
     G2 = torch.zeros((m, m), dtype=torch.float32, device="cuda")
