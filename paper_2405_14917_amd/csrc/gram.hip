@@ -24,6 +24,8 @@
 //    the power of two for which a model of the rounds and of the reduction is shortest (a 4096-wide Gram matrix
 //    has 136 tiles: S = 2, one round of 128 tiles x 2 ranges and a round of 8 tiles cut 32 ways).
 #include <algorithm>
+#include <utility>
+#include <vector>
 
 #include "slim_internal.h"
 
@@ -54,6 +56,7 @@ struct GramArgs {
   float* P;            // partial tiles: [slot][TM][TM]
   int interleave;      // 1: consecutive workgroup ids (= consecutive XCDs) take consecutive tiles
   int super;           // edge of a supertile, in tiles
+  int id_base;         // id of the launch's first workgroup (the ring kernel may be launched round by round)
 };
 
 // Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  The slots of one
@@ -423,7 +426,7 @@ __global__ __launch_bounds__(NTHREADS) void gram_kernel_ring(GramArgs a) {
   extern __shared__ __align__(16) uint16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const WorkItem wk = decode_work(a, blockIdx.x);
+  const WorkItem wk = decode_work(a, a.id_base + (int)blockIdx.x);
   int bi, bj;
   decode_tile(wk.tile, (a.m + TM - 1) / TM, bi, bj, a.super);
   const int rowA0 = bi * TM, rowB0 = bj * TM;
@@ -707,6 +710,7 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.n_main = a.tiles_main * S;
   a.f = f;
   a.subchunk = subchunk;
+  a.id_base = 0;
   // Which tiles are on the chip together, and on which XCD (decode_work).  Measured with the ring kernel at 262144
   // tokens, three alternating runs each (one run scatters by 3 %): m = 11008 (946 tiles) 26.7 ms with supertiles of
   // 16 x 16 dealt round the XCDs against 27.3 ms with a run of consecutive tiles per XCD; m = 8192 (528 tiles) 14.8
@@ -739,17 +743,41 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
     attr_done = true;
   }
   const dim3 grid((unsigned)nwg), block(NTHREADS);
+  // Launches of the fast path.  Workgroups that share row blocks of X find each other's lines in their XCD's L2 only
+  // while they are at the same tokens, i.e. while they have started together; a workgroup that starts when another
+  // one ends (diagonal tiles end 14 % early) shares nothing.  With many rounds of workgroups the starts drift apart,
+  // so a long launch is cut into launches of one round each: the end of a launch is the point where all start
+  // together again.  Measured at 262144 tokens: m = 11008 (7.4 rounds) 25.8 against 27.4 ms, m = 12288 32.3 against
+  // 34.8 ms, m = 16384 (131072 tokens) 28.5 against 30.3 ms; with three rounds or fewer the ends of the launches cost
+  // what the lockstep gains (m = 5120: 5.76 against 5.52 ms), so short launches stay whole.
+  const int ncu_l = ctx->num_cus > 0 ? ctx->num_cus : 256;
+  std::vector<std::pair<int64_t, int64_t>> rounds;     // (first workgroup id, workgroups)
+  if (full && (int64_t)a.n_main >= 5 * (int64_t)ncu_l) {
+    int64_t base = 0;
+    for (; base + 2 * ncu_l <= nwg; base += ncu_l) rounds.emplace_back(base, (int64_t)ncu_l);
+    rounds.emplace_back(base, nwg - base);             // the rest of the last full round with the short tail workgroups
+  } else {
+    rounds.emplace_back((int64_t)0, nwg);
+  }
   if (x_dtype == SLIM_BF16) {
-    if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel_ring<true>", (gram_kernel_ring<true>), grid, block, kSmemRing, a);
-    else if (ragged)
+    if (full) {
+      for (const auto& r : rounds) {
+        a.id_base = (int)r.first;
+        SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel_ring<true>", (gram_kernel_ring<true>), dim3((unsigned)r.second), block,
+                    kSmemRing, a);
+      }
+    } else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, true>", (gram_kernel<true, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_bf16@gram_kernel<true, false>", (gram_kernel<true, false>), grid, block, kSmemBytes, a);
   } else {
-    if (full)
-      SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel_ring<false>", (gram_kernel_ring<false>), grid, block, kSmemRing, a);
-    else if (ragged)
+    if (full) {
+      for (const auto& r : rounds) {
+        a.id_base = (int)r.first;
+        SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel_ring<false>", (gram_kernel_ring<false>), dim3((unsigned)r.second), block,
+                    kSmemRing, a);
+      }
+    } else if (ragged)
       SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, true>", (gram_kernel<false, true>), grid, block, kSmemBytes, a);
     else
       SLIM_LAUNCH(ctx, "gram_mfma_f16@gram_kernel<false, false>", (gram_kernel<false, false>), grid, block, kSmemBytes, a);
