@@ -32,11 +32,12 @@ PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e
 # HBM bytes per launch of the dominant kernel function, from two `rocprofv3 --pmc` runs of this command (FETCH_SIZE,
 # then WRITE_SIZE, in KiB per dispatch), each scaled by what the same counter reads for the 64 MiB copy that this
 # program issues for that purpose; the files under profiles/ that are named here give the commands and the readings.
-# Keyed by (config, kernel function); a configuration without such a run reports null.
+# Keyed by (config, kernel function), in bytes per pass; the line reports them per launch, like `achieved`.  A
+# configuration without such a run reports null.
 TRAFFIC_BYTES = {
-    # profiles/gram_C3_hbm_traffic.md: FETCH_SIZE 5.727e7 KiB x 2.0 (the yardstick's 65536 KiB read as 32778),
-    # WRITE_SIZE 5.918e5 KiB x 1.0 (its 65536 KiB written read as 65536)
-    ("C3", "gram_kernel_ring<false>"): 2.0 * 5.727e7 * 1024 + 1.0 * 5.918e5 * 1024,
+    # profiles/gram_C3_hbm_traffic.md, per PASS (the launches of a pass together): FETCH_SIZE 5.073e7 KiB x 2.0 (the
+    # yardstick's 65536 KiB read as 32778), WRITE_SIZE 5.478e5 KiB x 1.0 (its 65536 KiB written read as 65536)
+    ("C3", "gram_kernel_ring<false>"): 2.0 * 5.073e7 * 1024 + 1.0 * 5.478e5 * 1024,
 }
 SHAPE_NAMES = {"C1": "tiny layer", "C2": "LLaMA-7B q_proj shaped layer", "C3": "LLaMA-7B down_proj shaped layer",
                "C4": "LLaMA-13B up_proj shaped layer", "C5": "LLaMA-70B-shaped MLP layer"}
@@ -325,7 +326,8 @@ def main():
             div = 1e9 if f["bound"] == "hbm" else 1e12
             roofline = {"kernel": dom.partition("#")[0], "bound": f["bound"], "achieved": achieved / div,
                         "peak": PEAK[f["peak_key"]] / div, "unit": unit, "frac": achieved / PEAK[f["peak_key"]],
-                        "traffic": TRAFFIC_BYTES.get((cfg.name, dom.partition("#")[0])),
+                        "traffic": (TRAFFIC_BYTES[(cfg.name, dom.partition("#")[0])] / (f["cnt"] / args.profile_steps)
+                                    if (cfg.name, dom.partition("#")[0]) in TRAFFIC_BYTES else None),
                         "avg_us": 1e3 * f["ms"] / f["cnt"], "launches_per_step": f["cnt"] / args.profile_steps,
                         "ms_per_step": f["ms"] / args.profile_steps}
     # every step of the path for the record: time, the roof that binds it, the fraction of that roof, and the time
