@@ -287,6 +287,14 @@ slim_status slim_dequant_matmul(slim_ctx* ctx, const uint32_t* packed, int64_t l
                                 int beta, int bit_base, const void* X, slim_dtype x_dtype, int t_x, int64_t ldx,
                                 float* Y, int64_t ldy);
 
+/* The same linear layer with the zero points in their packed form (App. B.2: the kernel dequantises the packed weights and
+ * the packed zeros): zpacked, ldzp, zbits as slim_pack_zeros writes them; everything else as above.  The zero points are
+ * unpacked into the context's workspace first (exact), so Y is bit for bit that of slim_dequant_matmul on them. */
+slim_status slim_dequant_matmul_zp(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
+                                   const int32_t* row_off, const double* scale, const uint32_t* zpacked, int64_t ldzp,
+                                   int zbits, int n, int m, int beta, int bit_base, const void* X, slim_dtype x_dtype,
+                                   int t_x, int64_t ldx, float* Y, int64_t ldy);
+
 /* ---------------------------------------------------------------------------------------------
  * n4  SliM-LLM+ on one layer (Sec. 3.4; Sec. 4; App. B; built from the list of next steps): the widths of SBA stay
  * fixed, SQC and the error compensation are left out, and every (row, group) gets a quantiser with learnable weight

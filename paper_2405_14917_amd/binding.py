@@ -29,7 +29,7 @@ EXPORTS = [
     "slim_default_params", "slim_default_tau", "slim_create", "slim_destroy", "slim_last_error",
     "slim_workspace_bytes", "slim_workspace_query", "slim_hessian_accumulate", "slim_hessian_inverse", "slim_salience",
     "slim_sba_allocate", "slim_sba_prepare", "slim_sqc_calibrate", "slim_gptq_quantize", "slim_pack", "slim_dequant_matmul",
-    "slim_dequant_matmul_noalloc", "slim_pack_zeros", "slim_unpack_zeros", "slim_lwc_quantize",
+    "slim_dequant_matmul_noalloc", "slim_dequant_matmul_zp", "slim_pack_zeros", "slim_unpack_zeros", "slim_lwc_quantize",
     "slim_profile_enable", "slim_profile_collect", "slim_profile_entry", "slim_profile_reset",
 ]
 
@@ -110,6 +110,8 @@ def load() -> ctypes.CDLL:
     lib.slim_dequant_matmul.argtypes = [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
                                         c_int, c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
     lib.slim_dequant_matmul_noalloc.argtypes = lib.slim_dequant_matmul.argtypes
+    lib.slim_dequant_matmul_zp.argtypes = [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_i64, c_int,
+                                           c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_i64, c_void_p, c_i64]
     lib.slim_pack.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_void_p, c_int, c_int, c_void_p, c_i64,
                               c_void_p, c_void_p, P(c_int)]
     lib.slim_pack_zeros.argtypes = [c_void_p, c_void_p, c_int, c_int, c_i64, c_int, c_void_p, c_i64, P(c_int)]
@@ -380,6 +382,18 @@ class Slim:
         self._check(fn(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
                                                  _ptr(scale), _ptr(zero), n, m, beta, bit_base, _ptr(X), _DT[X.dtype], t_x,
                                                  X.stride(0), _ptr(Y), Y.stride(0)))
+        return Y
+
+    def dequant_matmul_zp(self, packed: torch.Tensor, gbits: torch.Tensor, row_off: torch.Tensor, scale: torch.Tensor,
+                          zpacked: torch.Tensor, zbits: int, beta: int, X: torch.Tensor, bit_base: int = 1):
+        """The linear layer on the stored form with packed zero points (from pack_zeros)."""
+        _need_cuda(packed, gbits, row_off, scale, zpacked, X)
+        n = packed.shape[1]
+        t_x, m = X.shape
+        Y = torch.empty((t_x, n), dtype=torch.float32, device=X.device)
+        self._check(self.lib.slim_dequant_matmul_zp(self.ctx, _ptr(packed), packed.stride(0), _ptr(gbits), _ptr(row_off),
+                                                    _ptr(scale), _ptr(zpacked), zpacked.stride(0), zbits, n, m, beta,
+                                                    bit_base, _ptr(X), _DT[X.dtype], t_x, X.stride(0), _ptr(Y), Y.stride(0)))
         return Y
 
     # ---- measurement aid

@@ -192,7 +192,9 @@ size_t slim_workspace_query(const slim_shape* s, int num_cus) {
     need = std::max(need, slim_ws_need_sqc(s->n));
     need = std::max(need, slim_ws_need_gptq(s->n, s->m));
     if (s->beta > 0 && s->t_s > 0) need = std::max(need, slim_ws_need_sba(s->n, s->m, s->beta, s->t_s));
-    if (s->beta > 0 && s->t_x > 0) need = std::max(need, slim_ws_need_dequant(s->n, s->m, s->beta, s->t_x, ncu));
+    if (s->beta > 0 && s->t_x > 0)     // (with room for the unpacked zero points of slim_dequant_matmul_zp)
+      need = std::max(need, slim_ws_need_dequant(s->n, s->m, s->beta, s->t_x, ncu) +
+                                slim_ws_round(sizeof(double) * (size_t)s->n * (s->m / s->beta)));
     if (s->beta > 0 && s->lwc_steps > 0) need = std::max(need, slim_ws_need_lwc(s->n, s->m, s->beta, s->lwc_steps));
   }
   return need;

@@ -578,3 +578,29 @@ extern "C" slim_status slim_dequant_matmul_noalloc(slim_ctx* ctx, const uint32_t
   ctx->prof = prof;
   return st;
 }
+
+// The same layer with the zero points in their packed form (App. B.2: weights AND zeros are stored as packed integers
+// and the kernel dequantises both): the zero points are unpacked into the context's workspace (n x k doubles, exact:
+// stored value / 2) and the product runs as above, so the result is bit for bit that of slim_dequant_matmul on the
+// unpacked zero points.
+extern "C" slim_status slim_dequant_matmul_zp(slim_ctx* ctx, const uint32_t* packed, int64_t ldp, const uint32_t* gbits,
+                                              const int32_t* row_off, const double* scale, const uint32_t* zpacked,
+                                              int64_t ldzp, int zbits, int n, int m, int beta, int bit_base,
+                                              const void* X, slim_dtype x_dtype, int t_x, int64_t ldx, float* Y,
+                                              int64_t ldy) {
+  if (!ctx) return SLIM_ERR_INVALID_ARG;
+  SLIM_REQUIRE(ctx, zpacked != nullptr, "slim_dequant_matmul_zp: null pointer");
+  SLIM_REQUIRE(ctx, n > 0 && m > 0 && beta > 0 && m % beta == 0, "slim_dequant_matmul_zp: need n, m > 0 and beta | m");
+  SLIM_REQUIRE(ctx, t_x >= 1, "slim_dequant_matmul_zp: t_x must be at least 1");
+  const int k = m / beta;
+  const size_t need_dq = slim_ws_need_dequant(n, m, beta, t_x, std::max(1, ctx->num_cus));
+  const size_t need_z = slim_ws_round(sizeof(double) * (size_t)n * k);
+  slim_status st = slim_ws_reserve(ctx, need_dq + need_z);
+  if (st != SLIM_OK) return st;
+  // the zero points live behind the partial sums, which the product below takes from the start of the workspace
+  double* zero = reinterpret_cast<double*>(ctx->ws + need_dq);
+  st = slim_unpack_zeros(ctx, zpacked, ldzp, n, k, zbits, zero, k);
+  if (st != SLIM_OK) return st;
+  return dequant_matmul_tokens(ctx, "slim_dequant_matmul_zp", packed, ldp, gbits, row_off, scale, zero, n, m, beta,
+                               bit_base, X, x_dtype, t_x, ldx, Y, ldy, nullptr, 0);
+}

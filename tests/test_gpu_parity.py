@@ -840,7 +840,15 @@ def test_sequential_layers_on_quantised_predecessors(slim):
         check_end_to_end("chain, %s layer" % name, codes, What, o, *(E2E_FLOORS_C1 if name == "first" else E2E_FLOORS_CHAIN))
         rec = orc.reconstruction_error(W, What, o["G"])
         assert abs(rec - o["recon"]) <= 0.01 * o["recon"], name
-        # (4) its packed zero points
+        # (4) its packed zero points, and the layer applied from the fully packed form
+        Xin = dev(o["X"])[:, :20].t().contiguous()
+        Yz = slim.dequant_matmul_zp(g["packed"], g["gbits"], g["row_off"], g["scale"], g["zpacked"],
+                                    binding.zero_bits_for(N), beta, Xin, bit_base=g["bit_base"])
+        Yd = slim.dequant_matmul(g["packed"], g["gbits"], g["row_off"], g["scale"], g["zero"], beta, Xin,
+                                 bit_base=g["bit_base"])
+        assert torch.equal(Yz, Yd)
+        Xn = host(Xin).astype(np.float64)
+        assert np.all(np.abs(host(Yz) - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
         zo, bad = orc.pack_zeros(zero, binding.zero_bits_for(N))
         assert bad == 0 and np.array_equal(host(g["zpacked"]).view(np.uint32), zo)
         assert np.array_equal(host(slim.unpack_zeros(g["zpacked"], W.shape[0], binding.zero_bits_for(N))), zero)
