@@ -13,11 +13,11 @@
  *    the library's device workspace is either the caller's too (given to slim_create, sized with
  *    slim_workspace_query: then no entry point allocates) or an internal grow-only one that slim_destroy frees.
  *  - Work is enqueued on the HIP stream given to slim_create.  A call returns as soon as its work
- *    is enqueued, except where it has a host output (info, p_star, obj_curve, m_star): those calls
+ *    is enqueued, except where it has a host output (info, p_star, obj_curve, m_star, n_bad, loss_curve): those calls
  *    wait until that output has arrived (slim_hessian_inverse: until the factorisation is done, with
- *    the rest of its work still in flight).  p_star, obj_curve and m_star may be NULL: the call then
- *    does not wait, so a caller can run a whole pass without stalling the stream.  slim_gptq_quantize reads the
- *    widths back for validation and kernel selection, behind work it has already enqueued.
+ *    the rest of its work still in flight).  p_star, obj_curve, m_star, n_bad and loss_curve may be NULL: the call then
+ *    does not wait.  slim_gptq_quantize and slim_lwc_quantize read the widths back for validation (and kernel selection),
+ *    the former behind work it has already enqueued: the one wait of the host inside a pass.
  *  - Return value: SLIM_OK or a negative slim_status.  No exceptions, no aborts.  After an error
  *    slim_last_error(ctx) describes it; on SLIM_ERR_INVALID_ARG / SLIM_ERR_UNSUPPORTED no output
  *    was touched (at most work on the library's own workspace has been launched).  The one exception are the two
