@@ -54,9 +54,10 @@ struct GramArgs {
   int f;               // sub-splits per split of a tail tile
   int64_t subchunk;    // tokens per sub-split (multiple of BK)
   float* P;            // partial tiles: [slot][TM][TM]
-  int interleave;      // 1: consecutive workgroup ids (= consecutive XCDs) take consecutive tiles
-  int super;           // edge of a supertile, in tiles
+  int interleave;      // how the tiles are dealt to the XCDs: 0 runs, 1 interleaved, 2 patches per round (decode_work)
+  int super;           // tile order: edge of a supertile in tiles, or, negative, minus the height of a band (decode_tile)
   int id_base;         // id of the launch's first workgroup (the ring kernel may be launched round by round)
+  int ncu;             // workgroups per round (compute units of the device)
 };
 
 // Which piece of work a workgroup has: tile, token range, and the slot its partial tile goes to.  The slots of one
@@ -64,18 +65,15 @@ struct GramArgs {
 // are on the chip at the same time then cover every tile for one or two token ranges, so the chip as a whole reads
 // a narrow band of X at a time.  With the token range fastest instead (every XCD on a range of its own, the
 // requests of a moment spread over all of X) the kernel ran 4 % (m = 4096) to 10 % (m = 11008) slower, although its
-// L2s requested less.  Workgroup id mod 8 is the XCD.  Two dealings of the tiles to the XCDs:
-//   runs        XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the supertile order, a compact set
-//               that shares its row blocks in that XCD's L2;
-//   interleaved consecutive ids take consecutive tiles, so the 256 tiles of a round form ONE compact block of the
-//               triangle (a 16 x 16 supertile: 32 row blocks for 256 tiles) and every row block is wanted by all
-//               XCDs at about the same time: the first request for a line goes to memory, the other XCDs' find it
-//               in the memory-side cache.  Measured with counters and probes on this kernel: what costs time is not
-//               the number of L2 misses (a variant in which the 32 workgroups of an XCD read the same two row blocks,
-//               97 % hits, is 2 % faster than the real kernel) but how long a miss takes (the same variant with ALL
-//               XCDs on the same two row blocks, same hit rate, is 9 % faster): the workgroups that share a line wait
-//               for its first fetch together, one slab of prefetch distance does not cover a trip to HBM, and a
-//               fetch that another XCD has just made is served faster.
+// L2s requested less.  Workgroup id mod 8 is the XCD.  Dealings of the tiles to the XCDs (`interleave`):
+//   0  runs         XCD x (ids x, x + 8, ...) is given a run of consecutive tiles of the tile order, a compact set that
+//                   shares its row blocks in that XCD's L2;
+//   1  interleaved  consecutive ids take consecutive tiles, so that every row block is wanted by all XCDs at about
+//                   the same time (what the two-stage kernel before the ring needed: it could not hide the time of a
+//                   first fetch from HBM, and a fetch that another XCD has just made is served by the memory-side
+//                   cache; kept for reference, not chosen by the host any more);
+//   2  patches      for launches that are cut into rounds: round r takes the tiles ncu r .. ncu (r + 1) - 1, XCD x the
+//                   x-th run of ncu / 8 of them, so that the XCDs of a round work on neighbouring patches.
 struct WorkItem {
   int tile;
   int64_t kbeg, kend;
@@ -88,7 +86,13 @@ __device__ __forceinline__ WorkItem decode_work(const GramArgs& a, int id) {
     const int j = id - split * a.tiles_main;
     // j = c + 8 q: class c owns tiles_main / 8 consecutive tiles (one more for the first tiles_main % 8 classes)
     const int c = j % 8, per = a.tiles_main / 8, rest = a.tiles_main % 8;
-    w.tile = a.interleave ? j : c * per + min(c, rest) + j / 8;
+    if (a.interleave == 2) {
+      // a round of ncu workgroups takes ncu consecutive tiles, XCD c the c-th run of ncu / 8 of them
+      const int R = a.ncu, whole = (a.tiles_main / R) * R;
+      w.tile = (j < whole) ? (j / R) * R + c * (R / 8) + (j % R) / 8 : j;
+    } else {
+      w.tile = a.interleave ? j : c * per + min(c, rest) + j / 8;
+    }
     w.kbeg = (int64_t)split * a.kchunk;
     w.kend = min(a.t, w.kbeg + a.kchunk);
     w.slot = (int64_t)w.tile * a.S + split;
@@ -118,7 +122,37 @@ __device__ __forceinline__ void decode_triangle(int t, int& bi, int& bj) {
 // supertile (SUPER x SUPER tiles, the supertiles column by column over the triangle): a run of consecutive tile
 // indices, which is what one XCD works on at a time, then covers a compact patch of tiles that needs few row
 // blocks of X per slab, and most of its operand loads hit in that XCD's L2.
+// Band order (SUPER = -H): the triangle in bands of H tile rows, every band column by column from its diagonal to
+// the right.  A run of 32 consecutive tiles is then a patch of H rows by 32 / H columns (H + 32 / H row blocks of X),
+// and consecutive runs are neighbours in the same band, which share its H row blocks.
+__device__ __forceinline__ void decode_tile_band(int t, int nt, int H, int& bi, int& bj) {
+  for (int r0 = 0; r0 < nt; r0 += H) {
+    const int r1 = min(nt, r0 + H), hb = r1 - r0;
+    const int cnt = hb * (nt - r0) - hb * (hb - 1) / 2;      // sum over the band's rows of (nt - row)
+    if (t < cnt) {
+      const int tri = hb * (hb - 1) / 2;                      // columns r0 .. r1 - 2 hold 1, 2, .., hb - 1 tiles
+      if (t < tri) {
+        int c, x;
+        decode_triangle(t, x, c);                             // position t = c (c + 1) / 2 + x, x <= c
+        bj = r0 + c;
+        bi = r0 + x;
+      } else {
+        t -= tri;
+        bj = r1 - 1 + t / hb;
+        bi = r0 + t % hb;
+      }
+      return;
+    }
+    t -= cnt;
+  }
+  bi = bj = 0;   // not reached for t < nt (nt + 1) / 2
+}
+
 __device__ __forceinline__ void decode_tile(int t, int nt, int& bi, int& bj, int SUPER) {
+  if (SUPER < 0) {
+    decode_tile_band(t, nt, -SUPER, bi, bj);
+    return;
+  }
   const int ns = (nt + SUPER - 1) / SUPER;
   for (int J = 0; J < ns; ++J) {
     const int w = min(SUPER, nt - J * SUPER);          // columns of tiles in supertile column J
@@ -711,14 +745,16 @@ extern "C" slim_status slim_hessian_accumulate(slim_ctx* ctx, const void* X, sli
   a.f = f;
   a.subchunk = subchunk;
   a.id_base = 0;
-  // Which tiles are on the chip together, and on which XCD (decode_work).  Measured with the ring kernel at 262144
-  // tokens, three alternating runs each (one run scatters by 3 %): m = 11008 (946 tiles) 26.7 ms with supertiles of
-  // 16 x 16 dealt round the XCDs against 27.3 ms with a run of consecutive tiles per XCD; m = 8192 (528 tiles) 14.8
-  // against 13.9 ms (runs, supertiles of 8 x 8); m = 5120 (210 tiles) 5.71 against 5.53 ms.  With the two-stage
-  // kernel that preceded the ring the interleaved order won from 192 tiles on: the ring hides more of the time of a
-  // first fetch, which is what the interleaved order shortens, and the L2 hit rate of the runs counts again.
-  a.interleave = a.tiles_main >= 700 ? 1 : 0;
-  a.super = a.interleave ? 16 : (a.tiles_main >= 192 ? 8 : 6);
+  a.ncu = ctx->num_cus > 0 ? ctx->num_cus : 256;
+  // Which tiles are on the chip together, and on which XCD (decode_work).  Up to 700 tiles: a run of consecutive
+  // tiles of the supertile order per XCD (supertiles of 6 x 6, of 8 x 8 from 192 tiles on; measured with the ring
+  // kernel at 262144 tokens against 16 x 16 supertiles dealt round the XCDs: m = 8192 13.9 against 14.8 ms, m = 5120
+  // 5.53 against 5.71 ms).  Beyond that the launch is cut into rounds (below), and every round takes 256 consecutive
+  // tiles of the band order, 32 per XCD: a patch of 4 x 8 tiles with 12 row blocks of X.  Measured at m = 11008 with
+  // the L2 counters: hit rate 0.69 and 79 GB fetched per pass in 24.9 ms, against 0.58, 105 GB and 25.2 ms for 16 x 16
+  // supertiles dealt round the XCDs, and 0.67, 83 GB, 25.1 ms for runs of 8 x 8 supertiles.
+  a.interleave = a.tiles_main >= 700 ? 2 : 0;
+  a.super = a.interleave ? -4 : (a.tiles_main >= 192 ? 8 : 6);
   const int64_t nwg = (int64_t)a.n_main + (int64_t)tail_tiles * S * f;
 
   const size_t pbytes = sizeof(float) * (size_t)nwg * TM * TM;
