@@ -42,7 +42,7 @@ TRAFFIC_BYTES = {
 SHAPE_NAMES = {"C1": "tiny layer", "C2": "LLaMA-7B q_proj shaped layer", "C3": "LLaMA-7B down_proj shaped layer",
                "C4": "LLaMA-13B up_proj shaped layer", "C5": "LLaMA-70B-shaped MLP layer"}
 T_SBA = 2048
-INV_GRP = 4          # diagonal blocks of 64 columns per group of the factorisation (csrc/inverse.hip)
+INV_GRP = 8          # diagonal blocks of 64 columns per group of the factorisation (csrc/inverse.hip)
 
 
 def resident_inputs(cfg):

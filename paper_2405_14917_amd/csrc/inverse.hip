@@ -6,12 +6,12 @@
 // inverse, (2/3) m^3 flops instead of (4/3) m^3:
 //
 //   1. widen:   A = (2 / n_tokens) G + lambda I,  lambda = percdamp * mean(diag(2 / n_tokens G))
-//   2. for the diagonal blocks J = last .. first (64 columns each; four of them form a group):
+//   2. for the diagonal blocks J = last .. first (64 columns each; eight of them form a group):
 //        chol_step   one workgroup: applies the last pending rank-64 update to A_JJ itself, factors
 //                    A_JJ = R_JJ R_JJ^T in LDS and inverts R_JJ (V_JJ, written into U)
 //        panel       R[0:J, J] = A[0:J, J] V_JJ^T                            (fp64 MFMA GEMM)
 //        update      rank-64 update of the columns between the start of block J-1's group and block J
-//        group update  rank-256 updates of everything further left, once per group
+//        group update  rank-512 updates of everything further left, once per group
 //      The factorisation of the diagonal blocks and the GEMMs form two chains on two streams that only
 //      meet two steps apart, see the schedule at the call site.
 //   3. triangular inverse by recursive doubling: ranges of 2^l diagonal blocks that are already inverted
@@ -504,7 +504,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   //                         A[rows above block K-1, window of K] -= R[.., K] R[window, K]^T        (rank 64)
   //                         and, when K is the second block of its group G (all other panels of G are done):
   //                         A[0:G, columns of group G-1] -= the panels of G except the first block's
-  //   s2  far(G):           A[left of group G-1]^2 -= all panels of G, upper tiles only            (rank 256)
+  //   s2  far(G):           A[left of group G-1]^2 -= all panels of G, upper tiles only            (rank 512)
   // Every element of A thus receives each panel's contribution exactly once: from far() if it lies two or more
   // groups to the left, from the group update if one group to the left (the first block's panel comes through
   // that block's window), from a window update inside the group, and from the diagonal kernel for the
@@ -519,7 +519,10 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       done = true;
     }
   }
-  constexpr int GRP = 4;
+  // Blocks per group.  With 8 the far updates have rank 512 (64 flops per byte of A they move, against 32 with 4) and
+  // there are half as many of them; the windows of the chain get wider.  Inverse alone at m = 11008: 21.7 against 22.2
+  // ms; whole pass: 0.5 ms less on the 4096 x 11008 and 28672 x 8192 layers, 0.2 ms less on 4096 x 4096.
+  constexpr int GRP = 8;
   hipStream_t s0 = ctx->stream, s1 = ctx->side, s2 = ctx->side2;
   hipEvent_t ev_fork = ctx->ev[0];
   hipEvent_t* ev_step = &ctx->ev[1];   // ring of 4
