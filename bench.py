@@ -358,6 +358,16 @@ def main():
         "roofline": roofline,
         "whole_pass": whole_pass,
         "kernels": others,
+        "kernel_notes": {
+            "sqc_search": "alu peak counts an FMA as two operations; the search loop is mostly single-operation "
+                          "instructions (multiply, round, two clamps), so its fraction of the issue bound is about "
+                          "twice the frac given",
+            "inv_syrk_dgemm, inv_panel_dgemm, inv_window_dgemm, sba_output_dgemm": "run beside other streams' work by "
+                          "design (factorisation chains beside the SBA outputs on part of the chip): their durations "
+                          "overlap and their frac is not a fraction of the chip",
+            "gram_mfma_f16": "power-limited: the same kernel runs at 0.71 of the nominal peak on constant data and at "
+                             "0.49 to 0.51 on random data when Gram launches follow one another",
+        },
     }
     # beside the metric: the inference kernel of the stored form (next step of the path, not part of `value`)
     us, nbytes = job.inference(tokens=1)
