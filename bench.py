@@ -73,6 +73,41 @@ class Pass(pipeline.LayerPass):
         self.stored = (r["packed"], r["gbits"], r["row_off"], r["scale"], r["zero"])
         return r["p_star"], r["m_star"]      # 0-dim device tensors: reading them is the caller's synchronisation
 
+    def phases(self, reps=2):
+        """Not part of the step: the same pass with the host waiting between its phases, so that each phase's own
+        duration can be read (the timed pass runs them back to back and overlaps nothing across these borders except
+        the host's enqueueing).  Returns milliseconds per phase, averaged over `reps` passes."""
+        s, s2, W, X = self.slim, self.slim_sba, self.W, self.X
+        Xs = X[:, : min(self.t_sba, X.shape[1])]
+        acc = {}
+
+        def lap(name, t0):
+            torch.cuda.synchronize()
+            acc[name] = acc.get(name, 0.0) + (time.perf_counter() - t0) * 1e3
+            return time.perf_counter()
+
+        for _ in range(reps):
+            self.G.zero_()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nt = s.hessian_accumulate(X, self.G, 0)
+            t0 = lap("hessian", t0)
+            self.side.wait_stream(self.main)
+            s2.sba_prepare(W, self.beta, self.N, Xs)
+            s.hessian_inverse(self.G, nt, self.percdamp, U=self.U, hinv_diag=self.d)
+            t0 = lap("inverse_with_sba_outputs_beside", t0)
+            _, grp, _ = s.salience(W, self.d, self.beta)
+            t0 = lap("salience", t0)
+            with torch.cuda.stream(self.side):
+                bits, _, _ = s2.sba_allocate(W, grp, self.beta, self.N, Xs, host_outputs=False)
+            t0 = lap("sba_rank_and_search", t0)
+            out = s.gptq_quantize(W, self.U, bits, self.beta)
+            t0 = lap("sqc_and_gptq_sweep", t0)
+            s.pack(out["codes"], bits, self.beta, packed_rows=self.m * (self.N + 1) // 32, host_outputs=False,
+                   bit_base=self.bit_base)
+            t0 = lap("pack", t0)
+        return {k: v / reps for k, v in acc.items()}
+
     def inference(self, tokens=1, reps=100):
         """Not part of the step: the linear layer on the stored form of the last pass (App. B.2), `tokens`
         activations at a time; returns microseconds per call and the bytes of the stored form it streams."""
@@ -369,6 +404,16 @@ def main():
                              "0.49 to 0.51 on random data when Gram launches follow one another",
         },
     }
+    # beside the metric: the phases of a pass with the host waiting between them, and what the fp64 phase
+    # (inverse with the two SBA output products beside it) achieves as a whole
+    ph = job.phases()
+    ts = min(T_SBA, cfg.t)
+    fp64_flops = (2.0 / 3.0) * float(cfg.m) ** 3 + 2.0 * (2.0 * cfg.n * cfg.m * ts)
+    line["phases_ms"] = {k: round(v, 3) for k, v in ph.items()}
+    line["phases_ms"]["note"] = ("one pass with the host waiting at the borders of the phases (extra passes after the timed "
+                                 "region); inverse_with_sba_outputs_beside: (2/3) m^3 + 4 n m t_s fp64 flops = %.3g, i.e. "
+                                 "%.2f of the fp64 matrix peak over the phase" % (
+                                     fp64_flops, fp64_flops / (ph["inverse_with_sba_outputs_beside"] * 1e-3) / PEAK["mfma_f64"]))
     # beside the metric: the inference kernel of the stored form (next step of the path, not part of `value`)
     us, nbytes = job.inference(tokens=1)
     line["inference"] = {"kernel": "dequant_matmul", "tokens": 1, "us_per_call": us, "stored_bytes": nbytes,
