@@ -914,6 +914,12 @@ def test_whole_pass_plus(slim):
     assert np.array_equal(c2, codes) and np.array_equal(b2, o["bits"])
     zo, bad = orc.pack_zeros(zero, binding.zero_bits_for(N))
     assert bad == 0 and np.array_equal(host(r["zpacked"]).view(np.uint32), zo)
+    # the layer applied from its fully packed form (codes and zero points)
+    Xin = dev(X)[:, 5:12].t().contiguous()
+    Y = host(slim.dequant_matmul_zp(r["packed"], r["gbits"], r["row_off"], r["scale"], r["zpacked"],
+                                    binding.zero_bits_for(N), beta, Xin, bit_base=r["bit_base"]))
+    Xn = host(Xin).astype(np.float64)
+    assert np.all(np.abs(Y - Xn @ What.T) <= 1e-5 * (np.abs(Xn) @ np.abs(What).T))
 
 
 def test_pack_rejects_bad_input(slim):
