@@ -52,6 +52,7 @@ slim_status slim_ensure_side(slim_ctx* ctx) {
   if (ctx->side) return SLIM_OK;
   SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
   SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking));
+  SLIM_HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->side3, hipStreamNonBlocking));
   for (hipEvent_t& e : ctx->ev) SLIM_HIP_TRY(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   return SLIM_OK;
 }
@@ -164,10 +165,11 @@ slim_status slim_destroy(slim_ctx* ctx) {
     for (hipEvent_t e : ctx->ev)
       if (e) (void)hipEventDestroy(e);
     (void)hipStreamDestroy(ctx->side);
-    if (ctx->side2) {
-      (void)hipStreamSynchronize(ctx->side2);
-      (void)hipStreamDestroy(ctx->side2);
-    }
+    for (hipStream_t st : {ctx->side2, ctx->side3})
+      if (st) {
+        (void)hipStreamSynchronize(st);
+        (void)hipStreamDestroy(st);
+      }
   }
   if (ctx->ws && !ctx->ws_external) (void)hipFree(ctx->ws);
   if (ctx->tau_default) (void)hipFree(ctx->tau_default);

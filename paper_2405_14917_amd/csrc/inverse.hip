@@ -14,8 +14,10 @@
 //        group update  rank-512 updates of everything further left, once per group
 //      The factorisation of the diagonal blocks and the GEMMs form two chains on two streams that only
 //      meet two steps apart, see the schedule at the call site.
-//   3. triangular inverse by recursive doubling: ranges of 2^l diagonal blocks that are already inverted
-//      are merged pairwise, U12 = -U11 (R12 U22); all pairs of a level form one batched GEMM launch.
+//   3. triangular inverse U = R^-1 group by group on a further stream, beside the factorisation: inside a group
+//      by recursive doubling (ranges of 2^l inverted diagonal blocks merged pairwise, U12 = -U11 (R12 U22)), the
+//      rows right of the group from T = R[g, S] U[S, S], which is kept up to date for all rows above by one
+//      rank-512 product per finished group (see the schedule at the call site).
 //   4. hinv_diag_j = sum_i U_ij^2.
 #include "slim_device.h"
 #include "slim_internal.h"
@@ -25,6 +27,10 @@ namespace {
 using slimdev::read_lane_f64;
 
 constexpr int NB = 64;          // diagonal block
+// Diagonal blocks per group.  With 8 the far updates have rank 512 (64 flops per byte of A they move, against 32 with
+// 4) and there are half as many of them; the windows of the chain get wider.  Inverse alone at m = 11008: 21.7 against
+// 22.2 ms; whole pass: 0.5 ms less on the 4096 x 11008 and 28672 x 8192 layers, 0.2 ms less on 4096 x 4096.
+constexpr int GRP = 8;
 
 // mean of the diagonal of H = s * G, then lambda; single workgroup, fixed order
 __global__ __launch_bounds__(1024) void damp_lambda(const float* __restrict__ G, int64_t ldg, int m, double s,
@@ -400,7 +406,6 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   // descriptors of the triangular inverse, built on the host
   std::vector<slim_gemm_desc> descs;
   struct Level { int first, count, maxM, maxN; };
-  std::vector<Level> levels;
 
   // A: the matrix being factored (upper triangle), later the scratch of the triangular inverse.
   // R: the factor, panel by panel (only the blocks above the diagonal are ever written or read).
@@ -427,35 +432,40 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   else
     SLIM_LAUNCH(ctx, "inv_widen", widen_damp<1>, dim3(slim_cdiv(m, 256), slim_cdiv(m, 8)), dim3(256), 0, G, ldg, m, s, lam, A, lda, U, ldu);
 
-  // ---- descriptors of the triangular inverse (pairwise merging of inverted diagonal ranges), staged first so
-  //      that no host synchronisation falls between the factorisation and the inverse
-  for (int64_t sz = NB; sz < m; sz *= 2) {
-    Level lv{(int)descs.size(), 0, 0, 0};
-    for (int64_t lo = 0; lo + sz < m; lo += 2 * sz) {
-      const int64_t mid = lo + sz, hi = std::min<int64_t>(lo + 2 * sz, m);
-      const int a = (int)sz, b = (int)(hi - mid);
-      slim_gemm_desc d;
-      // T12 = R12 * U22 (into the scratch, at the position of the block)
-      d.A = R + lo * lda + mid;
-      d.lda = lda;
-      d.B = U + mid * ldu + mid;
-      d.ldb = ldu;
-      d.C = A + lo * lda + mid;
-      d.ldc = lda;
-      d.C2 = nullptr;
-      d.ldc2 = 0;
-      d.M = a;
-      d.N = b;
-      d.K = b;
-      d.flags = SLIM_GEMM_B_UPPER;
-      d.alpha = 1.0;
-      d.beta = 0.0;
-      descs.push_back(d);
-      lv.count += 1;
-      lv.maxM = std::max(lv.maxM, a);
-      lv.maxN = std::max(lv.maxN, b);
+  // ---- descriptors of the triangular inverse inside the groups (pairwise merging of inverted diagonal ranges),
+  //      staged first so that no host synchronisation falls inside the factorisation
+  const int ngrp = slim_cdiv(nblk, GRP);
+  std::vector<std::vector<Level>> glevels(ngrp);
+  for (int Gi = 0; Gi < ngrp; ++Gi) {
+    const int64_t g0 = (int64_t)Gi * GRP * NB, g1 = std::min<int64_t>(m, g0 + GRP * NB);
+    for (int64_t sz = NB; sz < g1 - g0; sz *= 2) {
+      Level lv{(int)descs.size(), 0, 0, 0};
+      for (int64_t lo = g0; lo + sz < g1; lo += 2 * sz) {
+        const int64_t mid = lo + sz, hi = std::min<int64_t>(lo + 2 * sz, g1);
+        const int a = (int)sz, b = (int)(hi - mid);
+        slim_gemm_desc d;
+        // T12 = R12 * U22 (into the scratch, at the position of the block)
+        d.A = R + lo * lda + mid;
+        d.lda = lda;
+        d.B = U + mid * ldu + mid;
+        d.ldb = ldu;
+        d.C = A + lo * lda + mid;
+        d.ldc = lda;
+        d.C2 = nullptr;
+        d.ldc2 = 0;
+        d.M = a;
+        d.N = b;
+        d.K = b;
+        d.flags = SLIM_GEMM_B_UPPER;
+        d.alpha = 1.0;
+        d.beta = 0.0;
+        descs.push_back(d);
+        lv.count += 1;
+        lv.maxM = std::max(lv.maxM, a);
+        lv.maxN = std::max(lv.maxN, b);
+      }
+      glevels[Gi].push_back(lv);
     }
-    levels.push_back(lv);
   }
   const int n_first = (int)descs.size();
   // second product of every pair: U12 = -U11 * T12
@@ -519,11 +529,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       done = true;
     }
   }
-  // Blocks per group.  With 8 the far updates have rank 512 (64 flops per byte of A they move, against 32 with 4) and
-  // there are half as many of them; the windows of the chain get wider.  Inverse alone at m = 11008: 21.7 against 22.2
-  // ms; whole pass: 0.5 ms less on the 4096 x 11008 and 28672 x 8192 layers, 0.2 ms less on 4096 x 4096.
-  constexpr int GRP = 8;
-  hipStream_t s0 = ctx->stream, s1 = ctx->side, s2 = ctx->side2;
+  hipStream_t s0 = ctx->stream, s1 = ctx->side, s2 = ctx->side2, s3 = ctx->side3;
   hipEvent_t ev_fork = ctx->ev[0];
   hipEvent_t* ev_step = &ctx->ev[1];   // ring of 4
   hipEvent_t* ev_gemm = &ctx->ev[5];   // ring of 4
@@ -531,6 +537,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   SLIM_HIP_TRY(ctx, hipEventRecord(ev_fork, s0));
   SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s1, ev_fork, 0));
   SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s2, ev_fork, 0));
+  SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s3, ev_fork, 0));
   struct StreamSwap {
     slim_ctx* c;
     hipStream_t keep;
@@ -547,6 +554,77 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
     slim_ctx* c;
     ~AttachGuard() { c->attach_event = nullptr; }
   } attach_guard{ctx};
+  // ---- s3: the triangular inverse U = R^-1, group by group behind the factorisation.  With S the columns right of
+  //      group g, U[g, S] = -U[g, g] T[g, S] where T[g, S] = R[g, S] U[S, S] = sum over the groups h in S of
+  //      R[g, h] U[h, S]: the term of group h exists as soon as the rows U[h, :] do, for all rows above h at once
+  //      (a rank-512 product with a large result, like the far updates of the factorisation), so that the whole
+  //      inverse runs beside the factorisation, whose second half is a chain of small kernels on a nearly idle chip,
+  //      and only the last group's share is left when the last diagonal block is done.  Per group, in this order:
+  //        inside   U[g, g] by recursive doubling: ranges of 2^l inverted diagonal blocks are merged pairwise,
+  //                 U12 = -U11 (R12 U22); all pairs of a level form one batched launch
+  //        rows     U[g, S] = -U[g, g] T[g, S]
+  //        terms    T[0:g0, g0:m] (+)= R[0:g0, g] U[g, g0:m]   (first term of the columns of g itself, added to the
+  //                 columns right of it)
+  //      T lives in A right of the group, where the panels' inputs lay: the last reader of those columns of A is the
+  //      diagonal kernel of the block left of the group (its pending rank-64 update), which the caller waits for.
+  auto group_inverse = [&](int Gi) -> slim_status {
+    StreamSwap swap(ctx, s3);
+    const int64_t g0 = (int64_t)Gi * GRP * NB, g1 = std::min<int64_t>(m, g0 + GRP * NB);
+    const int gw = (int)(g1 - g0);
+    slim_status rs;
+    for (const Level& lv : glevels[Gi]) {
+      if (lv.count == 0) continue;
+      rs = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + lv.first, lv.count, lv.maxM, lv.maxN);
+      if (rs != SLIM_OK) return rs;
+      rs = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + n_first + lv.first, lv.count, lv.maxM, lv.maxN);
+      if (rs != SLIM_OK) return rs;
+    }
+    slim_gemm_desc d;
+    d.C2 = nullptr;
+    d.ldc2 = 0;
+    if (g1 < m) {
+      d.A = U + g0 * ldu + g0;
+      d.lda = ldu;
+      d.B = A + g0 * lda + g1;
+      d.ldb = lda;
+      d.C = U + g0 * ldu + g1;
+      d.ldc = ldu;
+      d.M = gw;
+      d.N = (int)(m - g1);
+      d.K = gw;
+      d.flags = SLIM_GEMM_A_UPPER;
+      d.alpha = -1.0;
+      d.beta = 0.0;
+      rs = slim_dgemm(ctx, "inv_trtri_rows_dgemm", 0, d);
+      if (rs != SLIM_OK) return rs;
+    }
+    if (g0 > 0) {
+      d.A = R + g0;
+      d.lda = lda;
+      d.B = U + g0 * ldu + g0;
+      d.ldb = ldu;
+      d.C = A + g0;
+      d.ldc = lda;
+      d.M = (int)g0;
+      d.N = gw;
+      d.K = gw;
+      d.flags = SLIM_GEMM_B_UPPER;
+      d.alpha = 1.0;
+      d.beta = 0.0;
+      rs = slim_dgemm(ctx, "inv_trtri_terms_dgemm", 0, d);
+      if (rs != SLIM_OK) return rs;
+      if (g1 < m) {
+        d.B = U + g0 * ldu + g1;
+        d.C = A + g1;
+        d.N = (int)(m - g1);
+        d.flags = 0;
+        d.beta = 1.0;
+        rs = slim_dgemm(ctx, "inv_trtri_terms_dgemm", 0, d);
+        if (rs != SLIM_OK) return rs;
+      }
+    }
+    return SLIM_OK;
+  };
   bool far_issued = false;
   int last_far_slot = 0;
   for (int J = nblk - 1; J >= 0; --J) {
@@ -571,6 +649,14 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
     SLIM_LAUNCH(ctx, "inv_chol_diag", chol_step, dim3(1), dim3(1024), CHOL_LDS, ca);
     if (J == 0) break;
     SLIM_HIP_TRY(ctx, slim_attach_flush(ctx));
+    // ---- s3: the group to the right is factored, its panels are complete (GEMMs of its first block), and with this
+    //      diagonal step the last reader of A right of this block is under way
+    if ((J + 1) % GRP == 0 && J + 1 < nblk) {
+      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s3, ev_gemm[(J + 1) & 3], 0));
+      SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s3, ev_step[J & 3], 0));
+      st = group_inverse((J + 1) / GRP);
+      if (st != SLIM_OK) return st;
+    }
 
     // ---- s1: GEMMs of block J
     const int G = J / GRP;                          // group of block J
@@ -678,20 +764,18 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
   hipEvent_t ev_info = ctx->ev[11];
   SLIM_HIP_TRY(ctx, hipMemcpyAsync(host, flag, sizeof(int), hipMemcpyDeviceToHost, s0));
   SLIM_HIP_TRY(ctx, hipEventRecord(ev_info, s0));
-  // the triangular inverse reads every panel of R and overwrites A
+  // the leftmost group's share of the triangular inverse: behind the last diagonal block and the last panels
+  hipEvent_t ev_last = ctx->ev[15], ev_tri = ctx->ev[14];
+  SLIM_HIP_TRY(ctx, hipEventRecord(ev_last, s0));
+  SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s3, ev_last, 0));
+  if (nblk > 1) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s3, ev_gemm[1 & 3], 0));
+  st = group_inverse(0);
+  if (st != SLIM_OK) return st;
+  SLIM_HIP_TRY(ctx, hipEventRecord(ev_tri, s3));
+  // every side stream has joined the caller's before the call's results are read (and before the workspace is reused)
   if (nblk > 1) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_gemm[1 & 3], 0));
   if (far_issued) SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_far[last_far_slot], 0));
-
-  // ---- triangular inverse U = R^-1: two batched GEMM launches per level
-  if (!descs.empty()) {
-    for (const Level& lv : levels) {
-      if (lv.count == 0) continue;
-      st = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + lv.first, lv.count, lv.maxM, lv.maxN);
-      if (st != SLIM_OK) return st;
-      st = slim_dgemm_batched(ctx, "inv_trtri_dgemm", 0, descs_dev + n_first + lv.first, lv.count, lv.maxM, lv.maxN);
-      if (st != SLIM_OK) return st;
-    }
-  }
+  SLIM_HIP_TRY(ctx, hipStreamWaitEvent(s0, ev_tri, 0));
 
   SLIM_LAUNCH(ctx, "inv_diag_colsumsq", colsumsq_upper, dim3(slim_cdiv(m, 64), parts), dim3(256), 0, U, ldu, m, partial);
   SLIM_LAUNCH(ctx, "inv_diag_finalize", colsum_finalize, dim3(slim_cdiv(m, 256)), dim3(256), 0, partial, parts, m, hinv_diag);

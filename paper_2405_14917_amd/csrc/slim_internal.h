@@ -26,7 +26,7 @@ struct slim_prof_pending {
   hipEvent_t start, stop;
 };
 
-constexpr int SLIM_NUM_EVENTS = 16;
+constexpr int SLIM_NUM_EVENTS = 20;
 
 // What slim_sba_prepare left in the workspace: valid until the next call that uses the workspace.
 struct slim_sba_prepared {
@@ -54,7 +54,7 @@ struct slim_ctx {
   int* dflags = nullptr;          // device, 64 ints (pivot failures, counters)
   char* hpin = nullptr;           // pinned host staging, SLIM_HPIN_BYTES
   // side streams (default priority) and events for work that overlaps with the main stream inside one call
-  hipStream_t side = nullptr, side2 = nullptr;
+  hipStream_t side = nullptr, side2 = nullptr, side3 = nullptr;
   bool on_side = false;           // `stream` temporarily names a side stream (profiling entries say so)
   hipEvent_t ev[SLIM_NUM_EVENTS] = {};
   // When set (and profiling is off), the next SLIM_LAUNCH signals this event through the kernel's own completion
