@@ -156,8 +156,14 @@ def algorithmic_work(name, cfg, launches_per_step):
     if name.startswith("inv_") and name.endswith("_dgemm"):
         # The factorisation and the triangular inverse together are (2/3) m^3 flops; the launch sites share them
         # as follows (each formula counts what that site's products compute, triangles once).
-        if name == "inv_trtri_dgemm":
-            tot = float(m) ** 3 / 3.0
+        w = INV_GRP * 64
+        groups = [(g0, min(m, g0 + w)) for g0 in range(0, m, w)]
+        if name == "inv_trtri_dgemm":          # inside the groups, beyond the diagonal blocks' own inverses
+            tot = sum(((g1 - g0) ** 3 - (g1 - g0) * 64.0 ** 2) / 3.0 for g0, g1 in groups)
+        elif name == "inv_trtri_rows_dgemm":   # U[g, S] = -U[g, g] T[g, S], U[g, g] triangular
+            tot = sum(float(g1 - g0) ** 2 * (m - g1) for g0, g1 in groups)
+        elif name == "inv_trtri_terms_dgemm":  # T[0:g0, g0:m] (+)= R[0:g0, g] U[g, g0:m], U[g, g] triangular
+            tot = sum(float(g0) * (g1 - g0) ** 2 + 2.0 * g0 * (g1 - g0) * (m - g1) for g0, g1 in groups)
         elif name == "inv_panel_dgemm":
             tot = sum(2.0 * j0 * 64 * 64 / 2 for j0 in range(64, m, 64))
         elif name == "inv_window_dgemm":
@@ -397,8 +403,9 @@ def main():
             "sqc_search": "alu peak counts an FMA as two operations; the search loop is mostly single-operation "
                           "instructions (multiply, round, two clamps), so its fraction of the issue bound is about "
                           "twice the frac given",
-            "inv_syrk_dgemm, inv_panel_dgemm, inv_window_dgemm, sba_output_dgemm": "run beside other streams' work by "
-                          "design (factorisation chains beside the SBA outputs on part of the chip): their durations "
+            "inv_syrk_dgemm, inv_panel_dgemm, inv_window_dgemm, inv_trtri_*_dgemm, sba_output_dgemm": "run beside other "
+                          "streams' work by design (the factorisation's chains, its far updates and the triangular "
+                          "inverse on four streams, beside the SBA outputs on part of the chip): their durations "
                           "overlap and their frac is not a fraction of the chip",
             "gram_mfma_f16": "power-limited: the same kernel runs at 0.71 of the nominal peak on constant data and at "
                              "0.49 to 0.51 on random data when Gram launches follow one another",

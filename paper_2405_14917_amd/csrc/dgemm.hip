@@ -348,6 +348,16 @@ slim_status slim_dgemm(slim_ctx* ctx, const char* name, int trans_b, const slim_
   slim_status st = check_desc(ctx, d);
   if (st != SLIM_OK) return st;
   if (d.M == 0 || d.N == 0) return SLIM_OK;
+  if (d.flags & SLIM_GEMM_CHAIN) {
+    const int tiles = slim_cdiv(d.M, 64) * slim_cdiv(d.N, 32);
+    if (trans_b)
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<1, 64, 32>"), (dgemm_kernel<1, 64, 32>), dim3(tiles),
+                  dim3(NTHREADS), smem_bytes(64, 32), d);
+    else
+      SLIM_LAUNCH(ctx, slim_prof_name(name, "dgemm_kernel<0, 64, 32>"), (dgemm_kernel<0, 64, 32>), dim3(tiles),
+                  dim3(NTHREADS), smem_bytes(64, 32), d);
+    return SLIM_OK;
+  }
   if (use_small_tiles(d.M, d.N, 1)) {
     const int tiles = slim_cdiv(d.M, 64) * slim_cdiv(d.N, 64);
     if (trans_b)

@@ -123,6 +123,20 @@ __device__ __forceinline__ void k_loop_fast(const slim_gemm_desc& d, int row0, i
           __builtin_amdgcn_sched_barrier(0);
         }
     }
+    // a tile with fewer MFMAs per slab than pieces to move issues the rest behind them
+    constexpr int NMFMA = (BK / 4) * MI * NJ;
+#pragma unroll
+    for (int g = NMFMA; g < NST + NLD; ++g) {
+      if (g < NST) {
+        store_piece(other, g);
+      } else {
+        if (g == NST) {
+          pa = pa_next;
+          pb = pb_next;
+        }
+        load_piece(g - NST);
+      }
+    }
     __syncthreads();
   }
 }

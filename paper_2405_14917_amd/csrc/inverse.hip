@@ -679,7 +679,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
       d.M = j0;
       d.N = nbk;
       d.K = nbk;
-      d.flags = 0;
+      d.flags = SLIM_GEMM_CHAIN;
       d.alpha = 1.0;
       d.beta = 0.0;
       // the stage's event goes with its last launch
@@ -720,6 +720,7 @@ extern "C" slim_status slim_hessian_inverse(slim_ctx* ctx, const float* G, int64
         d.M = g0;
         d.N = g0 - gp;
         d.K = g1 - j0;
+        d.flags = 0;
         d.alpha = -1.0;
         d.beta = 1.0;
         ctx->attach_event = ev_gemm[J & 3];

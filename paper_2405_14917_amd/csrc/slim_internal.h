@@ -160,8 +160,13 @@ inline int slim_cdiv(int64_t a, int64_t b) { return static_cast<int>((a + b - 1)
 //          SLIM_GEMM_ONE_PER_CU runs the product as a persistent kernel on all but a few CUs, one workgroup per
 //          CU, with an LDS request that lets nothing else share those CUs: for bulk work on a side stream next to
 //          a latency-critical chain of small kernels on other streams, which then finds the remaining CUs free.
+//          SLIM_GEMM_CHAIN marks a small product on a latency-critical chain that runs beside bulk products of other
+//          streams: 64 x 32 tiles, whose 24 KiB of LDS and 80 registers fit on a CU beside two workgroups of the
+//          128 x 128 form (LDS is handed out in pieces of 1280 bytes: two times 52 of the 128 pieces are taken, and
+//          the 32 KiB of a 64 x 64 tile need 26), so that its workgroups start at once instead of waiting for a
+//          bulk tile to end (panels and windows of the factorisation: a quarter less kernel time inside a pass).
 // K and N even, all pointers 16-byte aligned, leading dimensions even.
-enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4, SLIM_GEMM_ONE_PER_CU = 8 };
+enum { SLIM_GEMM_UPPER_ONLY = 1, SLIM_GEMM_A_UPPER = 2, SLIM_GEMM_B_UPPER = 4, SLIM_GEMM_ONE_PER_CU = 8, SLIM_GEMM_CHAIN = 16 };
 struct slim_gemm_desc {
   const double* A;
   const double* B;

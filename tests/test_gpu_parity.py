@@ -104,7 +104,9 @@ def test_hessian_accumulate_bf16_and_determinism(slim):
 
 
 # ------------------------------------------------------------------------------------------ a2
-@pytest.mark.parametrize("m", [64, 256, 320, 200, 72])
+# 576, 1090 and 1664: several groups of eight diagonal blocks, the last group (and, at 1090, the last block) ragged,
+# so that the group-by-group triangular inverse beside the factorisation is compared element by element too
+@pytest.mark.parametrize("m", [64, 256, 320, 200, 72, 576, 1090, 1664])
 def test_hessian_inverse(slim, m):
     rng = np.random.default_rng(m)
     t = 4 * m
