@@ -35,9 +35,9 @@ PEAK = {"mfma_f16": 2.5e15, "mfma_f64": 78.6e12, "alu_f64": 78.6e12, "hbm": 8.0e
 # Keyed by (config, kernel function), in bytes per pass; the line reports them per launch, like `achieved`.  A
 # configuration without such a run reports null.
 TRAFFIC_BYTES = {
-    # profiles/gram_C3_hbm_traffic.md, per PASS (the launches of a pass together): FETCH_SIZE 3.841e7 KiB x 2.0 (the
-    # yardstick's 65536 KiB read as 32778), WRITE_SIZE 5.475e5 KiB x 1.0 (its 65536 KiB written read as 65536)
-    ("C3", "gram_kernel_ring<false>"): 2.0 * 3.841e7 * 1024 + 1.0 * 5.475e5 * 1024,
+    # profiles/gram_C3_hbm_traffic.md, per PASS (the launches of a pass together): FETCH_SIZE 3.973e7 KiB x 2.0 (the
+    # yardstick's 65536 KiB read as 32778), WRITE_SIZE 5.566e5 KiB x 1.0 (its 65536 KiB written read as 65536)
+    ("C3", "gram_kernel_ring<false>"): 2.0 * 3.973e7 * 1024 + 1.0 * 5.566e5 * 1024,
 }
 SHAPE_NAMES = {"C1": "tiny layer", "C2": "LLaMA-7B q_proj shaped layer", "C3": "LLaMA-7B down_proj shaped layer",
                "C4": "LLaMA-13B up_proj shaped layer", "C5": "LLaMA-70B-shaped MLP layer"}
