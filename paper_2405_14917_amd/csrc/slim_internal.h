@@ -26,7 +26,7 @@ struct slim_prof_pending {
   hipEvent_t start, stop;
 };
 
-constexpr int SLIM_NUM_EVENTS = 20;
+constexpr int SLIM_NUM_EVENTS = 16;
 
 // What slim_sba_prepare left in the workspace: valid until the next call that uses the workspace.
 struct slim_sba_prepared {
