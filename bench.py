@@ -407,6 +407,8 @@ def main():
                           "streams' work by design (the factorisation's chains, its far updates and the triangular "
                           "inverse on four streams, beside the SBA outputs on part of the chip): their durations "
                           "overlap and their frac is not a fraction of the chip",
+            "hbm entries": "yardsticks on the same chip (plain PyTorch kernels, 1 to 4 GB): fill 6.9 TB/s, copy 4.9 to 5.3 TB/s "
+                           "read plus written (0.61 to 0.66 of the peak), read-only sum 4.0 TB/s, fp16 -> fp64 conversion 3.2 TB/s",
             "gram_mfma_f16": "power-limited: the same kernel runs at 0.71 of the nominal peak on constant data and at "
                              "0.49 to 0.51 on random data when Gram launches follow one another",
         },
