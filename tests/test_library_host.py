@@ -106,3 +106,24 @@ def test_workspace_query_is_host_only_and_follows_the_entry_points(binding):
     assert full == max(q(0, m, 0, t_c=131072, num_cus=256), q(n, m, beta, t_s=ts), q(n, m, beta, t_x=16, num_cus=256))
     # a small Gram matrix is split into more token ranges: the requirement is not monotone in m
     assert q(0, 256, 0, t_c=1 << 20, num_cus=256) > 0
+
+
+def test_bench_inverse_work_formulas_add_up():
+    """The per-site flop counts that bench.py rates the inverse's products with share out (2/3) m^3 (the factorisation
+    and the triangular inverse, triangles counted once) without gaps or double counting; the diagonal blocks' own
+    work (64^3 each, inside the diagonal kernel) is what is left."""
+    import bench
+    from paper_2405_14917_amd import synth
+    for name in ("C2", "C3", "C4", "C5"):
+        cfg = synth.CONFIGS[name]
+        m = cfg.m
+        sites = ("inv_panel_dgemm", "inv_window_dgemm", "inv_group_next_dgemm", "inv_syrk_dgemm", "inv_trtri_dgemm",
+                 "inv_trtri_rows_dgemm", "inv_trtri_terms_dgemm")
+        total = 0.0
+        for s in sites:
+            bound, peak, work = bench.algorithmic_work(s, cfg, 1)
+            assert bound == "mfma" and work > 0.0
+            total += work
+        whole = 2.0 * m ** 3 / 3.0
+        # the diagonal kernel's share is about (m / 64) * 64^3 flops: a few parts in ten thousand at these sizes
+        assert 0.97 * whole < total < 1.03 * whole, (name, total / whole)
