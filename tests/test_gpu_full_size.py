@@ -237,6 +237,47 @@ def test_default_scope_sweep_code_for_code(slim, layer):
     assert fro < 1e-3
 
 
+def test_chained_pass_from_the_same_gram_matrix(slim, layer):
+    """The whole C2 layer end to end behind the Gram matrix: the HIP path's inverse, salience, bit allocation and sweep,
+    each on the HIP path's own earlier results, against the oracle's steps in the same order, both started from the
+    SAME Gram matrix (the HIP path's, over all 131072 tokens).  Behind the Gram matrix both sides work in fp64, so the
+    the benchmark spec's end-to-end bar is asserted as it stands: dequantised weights within 1e-3 in relative Frobenius norm
+    (the pass from X on differs from the oracle's by the fp32 accumulation of the Gram matrix alone)."""
+    cfg = layer["cfg"]
+    if cfg.name != "C2":
+        pytest.skip("a whole oracle pass takes minutes beyond C2; the reduced shapes run the same chain")
+    Wd, Xd, W = layer["Wd"], layer["Xd"], layer["W"]
+    G = torch.zeros((cfg.m, cfg.m), dtype=torch.float32, device="cuda")
+    nt = slim.hessian_accumulate(Xd, G, 0)
+    U, d = slim.hessian_inverse(G, nt, cfg.percdamp)
+    _, grp, _ = slim.salience(Wd, d, cfg.beta)
+    bits, p_star, obj = slim.sba_allocate(Wd, grp, cfg.beta, cfg.N, Xd[:, :T_SBA])
+    out = slim.gptq_quantize(Wd, U, bits, cfg.beta, want_what=torch.float64)
+    t0 = time.perf_counter()
+    W64 = W.astype(np.float64)
+    Uo, do, _ = orc.hessian_inverse(host(G).astype(np.float64), nt, cfg.percdamp)
+    _, grp_o, _ = orc.salience(W64, do, cfg.beta)
+    assert layer["chunks"][0].shape[1] >= T_SBA
+    Xs = layer["chunks"][0][:, :T_SBA].astype(np.float64)
+    bits_o, p_o, obj_o, margin_o = orc.sba_allocate(W64, grp_o, cfg.beta, cfg.N, Xs)
+    ref = orc.gptq_quantize(W64, Uo, bits_o, cfg.beta, orc.tau_grid(), hinv_diag=do)
+    say("C2 chained pass: the oracle's steps took %.1f s" % (time.perf_counter() - t0))
+    assert np.linalg.norm(host(U) - Uo) / np.linalg.norm(Uo) < 1e-9
+    assert np.allclose(host(grp), grp_o, rtol=1e-9)
+    assert np.allclose(obj, obj_o, rtol=1e-8)
+    if margin_o > MARGIN:
+        assert p_star == p_o
+    assert np.array_equal(host(bits), bits_o)
+    codes = host(out["codes"])
+    ok = (ref["round_margin"].min(axis=1) > MARGIN) & (ref["sqc_margin"].min(axis=1) > MARGIN)
+    equal = float((codes == ref["codes"]).mean())
+    fro = np.linalg.norm(host(out["What"]) - ref["What"]) / np.linalg.norm(ref["What"])
+    say("C2 chained pass from the same Gram matrix: p* = %d, %d of %d rows outside the margin, equal codes %.6f, "
+        "||What - What_o||_F / ||What_o||_F = %.3e" % (p_star, ok.sum(), ok.size, equal, fro))
+    assert np.array_equal(codes[ok], ref["codes"][ok])
+    assert fro <= 1e-3
+
+
 def test_learnable_clipping_full_size(slim, layer):
     """SliM-LLM+ (learnable weight clipping, three AdamW steps) on the whole layer against the oracle, fed with the
     oracle-side Gram matrix and a fixed allocation."""
