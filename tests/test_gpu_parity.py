@@ -126,15 +126,17 @@ def test_hessian_inverse(slim, m):
     assert np.max(np.abs(U.T @ U @ Hd - np.eye(m))) < 1e-8
 
 
-def test_hessian_inverse_not_positive_definite(slim):
+# 128: one group of diagonal blocks; 1216: three groups (the last one ragged), with the triangular inverse and the far
+# updates on their own streams behind the failing block
+@pytest.mark.parametrize("m,bad", [(128, 37), (1216, 37), (1216, 700), (1216, 1200)])
+def test_hessian_inverse_not_positive_definite(slim, m, bad):
     from paper_2405_14917_amd import binding
-    m = 128
     G = np.eye(m, dtype=np.float32)
-    G[37, 37] = -4.0
+    G[bad, bad] = -4.0
     with pytest.raises(binding.SlimError) as ei:
         slim.hessian_inverse(dev(G), 16, 0.0)
     assert ei.value.status == binding.ERR_NOT_PD
-    assert slim.last_info == 38
+    assert slim.last_info == bad + 1
     # the context stays usable
     U, d = slim.hessian_inverse(dev(np.eye(m, dtype=np.float32)), 2, 0.0)
     assert np.allclose(host(U), np.eye(m))
